@@ -1,0 +1,163 @@
+"""ctypes access to the CPU oracle (oracle/uref.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, the smoke check and the
+benchmark's cpu_baseline leg; never by the product package.  Argument
+marshalling only -- all arithmetic is in uref.c.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "uref.c")
+_LIB = os.path.join(_HERE, "liburef.so")
+_lib = None
+
+
+def build(force: bool = True) -> str:
+    """Compile uref.c with gcc into oracle/liburef.so."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+                               "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+            build(force=True)
+        L = C.CDLL(_LIB)
+        vp, i32, i64, dbl = C.c_void_p, C.c_int, C.c_int64, C.c_double
+        L.uref_half_to_double.restype = dbl
+        L.uref_half_to_double.argtypes = [C.c_uint16]
+        L.uref_double_to_half.restype = C.c_uint16
+        L.uref_double_to_half.argtypes = [dbl]
+        L.uref_set_threads.argtypes = [i32]
+        L.uref_get_max_threads.restype = i32
+        L.uref_count_kept.argtypes = [i32, i32, vp, vp, vp]
+        L.uref_w4_dequant.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
+        L.uref_w4_linear.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, i64, vp, i64, i32, vp, i32]
+        L.uref_pruned_rope.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, dbl, vp, vp]
+        L.uref_quantize_sym.argtypes = [vp, i32, i32, i32, vp, vp, vp]
+        L.uref_quantize_asym.argtypes = [vp, i32, i32, i32, vp, vp, vp]
+        _lib = L
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _chk(a: np.ndarray, dtype, name: str) -> np.ndarray:
+    if a.dtype != dtype or not a.flags["C_CONTIGUOUS"]:
+        raise TypeError(f"{name}: expected C-contiguous {np.dtype(dtype)}, got {a.dtype}")
+    return a
+
+
+def _keep_arr(keep) -> np.ndarray:
+    if keep is None:
+        return np.zeros(7, dtype=np.int32)
+    t = keep.as_tuple() if hasattr(keep, "as_tuple") else tuple(keep)
+    assert len(t) == 7
+    return np.asarray(t, dtype=np.int32)
+
+
+def set_threads(n: int) -> None:
+    lib().uref_set_threads(int(n))
+
+
+def max_threads() -> int:
+    return int(lib().uref_get_max_threads())
+
+
+def half_to_double(bits: int) -> float:
+    return float(lib().uref_half_to_double(int(bits)))
+
+
+def double_to_half(x: float) -> int:
+    return int(lib().uref_double_to_half(float(x)))
+
+
+def count_kept(N_total: int, K_total: int, keep) -> tuple:
+    n, k = C.c_int32(0), C.c_int32(0)
+    ka = _keep_arr(keep)
+    lib().uref_count_kept(N_total, K_total, _p(ka), C.addressof(n), C.addressof(k))
+    return n.value, k.value
+
+
+def w4_dequant(qweight, scales, zeros, keep=None, group: int = 128) -> np.ndarray:
+    """fp16 [n_keep][k_keep] dequantised weights, RN16((q - z) * s)."""
+    N, K8 = qweight.shape
+    K = K8 * 8
+    _chk(qweight, np.uint32, "qweight"); _chk(scales, np.float16, "scales"); _chk(zeros, np.uint8, "zeros")
+    assert scales.shape == (N, K // group) and zeros.shape == (N, K // group)
+    ka = _keep_arr(keep)
+    nk, kk = count_kept(N, K, ka)
+    out = np.empty((nk, kk), dtype=np.float16)
+    rc = lib().uref_w4_dequant(_p(qweight), _p(scales), _p(zeros), N, K, group, _p(ka), _p(out))
+    assert rc == 0
+    return out
+
+
+def w4_linear(qweight, scales, zeros, x, keep=None, group: int = 128,
+              rows: Optional[Sequence[int]] = None) -> np.ndarray:
+    """fp64 y [M][n_keep] (or [M][len(rows)] for sampled compact rows)."""
+    N, K8 = qweight.shape
+    K = K8 * 8
+    _chk(qweight, np.uint32, "qweight"); _chk(scales, np.float16, "scales"); _chk(zeros, np.uint8, "zeros")
+    _chk(x, np.float16, "x")
+    ka = _keep_arr(keep)
+    nk, kk = count_kept(N, K, ka)
+    M = x.shape[0]
+    assert x.shape == (M, kk), (x.shape, kk)
+    rl = None if rows is None else np.ascontiguousarray(rows, dtype=np.int32)
+    n_out = nk if rl is None else rl.size
+    y = np.empty((M, n_out), dtype=np.float64)
+    rc = lib().uref_w4_linear(_p(qweight), _p(scales), _p(zeros), N, K, group, _p(ka),
+                              _p(x), kk, _p(y), n_out, M, _p(rl), 0 if rl is None else rl.size)
+    assert rc == 0, rc
+    return y
+
+
+def pruned_rope(q, k, positions, kept_idx, D_full: int, theta: float):
+    """fp64 rotated copies of q [T][Hq][D_keep] and k [T][Hkv][D_keep] (k may be None)."""
+    _chk(q, np.float16, "q"); _chk(positions, np.int32, "positions"); _chk(kept_idx, np.int32, "kept_idx")
+    T, Hq, Dk = q.shape
+    H_tab = kept_idx.shape[0]
+    assert kept_idx.shape == (H_tab, Dk // 2) and positions.shape == (T,)
+    q_out = np.empty(q.shape, dtype=np.float64)
+    Hkv, k_out = 0, None
+    if k is not None:
+        _chk(k, np.float16, "k")
+        assert k.shape[0] == T and k.shape[2] == Dk
+        Hkv = k.shape[1]
+        k_out = np.empty(k.shape, dtype=np.float64)
+    rc = lib().uref_pruned_rope(_p(q), _p(k), _p(positions), _p(kept_idx), T, Hq, Hkv, H_tab,
+                                D_full, Dk, float(theta), _p(q_out), _p(k_out))
+    assert rc == 0, rc
+    return q_out, k_out
+
+
+def _quantize(fn, w: np.ndarray, group: int):
+    w = np.ascontiguousarray(w, dtype=np.float64)
+    N, K = w.shape
+    assert K % group == 0 and K % 8 == 0
+    qweight = np.zeros((N, K // 8), dtype=np.uint32)
+    scales = np.zeros((N, K // group), dtype=np.float16)
+    zeros = np.zeros((N, K // group), dtype=np.uint8)
+    fn(_p(w), N, K, group, _p(qweight), _p(scales), _p(zeros))
+    return qweight, scales, zeros
+
+
+def quantize_sym(w: np.ndarray, group: int = 128):
+    return _quantize(lib().uref_quantize_sym, w, group)
+
+
+def quantize_asym(w: np.ndarray, group: int = 128):
+    return _quantize(lib().uref_quantize_asym, w, group)
