@@ -1,0 +1,150 @@
+/*
+ * uniql.h — C ABI of the MI355X (gfx950) library for the inference hot path of
+ * UniQL (arxiv 2512.03383): linear layers of 4-bit group-quantised, structurally
+ * pruned models, and the fused rotary embedding on pruned Q/K heads.
+ *
+ * Because the model's channels are sorted by importance once (Sec. 3.2), an
+ * on-device pruning rate only truncates each weight matrix to leading rows /
+ * columns (Sec. 3.4, "On-device adaptive pruning").  Here that truncation is a
+ * run-time argument: nothing is repacked when the rate changes.
+ *
+ * General rules for every entry point
+ *   - All data pointers are DEVICE pointers on the current HIP device; the
+ *     descriptor structs themselves are HOST memory, read during the call only.
+ *   - The caller owns every buffer.  The library allocates nothing, keeps no
+ *     reference after return and never synchronises: work is enqueued on
+ *     `hip_stream` (a hipStream_t passed as void*, NULL = default stream).
+ *   - Arguments are validated on the host before anything is launched.  Return
+ *     value 0 = enqueued; negative = error, nothing was launched.
+ *   - Values inside device tables (kept_idx entries, zeros > 15) are not
+ *     checked; out-of-range table entries are undefined behaviour.
+ *   - Results are deterministic: no atomics, fixed reduction order, so repeated
+ *     calls with the same arguments return the same bits.
+ */
+#ifndef UNIQL_H
+#define UNIQL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  UNIQL_OK = 0,
+  UNIQL_E_NULL = -1,  /* a required pointer is NULL                                   */
+  UNIQL_E_SHAPE = -2, /* impossible size: group != 128, K_total % 128, M < 1, ld < dim */
+  UNIQL_E_KEEP = -3,  /* kept dims inconsistent with totals / segment rule / heads     */
+  UNIQL_E_ALIGN = -4, /* qweight not 16-byte, scales / x / y / q / k not 2-byte,
+                         positions / kept_idx not 4-byte aligned                       */
+  UNIQL_E_ARCH = -5,  /* current device is not gfx950                                  */
+  UNIQL_E_HIP = -6    /* HIP runtime / launch error; see uniql_last_hip_error()        */
+};
+
+/*
+ * One quantised linear with N_total outputs and K_total inputs (the paper's
+ * W in R^{D_in x D_out}, Sec. 3.1, stored output-major).  Group-wise uniform
+ * 4-bit weights, group = 128 along the input dimension (Sec. 3.4, Eq. 3); the
+ * 4-bit codes are packed eight to a 32-bit word (Sec. 3.4).
+ *
+ *   qweight [N_total][K_total/8] : nibble j (bits 4j..4j+3) of word w of a row is
+ *                                  the code q of input column 8w+j, 0..15
+ *   scales  [N_total][K_total/128]: fp16 bits, scale s of the group
+ *   zeros   [N_total][K_total/128]: zero point z, 0..15 (Eq. 3's symmetric scheme
+ *                                  is z = 8 with stored code = signed code + 8)
+ * The dequantised weight is the fp16 number nearest (ties to even) to (q - z) * s.
+ * Groups are those of the unpruned matrix (quantisation precedes pruning).
+ */
+typedef struct uniql_w4 {
+  const uint32_t* qweight; /* device, 16-byte aligned */
+  const uint16_t* scales;  /* device */
+  const uint8_t* zeros;    /* device */
+  int32_t N_total, K_total, group;
+} uniql_w4_t;
+
+/*
+ * Which stored rows (outputs) and columns (inputs) survive pruning.  An
+ * all-zero struct (or a NULL pointer) means unpruned.
+ *
+ * rows: row_seg_stride == 0 : the first n_keep rows (n_keep == 0 -> all)
+ *       row_seg_stride  > 0 : row r is kept iff r >= row_seg_limit or
+ *                             (r % row_seg_stride) < row_seg_keep.  row_seg_limit
+ *                             must be a multiple of the stride; n_keep must be 0
+ *                             or the resulting count.
+ *       (MLP gate/up: prefix of D_int.  Q/K heads: stride D_hd/2, keep D'_hd/2 —
+ *        the leading channels of each half, Alg. 2.  V heads: stride D_hd, keep
+ *        D'_hd.  Mamba in_proj: stride d_inner over the z and x segments with the
+ *        B/C/dt rows above row_seg_limit kept whole, Alg. 5.)
+ * cols: col_seg_stride == 0 : the first k_keep columns (k_keep == 0 -> all)
+ *       col_seg_stride  > 0 : column k is kept iff (k % col_seg_stride) <
+ *                             col_seg_keep; K_total must be a multiple of the
+ *                             stride; k_keep must be 0 or the resulting count.
+ *       (MLP down / Mamba out_proj: prefix.  Attention o_proj: per-head segments.)
+ * Kept rows / columns appear in the compact y / x in increasing stored order.
+ */
+typedef struct uniql_keep {
+  int32_t n_keep, k_keep;
+  int32_t row_seg_stride, row_seg_keep, row_seg_limit;
+  int32_t col_seg_stride, col_seg_keep;
+} uniql_keep_t;
+
+/*
+ * y[m][r'] = sum over kept columns k' of x[m][k'] * w[row(r')][col(k')]   (Y = X W
+ * of Sec. 3.1 on the truncated matrix; the linears of Eq. 1, Eq. 2 and the Mamba
+ * block).  w is the fp16 dequantised weight defined above, products are summed
+ * in fp32 and y is rounded once to fp16.
+ *   x_f16 : device, fp16 [M][ldx], first k_keep entries of a row are the kept inputs
+ *   y_f16 : device, fp16 [M][ldy], first n_keep entries of a row are written
+ *   ldx >= k_keep, ldy >= n_keep (elements); x and y must not overlap.
+ * M = 1..4 run the streaming GEMV, larger M the MFMA dequant-GEMM.
+ * Errors: E_NULL, E_SHAPE, E_KEEP, E_ALIGN, E_ARCH, E_HIP.
+ */
+int uniql_w4_linear(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_f16, int64_t ldx,
+                    void* y_f16, int64_t ldy, int32_t M, void* hip_stream);
+
+/*
+ * Bit-exact dequantised weights of the kept sub-matrix:
+ *   w_f16[r'][k'] = RN_fp16((q - z) * s), fp16 [n_keep][k_keep] compact, device.
+ * (Sec. 3.4: the unpack step of "unpack, prune channels, repack".)
+ * Errors: as uniql_w4_linear.
+ */
+int uniql_w4_dequant(const uniql_w4_t* W, const uniql_keep_t* keep, void* w_f16, void* hip_stream);
+
+/*
+ * Fused rotary embedding on pruned heads, in place (Sec. 3.2 MHSA paragraph,
+ * Alg. 2 / Alg. A1, Fig. 4a).  A head keeps D_keep of D_full channels: the
+ * leading D_keep/2 of each half in sorted order, so kept pair i of a head is
+ * (v[i], v[i + D_keep/2]).  Its original pair index j = kept_idx[h_tab][i] picks
+ * the frequency: phi = positions[t] * theta^(-2j / D_full), and
+ *   v[i]            <- v[i] cos(phi) - v[i + D_keep/2] sin(phi)
+ *   v[i + D_keep/2] <- v[i + D_keep/2] cos(phi) + v[i] sin(phi)
+ * (RoPE(X) = cos * X + sin * R(X), R([x1, x2]) = [-x2, x1]).  Only half of the
+ * symmetric index vector is stored.  Q and K are rotated by the same launch.
+ *   q_f16     : device fp16 [T][Hq][D_keep], rotated in place
+ *   k_f16     : device fp16 [T][Hkv][D_keep] or NULL (then Hkv must be 0)
+ *   positions : device int32 [T]
+ *   kept_idx  : device int32 [H_tab][D_keep/2], entries in [0, D_full/2)
+ *   H_tab     : table rows; head h of a tensor with H heads uses row
+ *               h / (H / H_tab) (one row per KV head under GQA, per head for MHSA),
+ *               so Hq and Hkv must be multiples of H_tab
+ * The angle is formed in fp64 and reduced before the fp32 sin/cos.
+ * Errors: E_NULL, E_SHAPE (T < 1, Hq < 1), E_KEEP (D_keep odd, < 2 or > D_full,
+ * D_full odd, head counts not multiples of H_tab, theta <= 0), E_ALIGN, E_ARCH, E_HIP.
+ */
+int uniql_pruned_rope(void* q_f16, void* k_f16, const int32_t* positions, const int32_t* kept_idx,
+                      int32_t T, int32_t Hq, int32_t Hkv, int32_t H_tab, int32_t D_full,
+                      int32_t D_keep, double theta, void* hip_stream);
+
+/* Static string for an error code (never NULL). */
+const char* uniql_strerror(int code);
+
+/* Raw hipError_t of the last UNIQL_E_HIP on this thread (0 if none). */
+int uniql_last_hip_error(void);
+
+/* Library version, e.g. 100 = 0.1.0. */
+int uniql_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* UNIQL_H */

@@ -1,0 +1,190 @@
+"""Thin Python binding of libuniql (the C ABI in include/uniql.h).
+
+Argument marshalling only: every step of the hot path runs in the HIP kernels
+behind the C ABI.  PyTorch is used for device memory and streams.  There is no
+CPU fallback: if the library has not been built, importing a function that
+needs it raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libuniql.so")
+HEADER_PATH = os.path.join(os.path.dirname(_HERE), "include", "uniql.h")
+
+UNIQL_OK = 0
+UNIQL_E_NULL, UNIQL_E_SHAPE, UNIQL_E_KEEP, UNIQL_E_ALIGN, UNIQL_E_ARCH, UNIQL_E_HIP = -1, -2, -3, -4, -5, -6
+
+
+class UniqlError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"uniql error {code}: {msg}")
+        self.code = code
+
+
+class W4(C.Structure):
+    """uniql_w4_t"""
+    _fields_ = [("qweight", C.c_void_p), ("scales", C.c_void_p), ("zeros", C.c_void_p),
+                ("N_total", C.c_int32), ("K_total", C.c_int32), ("group", C.c_int32)]
+
+
+class KeepDesc(C.Structure):
+    """uniql_keep_t"""
+    _fields_ = [("n_keep", C.c_int32), ("k_keep", C.c_int32),
+                ("row_seg_stride", C.c_int32), ("row_seg_keep", C.c_int32), ("row_seg_limit", C.c_int32),
+                ("col_seg_stride", C.c_int32), ("col_seg_keep", C.c_int32)]
+
+
+_lib = None
+
+
+def build() -> str:
+    from .build import build_lib
+    global _lib
+    _lib = None
+    return build_lib()
+
+
+def lib():
+    """Load libuniql.so (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it first (python -m paper_2512_03383_amd.build); "
+                "there is no fallback path")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+        L.uniql_w4_linear.restype = C.c_int
+        L.uniql_w4_linear.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, i64, vp, i64, i32, vp]
+        L.uniql_w4_dequant.restype = C.c_int
+        L.uniql_w4_dequant.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, vp]
+        L.uniql_pruned_rope.restype = C.c_int
+        L.uniql_pruned_rope.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, C.c_double, vp]
+        L.uniql_strerror.restype = C.c_char_p
+        L.uniql_strerror.argtypes = [C.c_int]
+        L.uniql_last_hip_error.restype = C.c_int
+        L.uniql_version.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().uniql_strerror(int(code)).decode()
+
+
+def _check(code: int) -> None:
+    if code != UNIQL_OK:
+        msg = strerror(code)
+        if code == UNIQL_E_HIP:
+            msg += f" [hipError {lib().uniql_last_hip_error()}]"
+        raise UniqlError(code, msg)
+
+
+def _keep_desc(keep) -> Optional[KeepDesc]:
+    if keep is None:
+        return None
+    if isinstance(keep, KeepDesc):
+        return keep
+    t = keep.as_tuple() if hasattr(keep, "as_tuple") else tuple(keep)
+    return KeepDesc(*[int(v) for v in t])
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+@dataclass
+class QuantLinear:
+    """Device tensors of one quantised linear (torch owns the memory)."""
+    qweight: "torch.Tensor"   # int32 [N][K/8] (bit pattern of the uint32 words)
+    scales: "torch.Tensor"    # float16 [N][K/128]
+    zeros: "torch.Tensor"     # uint8 [N][K/128]
+
+    @property
+    def N(self) -> int:
+        return self.qweight.shape[0]
+
+    @property
+    def K(self) -> int:
+        return self.qweight.shape[1] * 8
+
+    def desc(self) -> W4:
+        return W4(self.qweight.data_ptr(), self.scales.data_ptr(), self.zeros.data_ptr(), self.N, self.K, 128)
+
+    @staticmethod
+    def from_numpy(w: dict, device="cuda") -> "QuantLinear":
+        import numpy as np
+        import torch
+        return QuantLinear(torch.from_numpy(w["qweight"].view(np.int32)).to(device),
+                           torch.from_numpy(w["scales"]).to(device),
+                           torch.from_numpy(w["zeros"]).to(device))
+
+
+def kept_dims(W: QuantLinear, keep) -> tuple:
+    """(n_keep, k_keep) the descriptor yields (same rule as the C ABI)."""
+    kd = _keep_desc(keep) or KeepDesc()
+    if kd.row_seg_stride:
+        n = (kd.row_seg_limit // kd.row_seg_stride) * kd.row_seg_keep + (W.N - kd.row_seg_limit)
+    else:
+        n = kd.n_keep or W.N
+    if kd.col_seg_stride:
+        k = (W.K // kd.col_seg_stride) * kd.col_seg_keep
+    else:
+        k = kd.k_keep or W.K
+    return n, k
+
+
+def uniql_w4_linear(W: QuantLinear, keep, x, y=None, stream=None):
+    """y[M][n_keep] = x[M][k_keep] @ W'^T on the current device; returns y."""
+    import torch
+    n_keep, k_keep = kept_dims(W, keep)
+    assert x.dtype == torch.float16 and x.is_cuda and x.dim() == 2 and x.stride(1) == 1
+    M = x.shape[0]
+    if y is None:
+        y = torch.empty((M, n_keep), dtype=torch.float16, device=x.device)
+    assert y.dtype == torch.float16 and y.is_cuda and y.stride(1) == 1
+    d, kd = W.desc(), _keep_desc(keep)
+    rc = lib().uniql_w4_linear(C.byref(d), C.byref(kd) if kd is not None else None,
+                               C.c_void_p(x.data_ptr()), x.stride(0), C.c_void_p(y.data_ptr()), y.stride(0),
+                               M, _stream_ptr(stream))
+    _check(rc)
+    return y
+
+
+def uniql_w4_dequant(W: QuantLinear, keep=None, out=None, stream=None):
+    """fp16 [n_keep][k_keep] bit-exact dequantised weights."""
+    import torch
+    n_keep, k_keep = kept_dims(W, keep)
+    if out is None:
+        out = torch.empty((n_keep, k_keep), dtype=torch.float16, device=W.qweight.device)
+    assert out.is_contiguous() and out.dtype == torch.float16
+    d, kd = W.desc(), _keep_desc(keep)
+    rc = lib().uniql_w4_dequant(C.byref(d), C.byref(kd) if kd is not None else None,
+                                C.c_void_p(out.data_ptr()), _stream_ptr(stream))
+    _check(rc)
+    return out
+
+
+def uniql_pruned_rope(q, k, positions, kept_idx, D_full: int, theta: float, stream=None):
+    """Rotate q [T][Hq][D_keep] and k [T][Hkv][D_keep] (or None) in place."""
+    import torch
+    assert q.dtype == torch.float16 and q.is_cuda and q.is_contiguous() and q.dim() == 3
+    T, Hq, Dk = q.shape
+    Hkv = 0
+    if k is not None:
+        assert k.dtype == torch.float16 and k.is_contiguous() and k.shape[0] == T and k.shape[2] == Dk
+        Hkv = k.shape[1]
+    assert positions.dtype == torch.int32 and positions.shape == (T,) and positions.is_contiguous()
+    assert kept_idx.dtype == torch.int32 and kept_idx.is_contiguous() and kept_idx.shape[1] == Dk // 2
+    rc = lib().uniql_pruned_rope(C.c_void_p(q.data_ptr()), C.c_void_p(k.data_ptr()) if k is not None else None,
+                                 C.c_void_p(positions.data_ptr()), C.c_void_p(kept_idx.data_ptr()),
+                                 T, Hq, Hkv, kept_idx.shape[0], D_full, Dk, float(theta), _stream_ptr(stream))
+    _check(rc)
+    return q, k

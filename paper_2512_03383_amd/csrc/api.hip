@@ -1,0 +1,164 @@
+// C ABI of libuniql: host-side validation and dispatch (declared in include/uniql.h).
+// All checks that do not need the device run before the first HIP call, so the
+// error paths behave the same on a machine without a GPU.
+#include "../../include/uniql.h"
+#include "common.h"
+
+#include <string.h>
+
+using namespace uniql;
+
+static thread_local int g_last_hip_error = 0;
+
+static int hip_fail(hipError_t e) {
+  g_last_hip_error = (int)e;
+  return UNIQL_E_HIP;
+}
+
+// gfx950 check, cached per device ordinal.
+static int check_arch() {
+  static int cached[64];   // 0 unknown, 1 ok, -1 wrong arch
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e);
+  if (dev >= 0 && dev < 64 && cached[dev] != 0) return cached[dev] > 0 ? UNIQL_OK : UNIQL_E_ARCH;
+  hipDeviceProp_t prop;
+  e = hipGetDeviceProperties(&prop, dev);
+  if (e != hipSuccess) return hip_fail(e);
+  int ok = strncmp(prop.gcnArchName, "gfx950", 6) == 0;
+  if (dev >= 0 && dev < 64) cached[dev] = ok ? 1 : -1;
+  return ok ? UNIQL_OK : UNIQL_E_ARCH;
+}
+
+static bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+// Validate W / keep and normalise the keep rule.  Pure host arithmetic.
+static int make_keepmap(const uniql_w4_t* W, const uniql_keep_t* keep, KeepMap* km) {
+  if (!W || !W->qweight || !W->scales || !W->zeros) return UNIQL_E_NULL;
+  if (W->group != kGroup || W->N_total < 1 || W->K_total < kGroup || W->K_total % kGroup) return UNIQL_E_SHAPE;
+  if (!aligned(W->qweight, 16) || !aligned(W->scales, 2)) return UNIQL_E_ALIGN;
+  uniql_keep_t none;
+  memset(&none, 0, sizeof(none));
+  if (!keep) keep = &none;
+  const int N = W->N_total, K = W->K_total;
+  if (keep->n_keep < 0 || keep->k_keep < 0 || keep->row_seg_stride < 0 || keep->col_seg_stride < 0) return UNIQL_E_KEEP;
+
+  km->rs_stride = keep->row_seg_stride;
+  km->rs_keep = km->rs_limit = km->rs_segrows = 0;
+  if (keep->row_seg_stride == 0) {
+    if (keep->n_keep > N) return UNIQL_E_KEEP;
+    km->n_keep = keep->n_keep ? keep->n_keep : N;
+  } else {
+    if (keep->row_seg_keep < 1 || keep->row_seg_keep > keep->row_seg_stride) return UNIQL_E_KEEP;
+    if (keep->row_seg_limit < 0 || keep->row_seg_limit > N || keep->row_seg_limit % keep->row_seg_stride) return UNIQL_E_KEEP;
+    km->rs_keep = keep->row_seg_keep;
+    km->rs_limit = keep->row_seg_limit;
+    km->rs_segrows = (keep->row_seg_limit / keep->row_seg_stride) * keep->row_seg_keep;
+    km->n_keep = km->rs_segrows + (N - keep->row_seg_limit);
+    if (keep->n_keep && keep->n_keep != km->n_keep) return UNIQL_E_KEEP;
+  }
+
+  km->cs_stride = keep->col_seg_stride;
+  km->cs_keep = 0;
+  if (keep->col_seg_stride == 0) {
+    if (keep->k_keep > K) return UNIQL_E_KEEP;
+    km->k_keep = keep->k_keep ? keep->k_keep : K;
+    km->k_span = km->k_keep;
+  } else {
+    if (keep->col_seg_keep < 1 || keep->col_seg_keep > keep->col_seg_stride) return UNIQL_E_KEEP;
+    if (K % keep->col_seg_stride) return UNIQL_E_KEEP;
+    km->cs_keep = keep->col_seg_keep;
+    km->k_keep = (K / keep->col_seg_stride) * keep->col_seg_keep;
+    if (keep->k_keep && keep->k_keep != km->k_keep) return UNIQL_E_KEEP;
+    km->k_span = K - (keep->col_seg_stride - keep->col_seg_keep);   // last kept column + 1
+  }
+  return UNIQL_OK;
+}
+
+extern "C" int uniql_w4_linear(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_f16, int64_t ldx,
+                               void* y_f16, int64_t ldy, int32_t M, void* hip_stream) {
+  LinearArgs a;
+  int rc = make_keepmap(W, keep, &a.km);
+  if (rc) return rc;
+  if (!x_f16 || !y_f16) return UNIQL_E_NULL;
+  if (M < 1 || ldx < a.km.k_keep || ldy < a.km.n_keep) return UNIQL_E_SHAPE;
+  if (!aligned(x_f16, 2) || !aligned(y_f16, 2)) return UNIQL_E_ALIGN;
+  rc = check_arch();
+  if (rc) return rc;
+  a.qweight = W->qweight;
+  a.scales = W->scales;
+  a.zeros = W->zeros;
+  a.x = (const half_t*)x_f16;
+  a.y = (half_t*)y_f16;
+  a.ldx = ldx;
+  a.ldy = ldy;
+  a.N_total = W->N_total;
+  a.K_total = W->K_total;
+  a.M = M;
+  hipStream_t s = (hipStream_t)hip_stream;
+  hipError_t e = (M <= 4) ? launch_w4_gemv(a, s) : launch_w4_gemm(a, s);
+  if (e == hipErrorInvalidValue && M <= 4) return UNIQL_E_SHAPE;   // K too long for the GEMV's staging
+  return e == hipSuccess ? UNIQL_OK : hip_fail(e);
+}
+
+extern "C" int uniql_w4_dequant(const uniql_w4_t* W, const uniql_keep_t* keep, void* w_f16, void* hip_stream) {
+  LinearArgs a;
+  int rc = make_keepmap(W, keep, &a.km);
+  if (rc) return rc;
+  if (!w_f16) return UNIQL_E_NULL;
+  if (!aligned(w_f16, 2)) return UNIQL_E_ALIGN;
+  rc = check_arch();
+  if (rc) return rc;
+  a.qweight = W->qweight;
+  a.scales = W->scales;
+  a.zeros = W->zeros;
+  a.x = nullptr;
+  a.y = (half_t*)w_f16;
+  a.ldx = 0;
+  a.ldy = a.km.k_keep;
+  a.N_total = W->N_total;
+  a.K_total = W->K_total;
+  a.M = 0;
+  hipError_t e = launch_w4_dequant(a, (hipStream_t)hip_stream);
+  return e == hipSuccess ? UNIQL_OK : hip_fail(e);
+}
+
+extern "C" int uniql_pruned_rope(void* q_f16, void* k_f16, const int32_t* positions, const int32_t* kept_idx,
+                                 int32_t T, int32_t Hq, int32_t Hkv, int32_t H_tab, int32_t D_full,
+                                 int32_t D_keep, double theta, void* hip_stream) {
+  if (!q_f16 || !positions || !kept_idx) return UNIQL_E_NULL;
+  if ((Hkv > 0) != (k_f16 != nullptr)) return Hkv > 0 ? UNIQL_E_NULL : UNIQL_E_SHAPE;
+  if (T < 1 || Hq < 1 || Hkv < 0) return UNIQL_E_SHAPE;
+  if (D_full < 2 || D_full % 2 || D_keep < 2 || D_keep % 2 || D_keep > D_full) return UNIQL_E_KEEP;
+  if (H_tab < 1 || Hq % H_tab || Hkv % H_tab) return UNIQL_E_KEEP;
+  if (!(theta > 0.0)) return UNIQL_E_KEEP;
+  if (!aligned(q_f16, 2) || !aligned(k_f16, 2) || !aligned(positions, 4) || !aligned(kept_idx, 4)) return UNIQL_E_ALIGN;
+  int rc = check_arch();
+  if (rc) return rc;
+  RopeArgs a;
+  a.q = (half_t*)q_f16;
+  a.k = (half_t*)k_f16;
+  a.positions = positions;
+  a.kept_idx = kept_idx;
+  a.T = T; a.Hq = Hq; a.Hkv = Hkv; a.H_tab = H_tab; a.D_full = D_full; a.D_keep = D_keep;
+  a.theta = theta;
+  hipError_t e = launch_pruned_rope(a, (hipStream_t)hip_stream);
+  return e == hipSuccess ? UNIQL_OK : hip_fail(e);
+}
+
+extern "C" const char* uniql_strerror(int code) {
+  switch (code) {
+    case UNIQL_OK: return "ok";
+    case UNIQL_E_NULL: return "a required pointer is NULL";
+    case UNIQL_E_SHAPE: return "impossible shape (group != 128, K_total % 128, M < 1, leading dimension too small, or K too long)";
+    case UNIQL_E_KEEP: return "kept dimensions inconsistent with totals, segment rule or head counts";
+    case UNIQL_E_ALIGN: return "pointer alignment (qweight 16 B; fp16 tensors 2 B; int32 tables 4 B)";
+    case UNIQL_E_ARCH: return "current device is not gfx950";
+    case UNIQL_E_HIP: return "HIP runtime error (see uniql_last_hip_error)";
+    default: return "unknown uniql error code";
+  }
+}
+
+extern "C" int uniql_last_hip_error(void) { return g_last_hip_error; }
+
+extern "C" int uniql_version(void) { return 100; }

@@ -1,0 +1,115 @@
+// Internal declarations shared by the HIP translation units of libuniql.
+// Nothing here is part of the C ABI (see include/uniql.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace uniql {
+
+typedef _Float16 half_t;
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
+constexpr int kGroup = 128;    // quantisation group along the input dimension
+constexpr int kWave = 64;      // wavefront width on CDNA
+
+// Normalised keep descriptor, computed on the host from uniql_keep_t.
+struct KeepMap {
+  int n_keep;       // compact output rows
+  int k_keep;       // compact input columns
+  int rs_stride;    // 0 = row prefix
+  int rs_keep;
+  int rs_limit;
+  int rs_segrows;   // compact rows that come from the segmented part
+  int cs_stride;    // 0 = column prefix
+  int cs_keep;
+  int k_span;       // stored columns [0, k_span) contain every kept column
+};
+
+// Everything a linear kernel needs, passed by value.
+struct LinearArgs {
+  const uint32_t* qweight;
+  const uint16_t* scales;
+  const uint8_t* zeros;
+  const half_t* x;
+  half_t* y;
+  long long ldx, ldy;
+  int N_total, K_total, M;
+  KeepMap km;
+};
+
+// compact output row -> stored row
+__device__ __forceinline__ int stored_row(const KeepMap& km, int rc) {
+  if (km.rs_stride == 0) return rc;
+  if (rc >= km.rs_segrows) return km.rs_limit + (rc - km.rs_segrows);
+  int seg = rc / km.rs_keep;
+  return seg * km.rs_stride + (rc - seg * km.rs_keep);
+}
+
+// stored column -> compact column, or -1 when the column is pruned
+__device__ __forceinline__ int compact_col(const KeepMap& km, int k) {
+  if (km.cs_stride == 0) return k < km.k_keep ? k : -1;
+  int seg = k / km.cs_stride;
+  int off = k - seg * km.cs_stride;
+  return off < km.cs_keep ? seg * km.cs_keep + off : -1;
+}
+
+// ---- int4 -> fp16 ---------------------------------------------------------
+// A 32-bit word holds codes q0..q7.  OR-ing a masked word with an fp16 exponent
+// pattern yields exact fp16 numbers without any conversion instruction:
+//   (w      & 0x000F000F) | 0x64006400 = (1024 + q0, 1024 + q4)
+//   (w      & 0x00F000F0) | 0x54005400 = (  64 + q1,   64 + q5)   (ulp of 64 is 1/16)
+//   (w >> 8 & 0x000F000F) | 0x64006400 = (1024 + q2, 1024 + q6)
+//   (w >> 8 & 0x00F000F0) | 0x54005400 = (  64 + q3,   64 + q7)
+// Subtracting (1024 + z) resp. (64 + z) is exact in fp16 and the following fp16
+// multiply by s rounds (q - z) * s once, to nearest even: the canonical weight.
+struct GroupQ {   // per (row, group) constants, as packed halves
+  half2_t zlo;    // (1024 + z, 1024 + z)
+  half2_t zhi;    // (  64 + z,   64 + z)
+  half2_t s2;     // (s, s)
+};
+
+__device__ __forceinline__ half2_t as_half2(uint32_t u) { return __builtin_bit_cast(half2_t, u); }
+__device__ __forceinline__ uint32_t as_u32(half2_t h) { return __builtin_bit_cast(uint32_t, h); }
+
+__device__ __forceinline__ GroupQ make_groupq(uint32_t scale_bits, uint32_t z) {
+  GroupQ g;
+  uint32_t zz = z | (z << 16);
+  g.zlo = as_half2(zz | 0x64006400u);
+  g.zhi = as_half2((zz << 4) | 0x54005400u);
+  g.s2 = as_half2(scale_bits | (scale_bits << 16));
+  return g;
+}
+
+// Dequantise one word into four half2: d[0]=(w0,w4) d[1]=(w1,w5) d[2]=(w2,w6) d[3]=(w3,w7).
+__device__ __forceinline__ void dequant_word(uint32_t w, const GroupQ& g, half2_t d[4]) {
+  uint32_t w8 = w >> 8;
+  half2_t h0 = as_half2((w & 0x000F000Fu) | 0x64006400u);
+  half2_t h1 = as_half2((w & 0x00F000F0u) | 0x54005400u);
+  half2_t h2 = as_half2((w8 & 0x000F000Fu) | 0x64006400u);
+  half2_t h3 = as_half2((w8 & 0x00F000F0u) | 0x54005400u);
+  d[0] = (h0 - g.zlo) * g.s2;
+  d[1] = (h1 - g.zhi) * g.s2;
+  d[2] = (h2 - g.zlo) * g.s2;
+  d[3] = (h3 - g.zhi) * g.s2;
+}
+
+// host-side launchers (one per translation unit)
+hipError_t launch_w4_gemv(const LinearArgs& a, hipStream_t stream);
+hipError_t launch_w4_gemm(const LinearArgs& a, hipStream_t stream);
+hipError_t launch_w4_dequant(const LinearArgs& a, hipStream_t stream);
+
+struct RopeArgs {
+  half_t* q;
+  half_t* k;
+  const int32_t* positions;
+  const int32_t* kept_idx;
+  int T, Hq, Hkv, H_tab, D_full, D_keep;
+  double theta;
+};
+hipError_t launch_pruned_rope(const RopeArgs& a, hipStream_t stream);
+
+}  // namespace uniql

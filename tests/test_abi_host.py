@@ -1,0 +1,121 @@
+"""Host-side checks of the C ABI (no GPU): the library loads, exports every
+function the header declares, and rejects bad arguments before any launch."""
+import ctypes as C
+import re
+
+import numpy as np
+import pytest
+
+import paper_2512_03383_amd as uq
+from paper_2512_03383_amd import KeepDesc, W4
+
+
+def declared_functions():
+    text = open(uq.HEADER_PATH).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(uniql_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert {"uniql_w4_linear", "uniql_w4_dequant", "uniql_pruned_rope", "uniql_strerror",
+            "uniql_last_hip_error"} <= set(names)
+    L = uq.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+    assert uq.lib().uniql_version() >= 100
+
+
+def test_struct_layout_matches_header():
+    assert C.sizeof(W4) == 3 * 8 + 3 * 4 + 4      # three pointers, three int32, tail padding
+    assert C.sizeof(KeepDesc) == 7 * 4
+    assert W4.N_total.offset == 24 and W4.group.offset == 32
+    assert KeepDesc.col_seg_keep.offset == 24
+
+
+def test_strerror_covers_all_codes():
+    msgs = {c: uq.strerror(c) for c in range(0, -8, -1)}
+    assert msgs[0] == "ok" and "NULL" in msgs[-1] and "gfx950" in msgs[-5]
+    assert len(set(msgs.values())) == 8
+
+
+# fake but well-aligned "device" addresses: validation must reject before touching them
+P = 0x10000
+
+
+def _w(N=256, K=512, group=128, q=P, s=P, z=P):
+    return W4(q, s, z, N, K, group)
+
+
+def _lin(w, keep, x=P, ldx=512, y=P, ldy=256, M=1):
+    kd = C.byref(keep) if keep is not None else None
+    return uq.lib().uniql_w4_linear(C.byref(w) if w is not None else None, kd, C.c_void_p(x), ldx,
+                                    C.c_void_p(y), ldy, M, None)
+
+
+def test_linear_rejects_null_shape_keep_align():
+    L = uq
+    assert _lin(None, None) == L.UNIQL_E_NULL
+    assert _lin(_w(q=0), None) == L.UNIQL_E_NULL
+    assert _lin(_w(), None, x=0) == L.UNIQL_E_NULL
+    assert _lin(_w(), None, y=0) == L.UNIQL_E_NULL
+    assert _lin(_w(group=64), None) == L.UNIQL_E_SHAPE
+    assert _lin(_w(K=520), None) == L.UNIQL_E_SHAPE
+    assert _lin(_w(N=0), None) == L.UNIQL_E_SHAPE
+    assert _lin(_w(), None, M=0) == L.UNIQL_E_SHAPE
+    assert _lin(_w(), None, ldx=511) == L.UNIQL_E_SHAPE
+    assert _lin(_w(), None, ldy=255) == L.UNIQL_E_SHAPE
+    assert _lin(_w(), KeepDesc(n_keep=100), ldy=99) == L.UNIQL_E_SHAPE
+    assert _lin(_w(q=P + 8), None) == L.UNIQL_E_ALIGN
+    assert _lin(_w(s=P + 1), None) == L.UNIQL_E_ALIGN
+    assert _lin(_w(), None, x=P + 1) == L.UNIQL_E_ALIGN
+    assert _lin(_w(), KeepDesc(n_keep=257)) == L.UNIQL_E_KEEP
+    assert _lin(_w(), KeepDesc(k_keep=513)) == L.UNIQL_E_KEEP
+    assert _lin(_w(), KeepDesc(n_keep=-1)) == L.UNIQL_E_KEEP
+    assert _lin(_w(), KeepDesc(row_seg_stride=64, row_seg_keep=65, row_seg_limit=256)) == L.UNIQL_E_KEEP
+    assert _lin(_w(), KeepDesc(row_seg_stride=64, row_seg_keep=0, row_seg_limit=256)) == L.UNIQL_E_KEEP
+    assert _lin(_w(), KeepDesc(row_seg_stride=64, row_seg_keep=32, row_seg_limit=100)) == L.UNIQL_E_KEEP
+    assert _lin(_w(), KeepDesc(row_seg_stride=64, row_seg_keep=32, row_seg_limit=320)) == L.UNIQL_E_KEEP
+    assert _lin(_w(), KeepDesc(n_keep=100, row_seg_stride=64, row_seg_keep=32, row_seg_limit=256)) == L.UNIQL_E_KEEP
+    assert _lin(_w(), KeepDesc(col_seg_stride=100, col_seg_keep=50)) == L.UNIQL_E_KEEP
+    assert _lin(_w(), KeepDesc(col_seg_stride=128, col_seg_keep=129)) == L.UNIQL_E_KEEP
+    assert _lin(_w(), KeepDesc(k_keep=7, col_seg_stride=128, col_seg_keep=64)) == L.UNIQL_E_KEEP
+
+
+def test_dequant_rejects_bad_arguments():
+    L = uq.lib()
+    w = _w()
+    assert L.uniql_w4_dequant(None, None, C.c_void_p(P), None) == uq.UNIQL_E_NULL
+    assert L.uniql_w4_dequant(C.byref(w), None, None, None) == uq.UNIQL_E_NULL
+    assert L.uniql_w4_dequant(C.byref(w), C.byref(KeepDesc(n_keep=1000)), C.c_void_p(P), None) == uq.UNIQL_E_KEEP
+
+
+def _rope(q=P, k=P, pos=P, idx=P, T=1, Hq=8, Hkv=2, H_tab=2, D_full=128, D_keep=108, theta=1e4):
+    return uq.lib().uniql_pruned_rope(C.c_void_p(q), C.c_void_p(k) if k else None, C.c_void_p(pos),
+                                      C.c_void_p(idx), T, Hq, Hkv, H_tab, D_full, D_keep, theta, None)
+
+
+def test_rope_rejects_bad_arguments():
+    assert _rope(q=0) == uq.UNIQL_E_NULL
+    assert _rope(pos=0) == uq.UNIQL_E_NULL
+    assert _rope(idx=0) == uq.UNIQL_E_NULL
+    assert _rope(k=0) == uq.UNIQL_E_NULL                 # Hkv > 0 needs k
+    assert _rope(Hkv=0) == uq.UNIQL_E_SHAPE              # k given but Hkv == 0
+    assert _rope(T=0) == uq.UNIQL_E_SHAPE
+    assert _rope(D_keep=107) == uq.UNIQL_E_KEEP
+    assert _rope(D_keep=130) == uq.UNIQL_E_KEEP
+    assert _rope(D_keep=0) == uq.UNIQL_E_KEEP
+    assert _rope(Hq=7) == uq.UNIQL_E_KEEP
+    assert _rope(Hkv=3) == uq.UNIQL_E_KEEP
+    assert _rope(theta=0.0) == uq.UNIQL_E_KEEP
+    assert _rope(q=P + 1) == uq.UNIQL_E_ALIGN
+    assert _rope(pos=P + 2) == uq.UNIQL_E_ALIGN
+
+
+def test_valid_arguments_without_gfx950_fail_loudly():
+    """On a box without an MI355X a valid call must report E_HIP / E_ARCH, never pretend to work."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present; covered by the gpu tests")
+    assert _lin(_w(), None) in (uq.UNIQL_E_HIP, uq.UNIQL_E_ARCH)
+    assert _rope() in (uq.UNIQL_E_HIP, uq.UNIQL_E_ARCH)

@@ -1,0 +1,315 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from workloads import Keep
+from parity_util import TOL, linear_err, rope_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env(uref):
+    import torch
+    import paper_2512_03383_amd as uq
+    assert torch.cuda.is_available(), "gpu tests need an MI355X"
+    uq.lib()
+    uref.set_threads(min(16, uref.max_threads()))
+    return uq, torch
+
+
+def to_dev(torch, a):
+    return torch.from_numpy(a).cuda()
+
+
+def run_linear(uq, torch, w, qw, keep, x, pad=0):
+    """GPU y as numpy fp16; pad > 0 puts x and y in wider buffers (ld > kept dim) filled with sentinels."""
+    M, kk = x.shape
+    nk, _ = uq.kept_dims(qw, keep)
+    if pad:
+        xb = torch.full((M, kk + pad), 77.0, dtype=torch.float16, device="cuda")
+        xb[:, :kk] = to_dev(torch, x)
+        yb = torch.full((M, nk + pad), -5.0, dtype=torch.float16, device="cuda")
+        uq.uniql_w4_linear(qw, keep, xb[:, :kk], yb[:, :nk])
+        torch.cuda.synchronize()
+        assert torch.all(yb[:, nk:] == -5.0), "wrote past n_keep"
+        return yb[:, :nk].cpu().numpy()
+    y = uq.uniql_w4_linear(qw, keep, to_dev(torch, x))
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+# ------------------------------------------------------------------ dequant
+def test_dequant_bit_exact_exhaustive(env, uref):
+    """Every (q, z) pair with every fp16 scale in (0.005, 0.02) and a few extreme scales."""
+    uq, torch = env
+    s_bits = np.arange(np.float16(0.005).view(np.uint16), np.float16(0.02).view(np.uint16) + 1, dtype=np.uint16)
+    extra = np.array([0x0001, 0x0003, 0x03ff, 0x0400, 0x0401, 0x1400, 0x3c00, 0x3c01, 0x6bff, 0x7000, 0x8001, 0xbc00],
+                     dtype=np.uint16)
+    s_all = np.concatenate([s_bits, extra]).view(np.float16)
+    N, K = s_all.size, 16 * 128
+    word_lo = sum(j << (4 * j) for j in range(8))
+    word_hi = sum((8 + j) << (4 * j) for j in range(8))
+    qweight = np.zeros((N, K // 8), dtype=np.uint32)
+    qweight[:, 0::2] = word_lo
+    qweight[:, 1::2] = word_hi
+    w = {"qweight": qweight, "scales": np.repeat(s_all[:, None], 16, axis=1).copy(),
+         "zeros": np.tile(np.arange(16, dtype=np.uint8), (N, 1))}
+    ref = uref.w4_dequant(w["qweight"], w["scales"], w["zeros"])
+    qw = uq.QuantLinear.from_numpy(w)
+    got = uq.uniql_w4_dequant(qw).cpu().numpy()
+    assert np.array_equal(got.view(np.uint16), ref.view(np.uint16))
+    # the kernels' packed-fp16 dequantisation, observed through one-hot inputs: y[:, k] is column k
+    for M in (1, 8):
+        for k in (0, 5, 127, 128 + 9, K - 1):
+            x = np.zeros((M, K), dtype=np.float16)
+            x[:, k] = 1.0
+            y = run_linear(uq, torch, w, qw, None, x)
+            assert np.array_equal(y[0].view(np.uint16), ref[:, k].view(np.uint16)), (M, k)
+
+
+KEEPS = [
+    Keep(),
+    Keep(n_keep=870),
+    Keep(k_keep=870),
+    Keep(n_keep=333, k_keep=517),
+    Keep(n_keep=1, k_keep=1),
+    Keep(n_keep=16 * 54, row_seg_stride=64, row_seg_keep=54, row_seg_limit=1024),
+    Keep(k_keep=8 * 108, col_seg_stride=128, col_seg_keep=108),
+    Keep(n_keep=2 * 300 + 224, row_seg_stride=400, row_seg_keep=300, row_seg_limit=800),
+    Keep(n_keep=8 * 82, k_keep=16 * 41, row_seg_stride=128, row_seg_keep=82, row_seg_limit=1024,
+         col_seg_stride=64, col_seg_keep=41),
+]
+
+
+@pytest.mark.parametrize("keep", KEEPS)
+def test_dequant_bit_exact_pruned(env, uref, keep):
+    uq, torch = env
+    w = wl.gen_linear(wl.rng_for(0, 30), 1024, 1024)
+    ref = uref.w4_dequant(w["qweight"], w["scales"], w["zeros"], keep)
+    got = uq.uniql_w4_dequant(uq.QuantLinear.from_numpy(w), keep).cpu().numpy()
+    assert np.array_equal(got.view(np.uint16), ref.view(np.uint16))
+
+
+# ------------------------------------------------------------------- linear
+def test_small_case_config0(env, uref):
+    """1024x1024, first 870 output rows, M = 1 (the small benchmark configuration)."""
+    uq, torch = env
+    spec = wl.small_case()
+    rng = wl.rng_for(0)
+    w = wl.gen_linear(rng, spec.N, spec.K)
+    x = wl.gen_activations(rng, 1, spec.k_keep)
+    ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], x, spec.keep)
+    y = run_linear(uq, torch, w, uq.QuantLinear.from_numpy(w), spec.keep, x)
+    assert y.shape == (1, 870)
+    assert linear_err(y, ref) <= TOL
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 8, 16, 33, 64, 100])
+@pytest.mark.parametrize("keep", KEEPS)
+def test_linear_parity_1024(env, uref, keep, M):
+    uq, torch = env
+    rng = wl.rng_for(0, 31)
+    w = wl.gen_linear(rng, 1024, 1024)
+    qw = uq.QuantLinear.from_numpy(w)
+    nk, kk = uq.kept_dims(qw, keep)
+    x = wl.gen_activations(rng, M, kk)
+    ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], x, keep)
+    y = run_linear(uq, torch, w, qw, keep, x, pad=3 if M in (1, 5, 33) else 0)
+    assert linear_err(y, ref) <= TOL
+
+
+@pytest.mark.parametrize("N,K,keep", [
+    (48, 128, Keep()),                      # a single group, fewer rows than one block handles
+    (7, 256, Keep(k_keep=129)),             # one column into the second group
+    (130, 2176, Keep(n_keep=129, k_keep=2049)),   # one column past a 2048-column chunk
+    (64, 18944, Keep(k_keep=14208)),        # longest benchmark K (Qwen MLP down)
+    (300, 4096, Keep()),
+])
+@pytest.mark.parametrize("M", [1, 4, 7])
+def test_linear_parity_ragged_shapes(env, uref, N, K, keep, M):
+    uq, torch = env
+    rng = wl.rng_for(0, 32)
+    w = wl.gen_linear(rng, N, K)
+    qw = uq.QuantLinear.from_numpy(w)
+    nk, kk = uq.kept_dims(qw, keep)
+    x = wl.gen_activations(rng, M, kk)
+    ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], x, keep)
+    y = run_linear(uq, torch, w, qw, keep, x)
+    assert linear_err(y, ref) <= TOL
+
+
+def test_symmetric_zero8_and_extreme_values(env, uref):
+    """zero = 8 everywhere (the symmetric scheme), large activations, zero activations."""
+    uq, torch = env
+    rng = wl.rng_for(0, 33)
+    w = wl.gen_linear(rng, 256, 512, sym_zero=True)
+    qw = uq.QuantLinear.from_numpy(w)
+    for M in (1, 6):
+        x = (wl.gen_activations(rng, M, 512).astype(np.float32) * 50).astype(np.float16)
+        ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], x)
+        assert linear_err(run_linear(uq, torch, w, qw, None, x), ref) <= TOL
+        x0 = np.zeros((M, 512), dtype=np.float16)
+        assert np.all(run_linear(uq, torch, w, qw, None, x0) == 0)
+
+
+def test_keep_changes_between_calls_and_determinism(env, uref):
+    """The pruning rate is a run-time argument: alternate keeps on the same weights; identical bits on repeats;
+    row truncation returns exactly the matching outputs of the unpruned call."""
+    uq, torch = env
+    rng = wl.rng_for(0, 34)
+    w = wl.gen_linear(rng, 1024, 1024)
+    qw = uq.QuantLinear.from_numpy(w)
+    x = wl.gen_activations(rng, 1, 1024)
+    xd = to_dev(torch, x)
+    full = uq.uniql_w4_linear(qw, None, xd).cpu().numpy()
+    seen = {}
+    for rep in range(3):
+        for n in (1024, 870, 665, 870, 1024):
+            y = uq.uniql_w4_linear(qw, Keep(n_keep=n), xd).cpu().numpy()
+            assert np.array_equal(y.view(np.uint16), full[:, :n].view(np.uint16))
+            seen.setdefault(n, y)
+            assert np.array_equal(seen[n].view(np.uint16), y.view(np.uint16))
+    for kk in (870, 665):
+        ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], np.ascontiguousarray(x[:, :kk]), Keep(k_keep=kk))
+        y = uq.uniql_w4_linear(qw, Keep(k_keep=kk), xd[:, :kk].contiguous()).cpu().numpy()
+        assert linear_err(y, ref) <= TOL
+
+
+def _sample_rows(n, rng, count=192):
+    rows = np.unique(np.concatenate([[0, 1, n - 2, n - 1], rng.integers(0, n, count)]))
+    return rows.astype(np.int32)
+
+
+@pytest.mark.parametrize("rate", [0, 15, 35])
+def test_llama3_8b_decode_layer_full_size(env, uref, rate):
+    """All seven linears of the Llama-3-8B shaped layer at full size, M = 1; sampled rows against the oracle,
+    all rows against the row-truncation property."""
+    uq, torch = env
+    rng = wl.rng_for(1, rate)
+    for spec in wl.llama3_8b_layer(rate):
+        w = wl.gen_linear(rng, spec.N, spec.K)
+        qw = uq.QuantLinear.from_numpy(w)
+        x = wl.gen_activations(rng, 1, spec.k_keep)
+        y = run_linear(uq, torch, w, qw, spec.keep, x)
+        assert y.shape == (1, spec.n_keep)
+        rows = _sample_rows(spec.n_keep, rng)
+        ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], x, spec.keep, rows=rows)
+        full_ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], x, spec.keep) if spec.N <= 1024 else None
+        rms = np.sqrt(np.mean(ref ** 2))
+        den = np.maximum(np.abs(ref), 1e-2 * rms)
+        err = np.max(np.abs(y[:, rows].astype(np.float64) - ref) / den)
+        assert err <= TOL, (spec.name, err)
+        if full_ref is not None:
+            assert linear_err(y, full_ref) <= TOL
+        y2 = run_linear(uq, torch, w, qw, spec.keep, x)
+        assert np.array_equal(y.view(np.uint16), y2.view(np.uint16))
+
+
+@pytest.mark.parametrize("M", [1, 8, 16])
+def test_qwen25_7b_shapes(env, uref, M):
+    uq, torch = env
+    rng = wl.rng_for(2, M)
+    for spec in wl.qwen25_7b_layer(25):
+        if spec.name in ("up_proj", "v_proj"):
+            continue
+        w = wl.gen_linear(rng, spec.N, spec.K)
+        qw = uq.QuantLinear.from_numpy(w)
+        x = wl.gen_activations(rng, M, spec.k_keep)
+        y = run_linear(uq, torch, w, qw, spec.keep, x)
+        rows = _sample_rows(spec.n_keep, rng, 96)
+        ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], x, spec.keep, rows=rows)
+        rms = np.sqrt(np.mean(ref ** 2, axis=-1, keepdims=True))
+        err = np.max(np.abs(y[:, rows].astype(np.float64) - ref) / np.maximum(np.abs(ref), 1e-2 * rms))
+        assert err <= TOL, (spec.name, err)
+
+
+def test_mamba2_shapes(env, uref):
+    uq, torch = env
+    rng = wl.rng_for(3)
+    for spec in wl.mamba2_2p7b_layer(15):
+        w = wl.gen_linear(rng, spec.N, spec.K)
+        qw = uq.QuantLinear.from_numpy(w)
+        x = wl.gen_activations(rng, 1, spec.k_keep)
+        y = run_linear(uq, torch, w, qw, spec.keep, x)
+        rows = _sample_rows(spec.n_keep, rng, 128)
+        if spec.name == "in_proj":      # include the segment boundaries and the whole tail
+            rows = np.unique(np.concatenate([rows, [4351, 4352, 8703, 8704, 9039]])).astype(np.int32)
+        ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], x, spec.keep, rows=rows)
+        rms = np.sqrt(np.mean(ref ** 2))
+        err = np.max(np.abs(y[:, rows].astype(np.float64) - ref) / np.maximum(np.abs(ref), 1e-2 * rms))
+        assert err <= TOL, (spec.name, err)
+
+
+@pytest.mark.parametrize("M", [256, 1024])
+def test_prefill_gemm_sampled(env, uref, M):
+    """Prefill-sized dequant-GEMM at the gate/up and down shapes, 15 % pruning: sampled (token, row) pairs."""
+    uq, torch = env
+    rng = wl.rng_for(4, M)
+    for spec in wl.prefill_linears(15):
+        w = wl.gen_linear(rng, spec.N, spec.K)
+        qw = uq.QuantLinear.from_numpy(w)
+        x = wl.gen_activations(rng, M, spec.k_keep)
+        y = run_linear(uq, torch, w, qw, spec.keep, x)
+        toks = np.unique(np.concatenate([[0, M - 1], rng.integers(0, M, 6)]))
+        rows = _sample_rows(spec.n_keep, rng, 64)
+        ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], np.ascontiguousarray(x[toks]), spec.keep, rows=rows)
+        rms = np.sqrt(np.mean(ref ** 2, axis=-1, keepdims=True))
+        got = y[np.ix_(toks, rows)].astype(np.float64)
+        err = np.max(np.abs(got - ref) / np.maximum(np.abs(ref), 1e-2 * rms))
+        assert err <= TOL, (spec.name, err)
+
+
+# --------------------------------------------------------------------- RoPE
+def run_rope(uq, torch, r, spec):
+    q = to_dev(torch, r["q"])
+    k = to_dev(torch, r["k"]) if r["k"] is not None else None
+    uq.uniql_pruned_rope(q, k, to_dev(torch, r["positions"]), to_dev(torch, r["kept_idx"]), spec.D_full, spec.theta)
+    torch.cuda.synchronize()
+    return q.cpu().numpy(), (k.cpu().numpy() if k is not None else None)
+
+
+@pytest.mark.parametrize("spec", [
+    wl.small_rope(),
+    wl.llama3_8b_rope(0), wl.llama3_8b_rope(15), wl.llama3_8b_rope(35),
+    wl.qwen25_7b_rope(25, T=16),
+    wl.llama3_8b_rope(15, T=37),
+    wl.RopeSpec(T=3, Hq=4, Hkv=4, H_tab=4, D_full=64, D_keep=2, theta=1e4, pos_max=100),
+    wl.RopeSpec(T=5, Hq=6, Hkv=2, H_tab=1, D_full=256, D_keep=200, theta=1e6, pos_max=32768),
+    wl.RopeSpec(T=2, Hq=2, Hkv=0, H_tab=2, D_full=1024, D_keep=700, theta=1e4, pos_max=32768),
+], ids=lambda s: f"T{s.T}_H{s.Hq}-{s.Hkv}-{s.H_tab}_D{s.D_full}-{s.D_keep}")
+def test_rope_parity(env, uref, spec):
+    uq, torch = env
+    r = wl.gen_rope_inputs(wl.rng_for(1, 40), spec)
+    qo, ko = uref.pruned_rope(r["q"], r["k"], r["positions"], r["kept_idx"], spec.D_full, spec.theta)
+    gq, gk = run_rope(uq, torch, r, spec)
+    assert rope_err(gq, qo) <= TOL
+    if ko is not None:
+        assert rope_err(gk, ko) <= TOL
+    # pair norms survive up to fp16 rounding
+    hk = spec.D_keep // 2
+    n_in = r["q"].astype(np.float64)[..., :hk] ** 2 + r["q"].astype(np.float64)[..., hk:] ** 2
+    n_out = gq.astype(np.float64)[..., :hk] ** 2 + gq.astype(np.float64)[..., hk:] ** 2
+    assert np.max(np.abs(n_in - n_out) / np.maximum(n_in, 1e-3)) < 4e-3
+
+
+def test_rope_prefill_full_size(env, uref):
+    """[4096 tokens, 32 Q + 8 KV heads, 108 of 128 dims], positions 0..4095: every element against the oracle."""
+    uq, torch = env
+    spec = wl.prefill_rope(15, T=4096)
+    r = wl.gen_rope_inputs(wl.rng_for(4, 41), spec)
+    qo, ko = uref.pruned_rope(r["q"], r["k"], r["positions"], r["kept_idx"], spec.D_full, spec.theta)
+    gq, gk = run_rope(uq, torch, r, spec)
+    assert rope_err(gq, qo) <= TOL and rope_err(gk, ko) <= TOL
+    gq2, gk2 = run_rope(uq, torch, r, spec)
+    assert np.array_equal(gq.view(np.uint16), gq2.view(np.uint16))
+
+
+def test_rope_position_zero_and_identity_table(env, uref):
+    uq, torch = env
+    spec = wl.RopeSpec(T=4, Hq=8, Hkv=2, H_tab=2, D_full=128, D_keep=128, theta=5e5, pos_max=1)
+    r = wl.gen_rope_inputs(wl.rng_for(1, 42), spec)
+    gq, gk = run_rope(uq, torch, r, spec)          # all positions are 0: the identity
+    assert np.array_equal(gq.view(np.uint16), r["q"].view(np.uint16))
+    assert np.array_equal(gk.view(np.uint16), r["k"].view(np.uint16))
