@@ -1,0 +1,278 @@
+#!/usr/bin/env python3
+"""Benchmark of the pruned W4A16 decode hot path on one MI355X.
+
+A step is one pass of the whole hot path over one Llama-3-8B shaped decoder
+layer at batch 1: q/k/v projections, fused pruned RoPE on the fresh Q/K heads,
+o_proj, gate/up/down -- seven W4A16 linears and one RoPE launch, all through the
+C ABI.  Consecutive steps walk through a pool of distinct layers (a 32-layer
+model, several GB), so every step streams its weights from HBM, not from the
+256 MB Infinity Cache.  Inputs are seeded synthetic stand-ins (random nibbles,
+fp16 scales ~ U(0.005, 0.02), zeros ~ U{0..15}, activations ~ N(0, 1)).
+
+Prints one JSON line (see the keys below); human-readable detail goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import workloads as wl  # noqa: E402
+
+METRIC = "µs and achieved HBM GB/s per pruned W4A16 decode linear (Llama-3-8B shapes)"
+HBM_PEAK_GBS = 8000.0
+MFMA_F16_PEAK_TFLOPS = 2500.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class Layer:
+    """Device tensors and buffers of one decoder layer at one pruning rate."""
+
+    def __init__(self, torch, uq, specs, rope, layer_index, rate, host_first=True):
+        self.specs = specs
+        self.rope = rope
+        self.lin = {}
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(wl.SEED_BASE + 1000 * rate + layer_index)
+        for si, s in enumerate(specs):
+            if layer_index == 0 and host_first:
+                w = wl.gen_linear(wl.rng_for(1, 100 * rate + si), s.N, s.K)
+                self.lin[s.name] = uq.QuantLinear.from_numpy(w)
+                if not hasattr(self, "host"):
+                    self.host = {}
+                self.host[s.name] = w
+            else:
+                qw = (torch.randint(0, 2 ** 32, (s.N, s.K // 8), dtype=torch.int64, device="cuda", generator=gen)
+                      - 2 ** 31).to(torch.int32)
+                sc = (torch.rand((s.N, s.K // 128), device="cuda", generator=gen) * 0.015 + 0.005).to(torch.float16)
+                zr = torch.randint(0, 16, (s.N, s.K // 128), dtype=torch.uint8, device="cuda", generator=gen)
+                self.lin[s.name] = uq.QuantLinear(qw, sc, zr)
+
+
+class DecodeStep:
+    """Buffers shared by all layers plus the launch sequence of one step."""
+
+    def __init__(self, torch, uq, specs, rope, M=1):
+        self.torch, self.uq, self.specs, self.rope, self.M = torch, uq, specs, rope, M
+        rng = wl.rng_for(1, 999)
+        self.xin = {}
+        self.yout = {}
+        self.host_x = {}
+        for s in specs:
+            x = wl.gen_activations(rng, M, s.k_keep)
+            self.host_x[s.name] = x
+            self.xin[s.name] = torch.from_numpy(x).cuda()
+            self.yout[s.name] = torch.empty((M, s.n_keep), dtype=torch.float16, device="cuda")
+        r = wl.gen_rope_inputs(rng, rope)
+        self.host_rope = r
+        self.pos = torch.from_numpy(r["positions"]).cuda()
+        self.idx = torch.from_numpy(r["kept_idx"]).cuda()
+
+    def run(self, layer, only=None):
+        uq = self.uq
+        for s in self.specs:
+            if only is not None and s.name != only:
+                continue
+            uq.uniql_w4_linear(layer.lin[s.name], s.keep, self.xin[s.name], self.yout[s.name])
+            if s.name == "k_proj" and only is None:
+                # q and k were just produced: rotate them in place, one launch for both
+                q = self.yout["q_proj"].view(self.M, self.rope.Hq, self.rope.D_keep)
+                k = self.yout["k_proj"].view(self.M, self.rope.Hkv, self.rope.D_keep)
+                uq.uniql_pruned_rope(q, k, self.pos, self.idx, self.rope.D_full, self.rope.theta)
+
+
+def time_events(torch, fn, iters):
+    """Average GPU milliseconds of fn() over iters back-to-back calls (events on the launch stream)."""
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    s.record()
+    for i in range(iters):
+        fn(i)
+    e.record()
+    torch.cuda.synchronize()
+    return s.elapsed_time(e) / iters
+
+
+def cpu_baseline(specs, rope, layer0, step, M):
+    """The oracle, as it stands, on the host cores: one full layer step (all seven linears + RoPE)."""
+    import oracle
+    cores = min(oracle.max_threads(), int(os.environ.get("OMP_NUM_THREADS", "16") or 16), 16)
+    oracle.set_threads(cores)
+    r = step.host_rope
+    t0 = time.perf_counter()
+    reps = 0
+    while reps < 3 or time.perf_counter() - t0 < 10.0:      # about 10 s of CPU work, at least 3 passes
+        for s in specs:
+            w = layer0.host[s.name]
+            oracle.w4_linear(w["qweight"], w["scales"], w["zeros"], step.host_x[s.name], s.keep)
+        oracle.pruned_rope(r["q"], r["k"], r["positions"], r["kept_idx"], rope.D_full, rope.theta)
+        reps += 1
+    dt = (time.perf_counter() - t0) / reps
+    nbytes = sum(s.algorithmic_bytes(M) for s in specs) + rope.algorithmic_bytes()
+    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"{reps} passes of one full decode layer step (7 linears + RoPE, {nbytes / 1e6:.1f} MB "
+                      f"algorithmic each), {dt:.3f} s per pass, OpenMP over output rows"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3200)
+    ap.add_argument("--warmup", type=int, default=320)
+    ap.add_argument("--prune", type=int, default=15, help="pruning rate in percent (0, 15, 35)")
+    ap.add_argument("--layers", type=int, default=32, help="distinct layers in the weight pool")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--detail", action="store_true", help="per-linear isolated timings (cold and warm cache)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build measures the one-GPU hot path only; run with --gpus 1")
+
+    import torch
+    import paper_2512_03383_amd as uq
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    uq.lib()
+    torch.cuda.set_device(0)
+    M = 1
+    rate = args.prune
+    specs = wl.llama3_8b_layer(rate)
+    rope = wl.llama3_8b_rope(rate, T=M)
+    layers = [Layer(torch, uq, specs, rope, i, rate) for i in range(args.layers)]
+    step = DecodeStep(torch, uq, specs, rope, M)
+    lin_bytes = {s.name: s.algorithmic_bytes(M) for s in specs}
+    step_bytes = sum(lin_bytes.values()) + rope.algorithmic_bytes()
+    pool_gb = sum(s.N * s.K / 2 for s in specs) * args.layers / 1e9
+    log(f"pool: {args.layers} layers, {pool_gb:.2f} GB of packed weights; step = {step_bytes / 1e6:.2f} MB algorithmic")
+
+    # one eager pass (also warms the per-device caches of the library), then capture HIP graphs:
+    # one graph that walks the whole layer pool (the steady state of a decode loop) and one graph
+    # per layer for the remainder when --steps is not a multiple of the pool size
+    for L in layers:
+        step.run(L)
+    torch.cuda.synchronize()
+    graph_all, graphs = None, None
+    if not args.no_graph:
+        side = torch.cuda.Stream()
+        graph_all = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph_all, stream=side):
+            for L in layers:
+                step.run(L)
+        graphs = []
+        for L in layers:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                step.run(L)
+            graphs.append(g)
+        torch.cuda.synchronize()
+
+    def do_steps(n):
+        """Run exactly n steps, continuing the walk through the layer pool from layer 0."""
+        nl = len(layers)
+        if graphs is None:
+            for i in range(n):
+                step.run(layers[i % nl])
+            return
+        for _ in range(n // nl):
+            graph_all.replay()
+        for i in range(n % nl):
+            graphs[i].replay()
+
+    do_steps(args.warmup)
+    torch.cuda.synchronize()
+    ev_s, ev_e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev_s.record()
+    do_steps(args.steps)
+    ev_e.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step_gpu = ev_s.elapsed_time(ev_e) / args.steps
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # ---- attribution: duration of each linear launch, measured with HIP events on the launch
+    # stream around a graph that issues that one linear back to back over the whole layer pool
+    # (cold weights every launch, no host launch cost inside the bracket)
+    names = [s.name for s in specs]
+    iso_us = {}
+    for n in names:
+        if args.no_graph:
+            ms = time_events(torch, lambda i, n=n: step.run(layers[i % len(layers)], only=n), 8 * len(layers))
+            iso_us[n] = ms * 1e3
+            continue
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            for L in layers:
+                step.run(L, only=n)
+        g.replay()
+        ms = time_events(torch, lambda i: g.replay(), 8)
+        iso_us[n] = ms * 1e3 / len(layers)
+    per_linear = {n: {"MB": round(lin_bytes[n] / 1e6, 3), "us": round(iso_us[n], 3),
+                      "GBps": round(lin_bytes[n] / (iso_us[n] * 1e-6) / 1e9, 1),
+                      "frac_of_peak": round(lin_bytes[n] / (iso_us[n] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)} for n in names}
+    for n in names:
+        log(f"  {n:10s} {per_linear[n]}")
+    # the dominant kernel of the step: the GEMV instantiation that serves gate_proj and up_proj
+    dom = [n for n in ("gate_proj", "up_proj") if n in iso_us] or names
+    dom_bytes = float(np.mean([lin_bytes[n] for n in dom]))
+    dom_us = float(np.mean([iso_us[n] for n in dom]))
+    achieved = dom_bytes / (dom_us * 1e-6) / 1e9
+    # read-stream ceiling for the same byte count (plain 128-bit loads, no arithmetic)
+    pool_t = layers[0].lin[dom[0]].qweight
+    probe_out = torch.empty(1 << 16, dtype=torch.int32, device="cuda")
+    nb = int(dom_bytes) // 8192 * 8192
+    probe_src = [L.lin[dom[0]].qweight for L in layers]
+    nb = min(nb, probe_src[0].numel() * 4 // 8192 * 8192)
+    if not args.no_graph:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            for t in probe_src:
+                uq.uniql_stream_read_probe(t, nb, probe_out)
+        g.replay()
+        ceil_us = time_events(torch, lambda i: g.replay(), 8) * 1e3 / len(probe_src)
+    else:
+        ceil_us = time_events(torch, lambda i: uq.uniql_stream_read_probe(probe_src[i % len(probe_src)], nb, probe_out),
+                              8 * len(probe_src)) * 1e3
+    ceil_gbs = nb / (ceil_us * 1e-6) / 1e9
+    log(f"  step: wall {ms_per_step * 1e3:.2f} us, gpu events {ms_per_step_gpu * 1e3:.2f} us; "
+        f"read-stream ceiling for {nb / 1e6:.1f} MB: {ceil_us:.2f} us = {ceil_gbs:.0f} GB/s")
+
+    out = {
+        "metric": METRIC, "value": round(value, 2), "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 6),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+        "data": "synthetic",
+        "config": {"workload": f"Llama-3-8B shaped decode layer, batch 1, int4 group-128 weights, "
+                               f"pruning {rate}% (q/k/v/o/gate/up/down W4A16 GEMV + fused pruned RoPE), "
+                               f"{args.layers}-layer weight pool streamed from HBM",
+                   "prune_pct": rate, "M": M, "launch": "hip-graph over the layer pool" if graphs else "eager",
+                   "step_algorithmic_MB": round(step_bytes / 1e6, 3)},
+        "us_per_step_gpu_events": round(ms_per_step_gpu * 1e3, 3),
+        "per_linear": per_linear,
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "w4_gemv_kernel (gate_proj / up_proj launches)",
+                     "bytes_per_launch": int(dom_bytes), "us_per_launch": round(dom_us, 3),
+                     "stream_ceiling_GBps": round(ceil_gbs, 1),
+                     "frac_of_stream_ceiling": round(achieved / ceil_gbs, 4),
+                     "how": "algorithmic bytes of one gate/up launch / its mean duration, HIP events on the launch "
+                            "stream around a graph of back-to-back launches over the layer pool (cold HBM)"},
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(specs, rope, layers[0], step, M)
+    print(json.dumps(out, ensure_ascii=False), flush=True)
+
+
+if __name__ == "__main__":
+    main()

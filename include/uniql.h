@@ -77,8 +77,8 @@ typedef struct uniql_w4 {
  *        B/C/dt rows above row_seg_limit kept whole, Alg. 5.)
  * cols: col_seg_stride == 0 : the first k_keep columns (k_keep == 0 -> all)
  *       col_seg_stride  > 0 : column k is kept iff (k % col_seg_stride) <
- *                             col_seg_keep; K_total must be a multiple of the
- *                             stride; k_keep must be 0 or the resulting count.
+ *                             col_seg_keep; the stride is at least 8 and divides
+ *                             K_total; k_keep must be 0 or the resulting count.
  *       (MLP down / Mamba out_proj: prefix.  Attention o_proj: per-head segments.)
  * Kept rows / columns appear in the compact y / x in increasing stored order.
  */
@@ -134,6 +134,15 @@ int uniql_w4_dequant(const uniql_w4_t* W, const uniql_keep_t* keep, void* w_f16,
 int uniql_pruned_rope(void* q_f16, void* k_f16, const int32_t* positions, const int32_t* kept_idx,
                       int32_t T, int32_t Hq, int32_t Hkv, int32_t H_tab, int32_t D_full,
                       int32_t D_keep, double theta, void* hip_stream);
+
+/*
+ * Measurement aid, not part of the method: reads `bytes` of device memory at `src`
+ * (16-byte aligned) once with wave-wide 128-bit loads, the access shape of the GEMV's
+ * weight stream, and writes one xor word per 8 KB to `out_words` (device, at least
+ * ceil(bytes / 8192) uint32).  Its duration is the read-stream ceiling that the
+ * benchmark reports beside the GEMV.  Errors: E_NULL, E_SHAPE, E_ALIGN, E_ARCH, E_HIP.
+ */
+int uniql_stream_read_probe(const void* src, int64_t bytes, void* out_words, void* hip_stream);
 
 /* Static string for an error code (never NULL). */
 const char* uniql_strerror(int code);

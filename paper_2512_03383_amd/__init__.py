@@ -65,6 +65,8 @@ def lib():
         L.uniql_w4_dequant.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, vp]
         L.uniql_pruned_rope.restype = C.c_int
         L.uniql_pruned_rope.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, C.c_double, vp]
+        L.uniql_stream_read_probe.restype = C.c_int
+        L.uniql_stream_read_probe.argtypes = [vp, i64, vp, vp]
         L.uniql_strerror.restype = C.c_char_p
         L.uniql_strerror.argtypes = [C.c_int]
         L.uniql_last_hip_error.restype = C.c_int
@@ -188,3 +190,10 @@ def uniql_pruned_rope(q, k, positions, kept_idx, D_full: int, theta: float, stre
                                  T, Hq, Hkv, kept_idx.shape[0], D_full, Dk, float(theta), _stream_ptr(stream))
     _check(rc)
     return q, k
+
+
+def uniql_stream_read_probe(src, nbytes: int, out, stream=None):
+    """Read nbytes of the tensor src once (measurement aid: the read-stream ceiling)."""
+    rc = lib().uniql_stream_read_probe(C.c_void_p(src.data_ptr()), int(nbytes), C.c_void_p(out.data_ptr()),
+                                       _stream_ptr(stream))
+    _check(rc)

@@ -66,7 +66,7 @@ static int make_keepmap(const uniql_w4_t* W, const uniql_keep_t* keep, KeepMap* 
     km->k_span = km->k_keep;
   } else {
     if (keep->col_seg_keep < 1 || keep->col_seg_keep > keep->col_seg_stride) return UNIQL_E_KEEP;
-    if (K % keep->col_seg_stride) return UNIQL_E_KEEP;
+    if (K % keep->col_seg_stride || keep->col_seg_stride < 8) return UNIQL_E_KEEP;
     km->cs_keep = keep->col_seg_keep;
     km->k_keep = (K / keep->col_seg_stride) * keep->col_seg_keep;
     if (keep->k_keep && keep->k_keep != km->k_keep) return UNIQL_E_KEEP;
@@ -143,6 +143,16 @@ extern "C" int uniql_pruned_rope(void* q_f16, void* k_f16, const int32_t* positi
   a.T = T; a.Hq = Hq; a.Hkv = Hkv; a.H_tab = H_tab; a.D_full = D_full; a.D_keep = D_keep;
   a.theta = theta;
   hipError_t e = launch_pruned_rope(a, (hipStream_t)hip_stream);
+  return e == hipSuccess ? UNIQL_OK : hip_fail(e);
+}
+
+extern "C" int uniql_stream_read_probe(const void* src, int64_t bytes, void* out_words, void* hip_stream) {
+  if (!src || !out_words) return UNIQL_E_NULL;
+  if (bytes < 0) return UNIQL_E_SHAPE;
+  if (!aligned(src, 16) || !aligned(out_words, 4)) return UNIQL_E_ALIGN;
+  int rc = check_arch();
+  if (rc) return rc;
+  hipError_t e = launch_stream_read(src, bytes, (uint32_t*)out_words, (hipStream_t)hip_stream);
   return e == hipSuccess ? UNIQL_OK : hip_fail(e);
 }
 

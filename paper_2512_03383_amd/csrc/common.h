@@ -84,13 +84,32 @@ __device__ __forceinline__ GroupQ make_groupq(uint32_t scale_bits, uint32_t z) {
   return g;
 }
 
+// (a & mask) | orv in one VALU instruction.  The compiler splits this into v_and + v_or when
+// both constants are literals (a VOP3 encoding cannot carry two of them on this target), so the
+// mask is pinned to an SGPR and the exponent pattern to a VGPR.
+__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t orv) {
+  uint32_t r;
+  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask), "v"(orv));
+  return r;
+}
+
+// The two exponent patterns, materialised once per thread in VGPRs.
+struct Magic {
+  uint32_t m1024, m64;
+};
+__device__ __forceinline__ Magic make_magic() {
+  Magic m = {0x64006400u, 0x54005400u};
+  asm volatile("" : "+v"(m.m1024), "+v"(m.m64));   // keep them in registers, not re-materialised as literals
+  return m;
+}
+
 // Dequantise one word into four half2: d[0]=(w0,w4) d[1]=(w1,w5) d[2]=(w2,w6) d[3]=(w3,w7).
-__device__ __forceinline__ void dequant_word(uint32_t w, const GroupQ& g, half2_t d[4]) {
+__device__ __forceinline__ void dequant_word(uint32_t w, const GroupQ& g, const Magic& mg, half2_t d[4]) {
   uint32_t w8 = w >> 8;
-  half2_t h0 = as_half2((w & 0x000F000Fu) | 0x64006400u);
-  half2_t h1 = as_half2((w & 0x00F000F0u) | 0x54005400u);
-  half2_t h2 = as_half2((w8 & 0x000F000Fu) | 0x64006400u);
-  half2_t h3 = as_half2((w8 & 0x00F000F0u) | 0x54005400u);
+  half2_t h0 = as_half2(and_or(w, 0x000F000Fu, mg.m1024));
+  half2_t h1 = as_half2(and_or(w, 0x00F000F0u, mg.m64));
+  half2_t h2 = as_half2(and_or(w8, 0x000F000Fu, mg.m1024));
+  half2_t h3 = as_half2(and_or(w8, 0x00F000F0u, mg.m64));
   d[0] = (h0 - g.zlo) * g.s2;
   d[1] = (h1 - g.zhi) * g.s2;
   d[2] = (h2 - g.zlo) * g.s2;
@@ -111,5 +130,6 @@ struct RopeArgs {
   double theta;
 };
 hipError_t launch_pruned_rope(const RopeArgs& a, hipStream_t stream);
+hipError_t launch_stream_read(const void* src, long long bytes, uint32_t* out, hipStream_t stream);
 
 }  // namespace uniql

@@ -1,0 +1,306 @@
+// Streaming W4A16 GEMV, one token per launch (decode).
+//
+// The op is bound by the HBM stream of packed nibbles, so the kernel is built
+// around that stream: a wave reads a kept row in contiguous 1 KB pieces (64
+// lanes x 128-bit), i.e. every lane owns 32 consecutive input columns that lie
+// in one quantisation group.  Pruned rows are never touched (row truncation
+// saves their bytes); pruned columns are handled by staging the activations
+// once per block into LDS at their *stored* column positions with zeros in the
+// pruned slots, so the weight stream needs no per-element masking.
+//
+// Per 32-bit word (8 weights): 1 shift + 4 and-or build exact fp16 codes, 4
+// packed subtracts and 4 packed multiplies give the canonical fp16 weights
+// RN16((q - z) s), and 4 two-way dot instructions accumulate in fp32.
+//
+// The kernel is fully unrolled over the row's 2048-column chunks (template NCH):
+// a wave's tiles (row, chunk) are loaded up to kDepth ahead and consumed in issue
+// order, each as soon as it has arrived, so the arithmetic overlaps the stream
+// instead of starting after the last byte.
+#include "common.h"
+
+namespace uniql {
+
+constexpr int kGemvThreads = 512;
+constexpr int kGemvWaves = kGemvThreads / kWave;
+constexpr int kChunk = kWave * 32;   // stored columns one wave covers with one 128-bit load per lane
+constexpr int kDepth = 4;            // tiles (1 KB of codes each) a wave keeps in flight
+
+__device__ __forceinline__ float dpp_xor_reduce(float v) {
+  // butterfly within each row of 16 lanes with DPP, then across rows through the LDS crossbar
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));  // row_half_mirror
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));  // row_mirror
+  v += __shfl_xor(v, 16);
+  v += __shfl_xor(v, 32);
+  return v;
+}
+
+struct Tile {
+  uint4 w;          // 32 packed codes
+  uint32_t sbits;   // fp16 scale bits of the lane's group
+  uint32_t z;       // zero point of the lane's group
+};
+
+// LDS slot of the 8 stored columns k0..k0+7, k0 = c*2048 + l*32 + t*8: [c][t][l], 16 bytes,
+// halves ordered (k0,k0+4,k0+1,k0+5,k0+2,k0+6,k0+3,k0+7): dword p pairs with the dequantised
+// pair (w_p, w_{p+4}), and a wave reads one t-plane of a chunk with consecutive addresses.
+__device__ __forceinline__ int unit_k0(int u) { return (u >> 8) * kChunk + ((u >> 2) & 63) * 32 + (u & 3) * 8; }
+__device__ __forceinline__ int unit_slot(int u) { return ((u >> 8) * 4 + (u & 3)) * 64 + ((u >> 2) & 63); }
+
+__device__ __forceinline__ uint4 pack_unit(const half_t v[8]) {
+  half2_t p0 = {v[0], v[4]}, p1 = {v[1], v[5]}, p2 = {v[2], v[6]}, p3 = {v[3], v[7]};
+  return make_uint4(as_u32(p0), as_u32(p1), as_u32(p2), as_u32(p3));
+}
+
+// Branch-free map of a stored column to its compact column.  A column prefix is the
+// one-segment case: stride 2^30, keep k_keep.
+struct ColMap {
+  int stride, keep;
+};
+__device__ __forceinline__ ColMap make_colmap(const KeepMap& km) {
+  ColMap c;
+  c.stride = km.cs_stride ? km.cs_stride : (1 << 30);
+  c.keep = km.cs_stride ? km.cs_keep : km.k_keep;
+  return c;
+}
+
+// R rows per wave.  XVEC: the kept columns are a prefix and x is 16-byte aligned, so x is
+// fetched with 128-bit loads; otherwise element by element through the column map (segment
+// strides are at least 8, so a unit of 8 columns wraps at most once).  NCH: chunks per row,
+// compile-time, 1..8 (NCH = 0: run-time chunk count for rows longer than 8 chunks).
+template <int R, bool XVEC, int NCH>
+__global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(LinearArgs a, int m, int nchunk_rt) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint4* xs = reinterpret_cast<uint4*>(smem);   // [nchunk][4][64] units of 8 halves
+
+  const KeepMap& km = a.km;
+  const int nchunk = NCH > 0 ? NCH : nchunk_rt;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int rg = blockIdx.x * kGemvWaves + wave;   // row group of this wave
+  const int k_span32 = (km.k_span + 31) & ~31;
+  const int words_per_row = a.K_total >> 3;
+  const int groups_per_row = a.K_total / kGroup;
+  const half_t* xrow = a.x + (size_t)m * a.ldx;
+
+  // stored rows of this wave (clamped so that every address is valid)
+  int srow[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    int rc = rg * R + r;
+    rc = rc < km.n_keep ? rc : km.n_keep - 1;
+    srow[r] = stored_row(km, rc);
+  }
+
+  // one tile = the lane's 32 columns of one row in chunk c (16 B of codes + scale + zero).
+  // Lanes past the last kept column re-read the row start: their x slots hold zeros, so
+  // whatever they fetch contributes nothing and no select has to wait on the loads.
+  auto load_tile = [&](int c, int r, Tile& t) {
+    const int kb = c * kChunk + lane * 32;
+    const int kbc = kb < k_span32 ? kb : 0;
+    const size_t row = (size_t)srow[r];
+    t.w = *reinterpret_cast<const uint4*>(a.qweight + row * words_per_row + (kbc >> 3));
+    t.sbits = a.scales[row * groups_per_row + (kbc >> 7)];
+    t.z = a.zeros[row * groups_per_row + (kbc >> 7)];
+  };
+  const Magic mg = make_magic();
+  auto consume = [&](const Tile& t, const uint4 (&xr)[4], float& acc) {
+    const GroupQ g = make_groupq(t.sbits, t.z);
+    const uint32_t wv[4] = {t.w.x, t.w.y, t.w.z, t.w.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      half2_t d[4];
+      dequant_word(wv[q], g, mg, d);
+      acc = __builtin_amdgcn_fdot2(d[0], as_half2(xr[q].x), acc, false);
+      acc = __builtin_amdgcn_fdot2(d[1], as_half2(xr[q].y), acc, false);
+      acc = __builtin_amdgcn_fdot2(d[2], as_half2(xr[q].z), acc, false);
+      acc = __builtin_amdgcn_fdot2(d[3], as_half2(xr[q].w), acc, false);
+    }
+  };
+
+  float acc[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) acc[r] = 0.f;
+
+  const ColMap cm = make_colmap(km);
+  const int kv = km.k_keep & ~7;   // XVEC: columns below kv come from whole 128-bit loads
+  const int units = nchunk * 256;
+
+  if constexpr (NCH > 0) {
+    // ---- phase 1: issue the x loads.  Memory returns in issue order, so x (an L2 hit) goes
+    // first and never queues behind the HBM stream; it is consumed only after the first weight
+    // loads have been issued.  Every load is unconditional on a clamped, valid address.
+    constexpr int XI = (NCH * 256 + kGemvThreads - 1) / kGemvThreads;   // x units per thread
+    uint4 rawv[XVEC ? XI : 1];             // XVEC: 8 halves per unit, kept as opaque dwords
+    uint32_t rawe[XVEC ? 1 : XI][8];       // element path: one zero-extended half per register
+    uint32_t okmask[XI];                   // element path, bit j: element j of the unit is a kept column
+    uint32_t tailv[8];                     // XVEC: the up to 7 kept columns at and after kv
+    const uint16_t* xbits = reinterpret_cast<const uint16_t*>(xrow);
+#pragma unroll
+    for (int i = 0; i < XI; ++i) {
+      const int uraw = tid + i * kGemvThreads;
+      const int k0 = unit_k0(uraw < NCH * 256 ? uraw : NCH * 256 - 1);   // past the end: a redundant, valid load
+      okmask[i] = 0;
+      if constexpr (XVEC) {
+        const int k0c = k0 + 8 <= kv ? k0 : kv - 8;   // the host selects XVEC only when k_keep >= 8
+        rawv[i] = *reinterpret_cast<const uint4*>(xrow + k0c);
+      } else {
+        const int seg0 = k0 / cm.stride, off0 = k0 - seg0 * cm.stride;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          int seg = seg0, off = off0 + j;
+          if (off >= cm.stride) { off -= cm.stride; seg += 1; }
+          const bool ok = off < cm.keep && k0 + j < km.k_span;
+          rawe[i][j] = xbits[ok ? seg * cm.keep + off : 0];
+          okmask[i] |= ok ? (1u << j) : 0u;
+        }
+      }
+    }
+    if constexpr (XVEC) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) tailv[j] = xbits[kv + j < km.k_keep ? kv + j : km.k_keep - 1];
+    }
+
+    // ---- phase 2: start the weight stream.  Tile t = (chunk t / R, row t % R).
+    __builtin_amdgcn_sched_barrier(0);
+    constexpr int T = NCH * R;
+    constexpr int D = T < kDepth ? T : kDepth;
+    Tile ring[D];
+#pragma unroll
+    for (int t = 0; t < D; ++t) load_tile(t / R, t % R, ring[t]);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- phase 3: x registers -> LDS (zeros for pruned columns), in the pair order of the slot
+#pragma unroll
+    for (int i = 0; i < XI; ++i) {
+      const int u = tid + i * kGemvThreads;
+      const int k0 = unit_k0(u);
+      uint32_t e[8];
+      if constexpr (XVEC) {
+        // a unit is wholly kept (k0 + 8 <= kv), the one that starts at kv (tail values), or pruned
+        const uint4 r = rawv[i];
+        const uint32_t full[8] = {r.x & 0xffffu, r.x >> 16, r.y & 0xffffu, r.y >> 16,
+                                  r.z & 0xffffu, r.z >> 16, r.w & 0xffffu, r.w >> 16};
+        const bool whole = k0 + 8 <= kv, tail = k0 == kv;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) e[j] = whole ? full[j] : ((tail && kv + j < km.k_keep) ? tailv[j] : 0u);
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) e[j] = (okmask[i] >> j) & 1u ? rawe[i][j] : 0u;
+      }
+      if (u < NCH * 256)
+        xs[unit_slot(u)] = make_uint4(e[0] | (e[4] << 16), e[1] | (e[5] << 16), e[2] | (e[6] << 16), e[3] | (e[7] << 16));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+
+    // ---- phase 4: consume tiles in issue order, re-issuing D tiles ahead
+    uint4 xr[4];
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+      const int c = t / R, r = t % R;
+      if (r == 0) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) xr[q] = xs[(c * 4 + q) * 64 + lane];
+      }
+      // Order fence: the tile's registers and the accumulator of the previous tile pass through
+      // an empty asm, so this tile's unpacking cannot be hoisted above the previous tile's
+      // arithmetic (which would make the wave wait for loads that were issued later).
+      Tile& tl = ring[t % D];
+      asm volatile("" : "+v"(tl.w.x), "+v"(tl.w.y), "+v"(tl.w.z), "+v"(tl.w.w), "+v"(tl.sbits), "+v"(tl.z),
+                        "+v"(acc[(t + R - 1) % R]));
+      consume(tl, xr, acc[r]);
+      if (t + D < T) load_tile((t + D) / R, (t + D) % R, tl);
+    }
+  } else {
+    // ---- long rows: run-time chunk count, plain staging loop and a two-deep register pipeline
+    for (int u = tid; u < units; u += kGemvThreads) {
+      const int k0 = unit_k0(u);
+      half_t v[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int k = k0 + j;
+        const int kc = k < k_span32 ? compact_col(km, k) : -1;
+        const half_t val = xrow[kc >= 0 ? kc : 0];
+        v[j] = kc >= 0 ? val : (half_t)0;
+      }
+      xs[unit_slot(u)] = pack_unit(v);
+    }
+    Tile cur[R], nxt[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) load_tile(0, r, cur[r]);
+    __syncthreads();
+    for (int c = 0; c < nchunk; ++c) {
+      if (c + 1 < nchunk) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) load_tile(c + 1, r, nxt[r]);
+      }
+      uint4 xr[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) xr[q] = xs[(c * 4 + q) * 64 + lane];
+#pragma unroll
+      for (int r = 0; r < R; ++r) consume(cur[r], xr, acc[r]);
+#pragma unroll
+      for (int r = 0; r < R; ++r) cur[r] = nxt[r];
+    }
+  }
+
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const float v = dpp_xor_reduce(acc[r]);
+    const int rc = rg * R + r;
+    if (lane == 0 && rc < km.n_keep) a.y[(size_t)m * a.ldy + rc] = (half_t)v;
+  }
+}
+
+template <int R, bool XVEC, int NCH>
+static hipError_t launch_one(const LinearArgs& a, int m, int nchunk, hipStream_t stream) {
+  const size_t smem = (size_t)nchunk * 4096;
+  auto kern = w4_gemv_kernel<R, XVEC, NCH>;
+  if (smem > 160 * 1024) return hipErrorInvalidValue;
+  if (smem > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+  }
+  const int row_groups = (a.km.n_keep + R - 1) / R;
+  const int blocks = (row_groups + kGemvWaves - 1) / kGemvWaves;
+  hipLaunchKernelGGL(kern, dim3(blocks), dim3(kGemvThreads), smem, stream, a, m, nchunk);
+  return hipGetLastError();
+}
+
+template <int R, bool XVEC>
+static hipError_t launch_nch(const LinearArgs& a, int m, int nchunk, hipStream_t stream) {
+  switch (nchunk) {
+    case 1: return launch_one<R, XVEC, 1>(a, m, nchunk, stream);
+    case 2: return launch_one<R, XVEC, 2>(a, m, nchunk, stream);
+    case 3: return launch_one<R, XVEC, 3>(a, m, nchunk, stream);
+    case 4: return launch_one<R, XVEC, 4>(a, m, nchunk, stream);
+    case 5: return launch_one<R, XVEC, 5>(a, m, nchunk, stream);
+    case 6: return launch_one<R, XVEC, 6>(a, m, nchunk, stream);
+    case 7: return launch_one<R, XVEC, 7>(a, m, nchunk, stream);
+    case 8: return launch_one<R, XVEC, 8>(a, m, nchunk, stream);
+    default: return launch_one<R, XVEC, 0>(a, m, nchunk, stream);
+  }
+}
+
+template <bool XVEC>
+static hipError_t launch_rows(const LinearArgs& a, int r1, int m, int nchunk, hipStream_t stream) {
+  if (r1 == 2) return launch_nch<2, XVEC>(a, m, nchunk, stream);
+  return launch_nch<1, XVEC>(a, m, nchunk, stream);
+}
+
+hipError_t launch_w4_gemv(const LinearArgs& a, hipStream_t stream) {
+  const int k_span32 = (a.km.k_span + 31) & ~31;
+  const int nchunk = (k_span32 + kChunk - 1) / kChunk;
+  // rows per wave: fewer when the matrix is small, so that every CU still gets several waves
+  const int r1 = a.km.n_keep >= 8192 ? 2 : 1;
+  for (int m = 0; m < a.M; ++m) {
+    const half_t* xrow = a.x + (size_t)m * a.ldx;
+    const bool xvec = a.km.cs_stride == 0 && a.km.k_keep >= 8 && (reinterpret_cast<uintptr_t>(xrow) & 15) == 0;
+    hipError_t e = xvec ? launch_rows<true>(a, r1, m, nchunk, stream) : launch_rows<false>(a, r1, m, nchunk, stream);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+}  // namespace uniql

@@ -46,11 +46,12 @@ __global__ __launch_bounds__(kGemmThreads) void w4_gemm_kernel(LinearArgs a) {
       const uint4 wq = *reinterpret_cast<const uint4*>(a.qweight + srow * words_per_row + (k0 >> 3));
       const size_t g = srow * groups_per_row + kt;
       const GroupQ gq = make_groupq(a.scales[g], a.zeros[g]);
+      const Magic mg = make_magic();
       const uint32_t wv[4] = {wq.x, wq.y, wq.z, wq.w};
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
         half2_t d[4];
-        dequant_word(wv[t], gq, d);
+        dequant_word(wv[t], gq, mg, d);
         half8_t o = {d[0].x, d[1].x, d[2].x, d[3].x, d[0].y, d[1].y, d[2].y, d[3].y};
         *reinterpret_cast<half8_t*>(&Bs[lrow * LDT + lpart * 32 + t * 8]) = o;
       }
