@@ -124,6 +124,93 @@ def cpu_baseline(specs, rope, layer0, step, M):
                       f"algorithmic each), {dt:.3f} s per pass, OpenMP over output rows"}
 
 
+def graph_time_us(torch, side, fn, n_inner, reps=6):
+    """Mean GPU microseconds of one fn(i) call, issued n_inner times back to back inside a HIP graph."""
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        for i in range(n_inner):
+            fn(i)
+    g.replay()
+    return time_events(torch, lambda i: g.replay(), reps) * 1e3 / n_inner
+
+
+def detail_report(torch, uq, side):
+    """Other workloads of the benchmark configurations, each as isolated launches over a pool of
+    distinct weight copies: the three pruning rates, Qwen2.5-7B and Mamba2-2.7B shapes, the
+    prefill-sized MFMA GEMM and the prefill RoPE.  Returned as a dict; printed to stderr."""
+    rep = {}
+
+    def pool_for(spec, min_bytes=1.0e9, max_copies=32):
+        nb = spec.N * spec.K // 2
+        n = int(max(2, min(max_copies, min_bytes // nb + 1)))
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(wl.SEED_BASE + spec.N + spec.K)
+        out = []
+        for _ in range(n):
+            qw = (torch.randint(0, 2 ** 32, (spec.N, spec.K // 8), dtype=torch.int64, device="cuda", generator=gen)
+                  - 2 ** 31).to(torch.int32)
+            sc = (torch.rand((spec.N, spec.K // 128), device="cuda", generator=gen) * 0.015 + 0.005).to(torch.float16)
+            zr = torch.randint(0, 16, (spec.N, spec.K // 128), dtype=torch.uint8, device="cuda", generator=gen)
+            out.append(uq.QuantLinear(qw, sc, zr))
+        return out
+
+    def time_linear(spec, M, pool):
+        x = torch.randn((M, spec.k_keep), dtype=torch.float16, device="cuda")
+        y = torch.empty((M, spec.n_keep), dtype=torch.float16, device="cuda")
+        us = graph_time_us(torch, side, lambda i: uq.uniql_w4_linear(pool[i % len(pool)], spec.keep, x, y), len(pool))
+        nbytes = spec.algorithmic_bytes(M)
+        return {"M": M, "MB": round(nbytes / 1e6, 3), "us": round(us, 2), "GBps": round(nbytes / us / 1e3, 1),
+                "frac_hbm": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4),
+                "TFLOPs": round(spec.flops(M) / us / 1e6, 2)}
+
+    # Llama-3-8B shapes at the three rates (M = 1)
+    pools = {}
+    for rate in (0, 15, 35):
+        rows = {}
+        for spec in wl.llama3_8b_layer(rate):
+            key = (spec.N, spec.K)
+            if key not in pools:
+                pools[key] = pool_for(spec)
+            rows[spec.name] = time_linear(spec, 1, pools[key])
+        rows["layer_us"] = round(sum(v["us"] for v in rows.values()), 2)
+        rep[f"llama3_8b_p{rate}"] = rows
+    # prefill-sized GEMM on the gate/up and down shapes, 15 %
+    for spec in wl.prefill_linears(15):
+        for M in (256, 1024, 4096):
+            r = time_linear(spec, M, pools[(spec.N, spec.K)][:4])
+            r["frac_mfma"] = round(r["TFLOPs"] / MFMA_F16_PEAK_TFLOPS, 4)
+            rep[f"prefill_{spec.name}_M{M}"] = r
+    pools.clear()
+    torch.cuda.empty_cache()
+    # Qwen2.5-7B shapes, 25 %, batch 1 / 8 / 16
+    qpools = {}
+    for spec in wl.qwen25_7b_layer(25):
+        key = (spec.N, spec.K)
+        if key not in qpools:
+            qpools[key] = pool_for(spec)
+        for M in (1, 8, 16):
+            rep[f"qwen25_7b_p25_{spec.name}_M{M}"] = time_linear(spec, M, qpools[key])
+    qpools.clear()
+    torch.cuda.empty_cache()
+    # Mamba2-2.7B shapes, 15 %
+    for spec in wl.mamba2_2p7b_layer(15):
+        rep[f"mamba2_2p7b_p15_{spec.name}"] = time_linear(spec, 1, pool_for(spec))
+    torch.cuda.empty_cache()
+    # RoPE: decode and prefill
+    for name, rs in (("rope_decode_llama_p15", wl.llama3_8b_rope(15, T=1)), ("rope_prefill_llama_p15", wl.prefill_rope(15, 4096))):
+        r = wl.gen_rope_inputs(wl.rng_for(4, 7), rs)
+        bufs = [(torch.from_numpy(r["q"]).cuda(), torch.from_numpy(r["k"]).cuda()) for _ in range(8 if rs.T > 1 else 2)]
+        pos, idx = torch.from_numpy(r["positions"]).cuda(), torch.from_numpy(r["kept_idx"]).cuda()
+        us = graph_time_us(torch, side, lambda i: uq.uniql_pruned_rope(bufs[i % len(bufs)][0], bufs[i % len(bufs)][1],
+                                                                      pos, idx, rs.D_full, rs.theta), 16)
+        nb = rs.algorithmic_bytes()
+        rep[name] = {"MB": round(nb / 1e6, 3), "us": round(us, 2), "GBps": round(nb / us / 1e3, 1),
+                     "frac_hbm": round(nb / us / 1e3 / HBM_PEAK_GBS, 4)}
+    for k, v in rep.items():
+        log(f"  {k}: {v}")
+    return rep
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -133,7 +220,7 @@ def main():
     ap.add_argument("--layers", type=int, default=32, help="distinct layers in the weight pool")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--detail", action="store_true", help="per-linear isolated timings (cold and warm cache)")
+    ap.add_argument("--detail", action="store_true", help="also time the other benchmark configurations (three rates, Qwen / Mamba shapes, prefill GEMM, RoPE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build measures the one-GPU hot path only; run with --gpus 1")
@@ -271,6 +358,10 @@ def main():
     }
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(specs, rope, layers[0], step, M)
+    if args.detail:
+        del layers, graphs, graph_all
+        torch.cuda.empty_cache()
+        out["detail"] = detail_report(torch, uq, side if not args.no_graph else torch.cuda.Stream())
     print(json.dumps(out, ensure_ascii=False), flush=True)
 
 

@@ -96,8 +96,8 @@ extern "C" int uniql_w4_linear(const uniql_w4_t* W, const uniql_keep_t* keep, co
   a.K_total = W->K_total;
   a.M = M;
   hipStream_t s = (hipStream_t)hip_stream;
-  hipError_t e = (M <= 4) ? launch_w4_gemv(a, s) : launch_w4_gemm(a, s);
-  if (e == hipErrorInvalidValue && M <= 4) return UNIQL_E_SHAPE;   // K too long for the GEMV's staging
+  hipError_t e = (M == 1) ? launch_w4_gemv(a, s) : launch_w4_gemm(a, s);
+  if (e == hipErrorInvalidValue && M == 1) return UNIQL_E_SHAPE;   // K too long for the GEMV's staging
   return e == hipSuccess ? UNIQL_OK : hip_fail(e);
 }
 

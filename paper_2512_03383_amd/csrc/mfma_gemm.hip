@@ -1,0 +1,238 @@
+// W4A16 GEMM on MFMA for M >= 2 tokens: y[M][n_keep] = x[M][k_keep] * W'^T.
+//
+// "Direct-B" design: the packed weights never pass through LDS.  With
+// v_mfma_f32_16x16x32_f16 the weight operand of lane l is 8 consecutive input columns of
+// output row (l % 16) in k-slot (l / 16), which is exactly one 32-bit word of packed codes, so a
+// wave fetches its 16 rows x 128 columns (one quantisation group per row) with ONE 128-bit load
+// per lane (word t of the load feeds MFMA t of the group) and dequantises in registers to the
+// canonical fp16 weights.  Only the activations go through LDS: the block stages a slab of x
+// (its tokens x the columns of the current step) at *stored* column positions, zeros where
+// pruned, pre-permuted inside every 8-column block to the (0,4,1,5,2,6,3,7) order the unpack
+// produces, double-buffered so that the next slab is fetched while the current one is used.
+//
+// A wave owns BF fragments of 16 rows and AF fragments of 16 tokens (AF*BF accumulators of 4
+// VGPRs); a dequantised weight fragment is reused by AF MFMAs, an activation fragment by BF.
+// Small M (decode batches) is HBM-bound: AF = 1 and the K range is split over KS waves of the
+// block (reduced through LDS at the end) to get enough waves; large M (prefill) is MFMA-bound:
+// AF = 8, BF = 4, KS = 1.
+#include "common.h"
+
+namespace uniql {
+
+struct WTile {
+  uint4 w;
+  uint32_t sbits, z;
+};
+
+// AF token fragments, BF row fragments per wave, WN waves along rows, KS waves along K.
+template <int AF, int BF, int WN, int KS, bool XVEC>
+__global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
+  constexpr int NT = WN * KS * 64;
+  constexpr int BM = 16 * AF;               // tokens per block
+  constexpr int BN = WN * BF * 16;          // rows per block
+  constexpr int SC = KS * 128;              // columns per slab (one group per K-split wave)
+  constexpr int LDX = SC + 8;               // padded slab row (halves)
+  constexpr int UNITS = BM * SC / 8;        // 16-byte units per slab
+  static_assert(UNITS % NT == 0, "slab must divide evenly over the threads");
+  constexpr int UPT = UNITS / NT;           // units per thread
+  constexpr int PW = 2;                     // weight prefetch depth (iterations)
+
+  extern __shared__ __align__(16) unsigned char smem[];
+  half_t* xs = reinterpret_cast<half_t*>(smem);   // [2][BM][LDX]
+
+  const KeepMap& km = a.km;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wn = wave % WN, wk = wave / WN;
+  const int n = lane & 15, ks = lane >> 4;
+  const int n0 = blockIdx.x * BN, m0 = blockIdx.y * BM;
+  const int words_per_row = a.K_total >> 3, groups_per_row = a.K_total / kGroup;
+  const int ngroups = (km.k_span + kGroup - 1) / kGroup;
+  const int nit = (ngroups + KS - 1) / KS;
+  const int nit_pw = (nit + PW - 1) / PW * PW;   // loop trip count; extra iterations multiply zeros
+
+  // stored row of each of this lane's weight fragments (clamped: every address stays valid)
+  size_t wrow[BF];
+#pragma unroll
+  for (int bf = 0; bf < BF; ++bf) {
+    int rc = n0 + (wn * BF + bf) * 16 + n;
+    rc = rc < km.n_keep ? rc : km.n_keep - 1;
+    wrow[bf] = (size_t)stored_row(km, rc);
+  }
+  auto load_w = [&](int it, WTile (&t)[BF]) {
+    int g = it * KS + wk;
+    g = g < ngroups ? g : ngroups - 1;   // past the end: a valid, redundant load (x is zero there)
+#pragma unroll
+    for (int bf = 0; bf < BF; ++bf) {
+      t[bf].w = *reinterpret_cast<const uint4*>(a.qweight + wrow[bf] * words_per_row + g * 16 + ks * 4);
+      t[bf].sbits = a.scales[wrow[bf] * groups_per_row + g];
+      t[bf].z = a.zeros[wrow[bf] * groups_per_row + g];
+    }
+  };
+
+  // x slab staging: unit u of a slab = token (u / (SC/8)), 8-column block (u % (SC/8))
+  const int kv = km.k_keep & ~7;
+  const uint16_t* xbits = reinterpret_cast<const uint16_t*>(a.x);
+  auto fetch_x = [&](int it, uint4 (&xr)[UPT]) {
+#pragma unroll
+    for (int i = 0; i < UPT; ++i) {
+      const int u = tid + i * NT;
+      const int tk = u / (SC / 8), cb = u % (SC / 8);
+      const int k0 = it * SC + cb * 8;
+      const int tok = m0 + tk;
+      const bool tok_ok = tok < a.M;
+      const size_t xoff = (size_t)(tok_ok ? tok : a.M - 1) * a.ldx;
+      uint32_t e[8];
+      if (XVEC && k0 + 8 <= kv) {
+        const uint4 r = *reinterpret_cast<const uint4*>(a.x + xoff + k0);
+        e[0] = r.x & 0xffffu; e[1] = r.x >> 16; e[2] = r.y & 0xffffu; e[3] = r.y >> 16;
+        e[4] = r.z & 0xffffu; e[5] = r.z >> 16; e[6] = r.w & 0xffffu; e[7] = r.w >> 16;
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int k = k0 + j;
+          const int kc = k < km.k_span ? compact_col(km, k) : -1;
+          const uint32_t v = xbits[xoff + (kc >= 0 ? kc : 0)];
+          e[j] = kc >= 0 ? v : 0u;
+        }
+      }
+      if (!tok_ok) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) e[j] = 0u;
+      }
+      xr[i] = make_uint4(e[0] | (e[4] << 16), e[1] | (e[5] << 16), e[2] | (e[6] << 16), e[3] | (e[7] << 16));
+    }
+  };
+  auto store_x = [&](int buf, const uint4 (&xr)[UPT]) {
+#pragma unroll
+    for (int i = 0; i < UPT; ++i) {
+      const int u = tid + i * NT;
+      const int tk = u / (SC / 8), cb = u % (SC / 8);
+      *reinterpret_cast<uint4*>(xs + ((size_t)buf * BM + tk) * LDX + cb * 8) = xr[i];
+    }
+  };
+
+  float4_t acc[AF][BF];
+#pragma unroll
+  for (int af = 0; af < AF; ++af)
+#pragma unroll
+    for (int bf = 0; bf < BF; ++bf) acc[af][bf] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+  const Magic mg = make_magic();
+  WTile ring[PW][BF];
+  uint4 xr[UPT];
+#pragma unroll
+  for (int p = 0; p < PW; ++p) load_w(p, ring[p]);
+  fetch_x(0, xr);
+  store_x(0, xr);
+  __syncthreads();
+
+  for (int it0 = 0; it0 < nit_pw; it0 += PW) {
+#pragma unroll
+    for (int p = 0; p < PW; ++p) {
+      const int it = it0 + p;
+      const int buf = it & 1;
+      // fetch the next slab into registers while this one is consumed
+      if (it + 1 < nit_pw) fetch_x(it + 1, xr);
+
+      // dequantise this iteration's weight fragments: word t feeds MFMA t
+      uint4 bfrag[BF][4];
+#pragma unroll
+      for (int bf = 0; bf < BF; ++bf) {
+        const GroupQ gq = make_groupq(ring[p][bf].sbits, ring[p][bf].z);
+        const uint32_t wv[4] = {ring[p][bf].w.x, ring[p][bf].w.y, ring[p][bf].w.z, ring[p][bf].w.w};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          half2_t d[4];
+          dequant_word(wv[t], gq, mg, d);
+          bfrag[bf][t] = make_uint4(as_u32(d[0]), as_u32(d[1]), as_u32(d[2]), as_u32(d[3]));
+        }
+      }
+      load_w(it + PW, ring[p]);   // refill the ring slot (clamped past the end)
+
+      const half_t* xb = xs + (size_t)buf * BM * LDX + wk * 128 + ks * 32;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+#pragma unroll
+        for (int af = 0; af < AF; ++af) {
+          const uint4 av = *reinterpret_cast<const uint4*>(xb + (af * 16 + n) * LDX + t * 8);
+#pragma unroll
+          for (int bf = 0; bf < BF; ++bf)
+            acc[af][bf] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av),
+                                                                __builtin_bit_cast(half8_t, bfrag[bf][t]),
+                                                                acc[af][bf], 0, 0, 0);
+        }
+      }
+      if (it + 1 < nit_pw) store_x(buf ^ 1, xr);
+      __syncthreads();
+    }
+  }
+
+  // ---- epilogue.  Lane l holds, for fragment (af, bf): row (l % 16), tokens 4 * (l / 16) + v.
+  if constexpr (KS > 1) {
+    float* red = reinterpret_cast<float*>(smem);   // [KS][WN][AF][BF][4][64], reuses the slab space
+    constexpr int PER_WAVE = AF * BF * 4 * 64;
+    float* mine = red + (size_t)(wk * WN + wn) * PER_WAVE;
+#pragma unroll
+    for (int af = 0; af < AF; ++af)
+#pragma unroll
+      for (int bf = 0; bf < BF; ++bf)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) mine[((af * BF + bf) * 4 + v) * 64 + lane] = acc[af][bf][v];
+    __syncthreads();
+    if (wk != 0) return;
+#pragma unroll
+    for (int k2 = 1; k2 < KS; ++k2) {
+      const float* other = red + (size_t)(k2 * WN + wn) * PER_WAVE;
+#pragma unroll
+      for (int af = 0; af < AF; ++af)
+#pragma unroll
+        for (int bf = 0; bf < BF; ++bf)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) acc[af][bf][v] += other[((af * BF + bf) * 4 + v) * 64 + lane];
+    }
+  }
+#pragma unroll
+  for (int af = 0; af < AF; ++af)
+#pragma unroll
+    for (int bf = 0; bf < BF; ++bf) {
+      const int rc = n0 + (wn * BF + bf) * 16 + n;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int tok = m0 + af * 16 + 4 * ks + v;
+        if (tok < a.M && rc < km.n_keep) a.y[(size_t)tok * a.ldy + rc] = (half_t)acc[af][bf][v];
+      }
+    }
+}
+
+template <int AF, int BF, int WN, int KS, bool XVEC>
+static hipError_t launch_cfg(const LinearArgs& a, hipStream_t stream) {
+  constexpr int BM = 16 * AF, BN = WN * BF * 16, SC = KS * 128, LDX = SC + 8;
+  size_t smem = (size_t)2 * BM * LDX * sizeof(half_t);
+  const size_t red = KS > 1 ? (size_t)KS * WN * AF * BF * 4 * 64 * sizeof(float) : 0;
+  if (red > smem) smem = red;
+  auto kern = w4_mfma_kernel<AF, BF, WN, KS, XVEC>;
+  if (smem > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+  }
+  dim3 grid((a.km.n_keep + BN - 1) / BN, (a.M + BM - 1) / BM);
+  hipLaunchKernelGGL(kern, grid, dim3(WN * KS * 64), smem, stream, a);
+  return hipGetLastError();
+}
+
+template <bool XVEC>
+static hipError_t launch_m(const LinearArgs& a, hipStream_t stream) {
+  if (a.M <= 16) return launch_cfg<1, 1, 2, 4, XVEC>(a, stream);
+  if (a.M <= 32) return launch_cfg<2, 1, 2, 4, XVEC>(a, stream);
+  if (a.M <= 64) return launch_cfg<4, 2, 4, 1, XVEC>(a, stream);
+  return launch_cfg<8, 4, 4, 1, XVEC>(a, stream);
+}
+
+hipError_t launch_w4_gemm(const LinearArgs& a, hipStream_t stream) {
+  // 128-bit x loads need a column prefix and 16-byte aligned token rows
+  const bool xvec = a.km.cs_stride == 0 && a.km.k_keep >= 8 && (reinterpret_cast<uintptr_t>(a.x) & 15) == 0 &&
+                    ((a.ldx * 2) & 15) == 0;
+  return xvec ? launch_m<true>(a, stream) : launch_m<false>(a, stream);
+}
+
+}  // namespace uniql
