@@ -96,7 +96,8 @@ typedef struct uniql_keep {
  *   x_f16 : device, fp16 [M][ldx], first k_keep entries of a row are the kept inputs
  *   y_f16 : device, fp16 [M][ldy], first n_keep entries of a row are written
  *   ldx >= k_keep, ldy >= n_keep (elements); x and y must not overlap.
- * M = 1 runs the streaming GEMV, larger M the MFMA dequant-GEMM.
+ * M = 1 runs the streaming GEMV; M >= 2 the MFMA dequant-GEMM (K-split configuration for
+ * decode batches up to 32 tokens, large tiles for prefill).
  * Errors: E_NULL, E_SHAPE, E_KEEP, E_ALIGN, E_ARCH, E_HIP.
  */
 int uniql_w4_linear(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_f16, int64_t ldx,

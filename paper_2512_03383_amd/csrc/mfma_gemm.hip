@@ -24,18 +24,19 @@ struct WTile {
   uint32_t sbits, z;
 };
 
-// AF token fragments, BF row fragments per wave, WN waves along rows, KS waves along K.
-template <int AF, int BF, int WN, int KS, bool XVEC>
+// AF token fragments, BF row fragments per wave, WN waves along rows, KS waves along K,
+// S2 groups per wave and iteration (the slab holds KS * S2 groups: fewer, longer iterations hide
+// the latency of fetching the next slab), PW iterations of weight loads kept in flight.
+template <int AF, int BF, int WN, int KS, int S2, int PW, bool XVEC>
 __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
   constexpr int NT = WN * KS * 64;
   constexpr int BM = 16 * AF;               // tokens per block
   constexpr int BN = WN * BF * 16;          // rows per block
-  constexpr int SC = KS * 128;              // columns per slab (one group per K-split wave)
+  constexpr int SC = KS * S2 * 128;         // columns per slab (S2 groups per K-split wave)
   constexpr int LDX = SC + 8;               // padded slab row (halves)
   constexpr int UNITS = BM * SC / 8;        // 16-byte units per slab
   static_assert(UNITS % NT == 0, "slab must divide evenly over the threads");
   constexpr int UPT = UNITS / NT;           // units per thread
-  constexpr int PW = 2;                     // weight prefetch depth (iterations)
 
   extern __shared__ __align__(16) unsigned char smem[];
   half_t* xs = reinterpret_cast<half_t*>(smem);   // [2][BM][LDX]
@@ -47,7 +48,7 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
   const int n0 = blockIdx.x * BN, m0 = blockIdx.y * BM;
   const int words_per_row = a.K_total >> 3, groups_per_row = a.K_total / kGroup;
   const int ngroups = (km.k_span + kGroup - 1) / kGroup;
-  const int nit = (ngroups + KS - 1) / KS;
+  const int nit = (ngroups + KS * S2 - 1) / (KS * S2);
   const int nit_pw = (nit + PW - 1) / PW * PW;   // loop trip count; extra iterations multiply zeros
 
   // stored row of each of this lane's weight fragments (clamped: every address stays valid)
@@ -58,21 +59,35 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
     rc = rc < km.n_keep ? rc : km.n_keep - 1;
     wrow[bf] = (size_t)stored_row(km, rc);
   }
-  auto load_w = [&](int it, WTile (&t)[BF]) {
-    int g = it * KS + wk;
-    g = g < ngroups ? g : ngroups - 1;   // past the end: a valid, redundant load (x is zero there)
+  // group s2 of iteration it for this wave: slab-local group s2 * KS + wk
+  auto load_w = [&](int it, WTile (&t)[S2][BF]) {
 #pragma unroll
-    for (int bf = 0; bf < BF; ++bf) {
-      t[bf].w = *reinterpret_cast<const uint4*>(a.qweight + wrow[bf] * words_per_row + g * 16 + ks * 4);
-      t[bf].sbits = a.scales[wrow[bf] * groups_per_row + g];
-      t[bf].z = a.zeros[wrow[bf] * groups_per_row + g];
+    for (int s2 = 0; s2 < S2; ++s2) {
+      int g = (it * S2 + s2) * KS + wk;
+      g = g < ngroups ? g : ngroups - 1;   // past the end: a valid, redundant load (x is zero there)
+#pragma unroll
+      for (int bf = 0; bf < BF; ++bf) {
+        t[s2][bf].w = *reinterpret_cast<const uint4*>(a.qweight + wrow[bf] * words_per_row + g * 16 + ks * 4);
+        t[s2][bf].sbits = a.scales[wrow[bf] * groups_per_row + g];
+        t[s2][bf].z = a.zeros[wrow[bf] * groups_per_row + g];
+      }
     }
   };
 
-  // x slab staging: unit u of a slab = token (u / (SC/8)), 8-column block (u % (SC/8))
+  // x slab staging: unit u of a slab = token (u / (SC/8)), 8-column block (u % (SC/8)).
+  // fetch_x only issues loads (unconditional, on clamped addresses) and records which halves are
+  // real; store_x, one iteration later, masks, permutes and writes them to LDS.  Nothing touches
+  // the loaded registers in between, so the wave never waits for x at the point of issue.
+  // XVEC: whole 8-column blocks below kv come from one 128-bit load; the up to 7 kept columns at
+  // and after kv are added in the epilogue.  Otherwise: eight element loads through the column map.
   const int kv = km.k_keep & ~7;
   const uint16_t* xbits = reinterpret_cast<const uint16_t*>(a.x);
-  auto fetch_x = [&](int it, uint4 (&xr)[UPT]) {
+  struct XRegs {
+    uint4 v[XVEC ? UPT : 1];
+    uint32_t e[XVEC ? 1 : UPT][8];
+    uint32_t ok[UPT];   // XVEC: all-ones / zero word mask; element path: bit j = half j is real
+  };
+  auto fetch_x = [&](int it, XRegs& xr) {
 #pragma unroll
     for (int i = 0; i < UPT; ++i) {
       const int u = tid + i * NT;
@@ -81,33 +96,39 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
       const int tok = m0 + tk;
       const bool tok_ok = tok < a.M;
       const size_t xoff = (size_t)(tok_ok ? tok : a.M - 1) * a.ldx;
-      uint32_t e[8];
-      if (XVEC && k0 + 8 <= kv) {
-        const uint4 r = *reinterpret_cast<const uint4*>(a.x + xoff + k0);
-        e[0] = r.x & 0xffffu; e[1] = r.x >> 16; e[2] = r.y & 0xffffu; e[3] = r.y >> 16;
-        e[4] = r.z & 0xffffu; e[5] = r.z >> 16; e[6] = r.w & 0xffffu; e[7] = r.w >> 16;
+      if constexpr (XVEC) {
+        const bool full = k0 + 8 <= kv;
+        xr.v[i] = *reinterpret_cast<const uint4*>(a.x + xoff + (full ? k0 : 0));
+        xr.ok[i] = (full && tok_ok) ? 0xffffffffu : 0u;
       } else {
+        xr.ok[i] = 0;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           const int k = k0 + j;
           const int kc = k < km.k_span ? compact_col(km, k) : -1;
-          const uint32_t v = xbits[xoff + (kc >= 0 ? kc : 0)];
-          e[j] = kc >= 0 ? v : 0u;
+          xr.e[i][j] = xbits[xoff + (kc >= 0 ? kc : 0)];
+          xr.ok[i] |= (kc >= 0 && tok_ok) ? (1u << j) : 0u;
         }
       }
-      if (!tok_ok) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) e[j] = 0u;
-      }
-      xr[i] = make_uint4(e[0] | (e[4] << 16), e[1] | (e[5] << 16), e[2] | (e[6] << 16), e[3] | (e[7] << 16));
     }
   };
-  auto store_x = [&](int buf, const uint4 (&xr)[UPT]) {
+  auto store_x = [&](int buf, const XRegs& xr) {
 #pragma unroll
     for (int i = 0; i < UPT; ++i) {
       const int u = tid + i * NT;
       const int tk = u / (SC / 8), cb = u % (SC / 8);
-      *reinterpret_cast<uint4*>(xs + ((size_t)buf * BM + tk) * LDX + cb * 8) = xr[i];
+      uint32_t e[8];
+      if constexpr (XVEC) {
+        const uint4 r = xr.v[i];
+        const uint32_t m = xr.ok[i];
+        e[0] = r.x & 0xffffu & m; e[1] = (r.x >> 16) & m; e[2] = r.y & 0xffffu & m; e[3] = (r.y >> 16) & m;
+        e[4] = r.z & 0xffffu & m; e[5] = (r.z >> 16) & m; e[6] = r.w & 0xffffu & m; e[7] = (r.w >> 16) & m;
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) e[j] = (xr.ok[i] >> j) & 1u ? xr.e[i][j] : 0u;
+      }
+      *reinterpret_cast<uint4*>(xs + ((size_t)buf * BM + tk) * LDX + cb * 8) =
+          make_uint4(e[0] | (e[4] << 16), e[1] | (e[5] << 16), e[2] | (e[6] << 16), e[3] | (e[7] << 16));
     }
   };
 
@@ -118,8 +139,8 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
     for (int bf = 0; bf < BF; ++bf) acc[af][bf] = float4_t{0.f, 0.f, 0.f, 0.f};
 
   const Magic mg = make_magic();
-  WTile ring[PW][BF];
-  uint4 xr[UPT];
+  WTile ring[PW][S2][BF];
+  XRegs xr;
 #pragma unroll
   for (int p = 0; p < PW; ++p) load_w(p, ring[p]);
   fetch_x(0, xr);
@@ -134,34 +155,41 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
       // fetch the next slab into registers while this one is consumed
       if (it + 1 < nit_pw) fetch_x(it + 1, xr);
 
-      // dequantise this iteration's weight fragments: word t feeds MFMA t
-      uint4 bfrag[BF][4];
+      // Word t of a lane's 128-bit load feeds MFMA t of the group.  Dequantising word t of every
+      // row fragment right before its MFMAs keeps only BF operand fragments live and lets the
+      // VALU work of step t+1 issue while the matrix pipe is busy with step t.
 #pragma unroll
-      for (int bf = 0; bf < BF; ++bf) {
-        const GroupQ gq = make_groupq(ring[p][bf].sbits, ring[p][bf].z);
-        const uint32_t wv[4] = {ring[p][bf].w.x, ring[p][bf].w.y, ring[p][bf].w.z, ring[p][bf].w.w};
+      for (int s2 = 0; s2 < S2; ++s2) {
+        GroupQ gq[BF];
+        uint32_t wv[BF][4];
+#pragma unroll
+        for (int bf = 0; bf < BF; ++bf) {
+          const WTile& wt = ring[p][s2][bf];
+          gq[bf] = make_groupq(wt.sbits, wt.z);
+          wv[bf][0] = wt.w.x; wv[bf][1] = wt.w.y; wv[bf][2] = wt.w.z; wv[bf][3] = wt.w.w;
+        }
+        const half_t* xb = xs + (size_t)buf * BM * LDX + (s2 * KS + wk) * 128 + ks * 32;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-          half2_t d[4];
-          dequant_word(wv[t], gq, mg, d);
-          bfrag[bf][t] = make_uint4(as_u32(d[0]), as_u32(d[1]), as_u32(d[2]), as_u32(d[3]));
+          uint4 bfrag[BF];
+#pragma unroll
+          for (int bf = 0; bf < BF; ++bf) {
+            half2_t d[4];
+            dequant_word(wv[bf][t], gq[bf], mg, d);
+            bfrag[bf] = make_uint4(as_u32(d[0]), as_u32(d[1]), as_u32(d[2]), as_u32(d[3]));
+          }
+#pragma unroll
+          for (int af = 0; af < AF; ++af) {
+            const uint4 av = *reinterpret_cast<const uint4*>(xb + (af * 16 + n) * LDX + t * 8);
+#pragma unroll
+            for (int bf = 0; bf < BF; ++bf)
+              acc[af][bf] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av),
+                                                                  __builtin_bit_cast(half8_t, bfrag[bf]),
+                                                                  acc[af][bf], 0, 0, 0);
+          }
         }
       }
       load_w(it + PW, ring[p]);   // refill the ring slot (clamped past the end)
-
-      const half_t* xb = xs + (size_t)buf * BM * LDX + wk * 128 + ks * 32;
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-#pragma unroll
-        for (int af = 0; af < AF; ++af) {
-          const uint4 av = *reinterpret_cast<const uint4*>(xb + (af * 16 + n) * LDX + t * 8);
-#pragma unroll
-          for (int bf = 0; bf < BF; ++bf)
-            acc[af][bf] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av),
-                                                                __builtin_bit_cast(half8_t, bfrag[bf][t]),
-                                                                acc[af][bf], 0, 0, 0);
-        }
-      }
       if (it + 1 < nit_pw) store_x(buf ^ 1, xr);
       __syncthreads();
     }
@@ -191,6 +219,30 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
           for (int v = 0; v < 4; ++v) acc[af][bf][v] += other[((af * BF + bf) * 4 + v) * 64 + lane];
     }
   }
+  if constexpr (XVEC) {
+    // the kept columns kv .. k_keep-1 (fewer than 8: one word of one group per row), in fp32
+    if (kv < km.k_keep) {
+#pragma unroll
+      for (int bf = 0; bf < BF; ++bf) {
+        const uint32_t word = a.qweight[wrow[bf] * words_per_row + (kv >> 3)];
+        const size_t gi = wrow[bf] * groups_per_row + (kv >> 7);
+        const float sf = (float)__builtin_bit_cast(half_t, a.scales[gi]);
+        const int z = a.zeros[gi];
+        for (int j = 0; kv + j < km.k_keep; ++j) {
+          const int q = (int)((word >> (4 * j)) & 15u);
+          const float w = (float)(half_t)((float)(q - z) * sf);   // the canonical fp16 weight
+#pragma unroll
+          for (int af = 0; af < AF; ++af)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+              const int tok = m0 + af * 16 + 4 * ks + v;
+              const float xv = (float)a.x[(size_t)(tok < a.M ? tok : a.M - 1) * a.ldx + kv + j];
+              acc[af][bf][v] = __builtin_fmaf(xv, w, acc[af][bf][v]);
+            }
+        }
+      }
+    }
+  }
 #pragma unroll
   for (int af = 0; af < AF; ++af)
 #pragma unroll
@@ -204,13 +256,13 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
     }
 }
 
-template <int AF, int BF, int WN, int KS, bool XVEC>
+template <int AF, int BF, int WN, int KS, int S2, int PW, bool XVEC>
 static hipError_t launch_cfg(const LinearArgs& a, hipStream_t stream) {
-  constexpr int BM = 16 * AF, BN = WN * BF * 16, SC = KS * 128, LDX = SC + 8;
+  constexpr int BM = 16 * AF, BN = WN * BF * 16, SC = KS * S2 * 128, LDX = SC + 8;
   size_t smem = (size_t)2 * BM * LDX * sizeof(half_t);
   const size_t red = KS > 1 ? (size_t)KS * WN * AF * BF * 4 * 64 * sizeof(float) : 0;
   if (red > smem) smem = red;
-  auto kern = w4_mfma_kernel<AF, BF, WN, KS, XVEC>;
+  auto kern = w4_mfma_kernel<AF, BF, WN, KS, S2, PW, XVEC>;
   if (smem > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
@@ -222,10 +274,13 @@ static hipError_t launch_cfg(const LinearArgs& a, hipStream_t stream) {
 
 template <bool XVEC>
 static hipError_t launch_m(const LinearArgs& a, hipStream_t stream) {
-  if (a.M <= 16) return launch_cfg<1, 1, 2, 4, XVEC>(a, stream);
-  if (a.M <= 32) return launch_cfg<2, 1, 2, 4, XVEC>(a, stream);
-  if (a.M <= 64) return launch_cfg<4, 2, 4, 1, XVEC>(a, stream);
-  return launch_cfg<8, 4, 4, 1, XVEC>(a, stream);
+  // Decode batches (M <= 32) are bound by the weight stream: 16 rows per wave and the K range
+  // split over the block's 8 waves, four ways when there are many row tiles, eight ways otherwise.
+  const int row_tiles = (a.km.n_keep + 15) / 16;
+  if (a.M <= 16) return row_tiles >= 600 ? launch_cfg<1, 1, 2, 4, 2, 2, XVEC>(a, stream) : launch_cfg<1, 1, 1, 8, 1, 2, XVEC>(a, stream);
+  if (a.M <= 32) return row_tiles >= 600 ? launch_cfg<2, 1, 2, 4, 1, 4, XVEC>(a, stream) : launch_cfg<2, 1, 1, 8, 1, 2, XVEC>(a, stream);
+  if (a.M <= 64) return launch_cfg<4, 2, 4, 1, 1, 2, XVEC>(a, stream);
+  return launch_cfg<8, 4, 4, 1, 1, 1, XVEC>(a, stream);
 }
 
 hipError_t launch_w4_gemm(const LinearArgs& a, hipStream_t stream) {
