@@ -68,27 +68,61 @@ class DecodeStep:
         self.xin = {}
         self.yout = {}
         self.host_x = {}
+        self._calls = {}
+        shared = {"k_proj": "q_proj", "v_proj": "q_proj", "up_proj": "gate_proj"}   # same layer input
         for s in specs:
-            x = wl.gen_activations(rng, M, s.k_keep)
-            self.host_x[s.name] = x
-            self.xin[s.name] = torch.from_numpy(x).cuda()
+            if s.name in shared and shared[s.name] in self.xin:
+                self.host_x[s.name] = self.host_x[shared[s.name]]
+                self.xin[s.name] = self.xin[shared[s.name]]
+            else:
+                x = wl.gen_activations(rng, M, s.k_keep)
+                self.host_x[s.name] = x
+                self.xin[s.name] = torch.from_numpy(x).cuda()
             self.yout[s.name] = torch.empty((M, s.n_keep), dtype=torch.float16, device="cuda")
         r = wl.gen_rope_inputs(rng, rope)
         self.host_rope = r
         self.pos = torch.from_numpy(r["positions"]).cuda()
         self.idx = torch.from_numpy(r["kept_idx"]).cuda()
 
-    def run(self, layer, only=None):
+    FUSED = (("q_proj", "k_proj", "v_proj"), ("gate_proj", "up_proj"))
+
+    def multi_call(self, layer, names):
+        """Marshalled uniql_w4_linear_multi call for a group of linears of one layer (cached)."""
+        key = (id(layer), names)
+        if key not in self._calls:
+            sp = {s.name: s for s in self.specs}
+            self._calls[key] = self.uq.MultiCall([layer.lin[n] for n in names], [sp[n].keep for n in names],
+                                                 [self.xin[n] for n in names], [self.yout[n] for n in names])
+        return self._calls[key]
+
+    def rope_qk(self):
+        q = self.yout["q_proj"].view(self.M, self.rope.Hq, self.rope.D_keep)
+        k = self.yout["k_proj"].view(self.M, self.rope.Hkv, self.rope.D_keep)
+        self.uq.uniql_pruned_rope(q, k, self.pos, self.idx, self.rope.D_full, self.rope.theta)
+
+    def run(self, layer, only=None, fused=True):
+        """One step: q/k/v (one call), RoPE on the fresh Q/K, o_proj, gate/up (one call), down.
+        only = a linear name or a tuple of names: just that launch (for attribution)."""
         uq = self.uq
-        for s in self.specs:
-            if only is not None and s.name != only:
-                continue
-            uq.uniql_w4_linear(layer.lin[s.name], s.keep, self.xin[s.name], self.yout[s.name])
-            if s.name == "k_proj" and only is None:
-                # q and k were just produced: rotate them in place, one launch for both
-                q = self.yout["q_proj"].view(self.M, self.rope.Hq, self.rope.D_keep)
-                k = self.yout["k_proj"].view(self.M, self.rope.Hkv, self.rope.D_keep)
-                uq.uniql_pruned_rope(q, k, self.pos, self.idx, self.rope.D_full, self.rope.theta)
+        if only is not None:
+            if isinstance(only, tuple):
+                self.multi_call(layer, only).run()
+            else:
+                s = next(s for s in self.specs if s.name == only)
+                uq.uniql_w4_linear(layer.lin[s.name], s.keep, self.xin[s.name], self.yout[s.name])
+            return
+        if not fused:
+            for s in self.specs:
+                uq.uniql_w4_linear(layer.lin[s.name], s.keep, self.xin[s.name], self.yout[s.name])
+                if s.name == "k_proj":
+                    self.rope_qk()
+            return
+        sp = {s.name: s for s in self.specs}
+        self.multi_call(layer, self.FUSED[0]).run()
+        self.rope_qk()
+        uq.uniql_w4_linear(layer.lin["o_proj"], sp["o_proj"].keep, self.xin["o_proj"], self.yout["o_proj"])
+        self.multi_call(layer, self.FUSED[1]).run()
+        uq.uniql_w4_linear(layer.lin["down_proj"], sp["down_proj"].keep, self.xin["down_proj"], self.yout["down_proj"])
 
 
 def time_events(torch, fn, iters):
@@ -291,7 +325,10 @@ def main():
     # ---- attribution: duration of each linear launch, measured with HIP events on the launch
     # stream around a graph that issues that one linear back to back over the whole layer pool
     # (cold weights every launch, no host launch cost inside the bracket)
-    names = [s.name for s in specs]
+    names = [DecodeStep.FUSED[0], "o_proj", DecodeStep.FUSED[1], "down_proj"]
+    lin_bytes = dict(lin_bytes)
+    for grp in DecodeStep.FUSED:
+        lin_bytes[grp] = sum(lin_bytes[n] for n in grp)
     iso_us = {}
     for n in names:
         if args.no_graph:
@@ -308,19 +345,20 @@ def main():
     per_linear = {n: {"MB": round(lin_bytes[n] / 1e6, 3), "us": round(iso_us[n], 3),
                       "GBps": round(lin_bytes[n] / (iso_us[n] * 1e-6) / 1e9, 1),
                       "frac_of_peak": round(lin_bytes[n] / (iso_us[n] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)} for n in names}
-    for n in names:
-        log(f"  {n:10s} {per_linear[n]}")
-    # the dominant kernel of the step: the GEMV instantiation that serves gate_proj and up_proj
-    dom = [n for n in ("gate_proj", "up_proj") if n in iso_us] or names
+    per_linear = {("+".join(k) if isinstance(k, tuple) else k): v for k, v in per_linear.items()}
+    for n, v in per_linear.items():
+        log(f"  {n:22s} {v}")
+    # the dominant kernel of the step: the GEMV launch that serves gate_proj and up_proj together
+    dom = [DecodeStep.FUSED[1]]
     dom_bytes = float(np.mean([lin_bytes[n] for n in dom]))
     dom_us = float(np.mean([iso_us[n] for n in dom]))
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
     # read-stream ceiling for the same byte count (plain 128-bit loads, no arithmetic)
-    pool_t = layers[0].lin[dom[0]].qweight
     probe_out = torch.empty(1 << 16, dtype=torch.int32, device="cuda")
     nb = int(dom_bytes) // 8192 * 8192
-    probe_src = [L.lin[dom[0]].qweight for L in layers]
-    nb = min(nb, probe_src[0].numel() * 4 // 8192 * 8192)
+    probe_buf = torch.empty(2 * 2 ** 30 // 4, dtype=torch.int32, device="cuda")      # 2 GB to walk through
+    n_slots = max(1, probe_buf.numel() * 4 // nb)
+    probe_src = [probe_buf[(i % n_slots) * (nb // 4):] for i in range(len(layers))]
     if not args.no_graph:
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g, stream=side):
@@ -341,7 +379,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
         "data": "synthetic",
         "config": {"workload": f"Llama-3-8B shaped decode layer, batch 1, int4 group-128 weights, "
-                               f"pruning {rate}% (q/k/v/o/gate/up/down W4A16 GEMV + fused pruned RoPE), "
+                               f"pruning {rate}% (q+k+v, o, gate+up, down W4A16 GEMV launches + fused pruned RoPE), "
                                f"{args.layers}-layer weight pool streamed from HBM",
                    "prune_pct": rate, "M": M, "launch": "hip-graph over the layer pool" if graphs else "eager",
                    "step_algorithmic_MB": round(step_bytes / 1e6, 3)},
@@ -349,11 +387,11 @@ def main():
         "per_linear": per_linear,
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                     "kernel": "w4_gemv_kernel (gate_proj / up_proj launches)",
+                     "kernel": "w4_gemv_kernel<2,true,2> (gate_proj + up_proj in one launch)",
                      "bytes_per_launch": int(dom_bytes), "us_per_launch": round(dom_us, 3),
                      "stream_ceiling_GBps": round(ceil_gbs, 1),
                      "frac_of_stream_ceiling": round(achieved / ceil_gbs, 4),
-                     "how": "algorithmic bytes of one gate/up launch / its mean duration, HIP events on the launch "
+                     "how": "algorithmic bytes of the gate+up launch / its mean duration, HIP events on the launch "
                             "stream around a graph of back-to-back launches over the layer pool (cold HBM)"},
     }
     if not args.no_cpu:

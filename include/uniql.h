@@ -104,6 +104,20 @@ int uniql_w4_linear(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x
                     void* y_f16, int64_t ldy, int32_t M, void* hip_stream);
 
 /*
+ * n (1..4) independent linears with the same token count in one call, e.g. the q, k and v
+ * projections of a layer (Eq. 2) or gate and up (Eq. 1), which read the same x.  W, keep (or NULL
+ * = all unpruned), x_f16, ldx, y_f16, ldy are host arrays of n entries; each entry follows the
+ * rules of uniql_w4_linear.  At M = 1 linears that stream rows of the same length are served by
+ * ONE kernel launch (a decode step is launch-latency bound); otherwise they are launched one
+ * after the other on the stream.  Results are identical to n separate uniql_w4_linear calls.
+ * Errors: E_SHAPE also for n outside 1..4; otherwise as uniql_w4_linear (nothing is launched if
+ * any entry is invalid).
+ */
+int uniql_w4_linear_multi(int32_t n, const uniql_w4_t* W, const uniql_keep_t* keep,
+                          const void* const* x_f16, const int64_t* ldx, void* const* y_f16,
+                          const int64_t* ldy, int32_t M, void* hip_stream);
+
+/*
  * Bit-exact dequantised weights of the kept sub-matrix:
  *   w_f16[r'][k'] = RN_fp16((q - z) * s), fp16 [n_keep][k_keep] compact, device.
  * (Sec. 3.4: the unpack step of "unpack, prune channels, repack".)

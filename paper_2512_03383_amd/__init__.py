@@ -61,6 +61,9 @@ def lib():
         vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
         L.uniql_w4_linear.restype = C.c_int
         L.uniql_w4_linear.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, i64, vp, i64, i32, vp]
+        L.uniql_w4_linear_multi.restype = C.c_int
+        L.uniql_w4_linear_multi.argtypes = [i32, C.POINTER(W4), C.POINTER(KeepDesc), C.POINTER(vp), C.POINTER(i64),
+                                            C.POINTER(vp), C.POINTER(i64), i32, vp]
         L.uniql_w4_dequant.restype = C.c_int
         L.uniql_w4_dequant.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, vp]
         L.uniql_pruned_rope.restype = C.c_int
@@ -158,6 +161,38 @@ def uniql_w4_linear(W: QuantLinear, keep, x, y=None, stream=None):
                                M, _stream_ptr(stream))
     _check(rc)
     return y
+
+
+class MultiCall:
+    """Marshalled arguments of one uniql_w4_linear_multi call, reusable (e.g. for graph capture)."""
+
+    def __init__(self, Ws, keeps, xs, ys):
+        n = len(Ws)
+        assert 1 <= n <= 4 and len(keeps) == n and len(xs) == n and len(ys) == n
+        self.n = n
+        self.M = xs[0].shape[0]
+        self.W = (W4 * n)(*[w.desc() for w in Ws])
+        self.keep = (KeepDesc * n)(*[(_keep_desc(k) or KeepDesc()) for k in keeps])
+        self.x = (C.c_void_p * n)(*[t.data_ptr() for t in xs])
+        self.y = (C.c_void_p * n)(*[t.data_ptr() for t in ys])
+        self.ldx = (C.c_int64 * n)(*[t.stride(0) for t in xs])
+        self.ldy = (C.c_int64 * n)(*[t.stride(0) for t in ys])
+        self._refs = (Ws, xs, ys)      # keep the tensors alive
+
+    def run(self, stream=None):
+        rc = lib().uniql_w4_linear_multi(self.n, self.W, self.keep, self.x, self.ldx, self.y, self.ldy, self.M,
+                                         _stream_ptr(stream))
+        _check(rc)
+
+
+def uniql_w4_linear_multi(Ws, keeps, xs, ys, stream=None):
+    """Several independent linears with the same token count in one call; ys are written in place."""
+    import torch
+    for x, y in zip(xs, ys):
+        assert x.dtype == torch.float16 and y.dtype == torch.float16 and x.stride(1) == 1 and y.stride(1) == 1
+        assert x.shape[0] == xs[0].shape[0]
+    MultiCall(Ws, keeps, xs, ys).run(stream)
+    return ys
 
 
 def uniql_w4_dequant(W: QuantLinear, keep=None, out=None, stream=None):

@@ -75,30 +75,66 @@ static int make_keepmap(const uniql_w4_t* W, const uniql_keep_t* keep, KeepMap* 
   return UNIQL_OK;
 }
 
+// Validate one linear call and fill the kernel arguments.  Host arithmetic only.
+static int fill_linear(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_f16, int64_t ldx,
+                       void* y_f16, int64_t ldy, int32_t M, LinearArgs* a) {
+  int rc = make_keepmap(W, keep, &a->km);
+  if (rc) return rc;
+  if (!x_f16 || !y_f16) return UNIQL_E_NULL;
+  if (M < 1 || ldx < a->km.k_keep || ldy < a->km.n_keep) return UNIQL_E_SHAPE;
+  if (!aligned(x_f16, 2) || !aligned(y_f16, 2)) return UNIQL_E_ALIGN;
+  a->qweight = W->qweight;
+  a->scales = W->scales;
+  a->zeros = W->zeros;
+  a->x = (const half_t*)x_f16;
+  a->y = (half_t*)y_f16;
+  a->ldx = ldx;
+  a->ldy = ldy;
+  a->N_total = W->N_total;
+  a->K_total = W->K_total;
+  a->M = M;
+  return UNIQL_OK;
+}
+
+static int run_linear(const LinearArgs& a, hipStream_t s) {
+  hipError_t e = (a.M == 1) ? launch_w4_gemv(a, s) : launch_w4_gemm(a, s);
+  if (e == hipErrorInvalidValue && a.M == 1) return UNIQL_E_SHAPE;   // K too long for the GEMV's staging
+  return e == hipSuccess ? UNIQL_OK : hip_fail(e);
+}
+
 extern "C" int uniql_w4_linear(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_f16, int64_t ldx,
                                void* y_f16, int64_t ldy, int32_t M, void* hip_stream) {
   LinearArgs a;
-  int rc = make_keepmap(W, keep, &a.km);
+  int rc = fill_linear(W, keep, x_f16, ldx, y_f16, ldy, M, &a);
   if (rc) return rc;
-  if (!x_f16 || !y_f16) return UNIQL_E_NULL;
-  if (M < 1 || ldx < a.km.k_keep || ldy < a.km.n_keep) return UNIQL_E_SHAPE;
-  if (!aligned(x_f16, 2) || !aligned(y_f16, 2)) return UNIQL_E_ALIGN;
   rc = check_arch();
   if (rc) return rc;
-  a.qweight = W->qweight;
-  a.scales = W->scales;
-  a.zeros = W->zeros;
-  a.x = (const half_t*)x_f16;
-  a.y = (half_t*)y_f16;
-  a.ldx = ldx;
-  a.ldy = ldy;
-  a.N_total = W->N_total;
-  a.K_total = W->K_total;
-  a.M = M;
+  return run_linear(a, (hipStream_t)hip_stream);
+}
+
+extern "C" int uniql_w4_linear_multi(int32_t n, const uniql_w4_t* W, const uniql_keep_t* keep,
+                                     const void* const* x_f16, const int64_t* ldx, void* const* y_f16,
+                                     const int64_t* ldy, int32_t M, void* hip_stream) {
+  if (n < 1 || n > kMaxBatch) return UNIQL_E_SHAPE;
+  if (!W || !x_f16 || !ldx || !y_f16 || !ldy) return UNIQL_E_NULL;
+  LinearArgs a[kMaxBatch];
+  for (int i = 0; i < n; ++i) {
+    int rc = fill_linear(&W[i], keep ? &keep[i] : nullptr, x_f16[i], ldx[i], y_f16[i], ldy[i], M, &a[i]);
+    if (rc) return rc;
+  }
+  int rc = check_arch();
+  if (rc) return rc;
   hipStream_t s = (hipStream_t)hip_stream;
-  hipError_t e = (M == 1) ? launch_w4_gemv(a, s) : launch_w4_gemm(a, s);
-  if (e == hipErrorInvalidValue && M == 1) return UNIQL_E_SHAPE;   // K too long for the GEMV's staging
-  return e == hipSuccess ? UNIQL_OK : hip_fail(e);
+  if (M == 1) {
+    hipError_t e = launch_w4_gemv_batch(a, n, s);
+    if (e == hipErrorInvalidValue) return UNIQL_E_SHAPE;
+    return e == hipSuccess ? UNIQL_OK : hip_fail(e);
+  }
+  for (int i = 0; i < n; ++i) {
+    rc = run_linear(a[i], s);
+    if (rc) return rc;
+  }
+  return UNIQL_OK;
 }
 
 extern "C" int uniql_w4_dequant(const uniql_w4_t* W, const uniql_keep_t* keep, void* w_f16, void* hip_stream) {

@@ -41,6 +41,14 @@ struct LinearArgs {
   KeepMap km;
 };
 
+// Several independent linears served by one GEMV launch.
+constexpr int kMaxBatch = 4;
+struct GemvBatch {
+  LinearArgs p[kMaxBatch];
+  int first_block[kMaxBatch];
+  int n;
+};
+
 // compact output row -> stored row
 __device__ __forceinline__ int stored_row(const KeepMap& km, int rc) {
   if (km.rs_stride == 0) return rc;
@@ -118,6 +126,7 @@ __device__ __forceinline__ void dequant_word(uint32_t w, const GroupQ& g, const 
 
 // host-side launchers (one per translation unit)
 hipError_t launch_w4_gemv(const LinearArgs& a, hipStream_t stream);
+hipError_t launch_w4_gemv_batch(const LinearArgs* probs, int n, hipStream_t stream);
 hipError_t launch_w4_gemm(const LinearArgs& a, hipStream_t stream);
 hipError_t launch_w4_dequant(const LinearArgs& a, hipStream_t stream);
 

@@ -69,15 +69,22 @@ __device__ __forceinline__ ColMap make_colmap(const KeepMap& km) {
 // fetched with 128-bit loads; otherwise element by element through the column map (segment
 // strides are at least 8, so a unit of 8 columns wraps at most once).  NCH: chunks per row,
 // compile-time, 1..8 (NCH = 0: run-time chunk count for rows longer than 8 chunks).
+// The launch carries up to kMaxBatch independent linears (same R / XVEC / NCH, e.g. q, k and v
+// of one layer, or gate and up): problem i owns the blocks [first_block[i], first_block[i+1]).
 template <int R, bool XVEC, int NCH>
-__global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(LinearArgs a, int m, int nchunk_rt) {
+__global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, int m, int nchunk_rt) {
   extern __shared__ __align__(16) unsigned char smem[];
   uint4* xs = reinterpret_cast<uint4*>(smem);   // [nchunk][4][64] units of 8 halves
 
+  int pi = 0;
+#pragma unroll
+  for (int i = 1; i < kMaxBatch; ++i) pi += (i < batch.n && (int)blockIdx.x >= batch.first_block[i]) ? 1 : 0;
+  const LinearArgs& a = batch.p[pi];
+  const int block_id = (int)blockIdx.x - batch.first_block[pi];
   const KeepMap& km = a.km;
   const int nchunk = NCH > 0 ? NCH : nchunk_rt;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int rg = blockIdx.x * kGemvWaves + wave;   // row group of this wave
+  const int rg = block_id * kGemvWaves + wave;   // row group of this wave
   const int k_span32 = (km.k_span + 31) & ~31;
   const int words_per_row = a.K_total >> 3;
   const int groups_per_row = a.K_total / kGroup;
@@ -253,8 +260,14 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(LinearArgs a, int
   }
 }
 
+template <int R>
+static int blocks_for(const LinearArgs& a) {
+  const int row_groups = (a.km.n_keep + R - 1) / R;
+  return (row_groups + kGemvWaves - 1) / kGemvWaves;
+}
+
 template <int R, bool XVEC, int NCH>
-static hipError_t launch_one(const LinearArgs& a, int m, int nchunk, hipStream_t stream) {
+static hipError_t launch_one(const LinearArgs* probs, int n, int m, int nchunk, hipStream_t stream) {
   const size_t smem = (size_t)nchunk * 4096;
   auto kern = w4_gemv_kernel<R, XVEC, NCH>;
   if (smem > 160 * 1024) return hipErrorInvalidValue;
@@ -262,45 +275,78 @@ static hipError_t launch_one(const LinearArgs& a, int m, int nchunk, hipStream_t
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
   }
-  const int row_groups = (a.km.n_keep + R - 1) / R;
-  const int blocks = (row_groups + kGemvWaves - 1) / kGemvWaves;
-  hipLaunchKernelGGL(kern, dim3(blocks), dim3(kGemvThreads), smem, stream, a, m, nchunk);
+  GemvBatch b;
+  b.n = n;
+  int blocks = 0;
+  for (int i = 0; i < kMaxBatch; ++i) {
+    b.p[i] = probs[i < n ? i : 0];
+    b.first_block[i] = blocks;
+    if (i < n) blocks += blocks_for<R>(probs[i]);
+  }
+  hipLaunchKernelGGL(kern, dim3(blocks), dim3(kGemvThreads), smem, stream, b, m, nchunk);
   return hipGetLastError();
 }
 
 template <int R, bool XVEC>
-static hipError_t launch_nch(const LinearArgs& a, int m, int nchunk, hipStream_t stream) {
+static hipError_t launch_nch(const LinearArgs* probs, int n, int m, int nchunk, hipStream_t stream) {
   switch (nchunk) {
-    case 1: return launch_one<R, XVEC, 1>(a, m, nchunk, stream);
-    case 2: return launch_one<R, XVEC, 2>(a, m, nchunk, stream);
-    case 3: return launch_one<R, XVEC, 3>(a, m, nchunk, stream);
-    case 4: return launch_one<R, XVEC, 4>(a, m, nchunk, stream);
-    case 5: return launch_one<R, XVEC, 5>(a, m, nchunk, stream);
-    case 6: return launch_one<R, XVEC, 6>(a, m, nchunk, stream);
-    case 7: return launch_one<R, XVEC, 7>(a, m, nchunk, stream);
-    case 8: return launch_one<R, XVEC, 8>(a, m, nchunk, stream);
-    default: return launch_one<R, XVEC, 0>(a, m, nchunk, stream);
+    case 1: return launch_one<R, XVEC, 1>(probs, n, m, nchunk, stream);
+    case 2: return launch_one<R, XVEC, 2>(probs, n, m, nchunk, stream);
+    case 3: return launch_one<R, XVEC, 3>(probs, n, m, nchunk, stream);
+    case 4: return launch_one<R, XVEC, 4>(probs, n, m, nchunk, stream);
+    case 5: return launch_one<R, XVEC, 5>(probs, n, m, nchunk, stream);
+    case 6: return launch_one<R, XVEC, 6>(probs, n, m, nchunk, stream);
+    case 7: return launch_one<R, XVEC, 7>(probs, n, m, nchunk, stream);
+    case 8: return launch_one<R, XVEC, 8>(probs, n, m, nchunk, stream);
+    default: return launch_one<R, XVEC, 0>(probs, n, m, nchunk, stream);
   }
 }
 
 template <bool XVEC>
-static hipError_t launch_rows(const LinearArgs& a, int r1, int m, int nchunk, hipStream_t stream) {
-  if (r1 == 2) return launch_nch<2, XVEC>(a, m, nchunk, stream);
-  return launch_nch<1, XVEC>(a, m, nchunk, stream);
+static hipError_t launch_rows(const LinearArgs* probs, int n, int r1, int m, int nchunk, hipStream_t stream) {
+  if (r1 == 2) return launch_nch<2, XVEC>(probs, n, m, nchunk, stream);
+  return launch_nch<1, XVEC>(probs, n, m, nchunk, stream);
+}
+
+static int nchunk_of(const LinearArgs& a) {
+  const int k_span32 = (a.km.k_span + 31) & ~31;
+  return (k_span32 + kChunk - 1) / kChunk;
+}
+static bool xvec_of(const LinearArgs& a, int m) {
+  const half_t* xrow = a.x + (size_t)m * a.ldx;
+  return a.km.cs_stride == 0 && a.km.k_keep >= 8 && (reinterpret_cast<uintptr_t>(xrow) & 15) == 0;
 }
 
 hipError_t launch_w4_gemv(const LinearArgs& a, hipStream_t stream) {
-  const int k_span32 = (a.km.k_span + 31) & ~31;
-  const int nchunk = (k_span32 + kChunk - 1) / kChunk;
   // rows per wave: fewer when the matrix is small, so that every CU still gets several waves
   const int r1 = a.km.n_keep >= 8192 ? 2 : 1;
   for (int m = 0; m < a.M; ++m) {
-    const half_t* xrow = a.x + (size_t)m * a.ldx;
-    const bool xvec = a.km.cs_stride == 0 && a.km.k_keep >= 8 && (reinterpret_cast<uintptr_t>(xrow) & 15) == 0;
-    hipError_t e = xvec ? launch_rows<true>(a, r1, m, nchunk, stream) : launch_rows<false>(a, r1, m, nchunk, stream);
+    hipError_t e = xvec_of(a, m) ? launch_rows<true>(&a, 1, r1, m, nchunk_of(a), stream)
+                                 : launch_rows<false>(&a, 1, r1, m, nchunk_of(a), stream);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
+}
+
+// n single-token linears in one launch when they can share a kernel instantiation (same chunk
+// count and x access mode); otherwise one launch each.
+hipError_t launch_w4_gemv_batch(const LinearArgs* probs, int n, hipStream_t stream) {
+  bool same = n <= kMaxBatch;
+  long long rows = 0;
+  for (int i = 0; i < n; ++i) {
+    same = same && probs[i].M == 1 && nchunk_of(probs[i]) == nchunk_of(probs[0]) && xvec_of(probs[i], 0) == xvec_of(probs[0], 0);
+    rows += probs[i].km.n_keep;
+  }
+  if (!same) {
+    for (int i = 0; i < n; ++i) {
+      hipError_t e = launch_w4_gemv(probs[i], stream);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+  }
+  const int r1 = rows >= 8192 ? 2 : 1;
+  return xvec_of(probs[0], 0) ? launch_rows<true>(probs, n, r1, 0, nchunk_of(probs[0]), stream)
+                              : launch_rows<false>(probs, n, r1, 0, nchunk_of(probs[0]), stream);
 }
 
 }  // namespace uniql

@@ -324,3 +324,46 @@ def test_rope_position_zero_and_identity_table(env, uref):
     gq, gk = run_rope(uq, torch, r, spec)          # all positions are 0: the identity
     assert np.array_equal(gq.view(np.uint16), r["q"].view(np.uint16))
     assert np.array_equal(gk.view(np.uint16), r["k"].view(np.uint16))
+
+
+# ------------------------------------------------------- several linears per call
+@pytest.mark.parametrize("rate", [0, 15, 35])
+def test_multi_call_matches_single_calls(env, uref, rate):
+    """q/k/v and gate/up of the Llama-3-8B shaped layer through uniql_w4_linear_multi (one launch at
+    M = 1): bit-identical to separate calls, and within tolerance of the oracle on sampled rows."""
+    uq, torch = env
+    rng = wl.rng_for(1, 50 + rate)
+    specs = {s.name: s for s in wl.llama3_8b_layer(rate)}
+    for names in (("q_proj", "k_proj", "v_proj"), ("gate_proj", "up_proj")):
+        ws = [wl.gen_linear(rng, specs[n].N, specs[n].K) for n in names]
+        qws = [uq.QuantLinear.from_numpy(w) for w in ws]
+        x = wl.gen_activations(rng, 1, specs[names[0]].k_keep)
+        xd = to_dev(torch, x)
+        ys = [torch.full((1, specs[n].n_keep), 3.0, dtype=torch.float16, device="cuda") for n in names]
+        uq.uniql_w4_linear_multi(qws, [specs[n].keep for n in names], [xd] * len(names), ys)
+        torch.cuda.synchronize()
+        for n, w, qw, y in zip(names, ws, qws, ys):
+            single = uq.uniql_w4_linear(qw, specs[n].keep, xd).cpu().numpy()
+            got = y.cpu().numpy()
+            assert np.array_equal(got.view(np.uint16), single.view(np.uint16)), n
+            rows = _sample_rows(specs[n].n_keep, rng, 64)
+            ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], x, specs[n].keep, rows=rows)
+            rms = np.sqrt(np.mean(ref ** 2))
+            err = np.max(np.abs(got[:, rows].astype(np.float64) - ref) / np.maximum(np.abs(ref), 1e-2 * rms))
+            assert err <= TOL, (n, err)
+
+
+def test_multi_call_mixed_shapes_and_tokens(env, uref):
+    """Entries that cannot share a launch (different row lengths, or M > 1) still give the single-call results."""
+    uq, torch = env
+    rng = wl.rng_for(0, 60)
+    shapes = [(300, 1024, Keep(n_keep=257)), (64, 4096, Keep(k_keep=3000)), (128, 256, Keep())]
+    for M in (1, 3):
+        ws = [wl.gen_linear(rng, N, K) for N, K, _ in shapes]
+        qws = [uq.QuantLinear.from_numpy(w) for w in ws]
+        xs = [to_dev(torch, wl.gen_activations(rng, M, uq.kept_dims(qw, kp)[1])) for qw, (_, _, kp) in zip(qws, shapes)]
+        ys = [torch.zeros((M, uq.kept_dims(qw, kp)[0]), dtype=torch.float16, device="cuda") for qw, (_, _, kp) in zip(qws, shapes)]
+        uq.uniql_w4_linear_multi(qws, [kp for _, _, kp in shapes], xs, ys)
+        for qw, (_, _, kp), x, y in zip(qws, shapes, xs, ys):
+            single = uq.uniql_w4_linear(qw, kp, x)
+            assert torch.equal(single, y)
