@@ -23,7 +23,7 @@ namespace uniql {
 constexpr int kGemvThreads = 512;
 constexpr int kGemvWaves = kGemvThreads / kWave;
 constexpr int kChunk = kWave * 32;   // stored columns one wave covers with one 128-bit load per lane
-constexpr int kDepth = 4;            // tiles (1 KB of codes each) a wave keeps in flight
+constexpr int kDepth = 4;            // most tiles (1 KB of codes each) a wave keeps in flight
 
 __device__ __forceinline__ float dpp_xor_reduce(float v) {
   // butterfly within each row of 16 lanes with DPP, then across rows through the LDS crossbar
@@ -171,7 +171,8 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
     // ---- phase 2: start the weight stream.  Tile t = (chunk t / R, row t % R).
     __builtin_amdgcn_sched_barrier(0);
     constexpr int T = NCH * R;
-    constexpr int D = T < kDepth ? T : kDepth;
+    constexpr int DW = R >= 2 ? 2 : 4;   // tiles in flight: few per wave when a wave owns several rows (many waves), more for one-row waves
+    constexpr int D = T < DW ? T : DW;
     Tile ring[D];
 #pragma unroll
     for (int t = 0; t < D; ++t) load_tile(t / R, t % R, ring[t]);
@@ -304,6 +305,7 @@ static hipError_t launch_nch(const LinearArgs* probs, int n, int m, int nchunk, 
 
 template <bool XVEC>
 static hipError_t launch_rows(const LinearArgs* probs, int n, int r1, int m, int nchunk, hipStream_t stream) {
+  if (r1 == 4) return launch_nch<4, XVEC>(probs, n, m, nchunk, stream);
   if (r1 == 2) return launch_nch<2, XVEC>(probs, n, m, nchunk, stream);
   return launch_nch<1, XVEC>(probs, n, m, nchunk, stream);
 }
@@ -319,7 +321,7 @@ static bool xvec_of(const LinearArgs& a, int m) {
 
 hipError_t launch_w4_gemv(const LinearArgs& a, hipStream_t stream) {
   // rows per wave: fewer when the matrix is small, so that every CU still gets several waves
-  const int r1 = a.km.n_keep >= 8192 ? 2 : 1;
+  const int r1 = a.km.n_keep >= 16384 ? 4 : (a.km.n_keep >= 6144 ? 2 : 1);
   for (int m = 0; m < a.M; ++m) {
     hipError_t e = xvec_of(a, m) ? launch_rows<true>(&a, 1, r1, m, nchunk_of(a), stream)
                                  : launch_rows<false>(&a, 1, r1, m, nchunk_of(a), stream);
@@ -344,7 +346,7 @@ hipError_t launch_w4_gemv_batch(const LinearArgs* probs, int n, hipStream_t stre
     }
     return hipSuccess;
   }
-  const int r1 = rows >= 8192 ? 2 : 1;
+  const int r1 = rows >= 16384 ? 4 : (rows >= 6144 ? 2 : 1);
   return xvec_of(probs[0], 0) ? launch_rows<true>(probs, n, r1, 0, nchunk_of(probs[0]), stream)
                               : launch_rows<false>(probs, n, r1, 0, nchunk_of(probs[0]), stream);
 }
