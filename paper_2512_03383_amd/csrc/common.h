@@ -65,6 +65,14 @@ __device__ __forceinline__ int compact_col(const KeepMap& km, int k) {
   return off < km.cs_keep ? seg * km.cs_keep + off : -1;
 }
 
+// 128-bit global load from an address that is only 2-byte aligned (one global_load_dwordx4: the
+// target allows unaligned vector loads from global memory).
+__device__ __forceinline__ uint4 load_u4_unaligned(const half_t* p) {
+  typedef uint32_t u32x4_u2 __attribute__((ext_vector_type(4), aligned(2)));
+  u32x4_u2 v = *reinterpret_cast<const u32x4_u2*>(p);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 // ---- int4 -> fp16 ---------------------------------------------------------
 // A 32-bit word holds codes q0..q7.  OR-ing a masked word with an fp16 exponent
 // pattern yields exact fp16 numbers without any conversion instruction:

@@ -13,7 +13,7 @@
 // RN16((q - z) s), and 4 two-way dot instructions accumulate in fp32.
 //
 // The kernel is fully unrolled over the row's 2048-column chunks (template NCH):
-// a wave's tiles (row, chunk) are loaded up to kDepth ahead and consumed in issue
+// a wave's tiles (row, chunk) are loaded a few tiles ahead (DW in the kernel) and consumed in issue
 // order, each as soon as it has arrived, so the arithmetic overlaps the stream
 // instead of starting after the last byte.
 #include "common.h"
@@ -23,7 +23,6 @@ namespace uniql {
 constexpr int kGemvThreads = 512;
 constexpr int kGemvWaves = kGemvThreads / kWave;
 constexpr int kChunk = kWave * 32;   // stored columns one wave covers with one 128-bit load per lane
-constexpr int kDepth = 4;            // most tiles (1 KB of codes each) a wave keeps in flight
 
 __device__ __forceinline__ float dpp_xor_reduce(float v) {
   // butterfly within each row of 16 lanes with DPP, then across rows through the LDS crossbar
@@ -150,7 +149,7 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
       okmask[i] = 0;
       if constexpr (XVEC) {
         const int k0c = k0 + 8 <= kv ? k0 : kv - 8;   // the host selects XVEC only when k_keep >= 8
-        rawv[i] = *reinterpret_cast<const uint4*>(xrow + k0c);
+        rawv[i] = load_u4_unaligned(xrow + k0c);
       } else {
         const int seg0 = k0 / cm.stride, off0 = k0 - seg0 * cm.stride;
 #pragma unroll
@@ -314,9 +313,10 @@ static int nchunk_of(const LinearArgs& a) {
   const int k_span32 = (a.km.k_span + 31) & ~31;
   return (k_span32 + kChunk - 1) / kChunk;
 }
-static bool xvec_of(const LinearArgs& a, int m) {
-  const half_t* xrow = a.x + (size_t)m * a.ldx;
-  return a.km.cs_stride == 0 && a.km.k_keep >= 8 && (reinterpret_cast<uintptr_t>(xrow) & 15) == 0;
+static bool xvec_of(const LinearArgs& a, int) {
+  // a column prefix is fetched with 128-bit loads whatever the alignment of x (global loads may
+  // start on any 2-byte boundary on this target)
+  return a.km.cs_stride == 0 && a.km.k_keep >= 8;
 }
 
 hipError_t launch_w4_gemv(const LinearArgs& a, hipStream_t stream) {

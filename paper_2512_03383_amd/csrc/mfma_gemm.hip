@@ -98,7 +98,7 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
       const size_t xoff = (size_t)(tok_ok ? tok : a.M - 1) * a.ldx;
       if constexpr (XVEC) {
         const bool full = k0 + 8 <= kv;
-        xr.v[i] = *reinterpret_cast<const uint4*>(a.x + xoff + (full ? k0 : 0));
+        xr.v[i] = load_u4_unaligned(a.x + xoff + (full ? k0 : 0));
         xr.ok[i] = (full && tok_ok) ? 0xffffffffu : 0u;
       } else {
         xr.ok[i] = 0;
@@ -284,9 +284,9 @@ static hipError_t launch_m(const LinearArgs& a, hipStream_t stream) {
 }
 
 hipError_t launch_w4_gemm(const LinearArgs& a, hipStream_t stream) {
-  // 128-bit x loads need a column prefix and 16-byte aligned token rows
-  const bool xvec = a.km.cs_stride == 0 && a.km.k_keep >= 8 && (reinterpret_cast<uintptr_t>(a.x) & 15) == 0 &&
-                    ((a.ldx * 2) & 15) == 0;
+  // 128-bit x loads need a column prefix only: global loads of any size may start on any 2-byte
+  // boundary on this target, so odd leading dimensions (k_keep = 12185) take the same path
+  const bool xvec = a.km.cs_stride == 0 && a.km.k_keep >= 8;
   return xvec ? launch_m<true>(a, stream) : launch_m<false>(a, stream);
 }
 
