@@ -29,6 +29,10 @@ import workloads as wl  # noqa: E402
 METRIC = "µs and achieved HBM GB/s per pruned W4A16 decode linear (Llama-3-8B shapes)"
 HBM_PEAK_GBS = 8000.0
 MFMA_F16_PEAK_TFLOPS = 2500.0
+# HBM bytes per gate+up GEMV launch at pruning 15 %, from the two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE)
+# summarised in profiles/w4_gemv_llama3_8b_decode_p15.md: 25789.9 x 2.000 KiB read + 47.7 x 1.000 KiB written, each
+# scaled by what the counter reads for a 256 MiB elementwise copy (--pmc-calib).  Other rates were not measured.
+PMC_TRAFFIC_BYTES = {15: int(25789.9 * 2.0 * 1024 * (262144 / 2.0 / 131086)) + int(47.7 * 1024)}
 
 
 def log(*a):
@@ -254,6 +258,9 @@ def main():
     ap.add_argument("--layers", type=int, default=32, help="distinct layers in the weight pool")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--pmc-calib", action="store_true",
+                    help="also launch a plain 256 MiB elementwise copy four times: the kernel of known size that "
+                         "scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--detail", action="store_true", help="also time the other benchmark configurations (three rates, Qwen / Mamba shapes, prefill GEMM, RoPE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -386,14 +393,22 @@ def main():
         "us_per_step_gpu_events": round(ms_per_step_gpu * 1e3, 3),
         "per_linear": per_linear,
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                     "kernel": "w4_gemv_kernel<2,true,2> (gate_proj + up_proj in one launch)",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": PMC_TRAFFIC_BYTES.get(rate),
+                     "traffic_unit": "bytes per launch (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, copy-kernel scaled)",
+                     "kernel": "w4_gemv_kernel<4,true,2> (gate_proj + up_proj in one launch)",
                      "bytes_per_launch": int(dom_bytes), "us_per_launch": round(dom_us, 3),
                      "stream_ceiling_GBps": round(ceil_gbs, 1),
                      "frac_of_stream_ceiling": round(achieved / ceil_gbs, 4),
                      "how": "algorithmic bytes of the gate+up launch / its mean duration, HIP events on the launch "
                             "stream around a graph of back-to-back launches over the layer pool (cold HBM)"},
     }
+    if args.pmc_calib:
+        src = torch.ones(64 * 2 ** 20, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            torch.add(src, 1, out=dst)      # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(specs, rope, layers[0], step, M)
     if args.detail:

@@ -142,7 +142,7 @@ int uniql_w4_dequant(const uniql_w4_t* W, const uniql_keep_t* keep, void* w_f16,
  *   H_tab     : table rows; head h of a tensor with H heads uses row
  *               h / (H / H_tab) (one row per KV head under GQA, per head for MHSA),
  *               so Hq and Hkv must be multiples of H_tab
- * The angle is formed in fp64 and reduced before the fp32 sin/cos.
+ * The angle is formed in fp64, in revolutions; its fraction is rounded to fp32 for the sin/cos.
  * Errors: E_NULL, E_SHAPE (T < 1, Hq < 1), E_KEEP (D_keep odd, < 2 or > D_full,
  * D_full odd, head counts not multiples of H_tab, theta <= 0), E_ALIGN, E_ARCH, E_HIP.
  */
