@@ -33,13 +33,19 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
   constexpr int BM = 16 * AF;               // tokens per block
   constexpr int BN = WN * BF * 16;          // rows per block
   constexpr int SC = KS * S2 * 128;         // columns per slab (S2 groups per K-split wave)
-  constexpr int LDX = SC + 8;               // padded slab row (halves)
-  constexpr int UNITS = BM * SC / 8;        // 16-byte units per slab
+  constexpr int NCH = SC / 8;               // 8-column chunks per slab
+  constexpr int UNITS = BM * NCH;           // 16-byte units per slab
   static_assert(UNITS % NT == 0, "slab must divide evenly over the threads");
   constexpr int UPT = UNITS / NT;           // units per thread
 
   extern __shared__ __align__(16) unsigned char smem[];
-  half_t* xs = reinterpret_cast<half_t*>(smem);   // [2][BM][LDX]
+  // Slab layout [2][NCH][BM] of 16-byte units (8 columns of one token).  The 16 lanes that read one
+  // activation fragment (16 tokens, one chunk) touch one aligned 256-byte window, which is what
+  // ds_read_b128 needs to run at the full LDS rate on this target (a padded token-major slab reads
+  // at half rate).  Inside its window token j sits at slot j ^ swz(chunk), swz = (k-slot | step << 2)
+  // of the chunk, so that the 16 lanes that WRITE 16 consecutive chunks of one token also hit 16
+  // different bank groups; measured, both patterns are conflict-free.
+  uint4* xs = reinterpret_cast<uint4*>(smem);
 
   const KeepMap& km = a.km;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -74,12 +80,15 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
     }
   };
 
-  // x slab staging: unit u of a slab = token (u / (SC/8)), 8-column block (u % (SC/8)).
+  // x slab staging: unit u of a slab = token (u / NCH), 8-column chunk (u % NCH).
   // fetch_x only issues loads (unconditional, on clamped addresses) and records which halves are
   // real; store_x, one iteration later, masks, permutes and writes them to LDS.  Nothing touches
   // the loaded registers in between, so the wave never waits for x at the point of issue.
   // XVEC: whole 8-column blocks below kv come from one 128-bit load; the up to 7 kept columns at
   // and after kv are added in the epilogue.  Otherwise: eight element loads through the column map.
+  auto unit_token = [](int u) { return u / NCH; };
+  auto unit_chunk = [](int u) { return u % NCH; };
+  auto swz = [](int chunk) { return ((chunk >> 2) & 3) | ((chunk & 3) << 2); };
   const int kv = km.k_keep & ~7;
   const uint16_t* xbits = reinterpret_cast<const uint16_t*>(a.x);
   struct XRegs {
@@ -91,7 +100,7 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
 #pragma unroll
     for (int i = 0; i < UPT; ++i) {
       const int u = tid + i * NT;
-      const int tk = u / (SC / 8), cb = u % (SC / 8);
+      const int tk = unit_token(u), cb = unit_chunk(u);
       const int k0 = it * SC + cb * 8;
       const int tok = m0 + tk;
       const bool tok_ok = tok < a.M;
@@ -116,7 +125,7 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
 #pragma unroll
     for (int i = 0; i < UPT; ++i) {
       const int u = tid + i * NT;
-      const int tk = u / (SC / 8), cb = u % (SC / 8);
+      const int tk = unit_token(u), cb = unit_chunk(u);
       uint32_t e[8];
       if constexpr (XVEC) {
         const uint4 r = xr.v[i];
@@ -127,7 +136,7 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) e[j] = (xr.ok[i] >> j) & 1u ? xr.e[i][j] : 0u;
       }
-      *reinterpret_cast<uint4*>(xs + ((size_t)buf * BM + tk) * LDX + cb * 8) =
+      xs[(buf * NCH + cb) * BM + (tk ^ swz(cb))] =
           make_uint4(e[0] | (e[4] << 16), e[1] | (e[5] << 16), e[2] | (e[6] << 16), e[3] | (e[7] << 16));
     }
   };
@@ -168,7 +177,7 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
           gq[bf] = make_groupq(wt.sbits, wt.z);
           wv[bf][0] = wt.w.x; wv[bf][1] = wt.w.y; wv[bf][2] = wt.w.z; wv[bf][3] = wt.w.w;
         }
-        const half_t* xb = xs + (size_t)buf * BM * LDX + (s2 * KS + wk) * 128 + ks * 32;
+        const uint4* xb = xs + (buf * NCH + (s2 * KS + wk) * 16 + ks * 4) * BM;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
           uint4 bfrag[BF];
@@ -180,7 +189,7 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
           }
 #pragma unroll
           for (int af = 0; af < AF; ++af) {
-            const uint4 av = *reinterpret_cast<const uint4*>(xb + (af * 16 + n) * LDX + t * 8);
+            const uint4 av = xb[t * BM + af * 16 + (n ^ (ks | (t << 2)))];
 #pragma unroll
             for (int bf = 0; bf < BF; ++bf)
               acc[af][bf] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av),
@@ -258,8 +267,8 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
 
 template <int AF, int BF, int WN, int KS, int S2, int PW, bool XVEC>
 static hipError_t launch_cfg(const LinearArgs& a, hipStream_t stream) {
-  constexpr int BM = 16 * AF, BN = WN * BF * 16, SC = KS * S2 * 128, LDX = SC + 8;
-  size_t smem = (size_t)2 * BM * LDX * sizeof(half_t);
+  constexpr int BM = 16 * AF, BN = WN * BF * 16, SC = KS * S2 * 128;
+  size_t smem = (size_t)2 * BM * SC * sizeof(half_t);
   const size_t red = KS > 1 ? (size_t)KS * WN * AF * BF * 4 * 64 * sizeof(float) : 0;
   if (red > smem) smem = red;
   auto kern = w4_mfma_kernel<AF, BF, WN, KS, S2, PW, XVEC>;
