@@ -104,9 +104,14 @@ __device__ __forceinline__ GroupQ make_groupq(uint32_t scale_bits, uint32_t z) {
 // both constants are literals (a VOP3 encoding cannot carry two of them on this target), so the
 // mask is pinned to an SGPR and the exponent pattern to a VGPR.
 __device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t orv) {
+#ifdef UNIQL_ANDOR_PLAIN
+  asm("" : "+s"(mask));
+  return (a & mask) | orv;
+#else
   uint32_t r;
   asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask), "v"(orv));
   return r;
+#endif
 }
 
 // The two exponent patterns, materialised once per thread in VGPRs.

@@ -15,7 +15,9 @@
 // Small M (decode batches) is HBM-bound: AF = 1 and the K range is split over KS waves of the
 // block (reduced through LDS at the end) to get enough waves; large M (prefill) is MFMA-bound:
 // AF = 8, BF = 4, KS = 1.
+#define UNIQL_ANDOR_PLAIN   // and-or as plain C here: the scheduler must be able to classify it as VALU
 #include "common.h"
+#include <type_traits>
 
 namespace uniql {
 
@@ -178,25 +180,43 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
           wv[bf][0] = wt.w.x; wv[bf][1] = wt.w.y; wv[bf][2] = wt.w.z; wv[bf][3] = wt.w.w;
         }
         const uint4* xb = xs + (buf * NCH + (s2 * KS + wk) * 16 + ks * 4) * BM;
+        // Two-stage pipeline over the group's four MFMA steps: while step t multiplies, the
+        // activation fragments of step t+1 are read from LDS and its weights dequantised.
+        uint4 av[2][AF], bfrag[2][BF];
+        auto stage = [&](int t, uint4 (&ao)[AF], uint4 (&bo)[BF]) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          uint4 bfrag[BF];
+          for (int af = 0; af < AF; ++af) ao[af] = xb[t * BM + af * 16 + (n ^ (ks | (t << 2)))];
 #pragma unroll
           for (int bf = 0; bf < BF; ++bf) {
             half2_t d[4];
             dequant_word(wv[bf][t], gq[bf], mg, d);
-            bfrag[bf] = make_uint4(as_u32(d[0]), as_u32(d[1]), as_u32(d[2]), as_u32(d[3]));
+            bo[bf] = make_uint4(as_u32(d[0]), as_u32(d[1]), as_u32(d[2]), as_u32(d[3]));
           }
+        };
+        stage(0, av[0], bfrag[0]);
 #pragma unroll
-          for (int af = 0; af < AF; ++af) {
-            const uint4 av = xb[t * BM + af * 16 + (n ^ (ks | (t << 2)))];
+        for (int t = 0; t < 4; ++t) {
+          if (t < 3) stage(t + 1, av[(t + 1) & 1], bfrag[(t + 1) & 1]);
+#pragma unroll
+          for (int af = 0; af < AF; ++af)
 #pragma unroll
             for (int bf = 0; bf < BF; ++bf)
-              acc[af][bf] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av),
-                                                                  __builtin_bit_cast(half8_t, bfrag[bf]),
+              acc[af][bf] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av[t & 1][af]),
+                                                                  __builtin_bit_cast(half8_t, bfrag[t & 1][bf]),
                                                                   acc[af][bf], 0, 0, 0);
-          }
         }
+#ifdef UNIQL_SGB
+        // scheduling pipeline for this group: the first stage, then every MFMA followed by two
+        // VALU instructions, and one LDS read per BF MFMAs
+        __builtin_amdgcn_sched_group_barrier(0x100, AF, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 13 * BF + 8, 0);
+#pragma unroll
+        for (int i = 0; i < 4 * AF * BF; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          if (i % BF == 0 && i < 3 * AF * BF) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, UNIQL_SGB, 0);
+        }
+#endif
       }
       load_w(it + PW, ring[p]);   // refill the ring slot (clamped past the end)
       if (it + 1 < nit_pw) store_x(buf ^ 1, xr);
@@ -265,6 +285,234 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
     }
 }
 
+
+// ---- prefill kernel -------------------------------------------------------------------------
+// 128 tokens x 256 rows per block, four waves side by side over rows, each 8 x 4 fragments, one
+// wave per SIMD.  With a single wave per SIMD nothing hides a stall, so the body of a slab (one
+// quantisation group, four MFMA steps) is written in the order it should issue and pinned with
+// scheduling barriers: every MFMA is followed by the one or two VALU instructions of the NEXT
+// step's dequantisation (or, in the last step, of the next slab's first step and of the staging
+// of the next activation slab), and every fourth by one LDS read of the next step's activation
+// fragment.  The matrix pipe takes 16 clocks per MFMA and the wave issues one instruction per
+// 4 clocks, so three instructions fit behind each MFMA for free.
+// Column prefix only (XVEC staging); weights and activations are addressed as a uniform base plus
+// a 32-bit per-lane offset, which the host checks for.
+template <bool DUMMY>
+__global__ __launch_bounds__(256) void w4_mfma_prefill_kernel(LinearArgs a) {
+  constexpr int AF = 8, BF = 4, NT = 256, BM = 128, BN = 256, SC = 128, NCH = 16, UPT = 8;
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint4* xs = reinterpret_cast<uint4*>(smem);   // [2][NCH][BM], swizzled as in w4_mfma_kernel
+
+  const KeepMap& km = a.km;
+  const int tid = threadIdx.x, lane = tid & 63, wn = tid >> 6;
+  const int n = lane & 15, ks = lane >> 4;
+  const int n0 = blockIdx.x * BN, m0 = blockIdx.y * BM;
+  const int words_per_row = a.K_total >> 3, groups_per_row = a.K_total / kGroup;
+  const int kv = km.k_keep & ~7;
+  const int nit = (km.k_span + kGroup - 1) / kGroup;
+  auto swz = [](int chunk) { return ((chunk >> 2) & 3) | ((chunk & 3) << 2); };
+
+  // per-lane byte offsets of this lane's weight fragments (rows clamped: every address is valid)
+  size_t wrow[BF];
+  uint32_t woff[BF], soff[BF], zoff[BF];
+#pragma unroll
+  for (int bf = 0; bf < BF; ++bf) {
+    int rc = n0 + (wn * BF + bf) * 16 + n;
+    rc = rc < km.n_keep ? rc : km.n_keep - 1;
+    wrow[bf] = (size_t)stored_row(km, rc);
+    woff[bf] = (uint32_t)(wrow[bf] * words_per_row * 4 + ks * 16);
+    soff[bf] = (uint32_t)(wrow[bf] * groups_per_row * 2);
+    zoff[bf] = (uint32_t)(wrow[bf] * groups_per_row);
+  }
+  const char* qbase = reinterpret_cast<const char*>(a.qweight);
+  const char* sbase = reinterpret_cast<const char*>(a.scales);
+  const char* zbase = reinterpret_cast<const char*>(a.zeros);
+  struct WSet {
+    uint32_t w[BF][4];
+    uint32_t sbits[BF], z[BF];
+  };
+  auto load_w = [&](int g, WSet& t) {
+    g = g < nit ? g : nit - 1;
+#pragma unroll
+    for (int bf = 0; bf < BF; ++bf) {
+      const uint4 v = *reinterpret_cast<const uint4*>(qbase + (size_t)g * 64 + woff[bf]);
+      t.w[bf][0] = v.x; t.w[bf][1] = v.y; t.w[bf][2] = v.z; t.w[bf][3] = v.w;
+      t.sbits[bf] = *reinterpret_cast<const uint16_t*>(sbase + (size_t)g * 2 + soff[bf]);
+      t.z[bf] = *reinterpret_cast<const uint8_t*>(zbase + (size_t)g + zoff[bf]);
+    }
+  };
+
+  // activation staging: unit u = token u / 16, chunk u % 16 of the slab; per-unit constants
+  const char* xbase = reinterpret_cast<const char*>(a.x + (size_t)m0 * a.ldx);
+  uint32_t xoff[UPT], lds_slot[UPT];
+#pragma unroll
+  for (int i = 0; i < UPT; ++i) {
+    const int u = tid + i * NT, tk = u / NCH, cb = u % NCH;
+    const int tok = m0 + tk < a.M ? tk : a.M - 1 - m0;    // rows past M are never stored: any valid row will do
+    xoff[i] = (uint32_t)(((size_t)tok * a.ldx + cb * 8) * 2);
+    lds_slot[i] = cb * BM + (tk ^ swz(cb));
+  }
+  uint4 xr[UPT];
+  auto fetch_x = [&](int it, bool masked) {
+    it = it < nit ? it : nit - 1;
+#pragma unroll
+    for (int i = 0; i < UPT; ++i) {
+      const int cb = (tid + i * NT) % NCH;
+      if (!masked) {
+        xr[i] = load_u4_unaligned(reinterpret_cast<const half_t*>(xbase + (size_t)it * (SC * 2) + xoff[i]));
+      } else {
+        // a chunk that is not entirely below kv reads the first chunk of its row instead (zeroed when stored)
+        const bool full = it * SC + cb * 8 + 8 <= kv;
+        const uint32_t o = full ? (uint32_t)it * (SC * 2) + xoff[i] : xoff[i] - (uint32_t)cb * 16;
+        xr[i] = load_u4_unaligned(reinterpret_cast<const half_t*>(xbase + o));
+      }
+    }
+  };
+  // one unit: permute the 8 halves to (0,4,1,5,2,6,3,7), zero it when its columns are not all kept
+  auto store_unit = [&](int i, int it, int buf, bool masked) {
+    const uint4 r = xr[i];
+    uint32_t o0 = __builtin_amdgcn_perm(r.z, r.x, 0x05040100u), o1 = __builtin_amdgcn_perm(r.z, r.x, 0x07060302u);
+    uint32_t o2 = __builtin_amdgcn_perm(r.w, r.y, 0x05040100u), o3 = __builtin_amdgcn_perm(r.w, r.y, 0x07060302u);
+    if (masked) {
+      const int cb = (tid + i * NT) % NCH;
+      const uint32_t m = it * SC + cb * 8 + 8 <= kv ? 0xffffffffu : 0u;
+      o0 &= m; o1 &= m; o2 &= m; o3 &= m;
+    }
+    xs[buf * (NCH * BM) + lds_slot[i]] = make_uint4(o0, o1, o2, o3);
+  };
+
+  float4_t acc[AF][BF];
+#pragma unroll
+  for (int af = 0; af < AF; ++af)
+#pragma unroll
+    for (int bf = 0; bf < BF; ++bf) acc[af][bf] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+  const Magic mg = make_magic();
+  WSet cur, nxt;
+  GroupQ gq[BF], gqn[BF];
+  uint4 av[2][AF], bfr[2][BF];
+  uint32_t w8[BF];
+  half2_t h[BF][4];
+
+  // micro-op o (0..51) of dequantising word t of every row fragment of W into out[]
+  auto dq_op = [&](int o, const WSet& W, const GroupQ (&G)[BF], int t, uint4 (&out)[BF]) {
+    const int bf = o / 13, k = o % 13;
+    const uint32_t w = W.w[bf][t];
+    if (k == 0) w8[bf] = w >> 8;
+    else if (k == 1) h[bf][0] = as_half2(and_or(w, 0x000F000Fu, mg.m1024));
+    else if (k == 2) h[bf][1] = as_half2(and_or(w, 0x00F000F0u, mg.m64));
+    else if (k == 3) h[bf][2] = as_half2(and_or(w8[bf], 0x000F000Fu, mg.m1024));
+    else if (k == 4) h[bf][3] = as_half2(and_or(w8[bf], 0x00F000F0u, mg.m64));
+    else if (k <= 8) h[bf][k - 5] = h[bf][k - 5] - ((k - 5) & 1 ? G[bf].zhi : G[bf].zlo);
+    else {
+      const uint32_t d = as_u32(h[bf][k - 9] * G[bf].s2);
+      if (k == 9) out[bf].x = d; else if (k == 10) out[bf].y = d; else if (k == 11) out[bf].z = d; else out[bf].w = d;
+    }
+  };
+  auto read_a = [&](int buf, int t, int af) {
+    return xs[(buf * NCH + ks * 4 + t) * BM + af * 16 + (n ^ (ks | (t << 2)))];
+  };
+
+  // prologue: slab 0 staged, its first step dequantised
+  load_w(0, cur);
+  fetch_x(0, true);
+#pragma unroll
+  for (int i = 0; i < UPT; ++i) store_unit(i, 0, 0, true);
+#pragma unroll
+  for (int bf = 0; bf < BF; ++bf) gq[bf] = make_groupq(cur.sbits[bf], cur.z[bf]);
+#pragma unroll
+  for (int o = 0; o < 13 * BF; ++o) dq_op(o, cur, gq, 0, bfr[0]);
+  __syncthreads();
+
+  // masked = the NEXT slab (staged during this one) has columns at or past kv
+  auto slab = [&](int it, auto masked_tag) {
+    constexpr bool masked = decltype(masked_tag)::value;
+    const int buf = it & 1;
+#pragma unroll
+    for (int af = 0; af < AF; ++af) av[0][af] = read_a(buf, 0, af);
+    fetch_x(it + 1, masked);
+    load_w(it + 1, nxt);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+#pragma unroll
+      for (int af = 0; af < AF; ++af) {
+#pragma unroll
+        for (int bf = 0; bf < BF; ++bf) {
+          const int s = af * BF + bf;   // slot 0..31 of the step
+          acc[af][bf] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av[t & 1][af]),
+                                                              __builtin_bit_cast(half8_t, bfr[t & 1][bf]),
+                                                              acc[af][bf], 0, 0, 0);
+          if (t < 3) {
+            for (int o = s * 52 / 32; o < (s + 1) * 52 / 32; ++o) dq_op(o, cur, gq, t + 1, bfr[(t + 1) & 1]);
+            if (bf == BF - 1) av[(t + 1) & 1][af] = read_a(buf, t + 1, af);
+          } else {
+            // last step: the next slab's group constants and first step, and the staging of its activations
+            if (s < BF) gqn[s] = make_groupq(nxt.sbits[s], nxt.z[s]);
+            else if (s >= 6) for (int o = (s - 6) * 2; o < (s - 6) * 2 + 2; ++o) dq_op(o, nxt, gqn, 0, bfr[0]);
+            if (s % 4 == 1) store_unit(s / 4, it + 1, buf ^ 1, masked);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    }
+    cur = nxt;
+#pragma unroll
+    for (int bf = 0; bf < BF; ++bf) gq[bf] = gqn[bf];
+    __syncthreads();
+  };
+  const int n_plain = kv / SC - 1;   // slabs it < n_plain stage a next slab that lies entirely below kv
+  int it = 0;
+  for (; it < n_plain; ++it) slab(it, std::false_type{});
+  for (; it < nit; ++it) slab(it, std::true_type{});
+
+  // ---- epilogue.  Lane l holds, for fragment (af, bf): row (l % 16), tokens 4 * (l / 16) + v.
+  if (kv < km.k_keep) {
+    // the kept columns kv .. k_keep-1 (fewer than 8: one word of one group per row), in fp32
+#pragma unroll
+    for (int bf = 0; bf < BF; ++bf) {
+      const uint32_t word = a.qweight[wrow[bf] * words_per_row + (kv >> 3)];
+      const size_t gi = wrow[bf] * groups_per_row + (kv >> 7);
+      const float sf = (float)__builtin_bit_cast(half_t, a.scales[gi]);
+      const int z = a.zeros[gi];
+      for (int j = 0; kv + j < km.k_keep; ++j) {
+        const int q = (int)((word >> (4 * j)) & 15u);
+        const float w = (float)(half_t)((float)(q - z) * sf);   // the canonical fp16 weight
+#pragma unroll
+        for (int af = 0; af < AF; ++af)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const int tok = m0 + af * 16 + 4 * ks + v;
+            const float xv = (float)a.x[(size_t)(tok < a.M ? tok : a.M - 1) * a.ldx + kv + j];
+            acc[af][bf][v] = __builtin_fmaf(xv, w, acc[af][bf][v]);
+          }
+      }
+    }
+  }
+#pragma unroll
+  for (int af = 0; af < AF; ++af)
+#pragma unroll
+    for (int bf = 0; bf < BF; ++bf) {
+      const int rc = n0 + (wn * BF + bf) * 16 + n;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int tok = m0 + af * 16 + 4 * ks + v;
+        if (tok < a.M && rc < km.n_keep) a.y[(size_t)tok * a.ldy + rc] = (half_t)acc[af][bf][v];
+      }
+    }
+}
+
+static hipError_t launch_prefill(const LinearArgs& a, hipStream_t stream) {
+  constexpr int BM = 128, BN = 256;
+  const size_t smem = (size_t)2 * BM * 128 * sizeof(half_t);
+  auto kern = w4_mfma_prefill_kernel<true>;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (e != hipSuccess) return e;
+  dim3 grid((a.km.n_keep + BN - 1) / BN, (a.M + BM - 1) / BM);
+  hipLaunchKernelGGL(kern, grid, dim3(256), smem, stream, a);
+  return hipGetLastError();
+}
+
 template <int AF, int BF, int WN, int KS, int S2, int PW, bool XVEC>
 static hipError_t launch_cfg(const LinearArgs& a, hipStream_t stream) {
   constexpr int BM = 16 * AF, BN = WN * BF * 16, SC = KS * S2 * 128;
@@ -289,6 +537,10 @@ static hipError_t launch_m(const LinearArgs& a, hipStream_t stream) {
   if (a.M <= 16) return row_tiles >= 600 ? launch_cfg<1, 1, 2, 4, 2, 2, XVEC>(a, stream) : launch_cfg<1, 1, 1, 8, 1, 2, XVEC>(a, stream);
   if (a.M <= 32) return row_tiles >= 600 ? launch_cfg<2, 1, 2, 4, 1, 4, XVEC>(a, stream) : launch_cfg<2, 1, 1, 8, 1, 2, XVEC>(a, stream);
   if (a.M <= 64) return launch_cfg<4, 2, 4, 1, 1, 2, XVEC>(a, stream);
+  // the prefill kernel addresses weights and one block's activations with 32-bit offsets
+  const bool small_offsets = (unsigned long long)a.N_total * (unsigned long long)a.K_total / 2 < (1ull << 32) &&
+                             128ull * (unsigned long long)a.ldx * 2 < (1ull << 32);
+  if (XVEC && small_offsets && a.km.k_keep >= 128) return launch_prefill(a, stream);
   return launch_cfg<8, 4, 4, 1, 1, 1, XVEC>(a, stream);
 }
 
