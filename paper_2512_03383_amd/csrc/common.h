@@ -73,6 +73,11 @@ __device__ __forceinline__ uint4 load_u4_unaligned(const half_t* p) {
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+__device__ __forceinline__ uint32_t load_u32_unaligned(const void* p) {
+  typedef uint32_t u32_u1 __attribute__((aligned(1)));
+  return *reinterpret_cast<const u32_u1*>(p);
+}
+
 // ---- int4 -> fp16 ---------------------------------------------------------
 // A 32-bit word holds codes q0..q7.  OR-ing a masked word with an fp16 exponent
 // pattern yields exact fp16 numbers without any conversion instruction:

@@ -287,19 +287,22 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
 
 
 // ---- prefill kernel -------------------------------------------------------------------------
-// 128 tokens x 256 rows per block, four waves side by side over rows, each 8 x 4 fragments, one
-// wave per SIMD.  With a single wave per SIMD nothing hides a stall, so the body of a slab (one
-// quantisation group, four MFMA steps) is written in the order it should issue and pinned with
-// scheduling barriers: every MFMA is followed by the one or two VALU instructions of the NEXT
-// step's dequantisation (or, in the last step, of the next slab's first step and of the staging
-// of the next activation slab), and every fourth by one LDS read of the next step's activation
-// fragment.  The matrix pipe takes 16 clocks per MFMA and the wave issues one instruction per
-// 4 clocks, so three instructions fit behind each MFMA for free.
+// 128 tokens x 256 rows per block; eight waves side by side over rows, each 8 x 2 fragments, two
+// waves per SIMD (at most 256 registers), so that one wave's LDS / memory / scalar instructions and
+// waits overlap the other's MFMAs.  A wave issues at most one instruction per 4 clocks and the
+// matrix pipe takes 16 clocks per MFMA, so the body of a slab (one quantisation group, four MFMA
+// steps) is written in the order it should issue and pinned with scheduling barriers: every MFMA
+// is followed by the one or two VALU instructions of the NEXT step's dequantisation (in the last
+// steps also the staging of the next activation slab and the next slab's first step), and every
+// second MFMA by the LDS read that refills the activation fragment it just consumed.
 // Column prefix only (XVEC staging); weights and activations are addressed as a uniform base plus
 // a 32-bit per-lane offset, which the host checks for.
 template <bool DUMMY>
-__global__ __launch_bounds__(256) void w4_mfma_prefill_kernel(LinearArgs a) {
-  constexpr int AF = 8, BF = 4, NT = 256, BM = 128, BN = 256, SC = 128, NCH = 16, UPT = 8;
+__global__ __launch_bounds__(512) void w4_mfma_prefill_kernel(LinearArgs a) {
+  constexpr int AF = 8, BF = 2, WN = 8, NT = WN * 64, BM = 16 * AF, BN = WN * BF * 16, SC = 128, NCH = 16;
+  constexpr int UPT = BM * NCH / NT;          // 16-byte staging units per thread and slab
+  constexpr int SLOTS = AF * BF;              // MFMAs per step
+  constexpr int DQ = 13 * BF;                 // dequantisation micro-ops per step
   extern __shared__ __align__(16) unsigned char smem[];
   uint4* xs = reinterpret_cast<uint4*>(smem);   // [2][NCH][BM], swizzled as in w4_mfma_kernel
 
@@ -313,23 +316,23 @@ __global__ __launch_bounds__(256) void w4_mfma_prefill_kernel(LinearArgs a) {
   auto swz = [](int chunk) { return ((chunk >> 2) & 3) | ((chunk & 3) << 2); };
 
   // per-lane byte offsets of this lane's weight fragments (rows clamped: every address is valid)
-  size_t wrow[BF];
-  uint32_t woff[BF], soff[BF], zoff[BF];
-#pragma unroll
-  for (int bf = 0; bf < BF; ++bf) {
+  auto frag_row = [&](int bf) {
     int rc = n0 + (wn * BF + bf) * 16 + n;
     rc = rc < km.n_keep ? rc : km.n_keep - 1;
-    wrow[bf] = (size_t)stored_row(km, rc);
-    woff[bf] = (uint32_t)(wrow[bf] * words_per_row * 4 + ks * 16);
-    soff[bf] = (uint32_t)(wrow[bf] * groups_per_row * 2);
-    zoff[bf] = (uint32_t)(wrow[bf] * groups_per_row);
+    return (size_t)stored_row(km, rc);
+  };
+  uint32_t woff[BF], zoff[BF];
+#pragma unroll
+  for (int bf = 0; bf < BF; ++bf) {
+    const size_t r = frag_row(bf);
+    woff[bf] = (uint32_t)(r * words_per_row * 4 + ks * 16);
+    zoff[bf] = (uint32_t)(r * groups_per_row);
   }
   const char* qbase = reinterpret_cast<const char*>(a.qweight);
   const char* sbase = reinterpret_cast<const char*>(a.scales);
   const char* zbase = reinterpret_cast<const char*>(a.zeros);
   struct WSet {
     uint32_t w[BF][4];
-    uint32_t sbits[BF], z[BF];
   };
   auto load_w = [&](int g, WSet& t) {
     g = g < nit ? g : nit - 1;
@@ -337,21 +340,56 @@ __global__ __launch_bounds__(256) void w4_mfma_prefill_kernel(LinearArgs a) {
     for (int bf = 0; bf < BF; ++bf) {
       const uint4 v = *reinterpret_cast<const uint4*>(qbase + (size_t)g * 64 + woff[bf]);
       t.w[bf][0] = v.x; t.w[bf][1] = v.y; t.w[bf][2] = v.z; t.w[bf][3] = v.w;
-      t.sbits[bf] = *reinterpret_cast<const uint16_t*>(sbase + (size_t)g * 2 + soff[bf]);
-      t.z[bf] = *reinterpret_cast<const uint8_t*>(zbase + (size_t)g + zoff[bf]);
     }
+  };
+  // Scales and zero points.  A load instruction whose 64 lanes touch 16 different rows costs the
+  // memory pipeline about 4 clocks per row whatever its width, so a lane fetches those of EIGHT
+  // consecutive groups of its row at once (16 + 8 bytes) and shifts the set down by one group per
+  // slab: element 0 is always the next group to be used.  A set that would run past the row's last
+  // group starts early and is shifted into place when it is loaded.
+  uint4 sc[BF];
+  uint2 zz[BF];
+  auto shift_set = [&](int bf) {
+    sc[bf].x = __builtin_amdgcn_alignbit(sc[bf].y, sc[bf].x, 16);
+    sc[bf].y = __builtin_amdgcn_alignbit(sc[bf].z, sc[bf].y, 16);
+    sc[bf].z = __builtin_amdgcn_alignbit(sc[bf].w, sc[bf].z, 16);
+    sc[bf].w >>= 16;
+    zz[bf].x = __builtin_amdgcn_alignbit(zz[bf].y, zz[bf].x, 8);
+    zz[bf].y >>= 8;
+  };
+  auto load_set = [&](int g0) {   // g0: first group the set must hold (a multiple of 8)
+    const int start = g0 + 8 <= groups_per_row ? g0 : groups_per_row - 8;
+#pragma unroll
+    for (int bf = 0; bf < BF; ++bf) {
+      sc[bf] = load_u4_unaligned(reinterpret_cast<const half_t*>(sbase + ((size_t)start + zoff[bf]) * 2));
+      const uint32_t* zp = reinterpret_cast<const uint32_t*>(zbase + (size_t)start + zoff[bf]);
+      zz[bf] = make_uint2(load_u32_unaligned(zp), load_u32_unaligned(zp + 1));
+    }
+    for (int i = start; i < g0; ++i) {   // only the last set of a row whose group count is not a multiple of 8
+#pragma unroll
+      for (int bf = 0; bf < BF; ++bf) shift_set(bf);
+    }
+  };
+  auto groupq_from_set = [&](int bf) {
+    GroupQ g;
+    const uint32_t zp = __builtin_amdgcn_perm(0u, zz[bf].x, 0x0c000c00u);   // (z, z) as 16-bit integers
+    g.zlo = as_half2(zp | 0x64006400u);
+    g.zhi = as_half2((zp << 4) | 0x54005400u);
+    g.s2 = as_half2(__builtin_amdgcn_perm(0u, sc[bf].x, 0x01000100u));      // (s, s)
+    return g;
   };
 
   // activation staging: unit u = token u / 16, chunk u % 16 of the slab; per-unit constants
   const char* xbase = reinterpret_cast<const char*>(a.x + (size_t)m0 * a.ldx);
-  uint32_t xoff[UPT], lds_slot[UPT];
+  uint32_t xoff[UPT];
 #pragma unroll
   for (int i = 0; i < UPT; ++i) {
     const int u = tid + i * NT, tk = u / NCH, cb = u % NCH;
     const int tok = m0 + tk < a.M ? tk : a.M - 1 - m0;    // rows past M are never stored: any valid row will do
     xoff[i] = (uint32_t)(((size_t)tok * a.ldx + cb * 8) * 2);
-    lds_slot[i] = cb * BM + (tk ^ swz(cb));
   }
+  // unit i of a thread is token tid / 16 + i * NT / 16 of the same chunk: the swizzle only touches the low 4 bits
+  const int lds_slot0 = (tid % NCH) * BM + ((tid / NCH) ^ swz(tid % NCH));
   uint4 xr[UPT];
   auto fetch_x = [&](int it, bool masked) {
     it = it < nit ? it : nit - 1;
@@ -378,7 +416,7 @@ __global__ __launch_bounds__(256) void w4_mfma_prefill_kernel(LinearArgs a) {
       const uint32_t m = it * SC + cb * 8 + 8 <= kv ? 0xffffffffu : 0u;
       o0 &= m; o1 &= m; o2 &= m; o3 &= m;
     }
-    xs[buf * (NCH * BM) + lds_slot[i]] = make_uint4(o0, o1, o2, o3);
+    xs[buf * (NCH * BM) + lds_slot0 + i * (NT / NCH)] = make_uint4(o0, o1, o2, o3);
   };
 
   float4_t acc[AF][BF];
@@ -388,13 +426,13 @@ __global__ __launch_bounds__(256) void w4_mfma_prefill_kernel(LinearArgs a) {
     for (int bf = 0; bf < BF; ++bf) acc[af][bf] = float4_t{0.f, 0.f, 0.f, 0.f};
 
   const Magic mg = make_magic();
-  WSet cur, nxt;
-  GroupQ gq[BF], gqn[BF];
-  uint4 av[2][AF], bfr[2][BF];
+  WSet wa, wb;              // the weights of the current and of the next slab, roles alternate
+  GroupQ ga[BF], gb[BF];
+  uint4 av[AF], bfr[2][BF];
   uint32_t w8[BF];
   half2_t h[BF][4];
 
-  // micro-op o (0..51) of dequantising word t of every row fragment of W into out[]
+  // micro-op o (0 .. DQ-1) of dequantising word t of every row fragment of W into out[]
   auto dq_op = [&](int o, const WSet& W, const GroupQ (&G)[BF], int t, uint4 (&out)[BF]) {
     const int bf = o / 13, k = o % 13;
     const uint32_t w = W.w[bf][t];
@@ -414,24 +452,30 @@ __global__ __launch_bounds__(256) void w4_mfma_prefill_kernel(LinearArgs a) {
   };
 
   // prologue: slab 0 staged, its first step dequantised
-  load_w(0, cur);
+  load_w(0, wa);
   fetch_x(0, true);
 #pragma unroll
   for (int i = 0; i < UPT; ++i) store_unit(i, 0, 0, true);
+  load_set(0);
 #pragma unroll
-  for (int bf = 0; bf < BF; ++bf) gq[bf] = make_groupq(cur.sbits[bf], cur.z[bf]);
+  for (int bf = 0; bf < BF; ++bf) {
+    ga[bf] = groupq_from_set(bf);
+    shift_set(bf);
+  }
 #pragma unroll
-  for (int o = 0; o < 13 * BF; ++o) dq_op(o, cur, gq, 0, bfr[0]);
+  for (int o = 0; o < DQ; ++o) dq_op(o, wa, ga, 0, bfr[0]);
   __syncthreads();
 
-  // masked = the NEXT slab (staged during this one) has columns at or past kv
-  auto slab = [&](int it, auto masked_tag) {
+  // One slab.  cur / gq: this slab's weights and group constants; nxt / gqn: the next slab's, loaded
+  // and derived here.  masked = the next slab (staged during this one) has columns at or past kv.
+  auto slab = [&](int it, WSet& cur, GroupQ (&gq)[BF], WSet& nxt, GroupQ (&gqn)[BF], auto masked_tag) {
     constexpr bool masked = decltype(masked_tag)::value;
     const int buf = it & 1;
 #pragma unroll
-    for (int af = 0; af < AF; ++af) av[0][af] = read_a(buf, 0, af);
+    for (int af = 0; af < AF; ++af) av[af] = read_a(buf, 0, af);
     fetch_x(it + 1, masked);
     load_w(it + 1, nxt);
+    if (((it + 1) & 7) == 0 && it + 1 < nit) load_set(it + 1);   // the previous set has no element left
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
@@ -439,40 +483,50 @@ __global__ __launch_bounds__(256) void w4_mfma_prefill_kernel(LinearArgs a) {
       for (int af = 0; af < AF; ++af) {
 #pragma unroll
         for (int bf = 0; bf < BF; ++bf) {
-          const int s = af * BF + bf;   // slot 0..31 of the step
-          acc[af][bf] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av[t & 1][af]),
+          const int s = af * BF + bf;   // slot 0 .. SLOTS-1 of the step
+          acc[af][bf] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av[af]),
                                                               __builtin_bit_cast(half8_t, bfr[t & 1][bf]),
                                                               acc[af][bf], 0, 0, 0);
           if (t < 3) {
-            for (int o = s * 52 / 32; o < (s + 1) * 52 / 32; ++o) dq_op(o, cur, gq, t + 1, bfr[(t + 1) & 1]);
-            if (bf == BF - 1) av[(t + 1) & 1][af] = read_a(buf, t + 1, af);
+            for (int o = s * DQ / SLOTS; o < (s + 1) * DQ / SLOTS; ++o) dq_op(o, cur, gq, t + 1, bfr[(t + 1) & 1]);
+            if (bf == BF - 1) av[af] = read_a(buf, t + 1, af);   // refill the fragment just consumed
+            // the first half of the next slab's staging rides on the third step
+            if (t == 2 && s % (2 * SLOTS / UPT) == 1) store_unit(s / (2 * SLOTS / UPT), it + 1, buf ^ 1, masked);
           } else {
-            // last step: the next slab's group constants and first step, and the staging of its activations
-            if (s < BF) gqn[s] = make_groupq(nxt.sbits[s], nxt.z[s]);
-            else if (s >= 6) for (int o = (s - 6) * 2; o < (s - 6) * 2 + 2; ++o) dq_op(o, nxt, gqn, 0, bfr[0]);
-            if (s % 4 == 1) store_unit(s / 4, it + 1, buf ^ 1, masked);
+            // last step: the next slab's group constants and first step, the rest of the staging
+            if (s < BF) {
+              gqn[s] = groupq_from_set(s);
+              shift_set(s);
+            }
+            else for (int o = (s - BF) * DQ / (SLOTS - BF); o < (s - BF + 1) * DQ / (SLOTS - BF); ++o) dq_op(o, nxt, gqn, 0, bfr[0]);
+            if (s % (2 * SLOTS / UPT) == 1) store_unit(UPT / 2 + s / (2 * SLOTS / UPT), it + 1, buf ^ 1, masked);
           }
           __builtin_amdgcn_sched_barrier(0);
         }
       }
     }
-    cur = nxt;
-#pragma unroll
-    for (int bf = 0; bf < BF; ++bf) gq[bf] = gqn[bf];
     __syncthreads();
   };
-  const int n_plain = kv / SC - 1;   // slabs it < n_plain stage a next slab that lies entirely below kv
+  // slabs it < n_plain stage a next slab that lies entirely below kv; roles of (wa, ga) / (wb, gb) alternate
+  const int n_plain = kv / SC - 1;
   int it = 0;
-  for (; it < n_plain; ++it) slab(it, std::false_type{});
-  for (; it < nit; ++it) slab(it, std::true_type{});
+  for (; it + 1 < n_plain; it += 2) {
+    slab(it, wa, ga, wb, gb, std::false_type{});
+    slab(it + 1, wb, gb, wa, ga, std::false_type{});
+  }
+  for (; it < nit; ++it) {
+    if (it & 1) slab(it, wb, gb, wa, ga, std::true_type{});
+    else slab(it, wa, ga, wb, gb, std::true_type{});
+  }
 
   // ---- epilogue.  Lane l holds, for fragment (af, bf): row (l % 16), tokens 4 * (l / 16) + v.
   if (kv < km.k_keep) {
     // the kept columns kv .. k_keep-1 (fewer than 8: one word of one group per row), in fp32
 #pragma unroll
     for (int bf = 0; bf < BF; ++bf) {
-      const uint32_t word = a.qweight[wrow[bf] * words_per_row + (kv >> 3)];
-      const size_t gi = wrow[bf] * groups_per_row + (kv >> 7);
+      const size_t wr = frag_row(bf);
+      const uint32_t word = a.qweight[wr * words_per_row + (kv >> 3)];
+      const size_t gi = wr * groups_per_row + (kv >> 7);
       const float sf = (float)__builtin_bit_cast(half_t, a.scales[gi]);
       const int z = a.zeros[gi];
       for (int j = 0; kv + j < km.k_keep; ++j) {
@@ -509,7 +563,7 @@ static hipError_t launch_prefill(const LinearArgs& a, hipStream_t stream) {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (e != hipSuccess) return e;
   dim3 grid((a.km.n_keep + BN - 1) / BN, (a.M + BM - 1) / BM);
-  hipLaunchKernelGGL(kern, grid, dim3(256), smem, stream, a);
+  hipLaunchKernelGGL(kern, grid, dim3(512), smem, stream, a);
   return hipGetLastError();
 }
 
@@ -540,7 +594,8 @@ static hipError_t launch_m(const LinearArgs& a, hipStream_t stream) {
   // the prefill kernel addresses weights and one block's activations with 32-bit offsets
   const bool small_offsets = (unsigned long long)a.N_total * (unsigned long long)a.K_total / 2 < (1ull << 32) &&
                              128ull * (unsigned long long)a.ldx * 2 < (1ull << 32);
-  if (XVEC && small_offsets && a.km.k_keep >= 128) return launch_prefill(a, stream);
+  // ... and fetches scales eight groups at a time
+  if (XVEC && small_offsets && a.km.k_keep >= 128 && a.K_total >= 8 * kGroup) return launch_prefill(a, stream);
   return launch_cfg<8, 4, 4, 1, 1, 1, XVEC>(a, stream);
 }
 
