@@ -23,7 +23,6 @@ namespace uniql {
 
 struct WTile {
   uint4 w;
-  uint32_t sbits, z;
 };
 
 // AF token fragments, BF row fragments per wave, WN waves along rows, KS waves along K,
@@ -48,6 +47,14 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
   // of the chunk, so that the 16 lanes that WRITE 16 consecutive chunks of one token also hit 16
   // different bank groups; measured, both patterns are conflict-free.
   uint4* xs = reinterpret_cast<uint4*>(smem);
+  // Scales and zero points of the slab's groups ride along: [2][BN][KS * S2] words (scale bits |
+  // zero << 16).  A load whose lanes touch 16 different rows costs the memory pipeline about 4
+  // clocks per row whatever its width, so instead of every wave fetching the two values of its 16
+  // rows per group, one thread per (row, group) of the block fetches them with the slab, adjacent
+  // lanes reading adjacent groups of a row.
+  constexpr int NG = KS * S2;                // groups per slab
+  static_assert(BN * NG <= NT, "one thread per (row, group) of a slab");
+  uint32_t* szs = reinterpret_cast<uint32_t*>(smem + (size_t)2 * UNITS * sizeof(uint4));
 
   const KeepMap& km = a.km;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -74,12 +81,23 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
       int g = (it * S2 + s2) * KS + wk;
       g = g < ngroups ? g : ngroups - 1;   // past the end: a valid, redundant load (x is zero there)
 #pragma unroll
-      for (int bf = 0; bf < BF; ++bf) {
+      for (int bf = 0; bf < BF; ++bf)
         t[s2][bf].w = *reinterpret_cast<const uint4*>(a.qweight + wrow[bf] * words_per_row + g * 16 + ks * 4);
-        t[s2][bf].sbits = a.scales[wrow[bf] * groups_per_row + g];
-        t[s2][bf].z = a.zeros[wrow[bf] * groups_per_row + g];
-      }
     }
+  };
+  // this thread's (row, group) of the scale / zero staging, if it has one
+  const bool sz_owner = tid < BN * NG;
+  size_t sz_row;
+  {
+    int rc = n0 + tid / NG;
+    rc = rc < km.n_keep ? rc : km.n_keep - 1;
+    sz_row = (size_t)stored_row(km, rc) * groups_per_row;
+  }
+  auto fetch_sz = [&](int it, uint32_t& sbits, uint32_t& z) {
+    int g = it * NG + tid % NG;
+    g = g < ngroups ? g : ngroups - 1;
+    sbits = a.scales[sz_row + g];
+    z = a.zeros[sz_row + g];
   };
 
   // x slab staging: unit u of a slab = token (u / NCH), 8-column chunk (u % NCH).
@@ -152,10 +170,13 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
   const Magic mg = make_magic();
   WTile ring[PW][S2][BF];
   XRegs xr;
+  uint32_t sz_s = 0, sz_z = 0;
 #pragma unroll
   for (int p = 0; p < PW; ++p) load_w(p, ring[p]);
   fetch_x(0, xr);
+  if (sz_owner) fetch_sz(0, sz_s, sz_z);
   store_x(0, xr);
+  if (sz_owner) szs[tid] = sz_s | (sz_z << 16);
   __syncthreads();
 
   for (int it0 = 0; it0 < nit_pw; it0 += PW) {
@@ -163,8 +184,16 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
     for (int p = 0; p < PW; ++p) {
       const int it = it0 + p;
       const int buf = it & 1;
+      // this slab's scales and zero points, read before anything else so that the LDS latency is
+      // covered by issuing the loads below
+      uint32_t szv[S2][BF];
+#pragma unroll
+      for (int s2 = 0; s2 < S2; ++s2)
+#pragma unroll
+        for (int bf = 0; bf < BF; ++bf) szv[s2][bf] = szs[(buf * BN + (wn * BF + bf) * 16 + n) * NG + s2 * KS + wk];
       // fetch the next slab into registers while this one is consumed
       if (it + 1 < nit_pw) fetch_x(it + 1, xr);
+      if (sz_owner) fetch_sz(it + 1, sz_s, sz_z);
 
       // Word t of a lane's 128-bit load feeds MFMA t of the group.  Dequantising word t of every
       // row fragment right before its MFMAs keeps only BF operand fragments live and lets the
@@ -176,7 +205,7 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
 #pragma unroll
         for (int bf = 0; bf < BF; ++bf) {
           const WTile& wt = ring[p][s2][bf];
-          gq[bf] = make_groupq(wt.sbits, wt.z);
+          gq[bf] = make_groupq(szv[s2][bf] & 0xffffu, szv[s2][bf] >> 16);
           wv[bf][0] = wt.w.x; wv[bf][1] = wt.w.y; wv[bf][2] = wt.w.z; wv[bf][3] = wt.w.w;
         }
         const uint4* xb = xs + (buf * NCH + (s2 * KS + wk) * 16 + ks * 4) * BM;
@@ -220,6 +249,7 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
       }
       load_w(it + PW, ring[p]);   // refill the ring slot (clamped past the end)
       if (it + 1 < nit_pw) store_x(buf ^ 1, xr);
+      if (sz_owner) szs[(buf ^ 1) * BN * NG + tid] = sz_s | (sz_z << 16);
       __syncthreads();
     }
   }
@@ -570,7 +600,7 @@ static hipError_t launch_prefill(const LinearArgs& a, hipStream_t stream) {
 template <int AF, int BF, int WN, int KS, int S2, int PW, bool XVEC>
 static hipError_t launch_cfg(const LinearArgs& a, hipStream_t stream) {
   constexpr int BM = 16 * AF, BN = WN * BF * 16, SC = KS * S2 * 128;
-  size_t smem = (size_t)2 * BM * SC * sizeof(half_t);
+  size_t smem = (size_t)2 * BM * SC * sizeof(half_t) + (size_t)2 * BN * KS * S2 * sizeof(uint32_t);
   const size_t red = KS > 1 ? (size_t)KS * WN * AF * BF * 4 * 64 * sizeof(float) : 0;
   if (red > smem) smem = red;
   auto kern = w4_mfma_kernel<AF, BF, WN, KS, S2, PW, XVEC>;
