@@ -621,12 +621,20 @@ static hipError_t launch_m(const LinearArgs& a, hipStream_t stream) {
   if (a.M <= 16) return row_tiles >= 600 ? launch_cfg<1, 1, 2, 4, 2, 2, XVEC>(a, stream) : launch_cfg<1, 1, 1, 8, 1, 2, XVEC>(a, stream);
   if (a.M <= 32) return row_tiles >= 600 ? launch_cfg<2, 1, 2, 4, 1, 4, XVEC>(a, stream) : launch_cfg<2, 1, 1, 8, 1, 2, XVEC>(a, stream);
   if (a.M <= 64) return launch_cfg<4, 2, 4, 1, 1, 2, XVEC>(a, stream);
-  // the prefill kernel addresses weights and one block's activations with 32-bit offsets
-  const bool small_offsets = (unsigned long long)a.N_total * (unsigned long long)a.K_total / 2 < (1ull << 32) &&
-                             128ull * (unsigned long long)a.ldx * 2 < (1ull << 32);
-  // ... and fetches scales eight groups at a time
-  if (XVEC && small_offsets && a.km.k_keep >= 128 && a.K_total >= 8 * kGroup) return launch_prefill(a, stream);
-  return launch_cfg<8, 4, 4, 1, 1, 1, XVEC>(a, stream);
+  // Prefill: the largest tile that still gives the chip about a block per CU.
+  auto blocks = [&](int bm, int bn) { return (long long)((a.km.n_keep + bn - 1) / bn) * ((a.M + bm - 1) / bm); };
+  constexpr long long kEnough = 192;
+  if (blocks(128, 256) >= kEnough) {
+    // the prefill kernel addresses weights and one block's activations with 32-bit offsets
+    // and fetches scales eight groups at a time
+    const bool small_offsets = (unsigned long long)a.N_total * (unsigned long long)a.K_total / 2 < (1ull << 32) &&
+                               128ull * (unsigned long long)a.ldx * 2 < (1ull << 32);
+    if (XVEC && small_offsets && a.km.k_keep >= 128 && a.K_total >= 8 * kGroup) return launch_prefill(a, stream);
+    return launch_cfg<8, 4, 4, 1, 1, 1, XVEC>(a, stream);
+  }
+  if (blocks(64, 256) >= kEnough) return launch_cfg<4, 2, 8, 1, 1, 2, XVEC>(a, stream);
+  if (blocks(64, 128) >= kEnough) return launch_cfg<4, 2, 4, 2, 2, 1, XVEC>(a, stream);   // K split over two waves
+  return launch_cfg<4, 1, 4, 2, 1, 2, XVEC>(a, stream);
 }
 
 hipError_t launch_w4_gemm(const LinearArgs& a, hipStream_t stream) {

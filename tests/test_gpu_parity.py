@@ -272,6 +272,34 @@ def test_prefill_gemm_sampled(env, uref, M):
         assert err <= TOL, (spec.name, err)
 
 
+@pytest.mark.parametrize("N,K,keep,M", [
+    (6144, 2176, Keep(n_keep=6100, k_keep=2049), 1000),    # ragged rows, tokens and K tail; one column into a group
+    (6144, 1152, Keep(k_keep=1100), 1024),                 # 9 groups per row: the last set of scales starts early
+    (6400, 1024, Keep(n_keep=6200, row_seg_stride=128, row_seg_keep=124, row_seg_limit=6400), 1024),   # row segments
+    (3072, 1280, Keep(k_keep=1279), 500),                  # 64 x 128 tiles with K split over two waves
+    (6144, 1024, Keep(k_keep=1000), 500),                  # 64 x 256 tiles
+    (512, 2048, Keep(), 130),
+])
+def test_prefill_tiles_ragged(env, uref, N, K, keep, M):
+    """The prefill tile configurations (128 x 256 hand-scheduled kernel when the grid fills the chip, smaller
+    tiles otherwise) on shapes with ragged row / token / column tails: sampled (token, row) pairs."""
+    uq, torch = env
+    rng = wl.rng_for(4, N + K + M)
+    w = wl.gen_linear(rng, N, K)
+    qw = uq.QuantLinear.from_numpy(w)
+    nk, kk = uq.kept_dims(qw, keep)
+    x = wl.gen_activations(rng, M, kk)
+    y = run_linear(uq, torch, w, qw, keep, x)
+    toks = np.unique(np.concatenate([[0, 63, 64, 127, 128, M - 1], rng.integers(0, M, 6)]))
+    rows = _sample_rows(nk, rng, 96)
+    rows = np.unique(np.concatenate([rows, [255, 256, min(nk - 1, 4095)]])).astype(np.int32)
+    ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], np.ascontiguousarray(x[toks]), keep, rows=rows)
+    rms = np.sqrt(np.mean(ref ** 2, axis=-1, keepdims=True))
+    got = y[np.ix_(toks, rows)].astype(np.float64)
+    err = np.max(np.abs(got - ref) / np.maximum(np.abs(ref), 1e-2 * rms))
+    assert err <= TOL, err
+
+
 # --------------------------------------------------------------------- RoPE
 def run_rope(uq, torch, r, spec):
     q = to_dev(torch, r["q"])
