@@ -8,6 +8,7 @@
 // the angle is formed and reduced in fp64 (in revolutions), and one fp32 sin/cos is
 // reused by every Q head of the group and by the K head.
 #include "common.h"
+#include <type_traits>
 
 namespace uniql {
 
@@ -24,16 +25,75 @@ __device__ __forceinline__ void angle_sincos(double pos, double inv_freq, float*
   *cs = __builtin_amdgcn_cosf(r);
 }
 
-// V2: two adjacent pairs per item (needs an even number of kept pairs and 4-byte aligned tensors)
-template <bool V2>
+// V2: two adjacent pairs per item (needs an even number of kept pairs and 4-byte aligned tensors).
+// A thread owns up to kBatch items of its block (4 for prefill, 1 when the whole block has at most
+// one item per thread: decode) and handles them TOGETHER: all loads of a chunk of
+// heads for all of its items are issued before anything is stored (the rotation is in place, so
+// the compiler would not move a load above an earlier store), which keeps tens of loads per wave
+// in flight instead of a chain of load - rotate - store round trips.  The first chunk's loads are
+// issued before the block builds its frequency table, whose latency they hide.
+constexpr int kHeadChunk = 4;
+
+template <bool V2, int kBatch>
 __global__ __launch_bounds__(kRopeThreads) void pruned_rope_kernel(RopeArgs a, int tokens_per_block) {
   extern __shared__ __align__(8) unsigned char rope_smem[];
   double* invf = reinterpret_cast<double*>(rope_smem);   // [D_keep / 2]
+  typedef typename std::conditional<V2, half2_t, half_t>::type elem_t;   // one or two adjacent channels
+  constexpr int W = V2 ? 2 : 1;
 
   const int hk = a.D_keep >> 1;
   const int g = blockIdx.y;
   const int t0 = blockIdx.x * tokens_per_block;
   const int qper = a.Hq / a.H_tab, kper = a.Hkv / a.H_tab;
+  const int nheads = qper + kper;                 // heads that share this table row: Q heads, then K heads
+  const int per_tok = hk / W;
+  const int tb = min(tokens_per_block, a.T - t0);
+  const int n_items = tb * per_tok;               // one batch (kBatch * kRopeThreads) unless a single token has more
+
+  // this thread's items of a batch: token and first channel of each, and whether it exists
+  int tok[kBatch], ch[kBatch];
+  bool live[kBatch];
+  auto take_items = [&](int base) {
+#pragma unroll
+    for (int b = 0; b < kBatch; ++b) {
+      const int item = base + threadIdx.x + b * kRopeThreads;
+      live[b] = item < n_items;
+      const int tl = live[b] ? item / per_tok : 0;
+      tok[b] = t0 + tl;
+      ch[b] = live[b] ? (item - tl * per_tok) * W : 0;
+    }
+  };
+  take_items(0);
+  // head hh of the group (0 .. nheads-1): address of channel ch[b] of token tok[b]
+  auto elem_ptr = [&](int b, int hh) -> half_t* {
+    return hh < qper ? a.q + ((size_t)tok[b] * a.Hq + g * qper + hh) * a.D_keep + ch[b]
+                     : a.k + ((size_t)tok[b] * a.Hkv + g * kper + (hh - qper)) * a.D_keep + ch[b];
+  };
+  elem_t x1[kBatch][kHeadChunk] = {}, x2[kBatch][kHeadChunk] = {};
+  auto load_chunk = [&](int h0) {
+#pragma unroll
+    for (int u = 0; u < kHeadChunk; ++u) {
+      if (h0 + u < nheads) {   // uniform
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b) {
+          if (live[b]) {
+            const half_t* v = elem_ptr(b, h0 + u);
+            x1[b][u] = *reinterpret_cast<const elem_t*>(v);
+            x2[b][u] = *reinterpret_cast<const elem_t*>(v + hk);
+          }
+        }
+      }
+    }
+  };
+  double pos[kBatch];
+  auto load_pos = [&]() {
+#pragma unroll
+    for (int b = 0; b < kBatch; ++b) pos[b] = (double)a.positions[tok[b]];
+  };
+  load_pos();
+  load_chunk(0);
+
+  // theta^(-2j/D) of the block's kept pairs, once, in fp64
   const double l2t = log2(a.theta);
   for (int i = threadIdx.x; i < hk; i += kRopeThreads) {
     const int j = a.kept_idx[(size_t)g * hk + i];
@@ -41,68 +101,51 @@ __global__ __launch_bounds__(kRopeThreads) void pruned_rope_kernel(RopeArgs a, i
   }
   __syncthreads();
 
-  const int per_tok = V2 ? hk >> 1 : hk;
-  const int tb = min(tokens_per_block, a.T - t0);
-  for (int item = threadIdx.x; item < tb * per_tok; item += kRopeThreads) {
-    const int tl = item / per_tok, ii = item - tl * per_tok;
-    const int t = t0 + tl;
-    const double pos = (double)a.positions[t];
-    if constexpr (V2) {
-      const int i0 = 2 * ii;
-      float s0, c0, s1, c1;
-      angle_sincos(pos, invf[i0], &s0, &c0);
-      angle_sincos(pos, invf[i0 + 1], &s1, &c1);
-      // The rotation is in place, so the compiler cannot move a later head's loads above an
-      // earlier head's stores: heads are processed four at a time, all loads first.
-      auto rot2_heads = [&](half_t* base, int H, int h_first, int count) {
-        for (int hb = 0; hb < count; hb += 4) {
-          half2_t x1[4], x2[4];
+  for (int base = 0;;) {
+    float sn[kBatch][W], cs[kBatch][W];
 #pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            const int h = h_first + (hb + u < count ? hb + u : count - 1);
-            const half_t* v = base + ((size_t)t * H + h) * a.D_keep;
-            x1[u] = *reinterpret_cast<const half2_t*>(v + i0);
-            x2[u] = *reinterpret_cast<const half2_t*>(v + i0 + hk);
+    for (int b = 0; b < kBatch; ++b)
+#pragma unroll
+      for (int w = 0; w < W; ++w) angle_sincos(pos[b], invf[ch[b] + w], &sn[b][w], &cs[b][w]);
+
+    for (int h0 = 0; h0 < nheads; h0 += kHeadChunk) {
+      // rotate into registers, fetch the next chunk, then store: the next chunk's loads are in
+      // flight while this one is written back
+      elem_t y1[kBatch][kHeadChunk], y2[kBatch][kHeadChunk];
+#pragma unroll
+      for (int u = 0; u < kHeadChunk; ++u)
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b) {
+          if constexpr (V2) {
+            const float a0 = (float)x1[b][u].x, a1 = (float)x1[b][u].y, b0 = (float)x2[b][u].x, b1 = (float)x2[b][u].y;
+            y1[b][u] = half2_t{(half_t)(a0 * cs[b][0] - b0 * sn[b][0]), (half_t)(a1 * cs[b][1] - b1 * sn[b][1])};
+            y2[b][u] = half2_t{(half_t)(b0 * cs[b][0] + a0 * sn[b][0]), (half_t)(b1 * cs[b][1] + a1 * sn[b][1])};
+          } else {
+            const float a0 = (float)x1[b][u], b0 = (float)x2[b][u];
+            y1[b][u] = (half_t)(a0 * cs[b][0] - b0 * sn[b][0]);
+            y2[b][u] = (half_t)(b0 * cs[b][0] + a0 * sn[b][0]);
           }
+        }
+      if (h0 + kHeadChunk < nheads) load_chunk(h0 + kHeadChunk);
 #pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            if (hb + u < count) {
-              half_t* v = base + ((size_t)t * H + h_first + hb + u) * a.D_keep;
-              const float a0 = (float)x1[u].x, a1 = (float)x1[u].y, b0 = (float)x2[u].x, b1 = (float)x2[u].y;
-              *reinterpret_cast<half2_t*>(v + i0) = half2_t{(half_t)(a0 * c0 - b0 * s0), (half_t)(a1 * c1 - b1 * s1)};
-              *reinterpret_cast<half2_t*>(v + i0 + hk) = half2_t{(half_t)(b0 * c0 + a0 * s0), (half_t)(b1 * c1 + a1 * s1)};
+      for (int u = 0; u < kHeadChunk; ++u) {
+        if (h0 + u < nheads) {
+#pragma unroll
+          for (int b = 0; b < kBatch; ++b) {
+            if (live[b]) {
+              half_t* v = elem_ptr(b, h0 + u);
+              *reinterpret_cast<elem_t*>(v) = y1[b][u];
+              *reinterpret_cast<elem_t*>(v + hk) = y2[b][u];
             }
           }
         }
-      };
-      rot2_heads(a.q, a.Hq, g * qper, qper);
-      if (kper) rot2_heads(a.k, a.Hkv, g * kper, kper);
-    } else {
-      float sn, cs;
-      angle_sincos(pos, invf[ii], &sn, &cs);
-      auto rot1_heads = [&](half_t* base, int H, int h_first, int count) {
-        for (int hb = 0; hb < count; hb += 4) {
-          float x1[4], x2[4];
-#pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            const int h = h_first + (hb + u < count ? hb + u : count - 1);
-            const half_t* v = base + ((size_t)t * H + h) * a.D_keep;
-            x1[u] = (float)v[ii];
-            x2[u] = (float)v[ii + hk];
-          }
-#pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            if (hb + u < count) {
-              half_t* v = base + ((size_t)t * H + h_first + hb + u) * a.D_keep;
-              v[ii] = (half_t)(x1[u] * cs - x2[u] * sn);
-              v[ii + hk] = (half_t)(x2[u] * cs + x1[u] * sn);
-            }
-          }
-        }
-      };
-      rot1_heads(a.q, a.Hq, g * qper, qper);
-      if (kper) rot1_heads(a.k, a.Hkv, g * kper, kper);
+      }
     }
+    base += kBatch * kRopeThreads;
+    if (base >= n_items) break;
+    take_items(base);
+    load_pos();
+    load_chunk(0);
   }
 }
 
@@ -114,13 +157,21 @@ hipError_t launch_pruned_rope(const RopeArgs& a, hipStream_t stream) {
                   (a.k == nullptr || reinterpret_cast<uintptr_t>(a.k) % 4 == 0);
   // tokens per block: enough items to fill the block, enough blocks to fill the chip
   const int per_tok = v2 ? hk >> 1 : hk;
-  int tpb = (4 * kRopeThreads + per_tok - 1) / per_tok;
+  // decode-sized calls: one item per thread, all tokens in one block per table row
+  const bool tiny = (long long)a.T * per_tok <= kRopeThreads;
+  const int batch = tiny ? 1 : 4;
+  int tpb = batch * kRopeThreads / per_tok;   // a thread owns at most `batch` items
   if (tpb > a.T) tpb = a.T;
   if (tpb < 1) tpb = 1;
   dim3 grid((a.T + tpb - 1) / tpb, a.H_tab);
   const size_t smem = (size_t)hk * sizeof(double);
-  if (v2) hipLaunchKernelGGL(pruned_rope_kernel<true>, grid, dim3(kRopeThreads), smem, stream, a, tpb);
-  else hipLaunchKernelGGL(pruned_rope_kernel<false>, grid, dim3(kRopeThreads), smem, stream, a, tpb);
+  if (v2) {
+    if (tiny) hipLaunchKernelGGL((pruned_rope_kernel<true, 1>), grid, dim3(kRopeThreads), smem, stream, a, tpb);
+    else hipLaunchKernelGGL((pruned_rope_kernel<true, 4>), grid, dim3(kRopeThreads), smem, stream, a, tpb);
+  } else {
+    if (tiny) hipLaunchKernelGGL((pruned_rope_kernel<false, 1>), grid, dim3(kRopeThreads), smem, stream, a, tpb);
+    else hipLaunchKernelGGL((pruned_rope_kernel<false, 4>), grid, dim3(kRopeThreads), smem, stream, a, tpb);
+  }
   return hipGetLastError();
 }
 
