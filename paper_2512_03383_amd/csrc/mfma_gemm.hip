@@ -28,8 +28,11 @@ struct WTile {
 // AF token fragments, BF row fragments per wave, WN waves along rows, KS waves along K,
 // S2 groups per wave and iteration (the slab holds KS * S2 groups: fewer, longer iterations hide
 // the latency of fetching the next slab), PW iterations of weight loads kept in flight.
-template <int AF, int BF, int WN, int KS, int S2, int PW, bool XVEC>
+template <int AF, int BF, int WN, int KS, int S2, int PW, int XM>
 __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
+  // activation staging mode: 0 = element by element through the column map, 1 = column prefix,
+  // 2 = column segments whose stride is a multiple of 8 (128-bit loads in both)
+  constexpr bool XVEC = XM == 1, XSEG = XM == 2;
   constexpr int NT = WN * KS * 64;
   constexpr int BM = 16 * AF;               // tokens per block
   constexpr int BN = WN * BF * 16;          // rows per block
@@ -105,16 +108,19 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
   // real; store_x, one iteration later, masks, permutes and writes them to LDS.  Nothing touches
   // the loaded registers in between, so the wave never waits for x at the point of issue.
   // XVEC: whole 8-column blocks below kv come from one 128-bit load; the up to 7 kept columns at
-  // and after kv are added in the epilogue.  Otherwise: eight element loads through the column map.
+  // and after kv are added in the epilogue.  XSEG: a block lies in one segment and its kept columns
+  // are its first nk, contiguous in x: one 128-bit load and a per-half mask (only the block that
+  // holds a row's last kept columns, fewer than 8 of them, is read element by element).
+  // Otherwise: eight element loads through the column map.
   auto unit_token = [](int u) { return u / NCH; };
   auto unit_chunk = [](int u) { return u % NCH; };
   auto swz = [](int chunk) { return ((chunk >> 2) & 3) | ((chunk & 3) << 2); };
   const int kv = km.k_keep & ~7;
   const uint16_t* xbits = reinterpret_cast<const uint16_t*>(a.x);
   struct XRegs {
-    uint4 v[XVEC ? UPT : 1];
-    uint32_t e[XVEC ? 1 : UPT][8];
-    uint32_t ok[UPT];   // XVEC: all-ones / zero word mask; element path: bit j = half j is real
+    uint4 v[XM != 0 ? UPT : 1];
+    uint32_t e[XM != 0 ? 1 : UPT][8];
+    uint32_t ok[UPT];   // XVEC: all-ones / zero word mask; otherwise bit j = half j is real
   };
   auto fetch_x = [&](int it, XRegs& xr) {
 #pragma unroll
@@ -129,6 +135,21 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
         const bool full = k0 + 8 <= kv;
         xr.v[i] = load_u4_unaligned(a.x + xoff + (full ? k0 : 0));
         xr.ok[i] = (full && tok_ok) ? 0xffffffffu : 0u;
+      } else if constexpr (XSEG) {
+        const int seg = k0 / km.cs_stride, off = k0 - seg * km.cs_stride;
+        int nk = km.cs_keep - off;                       // kept columns at the start of this block
+        nk = nk < 0 ? 0 : (nk > 8 ? 8 : nk);
+        nk = k0 < km.k_span ? nk : 0;
+        const int c = seg * km.cs_keep + off;            // compact column of the block's first column
+        const bool vec = nk > 0 && c + 8 <= km.k_keep;   // the 16 bytes at c lie inside the token row
+        xr.v[i] = load_u4_unaligned(a.x + xoff + (vec ? c : 0));
+        xr.ok[i] = tok_ok ? (1u << nk) - 1u : 0u;
+        if (nk > 0 && !vec) {   // the row's last kept columns, fewer than 8 left
+          uint32_t h[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) h[j] = j < nk ? (uint32_t)xbits[xoff + c + j] : 0u;
+          xr.v[i] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+        }
       } else {
         xr.ok[i] = 0;
 #pragma unroll
@@ -152,6 +173,12 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
         const uint32_t m = xr.ok[i];
         e[0] = r.x & 0xffffu & m; e[1] = (r.x >> 16) & m; e[2] = r.y & 0xffffu & m; e[3] = (r.y >> 16) & m;
         e[4] = r.z & 0xffffu & m; e[5] = (r.z >> 16) & m; e[6] = r.w & 0xffffu & m; e[7] = (r.w >> 16) & m;
+      } else if constexpr (XSEG) {
+        const uint4 r = xr.v[i];
+        const uint32_t full[8] = {r.x & 0xffffu, r.x >> 16, r.y & 0xffffu, r.y >> 16,
+                                  r.z & 0xffffu, r.z >> 16, r.w & 0xffffu, r.w >> 16};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) e[j] = full[j] & (uint32_t)((int32_t)(xr.ok[i] << (31 - j)) >> 31);
       } else {
 #pragma unroll
         for (int j = 0; j < 8; ++j) e[j] = (xr.ok[i] >> j) & 1u ? xr.e[i][j] : 0u;
@@ -597,7 +624,7 @@ static hipError_t launch_prefill(const LinearArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
-template <int AF, int BF, int WN, int KS, int S2, int PW, bool XVEC>
+template <int AF, int BF, int WN, int KS, int S2, int PW, int XVEC>
 static hipError_t launch_cfg(const LinearArgs& a, hipStream_t stream) {
   constexpr int BM = 16 * AF, BN = WN * BF * 16, SC = KS * S2 * 128;
   size_t smem = (size_t)2 * BM * SC * sizeof(half_t) + (size_t)2 * BN * KS * S2 * sizeof(uint32_t);
@@ -613,7 +640,7 @@ static hipError_t launch_cfg(const LinearArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
-template <bool XVEC>
+template <int XVEC>
 static hipError_t launch_m(const LinearArgs& a, hipStream_t stream) {
   // Decode batches (M <= 32) are bound by the weight stream: 16 rows per wave and the K range
   // split over the block's 8 waves, four ways when there are many row tiles, eight ways otherwise.
@@ -629,7 +656,7 @@ static hipError_t launch_m(const LinearArgs& a, hipStream_t stream) {
     // and fetches scales eight groups at a time
     const bool small_offsets = (unsigned long long)a.N_total * (unsigned long long)a.K_total / 2 < (1ull << 32) &&
                                128ull * (unsigned long long)a.ldx * 2 < (1ull << 32);
-    if (XVEC && small_offsets && a.km.k_keep >= 128 && a.K_total >= 8 * kGroup) return launch_prefill(a, stream);
+    if (XVEC == 1 && small_offsets && a.km.k_keep >= 128 && a.K_total >= 8 * kGroup) return launch_prefill(a, stream);
     return launch_cfg<8, 4, 4, 1, 1, 1, XVEC>(a, stream);
   }
   if (blocks(64, 256) >= kEnough) return launch_cfg<4, 2, 8, 1, 1, 2, XVEC>(a, stream);
@@ -638,10 +665,12 @@ static hipError_t launch_m(const LinearArgs& a, hipStream_t stream) {
 }
 
 hipError_t launch_w4_gemm(const LinearArgs& a, hipStream_t stream) {
-  // 128-bit x loads need a column prefix only: global loads of any size may start on any 2-byte
-  // boundary on this target, so odd leading dimensions (k_keep = 12185) take the same path
-  const bool xvec = a.km.cs_stride == 0 && a.km.k_keep >= 8;
-  return xvec ? launch_m<true>(a, stream) : launch_m<false>(a, stream);
+  // 128-bit x loads: a column prefix (global loads of any size may start on any 2-byte boundary on
+  // this target, so odd leading dimensions such as k_keep = 12185 qualify), or column segments
+  // whose stride is a multiple of 8 and that keep at least 8 columns each
+  if (a.km.cs_stride == 0) return a.km.k_keep >= 8 ? launch_m<1>(a, stream) : launch_m<0>(a, stream);
+  if (a.km.cs_stride % 8 == 0 && a.km.cs_keep >= 8) return launch_m<2>(a, stream);
+  return launch_m<0>(a, stream);
 }
 
 }  // namespace uniql
