@@ -234,6 +234,10 @@ def detail_report(torch, uq, side):
     for spec in wl.mamba2_2p7b_layer(15):
         rep[f"mamba2_2p7b_p15_{spec.name}"] = time_linear(spec, 1, pool_for(spec))
     torch.cuda.empty_cache()
+    # the 4-bit output head (128256 x 4096), M = 1: the same GEMV at a size where launch latency is small
+    spec = wl.lm_head_llama3()
+    rep["lm_head_llama3_M1"] = time_linear(spec, 1, pool_for(spec, min_bytes=1.3e9, max_copies=5))
+    torch.cuda.empty_cache()
     # RoPE: decode and prefill
     for name, rs in (("rope_decode_llama_p15", wl.llama3_8b_rope(15, T=1)), ("rope_prefill_llama_p15", wl.prefill_rope(15, 4096))):
         r = wl.gen_rope_inputs(wl.rng_for(4, 7), rs)

@@ -44,6 +44,7 @@ def lib():
         L.uref_w4_dequant.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
         L.uref_w4_linear.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, i64, vp, i64, i32, vp, i32]
         L.uref_pruned_rope.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, dbl, vp, vp]
+        L.uref_pruned_rope_f64.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, dbl]
         L.uref_quantize_sym.argtypes = [vp, i32, i32, i32, vp, vp, vp]
         L.uref_quantize_asym.argtypes = [vp, i32, i32, i32, vp, vp, vp]
         _lib = L
@@ -142,6 +143,32 @@ def pruned_rope(q, k, positions, kept_idx, D_full: int, theta: float):
                                 D_full, Dk, float(theta), _p(q_out), _p(k_out))
     assert rc == 0, rc
     return q_out, k_out
+
+
+def pruned_rope_f64(x, positions, kept_idx, D_full: int, theta: float):
+    """Rotated fp64 copy of x [T][H][D_keep] (fp64 in, fp64 out): the rotation of `pruned_rope` without
+    the fp16 input format."""
+    x = np.array(x, dtype=np.float64, order="C", copy=True)
+    _chk(positions, np.int32, "positions"); _chk(kept_idx, np.int32, "kept_idx")
+    T, H, Dk = x.shape
+    H_tab = kept_idx.shape[0]
+    assert kept_idx.shape == (H_tab, Dk // 2) and positions.shape == (T,)
+    rc = lib().uref_pruned_rope_f64(_p(x), _p(positions), _p(kept_idx), T, H, H_tab, D_full, Dk, float(theta))
+    assert rc == 0, rc
+    return x
+
+
+def qkv_rope(wq, keep_q, wk, keep_k, wv, keep_v, x, positions, kept_idx, Hq: int, Hkv: int, D_full: int,
+             D_keep: int, theta: float):
+    """The fused decode step y = RoPE(x W) for the q and k projections and y = x W for v, all fp64:
+    each w* is a dict(qweight, scales, zeros); x is fp16 [T][k_keep].  Returns q [T][Hq][D_keep],
+    k [T][Hkv][D_keep], v [T][n_keep_v]."""
+    T = x.shape[0]
+    q = w4_linear(wq["qweight"], wq["scales"], wq["zeros"], x, keep_q).reshape(T, Hq, D_keep)
+    k = w4_linear(wk["qweight"], wk["scales"], wk["zeros"], x, keep_k).reshape(T, Hkv, D_keep)
+    v = w4_linear(wv["qweight"], wv["scales"], wv["zeros"], x, keep_v)
+    return (pruned_rope_f64(q, positions, kept_idx, D_full, theta),
+            pruned_rope_f64(k, positions, kept_idx, D_full, theta), v)
 
 
 def _quantize(fn, w: np.ndarray, group: int):

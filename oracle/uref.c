@@ -19,6 +19,8 @@
  *   uref_pruned_rope                   Sec. 3.2 MHSA paragraph: RoPE(X) =
  *        cos * X + sin * R(X), R([x1,x2]) = [-x2,x1]; Alg. 2 / Alg. A1 (symmetric
  *        index vector, one half stored; one table per KV head under GQA); Fig. 4a
+ *   uref_pruned_rope_f64               the same rotation on fp64 inputs: the second half of the
+ *        fused step y = RoPE(X W) (Eq. 2, then Sec. 3.2), no rounding in between
  *   uref_quantize_sym                  Eq. 3 (symmetric, N = 4)
  *   uref_quantize_asym                 the min/max asymmetric variant the
  *        benchmark configuration asks for (not in the paper; Eq. 3 is the case
@@ -223,6 +225,28 @@ int uref_pruned_rope(const uint16_t* q, const uint16_t* k, const int32_t* positi
     if (Hkv % H_tab) return -3;
     rope_tensor(k, k_out, positions, kept_idx, T, Hkv, H_tab, D_full, D_keep, theta);
   }
+  return 0;
+}
+
+/* The same rotation on fp64 inputs, in place: x [T][H][D_keep].  It defines the fused
+ * "project, then rotate" step (Eq. 2 followed by the RoPE of Sec. 3.2 / Alg. 2) without an
+ * intermediate rounding of the projected values: y = RoPE(X W) evaluated in fp64. */
+int uref_pruned_rope_f64(double* x, const int32_t* positions, const int32_t* kept_idx, int T, int H,
+                         int H_tab, int D_full, int D_keep, double theta) {
+  if (D_keep % 2 || D_keep > D_full || H_tab < 1 || H % H_tab) return -3;
+  int half = D_keep / 2, per = H / H_tab;
+  for (int t = 0; t < T; ++t)
+    for (int h = 0; h < H; ++h) {
+      double* v = x + ((size_t)t * H + h) * D_keep;
+      const int32_t* tab = kept_idx + (size_t)(h / per) * half;
+      for (int i = 0; i < half; ++i) {
+        int j = tab[i];
+        double phi = (double)positions[t] * pow(theta, -2.0 * (double)j / (double)D_full);
+        double a = v[i], b = v[i + half];
+        v[i] = a * cos(phi) - b * sin(phi);
+        v[i + half] = b * cos(phi) + a * sin(phi);
+      }
+    }
   return 0;
 }
 

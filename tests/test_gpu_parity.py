@@ -272,6 +272,21 @@ def test_prefill_gemm_sampled(env, uref, M):
         assert err <= TOL, (spec.name, err)
 
 
+def test_lm_head_sized_gemv_sampled(env, uref):
+    """The output-head shape (128256 x 4096, unpruned), M = 1: sampled rows against the oracle."""
+    uq, torch = env
+    spec = wl.lm_head_llama3()
+    rng = wl.rng_for(5, 1)
+    w = wl.gen_linear(rng, spec.N, spec.K)
+    x = wl.gen_activations(rng, 1, spec.K)
+    y = run_linear(uq, torch, w, uq.QuantLinear.from_numpy(w), spec.keep, x)
+    rows = _sample_rows(spec.N, rng, 256)
+    ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], x, spec.keep, rows=rows)
+    rms = np.sqrt(np.mean(ref ** 2))
+    err = np.max(np.abs(y[:, rows].astype(np.float64) - ref) / np.maximum(np.abs(ref), 1e-2 * rms))
+    assert err <= TOL, err
+
+
 @pytest.mark.parametrize("N,K,keep,M", [
     (6144, 2176, Keep(n_keep=6100, k_keep=2049), 1000),    # ragged rows, tokens and K tail; one column into a group
     (6144, 1152, Keep(k_keep=1100), 1024),                 # 9 groups per row: the last set of scales starts early

@@ -194,6 +194,12 @@ def mamba2_2p7b_layer(rate_pct: int = 15) -> List[LinearSpec]:
             LinearSpec("out_proj", d_inner, 2560, _cols_prefix(kd))]
 
 
+def lm_head_llama3() -> LinearSpec:
+    """The 4-bit output head of a Llama-3-8B shaped model (Sec. 3.4 quantises the embedding and
+    output layers too): 128256 vocabulary rows x 4096, not pruned.  The largest GEMV of a decode step."""
+    return LinearSpec("lm_head", K=4096, N=128256)
+
+
 def small_case() -> LinearSpec:
     """The 1024x1024 parity case: keep the first 870 output rows."""
     return LinearSpec("small", 1024, 1024, _rows_prefix(kept_dim(1024, 15)))
