@@ -2,9 +2,10 @@
 """Benchmark of the pruned W4A16 decode hot path on one MI355X.
 
 A step is one pass of the whole hot path over one Llama-3-8B shaped decoder
-layer at batch 1: q/k/v projections, fused pruned RoPE on the fresh Q/K heads,
-o_proj, gate/up/down -- seven W4A16 linears and one RoPE launch, all through the
-C ABI.  Consecutive steps walk through a pool of distinct layers (a 32-layer
+layer at batch 1: q/k/v projections with the pruned RoPE of the fresh Q/K heads
+as the epilogue of their launch, o_proj, gate/up (one launch), down -- seven W4A16
+linears and the rotation in four launches, all through the C ABI
+(--separate-rope: five launches).  Consecutive steps walk through a pool of distinct layers (a 32-layer
 model, several GB), so every step streams its weights from HBM, not from the
 256 MB Infinity Cache.  Inputs are seeded synthetic stand-ins (random nibbles,
 fp16 scales ~ U(0.005, 0.02), zeros ~ U{0..15}, activations ~ N(0, 1)).
@@ -104,12 +105,28 @@ class DecodeStep:
         k = self.yout["k_proj"].view(self.M, self.rope.Hkv, self.rope.D_keep)
         self.uq.uniql_pruned_rope(q, k, self.pos, self.idx, self.rope.D_full, self.rope.theta)
 
-    def run(self, layer, only=None, fused=True):
-        """One step: q/k/v (one call), RoPE on the fresh Q/K, o_proj, gate/up (one call), down.
+    def qkv_rope_call(self, layer):
+        """Marshalled uniql_w4_qkv_rope call of one layer (cached): q, k, v and the rotation in one launch."""
+        key = (id(layer), "qkv_rope")
+        if key not in self._calls:
+            sp = {s.name: s for s in self.specs}
+            names = self.FUSED[0]
+            r = self.rope
+            self._calls[key] = self.uq.QkvRopeCall(
+                [layer.lin[n] for n in names], [sp[n].keep for n in names], self.xin["q_proj"][0],
+                self.yout["q_proj"].view(r.Hq, r.D_keep), self.yout["k_proj"].view(r.Hkv, r.D_keep),
+                self.yout["v_proj"].view(-1), self.pos[:1], self.idx, r.D_full, r.theta)
+        return self._calls[key]
+
+    def run(self, layer, only=None, fused=True, fuse_rope=True):
+        """One step: q/k/v with the rotation of the fresh Q/K heads (one launch; fuse_rope=False: one
+        launch for q/k/v, one for the rotation), o_proj, gate/up (one launch), down.
         only = a linear name or a tuple of names: just that launch (for attribution)."""
         uq = self.uq
         if only is not None:
-            if isinstance(only, tuple):
+            if only == "qkv_rope":
+                self.qkv_rope_call(layer).run()
+            elif isinstance(only, tuple):
                 self.multi_call(layer, only).run()
             else:
                 s = next(s for s in self.specs if s.name == only)
@@ -122,8 +139,11 @@ class DecodeStep:
                     self.rope_qk()
             return
         sp = {s.name: s for s in self.specs}
-        self.multi_call(layer, self.FUSED[0]).run()
-        self.rope_qk()
+        if fuse_rope and self.M == 1:
+            self.qkv_rope_call(layer).run()
+        else:
+            self.multi_call(layer, self.FUSED[0]).run()
+            self.rope_qk()
         uq.uniql_w4_linear(layer.lin["o_proj"], sp["o_proj"].keep, self.xin["o_proj"], self.yout["o_proj"])
         self.multi_call(layer, self.FUSED[1]).run()
         uq.uniql_w4_linear(layer.lin["down_proj"], sp["down_proj"].keep, self.xin["down_proj"], self.yout["down_proj"])
@@ -262,6 +282,8 @@ def main():
     ap.add_argument("--layers", type=int, default=32, help="distinct layers in the weight pool")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--separate-rope", action="store_true",
+                    help="run the rotation as its own launch after q/k/v instead of as the epilogue of their launch")
     ap.add_argument("--pmc-calib", action="store_true",
                     help="also launch a plain 256 MiB elementwise copy four times: the kernel of known size that "
                          "scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -290,8 +312,9 @@ def main():
     # one eager pass (also warms the per-device caches of the library), then capture HIP graphs:
     # one graph that walks the whole layer pool (the steady state of a decode loop) and one graph
     # per layer for the remainder when --steps is not a multiple of the pool size
+    fuse_rope = not args.separate_rope
     for L in layers:
-        step.run(L)
+        step.run(L, fuse_rope=fuse_rope)
     torch.cuda.synchronize()
     graph_all, graphs = None, None
     if not args.no_graph:
@@ -299,12 +322,12 @@ def main():
         graph_all = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph_all, stream=side):
             for L in layers:
-                step.run(L)
+                step.run(L, fuse_rope=fuse_rope)
         graphs = []
         for L in layers:
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g, stream=side):
-                step.run(L)
+                step.run(L, fuse_rope=fuse_rope)
             graphs.append(g)
         torch.cuda.synchronize()
 
@@ -313,7 +336,7 @@ def main():
         nl = len(layers)
         if graphs is None:
             for i in range(n):
-                step.run(layers[i % nl])
+                step.run(layers[i % nl], fuse_rope=fuse_rope)
             return
         for _ in range(n // nl):
             graph_all.replay()
@@ -336,10 +359,12 @@ def main():
     # ---- attribution: duration of each linear launch, measured with HIP events on the launch
     # stream around a graph that issues that one linear back to back over the whole layer pool
     # (cold weights every launch, no host launch cost inside the bracket)
-    names = [DecodeStep.FUSED[0], "o_proj", DecodeStep.FUSED[1], "down_proj"]
+    first = "qkv_rope" if fuse_rope else DecodeStep.FUSED[0]
+    names = [first, "o_proj", DecodeStep.FUSED[1], "down_proj"]
     lin_bytes = dict(lin_bytes)
     for grp in DecodeStep.FUSED:
         lin_bytes[grp] = sum(lin_bytes[n] for n in grp)
+    lin_bytes["qkv_rope"] = lin_bytes[DecodeStep.FUSED[0]] + rope.algorithmic_bytes()
     iso_us = {}
     for n in names:
         if args.no_graph:
@@ -356,7 +381,8 @@ def main():
     per_linear = {n: {"MB": round(lin_bytes[n] / 1e6, 3), "us": round(iso_us[n], 3),
                       "GBps": round(lin_bytes[n] / (iso_us[n] * 1e-6) / 1e9, 1),
                       "frac_of_peak": round(lin_bytes[n] / (iso_us[n] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)} for n in names}
-    per_linear = {("+".join(k) if isinstance(k, tuple) else k): v for k, v in per_linear.items()}
+    per_linear = {("+".join(k) if isinstance(k, tuple) else k.replace("qkv_rope", "q_proj+k_proj+v_proj+rope")): v
+                  for k, v in per_linear.items()}
     for n, v in per_linear.items():
         log(f"  {n:22s} {v}")
     # the dominant kernel of the step: the GEMV launch that serves gate_proj and up_proj together
@@ -390,7 +416,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
         "data": "synthetic",
         "config": {"workload": f"Llama-3-8B shaped decode layer, batch 1, int4 group-128 weights, "
-                               f"pruning {rate}% (q+k+v, o, gate+up, down W4A16 GEMV launches + fused pruned RoPE), "
+                               f"pruning {rate}% (q+k+v{' with the pruned RoPE as epilogue' if fuse_rope else ', pruned RoPE'}, "
+                               f"o, gate+up, down: W4A16 GEMV launches), "
                                f"{args.layers}-layer weight pool streamed from HBM",
                    "prune_pct": rate, "M": M, "launch": "hip-graph over the layer pool" if graphs else "eager",
                    "step_algorithmic_MB": round(step_bytes / 1e6, 3)},

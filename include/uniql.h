@@ -151,6 +151,32 @@ int uniql_pruned_rope(void* q_f16, void* k_f16, const int32_t* positions, const 
                       int32_t D_keep, double theta, void* hip_stream);
 
 /*
+ * Decode step of an attention block's input side in ONE launch (Eq. 2 followed by the rotary
+ * embedding of Sec. 3.2 / Alg. 2 / Alg. A1, one token):
+ *   q = RoPE(x Wq'),  k = RoPE(x Wk'),  v = x Wv'
+ * with the linears of uniql_w4_linear and the rotation of uniql_pruned_rope.  The rotation is applied
+ * to the fp32 sums, so q and k are rounded to fp16 once (the separate calls round them before the
+ * rotation as well).
+ *   W, keep   : host arrays of 3 entries (q, k, v); keep may be NULL (all unpruned).  The kept rows
+ *               of q must number Hq * D_keep and those of k Hkv * D_keep: the compact outputs are
+ *               [heads][D_keep], kept pair i of a head = (y[i], y[i + D_keep / 2]).  The three
+ *               matrices read the same x, so their kept columns must agree in number.
+ *   x_f16     : device fp16 [k_keep], one token
+ *   q_f16, k_f16, v_f16 : device fp16 [Hq * D_keep], [Hkv * D_keep], [n_keep of v]
+ *   position  : device int32 [1];  kept_idx, H_tab, D_full, D_keep, theta as in uniql_pruned_rope
+ * One launch needs the three matrices to stream rows of the same length class (the same number of
+ * 2048-column pieces, at most 8) with a group count per row that is a multiple of 4; otherwise the
+ * call enqueues uniql_w4_linear_multi and uniql_pruned_rope instead: the same definition, but q and k
+ * are then rounded to fp16 before the rotation (an extra error of up to 2^-11 of each member of a pair).
+ * Errors: as uniql_w4_linear and uniql_pruned_rope; E_KEEP also when the kept rows of q / k do not
+ * match the head counts; E_SHAPE when Hkv < 1 or the kept column counts differ.
+ */
+int uniql_w4_qkv_rope(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_f16, void* q_f16,
+                      void* k_f16, void* v_f16, const int32_t* position, const int32_t* kept_idx,
+                      int32_t Hq, int32_t Hkv, int32_t H_tab, int32_t D_full, int32_t D_keep,
+                      double theta, void* hip_stream);
+
+/*
  * Measurement aid, not part of the method: reads `bytes` of device memory at `src`
  * (16-byte aligned) once with wave-wide 128-bit loads, the access shape of the GEMV's
  * weight stream, and writes one xor word per 8 KB to `out_words` (device, at least

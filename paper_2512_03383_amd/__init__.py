@@ -69,6 +69,9 @@ def lib():
         L.uniql_pruned_rope.restype = C.c_int
         L.uniql_pruned_rope.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, C.c_double, vp]
         L.uniql_stream_read_probe.restype = C.c_int
+        L.uniql_w4_qkv_rope.restype = C.c_int
+        L.uniql_w4_qkv_rope.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, vp, vp, vp, vp, vp,
+                                        i32, i32, i32, i32, i32, C.c_double, vp]
         L.uniql_stream_read_probe.argtypes = [vp, i64, vp, vp]
         L.uniql_strerror.restype = C.c_char_p
         L.uniql_strerror.argtypes = [C.c_int]
@@ -225,6 +228,41 @@ def uniql_pruned_rope(q, k, positions, kept_idx, D_full: int, theta: float, stre
                                  T, Hq, Hkv, kept_idx.shape[0], D_full, Dk, float(theta), _stream_ptr(stream))
     _check(rc)
     return q, k
+
+
+class QkvRopeCall:
+    """Marshalled arguments of one uniql_w4_qkv_rope call, reusable (e.g. for graph capture):
+    q, k, v projections of one token and the rotation of q and k in one launch."""
+
+    def __init__(self, Ws, keeps, x, q, k, v, position, kept_idx, D_full: int, theta: float):
+        import torch
+        assert len(Ws) == 3 and len(keeps) == 3
+        for t in (x, q, k, v):
+            assert t.dtype == torch.float16 and t.is_cuda and t.is_contiguous()
+        assert q.dim() == 2 and k.dim() == 2 and q.shape[1] == k.shape[1], "q [Hq][D_keep], k [Hkv][D_keep]"
+        assert position.dtype == torch.int32 and position.numel() == 1
+        assert kept_idx.dtype == torch.int32 and kept_idx.is_contiguous() and kept_idx.shape[1] == q.shape[1] // 2
+        self.W = (W4 * 3)(*[w.desc() for w in Ws])
+        self.keep = (KeepDesc * 3)(*[(_keep_desc(kp) or KeepDesc()) for kp in keeps])
+        self.args = (C.c_void_p(x.data_ptr()), C.c_void_p(q.data_ptr()), C.c_void_p(k.data_ptr()),
+                     C.c_void_p(v.data_ptr()), C.c_void_p(position.data_ptr()), C.c_void_p(kept_idx.data_ptr()),
+                     q.shape[0], k.shape[0], kept_idx.shape[0], int(D_full), q.shape[1], float(theta))
+        self._refs = (Ws, x, q, k, v, position, kept_idx)
+
+    def run(self, stream=None):
+        _check(lib().uniql_w4_qkv_rope(self.W, self.keep, *self.args, _stream_ptr(stream)))
+
+
+def uniql_w4_qkv_rope(Ws, keeps, x, position, kept_idx, Hq: int, Hkv: int, D_full: int, D_keep: int, theta: float,
+                      stream=None):
+    """q = RoPE(x Wq'), k = RoPE(x Wk'), v = x Wv' for one token x [k_keep]; returns fp16 q [Hq][D_keep],
+    k [Hkv][D_keep], v [n_keep of v]."""
+    import torch
+    q = torch.empty((Hq, D_keep), dtype=torch.float16, device=x.device)
+    k = torch.empty((Hkv, D_keep), dtype=torch.float16, device=x.device)
+    v = torch.empty((kept_dims(Ws[2], keeps[2])[0],), dtype=torch.float16, device=x.device)
+    QkvRopeCall(Ws, keeps, x, q, k, v, position, kept_idx, D_full, theta).run(stream)
+    return q, k, v
 
 
 def uniql_stream_read_probe(src, nbytes: int, out, stream=None):

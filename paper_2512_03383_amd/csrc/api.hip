@@ -3,6 +3,7 @@
 // error paths behave the same on a machine without a GPU.
 #include "../../include/uniql.h"
 #include "common.h"
+#include <cmath>
 
 #include <string.h>
 
@@ -179,6 +180,58 @@ extern "C" int uniql_pruned_rope(void* q_f16, void* k_f16, const int32_t* positi
   a.T = T; a.Hq = Hq; a.Hkv = Hkv; a.H_tab = H_tab; a.D_full = D_full; a.D_keep = D_keep;
   a.theta = theta;
   hipError_t e = launch_pruned_rope(a, (hipStream_t)hip_stream);
+  return e == hipSuccess ? UNIQL_OK : hip_fail(e);
+}
+
+extern "C" int uniql_w4_qkv_rope(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_f16, void* q_f16,
+                                 void* k_f16, void* v_f16, const int32_t* position, const int32_t* kept_idx,
+                                 int32_t Hq, int32_t Hkv, int32_t H_tab, int32_t D_full, int32_t D_keep,
+                                 double theta, void* hip_stream) {
+  if (!W || !position || !kept_idx) return UNIQL_E_NULL;
+  if (Hq < 1 || Hkv < 1) return UNIQL_E_SHAPE;
+  if (D_full < 2 || D_full % 2 || D_keep < 2 || D_keep % 2 || D_keep > D_full) return UNIQL_E_KEEP;
+  if (H_tab < 1 || Hq % H_tab || Hkv % H_tab) return UNIQL_E_KEEP;
+  if (!(theta > 0.0)) return UNIQL_E_KEEP;
+  if (!aligned(position, 4) || !aligned(kept_idx, 4)) return UNIQL_E_ALIGN;
+  void* y[3] = {q_f16, k_f16, v_f16};
+  LinearArgs a[3];
+  for (int i = 0; i < 3; ++i) {
+    // one token: the leading dimensions are the kept dimensions themselves
+    KeepMap km;
+    int rc = make_keepmap(&W[i], keep ? &keep[i] : nullptr, &km);
+    if (rc) return rc;
+    rc = fill_linear(&W[i], keep ? &keep[i] : nullptr, x_f16, km.k_keep, y[i], km.n_keep, 1, &a[i]);
+    if (rc) return rc;
+    if (km.k_keep != a[0].km.k_keep) return UNIQL_E_SHAPE;   // one x for all three
+  }
+  // q and k come out as [heads][D_keep]
+  if ((long long)a[0].km.n_keep != (long long)Hq * D_keep || (long long)a[1].km.n_keep != (long long)Hkv * D_keep) return UNIQL_E_KEEP;
+  int rc = check_arch();
+  if (rc) return rc;
+  hipStream_t s = (hipStream_t)hip_stream;
+  RopeFuse rf = {};
+  rf.positions = position;
+  rf.kept_idx = kept_idx;
+  rf.H_tab = H_tab;
+  rf.D_keep = D_keep;
+  rf.exp2_coeff = -(2.0 / (double)D_full) * log2(theta);
+  rf.heads[0] = Hq;
+  rf.heads[1] = Hkv;
+  bool fused = false;
+  hipError_t e = launch_w4_qkv_rope(a, rf, s, &fused);
+  if (e != hipSuccess) return e == hipErrorInvalidValue ? UNIQL_E_SHAPE : hip_fail(e);
+  if (fused) return UNIQL_OK;
+  // shapes that cannot share one launch: the three projections, then the stand-alone rotation
+  e = launch_w4_gemv_batch(a, 3, s);
+  if (e != hipSuccess) return e == hipErrorInvalidValue ? UNIQL_E_SHAPE : hip_fail(e);
+  RopeArgs r;
+  r.q = (half_t*)q_f16;
+  r.k = (half_t*)k_f16;
+  r.positions = position;
+  r.kept_idx = kept_idx;
+  r.T = 1; r.Hq = Hq; r.Hkv = Hkv; r.H_tab = H_tab; r.D_full = D_full; r.D_keep = D_keep;
+  r.theta = theta;
+  e = launch_pruned_rope(r, s);
   return e == hipSuccess ? UNIQL_OK : hip_fail(e);
 }
 

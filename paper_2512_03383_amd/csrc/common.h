@@ -43,10 +43,20 @@ struct LinearArgs {
 
 // Several independent linears served by one GEMV launch.
 constexpr int kMaxBatch = 4;
+// Rotary epilogue of a fused q / k / v launch: problem i is rotated when heads[i] > 0; its compact
+// output is [heads[i]][D_keep] and kept pair p of a head is (y[p], y[p + D_keep / 2]).
+struct RopeFuse {
+  const int32_t* positions;       // device, [1]: the token's position
+  const int32_t* kept_idx;        // device, [H_tab][D_keep / 2]
+  int H_tab, D_keep;
+  double exp2_coeff;              // -(2 / D_full) * log2(theta): inv_freq_j = exp2(j * exp2_coeff)
+  int heads[kMaxBatch];
+};
 struct GemvBatch {
   LinearArgs p[kMaxBatch];
   int first_block[kMaxBatch];
   int n;
+  RopeFuse rf;
 };
 
 // compact output row -> stored row
@@ -145,6 +155,9 @@ __device__ __forceinline__ void dequant_word(uint32_t w, const GroupQ& g, const 
 // host-side launchers (one per translation unit)
 hipError_t launch_w4_gemv(const LinearArgs& a, hipStream_t stream);
 hipError_t launch_w4_gemv_batch(const LinearArgs* probs, int n, hipStream_t stream);
+// q, k, v of one token with the rotation of q and k fused into the launch; *fused = false (and nothing
+// launched) when the shapes do not allow it
+hipError_t launch_w4_qkv_rope(const LinearArgs* probs, const RopeFuse& rf, hipStream_t stream, bool* fused);
 hipError_t launch_w4_gemm(const LinearArgs& a, hipStream_t stream);
 hipError_t launch_w4_dequant(const LinearArgs& a, hipStream_t stream);
 

@@ -70,8 +70,14 @@ __device__ __forceinline__ ColMap make_colmap(const KeepMap& km) {
 // compile-time, 1..8 (NCH = 0: run-time chunk count for rows longer than 8 chunks).
 // The launch carries up to kMaxBatch independent linears (same R / XVEC / NCH, e.g. q, k and v
 // of one layer, or gate and up): problem i owns the blocks [first_block[i], first_block[i+1]).
-template <int R, bool XVEC, int NCH>
+// ROPE (R = 1 only): problems with batch.rf.heads[i] > 0 get the rotary embedding of their output as
+// an epilogue.  Their blocks own four kept pairs instead of eight consecutive rows: waves 0..3 compute
+// the first-half rows of the pairs, waves 4..7 the second-half rows, the two fp32 sums of a pair meet
+// in LDS and are rotated before the one rounding to fp16.  The pair's sin / cos are formed while the
+// weight stream is in flight, with the arithmetic of the stand-alone RoPE kernel.
+template <int R, bool XVEC, int NCH, bool ROPE = false>
 __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, int m, int nchunk_rt) {
+  static_assert(!ROPE || R == 1, "the rotary epilogue pairs single-row waves");
   extern __shared__ __align__(16) unsigned char smem[];
   uint4* xs = reinterpret_cast<uint4*>(smem);   // [nchunk][4][64] units of 8 halves
 
@@ -91,11 +97,27 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
 
   // stored rows of this wave (clamped so that every address is valid)
   int srow[R];
+  const int rope_heads = ROPE ? batch.rf.heads[pi] : 0;   // block-uniform
+  int rope_row = 0, rope_j = 0, rope_pos = 0;
+  bool rope_ok = false;
+  if (ROPE && rope_heads > 0) {
+    const int hk = batch.rf.D_keep >> 1;
+    const int p = block_id * 4 + (wave & 3);              // kept pair of this wave, over all heads
+    rope_ok = p < rope_heads * hk;
+    const int pc = rope_ok ? p : rope_heads * hk - 1;
+    const int head = pc / hk, i = pc - head * hk;
+    rope_row = head * batch.rf.D_keep + i + (wave >> 2) * hk;
+    srow[0] = stored_row(km, rope_row);
+    // original pair index and position: issued first, consumed after the activations are staged
+    rope_j = batch.rf.kept_idx[(size_t)(head / (rope_heads / batch.rf.H_tab)) * hk + i];
+    rope_pos = batch.rf.positions[0];
+  } else {
 #pragma unroll
-  for (int r = 0; r < R; ++r) {
-    int rc = rg * R + r;
-    rc = rc < km.n_keep ? rc : km.n_keep - 1;
-    srow[r] = stored_row(km, rc);
+    for (int r = 0; r < R; ++r) {
+      int rc = rg * R + r;
+      rc = rc < km.n_keep ? rc : km.n_keep - 1;
+      srow[r] = stored_row(km, rc);
+    }
   }
 
   // Scales and zero points of ALL of the wave's tiles, fetched up front by two wide loads (one dword
@@ -187,6 +209,7 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
   float acc[R];
 #pragma unroll
   for (int r = 0; r < R; ++r) acc[r] = 0.f;
+  float rope_sn = 0.f, rope_cs = 1.f;
 
   const ColMap cm = make_colmap(km);
   const int kv = km.k_keep & ~7;   // XVEC: columns below kv come from whole 128-bit loads
@@ -261,6 +284,13 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
     }
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
+    if (ROPE && rope_heads > 0) {
+      // sin / cos of pos * theta^(-2j/D): fp64 angle in revolutions, its fraction to the hardware sin / cos
+      const double rev = (double)rope_pos * exp2((double)rope_j * batch.rf.exp2_coeff) * 0.15915494309189534561;
+      const float rr = (float)(rev - rint(rev));
+      rope_sn = __builtin_amdgcn_sinf(rr);
+      rope_cs = __builtin_amdgcn_cosf(rr);
+    }
 
     // ---- phase 4: consume tiles in issue order, re-issuing D tiles ahead
     uint4 xr[4];
@@ -317,6 +347,16 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
     }
   }
 
+  if (ROPE && rope_heads > 0) {
+    __shared__ float pair_sum[kGemvWaves];
+    const float v = dpp_xor_reduce(acc[0]);
+    if (lane == 0) pair_sum[wave] = v;
+    __syncthreads();
+    const float x1 = pair_sum[wave & 3], x2 = pair_sum[(wave & 3) + 4];
+    const float out = wave < 4 ? x1 * rope_cs - x2 * rope_sn : x2 * rope_cs + x1 * rope_sn;
+    if (lane == 0 && rope_ok) a.y[(size_t)m * a.ldy + rope_row] = (half_t)out;
+    return;
+  }
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     const float v = dpp_xor_reduce(acc[r]);
@@ -331,10 +371,10 @@ static int blocks_for(const LinearArgs& a) {
   return (row_groups + kGemvWaves - 1) / kGemvWaves;
 }
 
-template <int R, bool XVEC, int NCH>
-static hipError_t launch_one(const LinearArgs* probs, int n, int m, int nchunk, hipStream_t stream) {
+template <int R, bool XVEC, int NCH, bool ROPE = false>
+static hipError_t launch_one(const LinearArgs* probs, int n, int m, int nchunk, hipStream_t stream, const RopeFuse* rf = nullptr) {
   const size_t smem = (size_t)nchunk * 4096;
-  auto kern = w4_gemv_kernel<R, XVEC, NCH>;
+  auto kern = w4_gemv_kernel<R, XVEC, NCH, ROPE>;
   if (smem > 160 * 1024) return hipErrorInvalidValue;
   if (smem > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -342,11 +382,16 @@ static hipError_t launch_one(const LinearArgs* probs, int n, int m, int nchunk, 
   }
   GemvBatch b;
   b.n = n;
+  b.rf = RopeFuse{};
+  if (rf) b.rf = *rf;
   int blocks = 0;
   for (int i = 0; i < kMaxBatch; ++i) {
     b.p[i] = probs[i < n ? i : 0];
     b.first_block[i] = blocks;
-    if (i < n) blocks += blocks_for<R>(probs[i]);
+    if (i >= n) continue;
+    // a rotated problem: four kept pairs per block; otherwise eight waves of R rows
+    if (ROPE && b.rf.heads[i] > 0) blocks += (b.rf.heads[i] * (b.rf.D_keep / 2) + 3) / 4;
+    else blocks += blocks_for<R>(probs[i]);
   }
   hipLaunchKernelGGL(kern, dim3(blocks), dim3(kGemvThreads), smem, stream, b, m, nchunk);
   return hipGetLastError();
@@ -417,6 +462,34 @@ hipError_t launch_w4_gemv_batch(const LinearArgs* probs, int n, hipStream_t stre
   const int r1 = rows >= 16384 ? 4 : (rows >= 6144 ? 2 : 1);
   return xvec_of(probs[0], 0) ? launch_rows<true>(probs, n, r1, 0, nchunk_of(probs[0]), stream)
                               : launch_rows<false>(probs, n, r1, 0, nchunk_of(probs[0]), stream);
+}
+
+template <bool XVEC>
+static hipError_t launch_rope_nch(const LinearArgs* probs, int nchunk, hipStream_t stream, const RopeFuse& rf) {
+  switch (nchunk) {
+    case 1: return launch_one<1, XVEC, 1, true>(probs, 3, 0, nchunk, stream, &rf);
+    case 2: return launch_one<1, XVEC, 2, true>(probs, 3, 0, nchunk, stream, &rf);
+    case 3: return launch_one<1, XVEC, 3, true>(probs, 3, 0, nchunk, stream, &rf);
+    case 4: return launch_one<1, XVEC, 4, true>(probs, 3, 0, nchunk, stream, &rf);
+    case 5: return launch_one<1, XVEC, 5, true>(probs, 3, 0, nchunk, stream, &rf);
+    case 6: return launch_one<1, XVEC, 6, true>(probs, 3, 0, nchunk, stream, &rf);
+    case 7: return launch_one<1, XVEC, 7, true>(probs, 3, 0, nchunk, stream, &rf);
+    default: return launch_one<1, XVEC, 8, true>(probs, 3, 0, nchunk, stream, &rf);
+  }
+}
+
+hipError_t launch_w4_qkv_rope(const LinearArgs* probs, const RopeFuse& rf, hipStream_t stream, bool* fused) {
+  // one launch needs the three problems to share a kernel instantiation: one token, the same
+  // compile-time chunk count and x access mode, rows of a multiple of four groups
+  bool ok = true;
+  for (int i = 0; i < 3; ++i)
+    ok = ok && probs[i].M == 1 && nchunk_of(probs[i]) == nchunk_of(probs[0]) && xvec_of(probs[i], 0) == xvec_of(probs[0], 0) &&
+         (probs[i].K_total / kGroup) % 4 == 0;
+  ok = ok && nchunk_of(probs[0]) >= 1 && nchunk_of(probs[0]) <= 8;
+  *fused = ok;
+  if (!ok) return hipSuccess;
+  return xvec_of(probs[0], 0) ? launch_rope_nch<true>(probs, nchunk_of(probs[0]), stream, rf)
+                              : launch_rope_nch<false>(probs, nchunk_of(probs[0]), stream, rf);
 }
 
 }  // namespace uniql

@@ -112,6 +112,55 @@ def test_rope_rejects_bad_arguments():
     assert _rope(pos=P + 2) == uq.UNIQL_E_ALIGN
 
 
+def _multi(n=2, ws=None, keeps=None, x=P, y=P, ldx=512, ldy=256, M=1):
+    ws = ws if ws is not None else [_w() for _ in range(max(n, 1))]
+    W = (W4 * len(ws))(*ws)
+    K = (KeepDesc * len(ws))(*keeps) if keeps is not None else None
+    cnt = len(ws)
+    xs = (C.c_void_p * cnt)(*[x] * cnt)
+    ys = (C.c_void_p * cnt)(*[y] * cnt)
+    lx = (C.c_int64 * cnt)(*[ldx] * cnt)
+    ly = (C.c_int64 * cnt)(*[ldy] * cnt)
+    return uq.lib().uniql_w4_linear_multi(n, W, K, xs, lx, ys, ly, M, None)
+
+
+def test_linear_multi_rejects_bad_arguments():
+    assert _multi(n=0) == uq.UNIQL_E_SHAPE
+    assert _multi(n=5, ws=[_w() for _ in range(5)]) == uq.UNIQL_E_SHAPE
+    assert uq.lib().uniql_w4_linear_multi(1, None, None, None, None, None, None, 1, None) == uq.UNIQL_E_NULL
+    assert _multi(ws=[_w(), _w(group=64)]) == uq.UNIQL_E_SHAPE           # any invalid entry fails the call
+    assert _multi(ws=[_w(), _w(q=P + 8)]) == uq.UNIQL_E_ALIGN
+    assert _multi(keeps=[KeepDesc(), KeepDesc(n_keep=257)]) == uq.UNIQL_E_KEEP
+    assert _multi(x=0) == uq.UNIQL_E_NULL
+    assert _multi(M=0) == uq.UNIQL_E_SHAPE
+
+
+def _qkv(ws=None, keeps=None, x=P, q=P, k=P, v=P, pos=P, idx=P, Hq=4, Hkv=2, H_tab=2, D_full=64, D_keep=64, theta=1e4):
+    ws = ws if ws is not None else [_w(N=Hq * D_full), _w(N=Hkv * D_full), _w(N=Hkv * D_full)]
+    W = (W4 * 3)(*ws)
+    K = (KeepDesc * 3)(*keeps) if keeps is not None else None
+    return uq.lib().uniql_w4_qkv_rope(W, K, C.c_void_p(x), C.c_void_p(q), C.c_void_p(k), C.c_void_p(v),
+                                      C.c_void_p(pos), C.c_void_p(idx), Hq, Hkv, H_tab, D_full, D_keep, theta, None)
+
+
+def test_qkv_rope_rejects_bad_arguments():
+    assert uq.lib().uniql_w4_qkv_rope(None, None, C.c_void_p(P), C.c_void_p(P), C.c_void_p(P), C.c_void_p(P),
+                                      C.c_void_p(P), C.c_void_p(P), 4, 2, 2, 64, 64, 1e4, None) == uq.UNIQL_E_NULL
+    assert _qkv(pos=0) == uq.UNIQL_E_NULL
+    assert _qkv(idx=0) == uq.UNIQL_E_NULL
+    assert _qkv(x=0) == uq.UNIQL_E_NULL
+    assert _qkv(k=0) == uq.UNIQL_E_NULL
+    assert _qkv(Hkv=0) == uq.UNIQL_E_SHAPE
+    assert _qkv(D_keep=63) == uq.UNIQL_E_KEEP
+    assert _qkv(D_keep=66) == uq.UNIQL_E_KEEP
+    assert _qkv(H_tab=3) == uq.UNIQL_E_KEEP
+    assert _qkv(theta=-1.0) == uq.UNIQL_E_KEEP
+    assert _qkv(pos=P + 2) == uq.UNIQL_E_ALIGN
+    assert _qkv(D_keep=32) == uq.UNIQL_E_KEEP                            # kept rows of q do not match Hq * D_keep
+    assert _qkv(ws=[_w(N=256), _w(N=128), _w(N=128, K=1024)]) == uq.UNIQL_E_SHAPE   # v reads a different x
+    assert _qkv(ws=[_w(N=256), _w(N=128, group=64), _w(N=128)]) == uq.UNIQL_E_SHAPE
+
+
 def test_valid_arguments_without_gfx950_fail_loudly():
     """On a box without an MI355X a valid call must report E_HIP / E_ARCH, never pretend to work."""
     import torch
@@ -119,3 +168,5 @@ def test_valid_arguments_without_gfx950_fail_loudly():
         pytest.skip("a GPU is present; covered by the gpu tests")
     assert _lin(_w(), None) in (uq.UNIQL_E_HIP, uq.UNIQL_E_ARCH)
     assert _rope() in (uq.UNIQL_E_HIP, uq.UNIQL_E_ARCH)
+    assert _multi() in (uq.UNIQL_E_HIP, uq.UNIQL_E_ARCH)
+    assert _qkv() in (uq.UNIQL_E_HIP, uq.UNIQL_E_ARCH)

@@ -410,3 +410,90 @@ def test_multi_call_mixed_shapes_and_tokens(env, uref):
         for qw, (_, _, kp), x, y in zip(qws, shapes, xs, ys):
             single = uq.uniql_w4_linear(qw, kp, x)
             assert torch.equal(single, y)
+
+
+# ------------------------------------------------- fused q / k / v projections + rotary embedding
+def _qkv_case(uq, torch, uref, specs, rope, rng):
+    """One token through uniql_w4_qkv_rope against the oracle's y = RoPE(x W).  The rotation preserves
+    norms, so q and k are judged with the metric of the linears (floor 1e-2 * rms of the tensor)."""
+    names = ("q_proj", "k_proj", "v_proj")
+    ws = [wl.gen_linear(rng, specs[n].N, specs[n].K) for n in names]
+    qws = [uq.QuantLinear.from_numpy(w) for w in ws]
+    keeps = [specs[n].keep for n in names]
+    x = wl.gen_activations(rng, 1, specs["q_proj"].k_keep)
+    r = wl.gen_rope_inputs(rng, rope)
+    pos, idx = r["positions"][:1].copy(), r["kept_idx"]
+    xd = to_dev(torch, x[0])
+    q, k, v = uq.uniql_w4_qkv_rope(qws, keeps, xd, to_dev(torch, pos), to_dev(torch, idx), rope.Hq, rope.Hkv,
+                                   rope.D_full, rope.D_keep, rope.theta)
+    torch.cuda.synchronize()
+    rq, rk, rv = uref.qkv_rope(ws[0], keeps[0], ws[1], keeps[1], ws[2], keeps[2], x, pos, idx, rope.Hq, rope.Hkv,
+                               rope.D_full, rope.D_keep, rope.theta)
+    # One launch (rotation of the fp32 sums) needs rows of a multiple of four groups and at most 16384
+    # columns; otherwise the entry point runs the separate kernels, which round q and k to fp16 before
+    # rotating: an extra error of up to 2^-11 of each member of the pair, so the floor is the pair's norm.
+    one_launch = (specs["q_proj"].K // 128) % 4 == 0 and specs["q_proj"].k_keep <= 16384
+
+    def qk_err(got, ref):
+        if one_launch:
+            return linear_err(got.cpu().numpy().reshape(1, -1), ref.reshape(1, -1))
+        hk = rope.D_keep // 2
+        pn = np.sqrt(ref[..., :hk] ** 2 + ref[..., hk:] ** 2)
+        pn = np.concatenate([pn, pn], axis=-1)
+        den = np.maximum(np.maximum(np.abs(ref), pn), 1e-2 * np.sqrt(np.mean(ref ** 2)))
+        return float(np.max(np.abs(got.cpu().numpy().astype(np.float64).reshape(ref.shape) - ref) / den))
+
+    errs = (qk_err(q, rq), qk_err(k, rk), linear_err(v.cpu().numpy().reshape(1, -1), rv.reshape(1, -1)))
+    # a second call returns the same bits
+    q2, k2, v2 = uq.uniql_w4_qkv_rope(qws, keeps, xd, to_dev(torch, pos), to_dev(torch, idx), rope.Hq, rope.Hkv,
+                                      rope.D_full, rope.D_keep, rope.theta)
+    assert torch.equal(q, q2) and torch.equal(k, k2) and torch.equal(v, v2)
+    # The separate calls round q and k to fp16 before rotating them, an error of up to 2^-11 of each
+    # member of a pair, so they are compared with the fused result relative to the pair's norm.
+    ys = [torch.empty((1, specs[n].n_keep), dtype=torch.float16, device="cuda") for n in names]
+    uq.uniql_w4_linear_multi(qws, keeps, [xd.view(1, -1)] * 3, ys)
+    qs, ks = ys[0].view(1, rope.Hq, rope.D_keep), ys[1].view(1, rope.Hkv, rope.D_keep)
+    uq.uniql_pruned_rope(qs, ks, to_dev(torch, pos), to_dev(torch, idx), rope.D_full, rope.theta)
+    torch.cuda.synchronize()
+    assert torch.equal(ys[2].view(-1), v)
+    sep = []
+    for fused_t, sep_t, ref in ((q, qs, rq), (k, ks, rk)):
+        hk = rope.D_keep // 2
+        pn = np.sqrt(ref[..., :hk] ** 2 + ref[..., hk:] ** 2)
+        pn = np.concatenate([pn, pn], axis=-1)
+        floor = 1e-2 * np.sqrt(np.mean(ref ** 2))
+        d = np.abs(fused_t.cpu().numpy().astype(np.float64).reshape(ref.shape) - sep_t.cpu().numpy().astype(np.float64).reshape(ref.shape))
+        sep.append(float(np.max(d / np.maximum(pn, floor))))
+    return errs, tuple(sep)
+
+
+@pytest.mark.parametrize("rate", [0, 15, 35])
+def test_fused_qkv_rope_llama3_8b(env, uref, rate):
+    uq, torch = env
+    specs = {s.name: s for s in wl.llama3_8b_layer(rate)}
+    errs, sep = _qkv_case(uq, torch, uref, specs, wl.llama3_8b_rope(rate, T=1), wl.rng_for(1, 70 + rate))
+    assert max(errs) <= TOL and max(sep) <= 2e-3, (errs, sep)
+
+
+def test_fused_qkv_rope_qwen25_7b(env, uref):
+    uq, torch = env
+    specs = {s.name: s for s in wl.qwen25_7b_layer(25)}
+    errs, sep = _qkv_case(uq, torch, uref, specs, wl.qwen25_7b_rope(25, T=1), wl.rng_for(2, 71))
+    assert max(errs) <= TOL and max(sep) <= 2e-3, (errs, sep)
+
+
+@pytest.mark.parametrize("hidden", [256, 512, 2176])
+def test_fused_qkv_rope_small_blocks(env, uref, hidden):
+    """Small attention blocks: 512 columns run fused; 256 (two groups per row) and 2176 (17 groups) take the
+    path of separate launches inside the same entry point."""
+    uq, torch = env
+    Hq, Hkv, D, Dk = 6, 2, 64, 50
+    hk = Dk // 2
+    specs = {
+        "q_proj": wl.LinearSpec("q_proj", K=hidden, N=Hq * D, keep=Keep(n_keep=Hq * Dk, row_seg_stride=D // 2, row_seg_keep=hk, row_seg_limit=Hq * D)),
+        "k_proj": wl.LinearSpec("k_proj", K=hidden, N=Hkv * D, keep=Keep(n_keep=Hkv * Dk, row_seg_stride=D // 2, row_seg_keep=hk, row_seg_limit=Hkv * D)),
+        "v_proj": wl.LinearSpec("v_proj", K=hidden, N=Hkv * D, keep=Keep(n_keep=Hkv * Dk, row_seg_stride=D, row_seg_keep=Dk, row_seg_limit=Hkv * D)),
+    }
+    rope = wl.RopeSpec(T=1, Hq=Hq, Hkv=Hkv, H_tab=Hkv, D_full=D, D_keep=Dk, theta=1.0e4, pos_max=4096)
+    errs, sep = _qkv_case(uq, torch, uref, specs, rope, wl.rng_for(0, 72 + hidden))
+    assert max(errs) <= TOL and max(sep) <= 2e-3, (errs, sep)
