@@ -31,9 +31,9 @@ METRIC = "µs and achieved HBM GB/s per pruned W4A16 decode linear (Llama-3-8B s
 HBM_PEAK_GBS = 8000.0
 MFMA_F16_PEAK_TFLOPS = 2500.0
 # HBM bytes per gate+up GEMV launch at pruning 15 %, from the two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE)
-# summarised in profiles/w4_gemv_llama3_8b_decode_p15.md: 25789.9 x 2.000 KiB read + 47.7 x 1.000 KiB written, each
+# summarised in profiles/w4_gemv_llama3_8b_decode_p15.md: 25783.0 x 2.000 KiB read + 47.6 x 1.000 KiB written, each
 # scaled by what the counter reads for a 256 MiB elementwise copy (--pmc-calib).  Other rates were not measured.
-PMC_TRAFFIC_BYTES = {15: int(25789.9 * 2.0 * 1024 * (262144 / 2.0 / 131086)) + int(47.7 * 1024)}
+PMC_TRAFFIC_BYTES = {15: int(25783.0 * 1024 * (262144 / 131086)) + int(47.6 * 1024)}
 
 
 def log(*a):
@@ -426,7 +426,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": PMC_TRAFFIC_BYTES.get(rate),
                      "traffic_unit": "bytes per launch (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, copy-kernel scaled)",
-                     "kernel": "w4_gemv_kernel<4,true,2> (gate_proj + up_proj in one launch)",
+                     "kernel": "w4_gemv_kernel<4,true,2,false> (gate_proj + up_proj in one launch)",
                      "bytes_per_launch": int(dom_bytes), "us_per_launch": round(dom_us, 3),
                      "stream_ceiling_GBps": round(ceil_gbs, 1),
                      "frac_of_stream_ceiling": round(achieved / ceil_gbs, 4),
