@@ -261,18 +261,6 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
                                                                   __builtin_bit_cast(half8_t, bfrag[t & 1][bf]),
                                                                   acc[af][bf], 0, 0, 0);
         }
-#ifdef UNIQL_SGB
-        // scheduling pipeline for this group: the first stage, then every MFMA followed by two
-        // VALU instructions, and one LDS read per BF MFMAs
-        __builtin_amdgcn_sched_group_barrier(0x100, AF, 0);
-        __builtin_amdgcn_sched_group_barrier(0x002, 13 * BF + 8, 0);
-#pragma unroll
-        for (int i = 0; i < 4 * AF * BF; ++i) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          if (i % BF == 0 && i < 3 * AF * BF) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x002, UNIQL_SGB, 0);
-        }
-#endif
       }
       load_w(it + PW, ring[p]);   // refill the ring slot (clamped past the end)
       if (it + 1 < nit_pw) store_x(buf ^ 1, xr);

@@ -315,6 +315,45 @@ def test_prefill_tiles_ragged(env, uref, N, K, keep, M):
     assert err <= TOL, err
 
 
+def _random_keep(rng, N, K):
+    """A random valid keep rule for an N x K matrix: prefixes or uniform segments on either side."""
+    kw = {}
+    mode = rng.integers(0, 4)
+    if mode == 1:
+        kw["n_keep"] = int(rng.integers(1, N + 1))
+    elif mode >= 2 and N >= 8:
+        stride = int(rng.choice([d for d in (8, 16, 32, 64, 128) if d <= N]))
+        limit = (int(rng.integers(1, N // stride + 1))) * stride
+        kw.update(row_seg_stride=stride, row_seg_keep=int(rng.integers(1, stride + 1)), row_seg_limit=limit)
+    mode = rng.integers(0, 4)
+    if mode == 1:
+        kw["k_keep"] = int(rng.integers(1, K + 1))
+    elif mode >= 2:
+        stride = int(rng.choice([d for d in (8, 16, 32, 64, 128, 256) if K % d == 0]))
+        kw.update(col_seg_stride=stride, col_seg_keep=int(rng.integers(1, stride + 1)))
+    return Keep(**kw)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_linear_random_shapes(env, uref, seed):
+    """Seeded random shapes, keep rules and token counts through every kernel selection (GEMV, K-split
+    decode batches, all prefill tiles), each against the full oracle output."""
+    uq, torch = env
+    rng = wl.rng_for(6, seed)
+    K = 128 * int(rng.choice([1, 2, 3, 4, 7, 8, 9, 12, 16, 17, 24, 32]))
+    N = int(rng.choice([1, 5, 16, 17, 48, 100, 256, 300, 513, 700]))
+    M = int(rng.choice([1, 1, 2, 7, 16, 17, 33, 64, 65, 130, 257]))
+    keep = _random_keep(rng, N, K)
+    w = wl.gen_linear(rng, N, K)
+    qw = uq.QuantLinear.from_numpy(w)
+    nk, kk = uq.kept_dims(qw, keep)
+    x = wl.gen_activations(rng, M, kk)
+    ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], x, keep)
+    y = run_linear(uq, torch, w, qw, keep, x, pad=int(rng.integers(0, 4)))
+    assert y.shape == (M, nk)
+    assert linear_err(y, ref) <= TOL, (N, K, M, keep)
+
+
 # --------------------------------------------------------------------- RoPE
 def run_rope(uq, torch, r, spec):
     q = to_dev(torch, r["q"])
