@@ -387,6 +387,28 @@ def test_rope_parity(env, uref, spec):
     assert np.max(np.abs(n_in - n_out) / np.maximum(n_in, 1e-3)) < 4e-3
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_rope_random_shapes(env, uref, seed):
+    """Seeded random head counts, table rows, head dimensions (odd and even pair counts), token counts that
+    span one item per thread, one batch and several batches, with and without K."""
+    uq, torch = env
+    rng = wl.rng_for(7, seed)
+    H_tab = int(rng.choice([1, 2, 4, 8]))
+    Hkv = H_tab * int(rng.choice([0, 1, 2]))
+    Hq = H_tab * int(rng.choice([1, 2, 4, 7]))
+    D_full = int(rng.choice([8, 32, 64, 128, 256]))
+    D_keep = 2 * int(rng.integers(1, D_full // 2 + 1))
+    T = int(rng.choice([1, 2, 3, 9, 40, 97, 300]))
+    spec = wl.RopeSpec(T=T, Hq=Hq, Hkv=Hkv, H_tab=H_tab, D_full=D_full, D_keep=D_keep,
+                       theta=float(rng.choice([1.0e4, 5.0e5, 1.0e6])), pos_max=int(rng.choice([64, 4096, 131072])))
+    r = wl.gen_rope_inputs(rng, spec)
+    qo, ko = uref.pruned_rope(r["q"], r["k"], r["positions"], r["kept_idx"], spec.D_full, spec.theta)
+    gq, gk = run_rope(uq, torch, r, spec)
+    assert rope_err(gq, qo) <= TOL, spec
+    if ko is not None:
+        assert rope_err(gk, ko) <= TOL, spec
+
+
 def test_rope_prefill_full_size(env, uref):
     """[4096 tokens, 32 Q + 8 KV heads, 108 of 128 dims], positions 0..4095: every element against the oracle."""
     uq, torch = env
