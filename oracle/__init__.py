@@ -171,6 +171,14 @@ def qkv_rope(wq, keep_q, wk, keep_k, wv, keep_v, x, positions, kept_idx, Hq: int
             pruned_rope_f64(k, positions, kept_idx, D_full, theta), v)
 
 
+def gate_up_silu(wg, keep_g, wu, keep_u, x):
+    """The gated MLP's hidden vector h = sigma(x W_gate) * (x W_up) of Eq. 1 with sigma = SiLU
+    (g / (1 + exp(-g))), fp64: each w* is a dict(qweight, scales, zeros); x is fp16 [T][k_keep]."""
+    g = w4_linear(wg["qweight"], wg["scales"], wg["zeros"], x, keep_g)
+    u = w4_linear(wu["qweight"], wu["scales"], wu["zeros"], x, keep_u)
+    return g / (1.0 + np.exp(-g)) * u
+
+
 def _quantize(fn, w: np.ndarray, group: int):
     w = np.ascontiguousarray(w, dtype=np.float64)
     N, K = w.shape

@@ -302,3 +302,30 @@ def test_symmetric_is_the_zero_8_case(uref):
     assert signed.min() >= -8 and signed.max() <= 7
     exp = (signed * w["scales"].astype(np.float64)).astype(np.float16).astype(np.float64)
     assert np.array_equal(Wd, exp)
+
+
+def test_gate_up_silu_is_numpy_matmul_then_silu(uref):
+    """h = SiLU(x Wg) * (x Wu) (Eq. 1) against an independently unpacked dense weight, numpy matmul and
+    the textbook SiLU written with tanh: x * (1 + tanh(x / 2)) / 2."""
+    rng = wl.rng_for(0, 24)
+    N, K, T = 96, 256, 3
+    keep = wl.Keep(n_keep=81)
+    wg, wu = wl.gen_linear(rng, N, K), wl.gen_linear(rng, N, K)
+    x = wl.gen_activations(rng, T, K)
+    h = uref.gate_up_silu(wg, keep, wu, keep, x)
+
+    def dense(w):
+        qw = w["qweight"]
+        nib = np.stack([(qw >> np.uint32(4 * j)) & np.uint32(15) for j in range(8)], axis=-1).reshape(qw.shape[0], -1)
+        s = np.repeat(w["scales"].astype(np.float64), 128, axis=1)
+        z = np.repeat(w["zeros"].astype(np.float64), 128, axis=1)
+        return ((nib.astype(np.float64) - z) * s).astype(np.float16).astype(np.float64)
+
+    xf = x.astype(np.float64)
+    g, u = (xf @ dense(wg).T)[:, :81], (xf @ dense(wu).T)[:, :81]
+    ref = g * (1.0 + np.tanh(g / 2.0)) / 2.0 * u
+    assert h.shape == (T, 81)
+    assert np.max(np.abs(h - ref)) < 1e-9 * max(1.0, np.max(np.abs(ref)))
+    # the gate closes for very negative pre-activations and passes very positive ones unchanged
+    big = np.array([[-60.0, 60.0]])
+    assert np.allclose(big / (1.0 + np.exp(-big)), [[0.0, 60.0]], atol=1e-20, rtol=1e-15)
