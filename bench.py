@@ -3,9 +3,9 @@
 
 A step is one pass of the whole hot path over one Llama-3-8B shaped decoder
 layer at batch 1: q/k/v projections with the pruned RoPE of the fresh Q/K heads
-as the epilogue of their launch, o_proj, gate/up (one launch), down -- seven W4A16
-linears and the rotation in four launches, all through the C ABI
-(--separate-rope: five launches).  Consecutive steps walk through a pool of distinct layers (a 32-layer
+as the epilogue of their launch, o_proj, gate/up with h = SiLU(gate) * up as the
+epilogue of their launch, down -- seven W4A16 linears, the rotation and the
+activation in four launches, all through the C ABI (--separate-rope: five).  Consecutive steps walk through a pool of distinct layers (a 32-layer
 model, several GB), so every step streams its weights from HBM, not from the
 256 MB Infinity Cache.  Inputs are seeded synthetic stand-ins (random nibbles,
 fp16 scales ~ U(0.005, 0.02), zeros ~ U{0..15}, activations ~ N(0, 1)).
@@ -30,10 +30,10 @@ import workloads as wl  # noqa: E402
 METRIC = "µs and achieved HBM GB/s per pruned W4A16 decode linear (Llama-3-8B shapes)"
 HBM_PEAK_GBS = 8000.0
 MFMA_F16_PEAK_TFLOPS = 2500.0
-# HBM bytes per gate+up GEMV launch at pruning 15 %, from the two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE)
-# summarised in profiles/w4_gemv_llama3_8b_decode_p15.md: 25783.0 x 2.000 KiB read + 47.6 x 1.000 KiB written, each
+# HBM bytes per gate+up+SiLU GEMV launch at pruning 15 %, from the two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE)
+# summarised in profiles/w4_gemv_llama3_8b_decode_p15.md: 25713.1 x 2.000 KiB read + 23.8 x 1.000 KiB written, each
 # scaled by what the counter reads for a 256 MiB elementwise copy (--pmc-calib).  Other rates were not measured.
-PMC_TRAFFIC_BYTES = {15: int(25783.0 * 1024 * (262144 / 131086)) + int(47.6 * 1024)}
+PMC_TRAFFIC_BYTES = {15: int(25713.1 * 1024 * (262144 / 131086)) + int(23.8 * 1024)}
 
 
 def log(*a):
@@ -118,6 +118,18 @@ class DecodeStep:
                 self.yout["v_proj"].view(-1), self.pos[:1], self.idx, r.D_full, r.theta)
         return self._calls[key]
 
+    def gate_up_call(self, layer):
+        """Marshalled uniql_w4_gate_up_silu call of one layer (cached): gate, up and SiLU(gate) * up in one launch."""
+        key = (id(layer), "gate_up_silu")
+        if key not in self._calls:
+            sp = {s.name: s for s in self.specs}
+            if not hasattr(self, "hbuf"):
+                self.hbuf = self.torch.empty((sp["gate_proj"].n_keep,), dtype=self.torch.float16, device="cuda")
+            self._calls[key] = self.uq.GateUpCall([layer.lin["gate_proj"], layer.lin["up_proj"]],
+                                                  [sp["gate_proj"].keep, sp["up_proj"].keep],
+                                                  self.xin["gate_proj"][0], self.hbuf)
+        return self._calls[key]
+
     def run(self, layer, only=None, fused=True, fuse_rope=True):
         """One step: q/k/v with the rotation of the fresh Q/K heads (one launch; fuse_rope=False: one
         launch for q/k/v, one for the rotation), o_proj, gate/up (one launch), down.
@@ -126,6 +138,8 @@ class DecodeStep:
         if only is not None:
             if only == "qkv_rope":
                 self.qkv_rope_call(layer).run()
+            elif only == "gate_up_silu":
+                self.gate_up_call(layer).run()
             elif isinstance(only, tuple):
                 self.multi_call(layer, only).run()
             else:
@@ -145,7 +159,10 @@ class DecodeStep:
             self.multi_call(layer, self.FUSED[0]).run()
             self.rope_qk()
         uq.uniql_w4_linear(layer.lin["o_proj"], sp["o_proj"].keep, self.xin["o_proj"], self.yout["o_proj"])
-        self.multi_call(layer, self.FUSED[1]).run()
+        if self.M == 1:
+            self.gate_up_call(layer).run()     # gate, up and h = SiLU(gate) * up (Eq. 1) in one launch
+        else:
+            self.multi_call(layer, self.FUSED[1]).run()
         uq.uniql_w4_linear(layer.lin["down_proj"], sp["down_proj"].keep, self.xin["down_proj"], self.yout["down_proj"])
 
 
@@ -360,11 +377,13 @@ def main():
     # stream around a graph that issues that one linear back to back over the whole layer pool
     # (cold weights every launch, no host launch cost inside the bracket)
     first = "qkv_rope" if fuse_rope else DecodeStep.FUSED[0]
-    names = [first, "o_proj", DecodeStep.FUSED[1], "down_proj"]
+    names = [first, "o_proj", "gate_up_silu", "down_proj"]
     lin_bytes = dict(lin_bytes)
     for grp in DecodeStep.FUSED:
         lin_bytes[grp] = sum(lin_bytes[n] for n in grp)
     lin_bytes["qkv_rope"] = lin_bytes[DecodeStep.FUSED[0]] + rope.algorithmic_bytes()
+    # gate + up with the activation as epilogue writes one hidden vector instead of two
+    lin_bytes["gate_up_silu"] = lin_bytes[DecodeStep.FUSED[1]] - 2 * next(s for s in specs if s.name == "gate_proj").n_keep
     iso_us = {}
     for n in names:
         if args.no_graph:
@@ -381,12 +400,12 @@ def main():
     per_linear = {n: {"MB": round(lin_bytes[n] / 1e6, 3), "us": round(iso_us[n], 3),
                       "GBps": round(lin_bytes[n] / (iso_us[n] * 1e-6) / 1e9, 1),
                       "frac_of_peak": round(lin_bytes[n] / (iso_us[n] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)} for n in names}
-    per_linear = {("+".join(k) if isinstance(k, tuple) else k.replace("qkv_rope", "q_proj+k_proj+v_proj+rope")): v
+    per_linear = {("+".join(k) if isinstance(k, tuple) else k.replace("qkv_rope", "q_proj+k_proj+v_proj+rope").replace("gate_up_silu", "gate_proj+up_proj+silu")): v
                   for k, v in per_linear.items()}
     for n, v in per_linear.items():
         log(f"  {n:22s} {v}")
     # the dominant kernel of the step: the GEMV launch that serves gate_proj and up_proj together
-    dom = [DecodeStep.FUSED[1]]
+    dom = ["gate_up_silu"]
     dom_bytes = float(np.mean([lin_bytes[n] for n in dom]))
     dom_us = float(np.mean([iso_us[n] for n in dom]))
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
@@ -417,7 +436,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"Llama-3-8B shaped decode layer, batch 1, int4 group-128 weights, "
                                f"pruning {rate}% (q+k+v{' with the pruned RoPE as epilogue' if fuse_rope else ', pruned RoPE'}, "
-                               f"o, gate+up, down: W4A16 GEMV launches), "
+                               f"o, gate+up with SiLU(gate)*up as epilogue, down: W4A16 GEMV launches), "
                                f"{args.layers}-layer weight pool streamed from HBM",
                    "prune_pct": rate, "M": M, "launch": "hip-graph over the layer pool" if graphs else "eager",
                    "step_algorithmic_MB": round(step_bytes / 1e6, 3)},
@@ -426,11 +445,11 @@ def main():
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": PMC_TRAFFIC_BYTES.get(rate),
                      "traffic_unit": "bytes per launch (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, copy-kernel scaled)",
-                     "kernel": "w4_gemv_kernel<4,true,2,false> (gate_proj + up_proj in one launch)",
+                     "kernel": "w4_gemv_kernel<4,true,2,2> (gate_proj + up_proj + SiLU(gate)*up in one launch)",
                      "bytes_per_launch": int(dom_bytes), "us_per_launch": round(dom_us, 3),
                      "stream_ceiling_GBps": round(ceil_gbs, 1),
                      "frac_of_stream_ceiling": round(achieved / ceil_gbs, 4),
-                     "how": "algorithmic bytes of the gate+up launch / its mean duration, HIP events on the launch "
+                     "how": "algorithmic bytes of the gate+up+SiLU launch / its mean duration, HIP events on the launch "
                             "stream around a graph of back-to-back launches over the layer pool (cold HBM)"},
     }
     if args.pmc_calib:

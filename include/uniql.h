@@ -177,6 +177,22 @@ int uniql_w4_qkv_rope(const uniql_w4_t* W, const uniql_keep_t* keep, const void*
                       double theta, void* hip_stream);
 
 /*
+ * Hidden vector of the gated MLP for one token in ONE launch (Eq. 1):
+ *   h = sigma(x W_gate') * (x W_up'),  sigma = SiLU: g / (1 + exp(-g))
+ * with the linears of uniql_w4_linear; gate and up sums stay in fp32 until h is rounded to fp16 once.
+ *   W, keep : host arrays of 2 entries (gate, up); keep may be NULL.  Both must keep the same number of
+ *             rows and the same columns (they read one x and fill one h).
+ *   x_f16   : device fp16 [k_keep], one token;  h_f16 : device fp16 [n_keep]
+ * The library has no scratch memory for separate gate and up vectors, so shapes that cannot share one
+ * launch are refused: rows longer than 16384 kept columns, or a group count per row that is not a
+ * multiple of 4 (E_SHAPE; run uniql_w4_linear_multi and the activation yourself).
+ * Errors: as uniql_w4_linear; E_KEEP when the two members keep different rows in number or different
+ * columns; E_SHAPE as above.
+ */
+int uniql_w4_gate_up_silu(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_f16, void* h_f16,
+                          void* hip_stream);
+
+/*
  * Measurement aid, not part of the method: reads `bytes` of device memory at `src`
  * (16-byte aligned) once with wave-wide 128-bit loads, the access shape of the GEMV's
  * weight stream, and writes one xor word per 8 KB to `out_words` (device, at least

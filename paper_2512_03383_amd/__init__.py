@@ -72,6 +72,8 @@ def lib():
         L.uniql_w4_qkv_rope.restype = C.c_int
         L.uniql_w4_qkv_rope.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, vp, vp, vp, vp, vp,
                                         i32, i32, i32, i32, i32, C.c_double, vp]
+        L.uniql_w4_gate_up_silu.restype = C.c_int
+        L.uniql_w4_gate_up_silu.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, vp, vp]
         L.uniql_stream_read_probe.argtypes = [vp, i64, vp, vp]
         L.uniql_strerror.restype = C.c_char_p
         L.uniql_strerror.argtypes = [C.c_int]
@@ -263,6 +265,32 @@ def uniql_w4_qkv_rope(Ws, keeps, x, position, kept_idx, Hq: int, Hkv: int, D_ful
     v = torch.empty((kept_dims(Ws[2], keeps[2])[0],), dtype=torch.float16, device=x.device)
     QkvRopeCall(Ws, keeps, x, q, k, v, position, kept_idx, D_full, theta).run(stream)
     return q, k, v
+
+
+class GateUpCall:
+    """Marshalled arguments of one uniql_w4_gate_up_silu call, reusable (e.g. for graph capture)."""
+
+    def __init__(self, Ws, keeps, x, h):
+        import torch
+        assert len(Ws) == 2 and len(keeps) == 2
+        for t in (x, h):
+            assert t.dtype == torch.float16 and t.is_cuda and t.is_contiguous() and t.dim() == 1
+        self.W = (W4 * 2)(*[w.desc() for w in Ws])
+        self.keep = (KeepDesc * 2)(*[(_keep_desc(kp) or KeepDesc()) for kp in keeps])
+        self.x, self.h = C.c_void_p(x.data_ptr()), C.c_void_p(h.data_ptr())
+        self._refs = (Ws, x, h)
+
+    def run(self, stream=None):
+        _check(lib().uniql_w4_gate_up_silu(self.W, self.keep, self.x, self.h, _stream_ptr(stream)))
+
+
+def uniql_w4_gate_up_silu(Ws, keeps, x, h=None, stream=None):
+    """h = SiLU(x W_gate') * (x W_up') for one token x [k_keep]; returns fp16 h [n_keep]."""
+    import torch
+    if h is None:
+        h = torch.empty((kept_dims(Ws[0], keeps[0])[0],), dtype=torch.float16, device=x.device)
+    GateUpCall(Ws, keeps, x, h).run(stream)
+    return h
 
 
 def uniql_stream_read_probe(src, nbytes: int, out, stream=None):

@@ -235,6 +235,29 @@ extern "C" int uniql_w4_qkv_rope(const uniql_w4_t* W, const uniql_keep_t* keep, 
   return e == hipSuccess ? UNIQL_OK : hip_fail(e);
 }
 
+extern "C" int uniql_w4_gate_up_silu(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_f16, void* h_f16,
+                                     void* hip_stream) {
+  if (!W) return UNIQL_E_NULL;
+  LinearArgs a[2];
+  for (int i = 0; i < 2; ++i) {
+    KeepMap km;
+    int rc = make_keepmap(&W[i], keep ? &keep[i] : nullptr, &km);
+    if (rc) return rc;
+    // both members write their sums to LDS only; h takes the place of y in the descriptor of either
+    rc = fill_linear(&W[i], keep ? &keep[i] : nullptr, x_f16, km.k_keep, h_f16, km.n_keep, 1, &a[i]);
+    if (rc) return rc;
+  }
+  // one x and one h: the same kept rows in number, the same rule for the kept columns
+  if (a[0].km.n_keep != a[1].km.n_keep || a[0].K_total != a[1].K_total || a[0].km.k_keep != a[1].km.k_keep ||
+      a[0].km.cs_stride != a[1].km.cs_stride || a[0].km.cs_keep != a[1].km.cs_keep) return UNIQL_E_KEEP;
+  int rc = check_arch();
+  if (rc) return rc;
+  bool fused = false;
+  hipError_t e = launch_w4_gate_up_silu(a, (hipStream_t)hip_stream, &fused);
+  if (e != hipSuccess) return e == hipErrorInvalidValue ? UNIQL_E_SHAPE : hip_fail(e);
+  return fused ? UNIQL_OK : UNIQL_E_SHAPE;   // no scratch to fall back on: the caller runs the two linears itself
+}
+
 extern "C" int uniql_stream_read_probe(const void* src, int64_t bytes, void* out_words, void* hip_stream) {
   if (!src || !out_words) return UNIQL_E_NULL;
   if (bytes < 0) return UNIQL_E_SHAPE;

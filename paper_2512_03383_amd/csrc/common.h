@@ -158,6 +158,8 @@ hipError_t launch_w4_gemv_batch(const LinearArgs* probs, int n, hipStream_t stre
 // q, k, v of one token with the rotation of q and k fused into the launch; *fused = false (and nothing
 // launched) when the shapes do not allow it
 hipError_t launch_w4_qkv_rope(const LinearArgs* probs, const RopeFuse& rf, hipStream_t stream, bool* fused);
+// gate and up of one token (probs[0], probs[1], same x) with h = SiLU(gate) * up written to probs[0].y
+hipError_t launch_w4_gate_up_silu(const LinearArgs* probs, hipStream_t stream, bool* fused);
 hipError_t launch_w4_gemm(const LinearArgs& a, hipStream_t stream);
 hipError_t launch_w4_dequant(const LinearArgs& a, hipStream_t stream);
 

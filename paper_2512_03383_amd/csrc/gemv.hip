@@ -70,26 +70,35 @@ __device__ __forceinline__ ColMap make_colmap(const KeepMap& km) {
 // compile-time, 1..8 (NCH = 0: run-time chunk count for rows longer than 8 chunks).
 // The launch carries up to kMaxBatch independent linears (same R / XVEC / NCH, e.g. q, k and v
 // of one layer, or gate and up): problem i owns the blocks [first_block[i], first_block[i+1]).
-// ROPE (R = 1 only): problems with batch.rf.heads[i] > 0 get the rotary embedding of their output as
+// EPI = 1 (R = 1 only): problems with batch.rf.heads[i] > 0 get the rotary embedding of their output as
 // an epilogue.  Their blocks own four kept pairs instead of eight consecutive rows: waves 0..3 compute
 // the first-half rows of the pairs, waves 4..7 the second-half rows, the two fp32 sums of a pair meet
 // in LDS and are rotated before the one rounding to fp16.  The pair's sin / cos are formed while the
 // weight stream is in flight, with the arithmetic of the stand-alone RoPE kernel.
-template <int R, bool XVEC, int NCH, bool ROPE = false>
+// EPI = 2: the launch holds exactly two problems, gate and up of a gated MLP (Eq. 1), over the same x.
+// Waves 0..3 of a block compute R gate rows each, waves 4..7 the up rows of the same indices; the
+// sums meet in LDS and h = SiLU(gate) * up is written to the first problem's y.
+template <int R, bool XVEC, int NCH, int EPI = 0>
 __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, int m, int nchunk_rt) {
+  constexpr bool ROPE = EPI == 1, GLU = EPI == 2;
   static_assert(!ROPE || R == 1, "the rotary epilogue pairs single-row waves");
   extern __shared__ __align__(16) unsigned char smem[];
   uint4* xs = reinterpret_cast<uint4*>(smem);   // [nchunk][4][64] units of 8 halves
 
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   int pi = 0;
+  if (GLU) {
+    pi = wave >> 2;   // wave-uniform: gate for the lower four waves, up for the upper four
+  } else {
 #pragma unroll
-  for (int i = 1; i < kMaxBatch; ++i) pi += (i < batch.n && (int)blockIdx.x >= batch.first_block[i]) ? 1 : 0;
+    for (int i = 1; i < kMaxBatch; ++i) pi += (i < batch.n && (int)blockIdx.x >= batch.first_block[i]) ? 1 : 0;
+  }
   const LinearArgs& a = batch.p[pi];
-  const int block_id = (int)blockIdx.x - batch.first_block[pi];
+  const int block_id = (int)blockIdx.x - batch.first_block[GLU ? 0 : pi];
   const KeepMap& km = a.km;
   const int nchunk = NCH > 0 ? NCH : nchunk_rt;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int rg = block_id * kGemvWaves + wave;   // row group of this wave
+  const int rg = GLU ? block_id * 4 + (wave & 3) : block_id * kGemvWaves + wave;   // row group of this wave
   const int k_span32 = (km.k_span + 31) & ~31;
   const int words_per_row = a.K_total >> 3;
   const int groups_per_row = a.K_total / kGroup;
@@ -357,6 +366,22 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
     if (lane == 0 && rope_ok) a.y[(size_t)m * a.ldy + rope_row] = (half_t)out;
     return;
   }
+  if (GLU) {
+    __shared__ float glu_sum[kGemvWaves][R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const float v = dpp_xor_reduce(acc[r]);
+      if (lane == 0) glu_sum[wave][r] = v;
+    }
+    __syncthreads();
+    if (wave < 4 && lane < R) {
+      const float g = glu_sum[wave][lane], u = glu_sum[wave + 4][lane];
+      const int rc = rg * R + lane;
+      // SiLU(g) * u; exp and the reciprocal are the hardware approximations (about 1 ulp of fp32)
+      if (rc < km.n_keep) batch.p[0].y[(size_t)m * batch.p[0].ldy + rc] = (half_t)(g * u * __builtin_amdgcn_rcpf(1.0f + __expf(-g)));
+    }
+    return;
+  }
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     const float v = dpp_xor_reduce(acc[r]);
@@ -371,10 +396,11 @@ static int blocks_for(const LinearArgs& a) {
   return (row_groups + kGemvWaves - 1) / kGemvWaves;
 }
 
-template <int R, bool XVEC, int NCH, bool ROPE = false>
+template <int R, bool XVEC, int NCH, int EPI = 0>
 static hipError_t launch_one(const LinearArgs* probs, int n, int m, int nchunk, hipStream_t stream, const RopeFuse* rf = nullptr) {
   const size_t smem = (size_t)nchunk * 4096;
-  auto kern = w4_gemv_kernel<R, XVEC, NCH, ROPE>;
+  auto kern = w4_gemv_kernel<R, XVEC, NCH, EPI>;
+  constexpr bool ROPE = EPI == 1, GLU = EPI == 2;
   if (smem > 160 * 1024) return hipErrorInvalidValue;
   if (smem > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -391,6 +417,7 @@ static hipError_t launch_one(const LinearArgs* probs, int n, int m, int nchunk, 
     if (i >= n) continue;
     // a rotated problem: four kept pairs per block; otherwise eight waves of R rows
     if (ROPE && b.rf.heads[i] > 0) blocks += (b.rf.heads[i] * (b.rf.D_keep / 2) + 3) / 4;
+    else if (GLU) blocks += i == 0 ? (probs[0].km.n_keep + 4 * R - 1) / (4 * R) : 0;   // a block = 4 R gate rows + their up rows
     else blocks += blocks_for<R>(probs[i]);
   }
   hipLaunchKernelGGL(kern, dim3(blocks), dim3(kGemvThreads), smem, stream, b, m, nchunk);
@@ -467,15 +494,44 @@ hipError_t launch_w4_gemv_batch(const LinearArgs* probs, int n, hipStream_t stre
 template <bool XVEC>
 static hipError_t launch_rope_nch(const LinearArgs* probs, int nchunk, hipStream_t stream, const RopeFuse& rf) {
   switch (nchunk) {
-    case 1: return launch_one<1, XVEC, 1, true>(probs, 3, 0, nchunk, stream, &rf);
-    case 2: return launch_one<1, XVEC, 2, true>(probs, 3, 0, nchunk, stream, &rf);
-    case 3: return launch_one<1, XVEC, 3, true>(probs, 3, 0, nchunk, stream, &rf);
-    case 4: return launch_one<1, XVEC, 4, true>(probs, 3, 0, nchunk, stream, &rf);
-    case 5: return launch_one<1, XVEC, 5, true>(probs, 3, 0, nchunk, stream, &rf);
-    case 6: return launch_one<1, XVEC, 6, true>(probs, 3, 0, nchunk, stream, &rf);
-    case 7: return launch_one<1, XVEC, 7, true>(probs, 3, 0, nchunk, stream, &rf);
-    default: return launch_one<1, XVEC, 8, true>(probs, 3, 0, nchunk, stream, &rf);
+    case 1: return launch_one<1, XVEC, 1, 1>(probs, 3, 0, nchunk, stream, &rf);
+    case 2: return launch_one<1, XVEC, 2, 1>(probs, 3, 0, nchunk, stream, &rf);
+    case 3: return launch_one<1, XVEC, 3, 1>(probs, 3, 0, nchunk, stream, &rf);
+    case 4: return launch_one<1, XVEC, 4, 1>(probs, 3, 0, nchunk, stream, &rf);
+    case 5: return launch_one<1, XVEC, 5, 1>(probs, 3, 0, nchunk, stream, &rf);
+    case 6: return launch_one<1, XVEC, 6, 1>(probs, 3, 0, nchunk, stream, &rf);
+    case 7: return launch_one<1, XVEC, 7, 1>(probs, 3, 0, nchunk, stream, &rf);
+    default: return launch_one<1, XVEC, 8, 1>(probs, 3, 0, nchunk, stream, &rf);
   }
+}
+
+template <int R, bool XVEC>
+static hipError_t launch_glu_nch(const LinearArgs* probs, int nchunk, hipStream_t stream) {
+  switch (nchunk) {
+    case 1: return launch_one<R, XVEC, 1, 2>(probs, 2, 0, nchunk, stream);
+    case 2: return launch_one<R, XVEC, 2, 2>(probs, 2, 0, nchunk, stream);
+    case 3: return launch_one<R, XVEC, 3, 2>(probs, 2, 0, nchunk, stream);
+    case 4: return launch_one<R, XVEC, 4, 2>(probs, 2, 0, nchunk, stream);
+    case 5: return launch_one<R, XVEC, 5, 2>(probs, 2, 0, nchunk, stream);
+    case 6: return launch_one<R, XVEC, 6, 2>(probs, 2, 0, nchunk, stream);
+    case 7: return launch_one<R, XVEC, 7, 2>(probs, 2, 0, nchunk, stream);
+    default: return launch_one<R, XVEC, 8, 2>(probs, 2, 0, nchunk, stream);
+  }
+}
+
+// gate and up of one token with h = SiLU(gate) * up as epilogue, written to probs[0].y; *fused = false
+// (nothing launched) when the shapes do not allow it
+hipError_t launch_w4_gate_up_silu(const LinearArgs* probs, hipStream_t stream, bool* fused) {
+  bool ok = probs[0].M == 1 && probs[1].M == 1 && nchunk_of(probs[0]) == nchunk_of(probs[1]) &&
+            xvec_of(probs[0], 0) == xvec_of(probs[1], 0) && nchunk_of(probs[0]) >= 1 && nchunk_of(probs[0]) <= 8 &&
+            (probs[0].K_total / kGroup) % 4 == 0 && (probs[1].K_total / kGroup) % 4 == 0;
+  *fused = ok;
+  if (!ok) return hipSuccess;
+  const int rows = 2 * probs[0].km.n_keep, nch = nchunk_of(probs[0]);
+  const bool xv = xvec_of(probs[0], 0);
+  if (rows >= 16384) return xv ? launch_glu_nch<4, true>(probs, nch, stream) : launch_glu_nch<4, false>(probs, nch, stream);
+  if (rows >= 6144) return xv ? launch_glu_nch<2, true>(probs, nch, stream) : launch_glu_nch<2, false>(probs, nch, stream);
+  return xv ? launch_glu_nch<1, true>(probs, nch, stream) : launch_glu_nch<1, false>(probs, nch, stream);
 }
 
 hipError_t launch_w4_qkv_rope(const LinearArgs* probs, const RopeFuse& rf, hipStream_t stream, bool* fused) {

@@ -161,6 +161,25 @@ def test_qkv_rope_rejects_bad_arguments():
     assert _qkv(ws=[_w(N=256), _w(N=128, group=64), _w(N=128)]) == uq.UNIQL_E_SHAPE
 
 
+def _glu(ws=None, keeps=None, x=P, h=P):
+    ws = ws if ws is not None else [_w(), _w()]
+    W = (W4 * 2)(*ws)
+    K = (KeepDesc * 2)(*keeps) if keeps is not None else None
+    return uq.lib().uniql_w4_gate_up_silu(W, K, C.c_void_p(x), C.c_void_p(h), None)
+
+
+def test_gate_up_silu_rejects_bad_arguments():
+    assert uq.lib().uniql_w4_gate_up_silu(None, None, C.c_void_p(P), C.c_void_p(P), None) == uq.UNIQL_E_NULL
+    assert _glu(x=0) == uq.UNIQL_E_NULL
+    assert _glu(h=0) == uq.UNIQL_E_NULL
+    assert _glu(ws=[_w(), _w(group=64)]) == uq.UNIQL_E_SHAPE
+    assert _glu(h=P + 1) == uq.UNIQL_E_ALIGN
+    assert _glu(keeps=[KeepDesc(n_keep=100), KeepDesc(n_keep=101)]) == uq.UNIQL_E_KEEP
+    assert _glu(keeps=[KeepDesc(k_keep=100), KeepDesc(k_keep=104)]) == uq.UNIQL_E_KEEP
+    assert _glu(ws=[_w(), _w(K=1024)]) == uq.UNIQL_E_KEEP
+    assert _glu(keeps=[KeepDesc(col_seg_stride=128, col_seg_keep=64), KeepDesc(k_keep=256)]) == uq.UNIQL_E_KEEP
+
+
 def test_valid_arguments_without_gfx950_fail_loudly():
     """On a box without an MI355X a valid call must report E_HIP / E_ARCH, never pretend to work."""
     import torch
@@ -170,3 +189,4 @@ def test_valid_arguments_without_gfx950_fail_loudly():
     assert _rope() in (uq.UNIQL_E_HIP, uq.UNIQL_E_ARCH)
     assert _multi() in (uq.UNIQL_E_HIP, uq.UNIQL_E_ARCH)
     assert _qkv() in (uq.UNIQL_E_HIP, uq.UNIQL_E_ARCH)
+    assert _glu() in (uq.UNIQL_E_HIP, uq.UNIQL_E_ARCH)

@@ -558,3 +558,38 @@ def test_fused_qkv_rope_small_blocks(env, uref, hidden):
     rope = wl.RopeSpec(T=1, Hq=Hq, Hkv=Hkv, H_tab=Hkv, D_full=D, D_keep=Dk, theta=1.0e4, pos_max=4096)
     errs, sep = _qkv_case(uq, torch, uref, specs, rope, wl.rng_for(0, 72 + hidden))
     assert max(errs) <= TOL and max(sep) <= 2e-3, (errs, sep)
+
+
+# ------------------------------------------------- gated MLP hidden vector: SiLU(x W_gate) * (x W_up)
+@pytest.mark.parametrize("N,K,keep", [
+    (14336, 4096, Keep(n_keep=12185)),     # Llama-3-8B gate / up at 15 %: four rows per wave
+    (14336, 4096, Keep(n_keep=9318)),      # 35 %
+    (18944, 3584, Keep(n_keep=14208)),     # Qwen2.5-7B at 25 %
+    (4000, 1024, Keep(n_keep=3333)),       # two rows per wave
+    (1030, 512, Keep()),                   # one row per wave, ragged last block
+    (300, 2048, Keep(n_keep=7, k_keep=1500)),   # column prefix as well
+    (512, 1024, Keep(k_keep=8 * 108, col_seg_stride=128, col_seg_keep=108)),   # column segments
+])
+def test_gate_up_silu(env, uref, N, K, keep):
+    uq, torch = env
+    rng = wl.rng_for(8, N + K)
+    wg, wu = wl.gen_linear(rng, N, K), wl.gen_linear(rng, N, K)
+    qg, qu = uq.QuantLinear.from_numpy(wg), uq.QuantLinear.from_numpy(wu)
+    nk, kk = uq.kept_dims(qg, keep)
+    x = wl.gen_activations(rng, 1, kk)
+    h = uq.uniql_w4_gate_up_silu([qg, qu], [keep, keep], to_dev(torch, x[0]))
+    h2 = uq.uniql_w4_gate_up_silu([qg, qu], [keep, keep], to_dev(torch, x[0]))
+    torch.cuda.synchronize()
+    assert torch.equal(h, h2)
+    ref = uref.gate_up_silu(wg, keep, wu, keep, x)
+    assert h.shape == (nk,)
+    assert linear_err(h.cpu().numpy().reshape(1, -1), ref) <= TOL
+
+
+def test_gate_up_silu_refuses_what_it_cannot_fuse(env):
+    uq, torch = env
+    rng = wl.rng_for(8, 1)
+    w = wl.gen_linear(rng, 64, 256)       # two groups per row: not a multiple of four
+    q = uq.QuantLinear.from_numpy(w)
+    with pytest.raises(Exception):
+        uq.uniql_w4_gate_up_silu([q, q], [None, None], torch.zeros(256, dtype=torch.float16, device="cuda"))
