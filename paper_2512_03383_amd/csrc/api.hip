@@ -214,7 +214,7 @@ extern "C" int uniql_w4_qkv_rope(const uniql_w4_t* W, const uniql_keep_t* keep, 
   rf.kept_idx = kept_idx;
   rf.H_tab = H_tab;
   rf.D_keep = D_keep;
-  rf.exp2_coeff = -(2.0 / (double)D_full) * log2(theta);
+  rf.base = pow(theta, -2.0 / (double)D_full);
   rf.heads[0] = Hq;
   rf.heads[1] = Hkv;
   bool fused = false;

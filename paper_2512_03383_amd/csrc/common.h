@@ -49,7 +49,7 @@ struct RopeFuse {
   const int32_t* positions;       // device, [1]: the token's position
   const int32_t* kept_idx;        // device, [H_tab][D_keep / 2]
   int H_tab, D_keep;
-  double exp2_coeff;              // -(2 / D_full) * log2(theta): inv_freq_j = exp2(j * exp2_coeff)
+  double base;                    // theta^(-2 / D_full): inv_freq_j = base^j
   int heads[kMaxBatch];
 };
 struct GemvBatch {

@@ -295,7 +295,14 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
     __syncthreads();
     if (ROPE && rope_heads > 0) {
       // sin / cos of pos * theta^(-2j/D): fp64 angle in revolutions, its fraction to the hardware sin / cos
-      const double rev = (double)rope_pos * exp2((double)rope_j * batch.rf.exp2_coeff) * 0.15915494309189534561;
+      // theta^(-2j/D) = base^j by binary powering (a dozen fp64 multiplies, error of a few ulp) instead
+      // of a library exp2
+      double inv_freq = 1.0, bpow = batch.rf.base;
+      for (int e = rope_j; e != 0; e >>= 1) {
+        inv_freq = e & 1 ? inv_freq * bpow : inv_freq;
+        bpow *= bpow;
+      }
+      const double rev = (double)rope_pos * inv_freq * 0.15915494309189534561;
       const float rr = (float)(rev - rint(rev));
       rope_sn = __builtin_amdgcn_sinf(rr);
       rope_cs = __builtin_amdgcn_cosf(rr);
