@@ -43,6 +43,7 @@ def lib():
         L.uref_count_kept.argtypes = [i32, i32, vp, vp, vp]
         L.uref_w4_dequant.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
         L.uref_w4_linear.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, i64, vp, i64, i32, vp, i32]
+        L.uref_w4_embedding.argtypes = [vp, vp, vp, i32, i32, i32, vp, i32, vp]
         L.uref_pruned_rope.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, dbl, vp, vp]
         L.uref_pruned_rope_f64.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, dbl]
         L.uref_quantize_sym.argtypes = [vp, i32, i32, i32, vp, vp, vp]
@@ -103,6 +104,18 @@ def w4_dequant(qweight, scales, zeros, keep=None, group: int = 128) -> np.ndarra
     out = np.empty((nk, kk), dtype=np.float16)
     rc = lib().uref_w4_dequant(_p(qweight), _p(scales), _p(zeros), N, K, group, _p(ka), _p(out))
     assert rc == 0
+    return out
+
+
+def w4_embedding(qweight, scales, zeros, ids, group: int = 128) -> np.ndarray:
+    """fp16 [len(ids)][K] dequantised rows ids of a quantised table."""
+    N, K8 = qweight.shape
+    K = K8 * 8
+    _chk(qweight, np.uint32, "qweight"); _chk(scales, np.float16, "scales"); _chk(zeros, np.uint8, "zeros")
+    _chk(ids, np.int32, "ids")
+    out = np.empty((ids.shape[0], K), dtype=np.float16)
+    rc = lib().uref_w4_embedding(_p(qweight), _p(scales), _p(zeros), N, K, group, _p(ids), ids.shape[0], _p(out))
+    assert rc == 0, rc
     return out
 
 

@@ -16,6 +16,8 @@
  *   uref_w4_dequant / uref_w4_linear   Sec. 3.1 (Y = X W), Eq. 1 / Eq. 2 (where
  *        the linears sit), Sec. 3.4 (group-wise 4-bit weights, group 128, pruned
  *        channels dropped from D_int / D_hd while D_h stays, INT4 packed in INT32)
+ *   uref_w4_embedding                  Sec. 3.4 (the embedding layer is quantised as well): rows of a
+ *        quantised table gathered by token id and dequantised
  *   uref_pruned_rope                   Sec. 3.2 MHSA paragraph: RoPE(X) =
  *        cos * X + sin * R(X), R([x1,x2]) = [-x2,x1]; Alg. 2 / Alg. A1 (symmetric
  *        index vector, one half stored; one table per KV head under GQA); Fig. 4a
@@ -156,6 +158,18 @@ int uref_w4_dequant(const uint32_t* qweight, const uint16_t* scales, const uint8
     for (int j = 0; j < kk; ++j)
       w_f16[(size_t)i * kk + j] = dequant_one(qweight, scales, zeros, K_total, group, rows[i], cols[j]);
   free(rows); free(cols);
+  return 0;
+}
+
+/* Rows of a quantised table gathered by token id (Sec. 3.4 also quantises the embedding layer):
+ * out[i][k] = RN16((q - z) * s) of row ids[i], every column; fp16 bits [n][K_total]. */
+int uref_w4_embedding(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
+                      int N_total, int K_total, int group, const int32_t* ids, int n, uint16_t* out) {
+  for (int i = 0; i < n; ++i) {
+    if (ids[i] < 0 || ids[i] >= N_total) return -3;
+    for (int k = 0; k < K_total; ++k)
+      out[(size_t)i * K_total + k] = dequant_one(qweight, scales, zeros, K_total, group, ids[i], k);
+  }
   return 0;
 }
 

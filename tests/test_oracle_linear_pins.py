@@ -329,3 +329,26 @@ def test_gate_up_silu_is_numpy_matmul_then_silu(uref):
     # the gate closes for very negative pre-activations and passes very positive ones unchanged
     big = np.array([[-60.0, 60.0]])
     assert np.allclose(big / (1.0 + np.exp(-big)), [[0.0, 60.0]], atol=1e-20, rtol=1e-15)
+
+
+def test_embedding_gather_is_row_selection_of_an_independent_unpack(uref):
+    """Gathered rows against a numpy unpack of the whole table (nibble j of word w = column 8w + j) rounded
+    to fp16 by numpy; repeated and out-of-order ids; and as a one-hot product: row id = e_id^T W."""
+    rng = wl.rng_for(0, 25)
+    N, K = 50, 384
+    w = wl.gen_linear(rng, N, K)
+    ids = np.array([7, 0, 49, 7, 13], dtype=np.int32)
+    got = uref.w4_embedding(w["qweight"], w["scales"], w["zeros"], ids)
+    qw = w["qweight"]
+    nib = np.stack([(qw >> np.uint32(4 * j)) & np.uint32(15) for j in range(8)], axis=-1).reshape(N, K)
+    s = np.repeat(w["scales"].astype(np.float64), 128, axis=1)
+    z = np.repeat(w["zeros"].astype(np.float64), 128, axis=1)
+    dense = ((nib.astype(np.float64) - z) * s).astype(np.float16)
+    assert got.shape == (5, K)
+    assert np.array_equal(got.view(np.uint16), dense[ids].view(np.uint16))
+    # the transposed table as a linear: a one-hot "activation" over rows is not expressible (rows are
+    # outputs), so check through columns instead: x = e_k picks column k of every row, row by row
+    for k in (0, 127, 128, 383):
+        x = np.zeros((1, K), dtype=np.float16); x[0, k] = 1.0
+        col = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], x)[0]
+        assert np.array_equal(col[ids], got[:, k].astype(np.float64))
