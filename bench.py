@@ -275,6 +275,17 @@ def detail_report(torch, uq, side):
     spec = wl.lm_head_llama3()
     rep["lm_head_llama3_M1"] = time_linear(spec, 1, pool_for(spec, min_bytes=1.3e9, max_copies=5))
     torch.cuda.empty_cache()
+    # 4-bit embedding rows (128256 x 4096 table) gathered for one token and for a 4096-token prompt
+    emb = pool_for(spec, min_bytes=1.0, max_copies=2)[0]
+    for T in (1, 4096):
+        ids = torch.randint(0, spec.N, (T,), dtype=torch.int32, device="cuda")
+        outs = [torch.empty((T, spec.K), dtype=torch.float16, device="cuda") for _ in range(4)]
+        us = graph_time_us(torch, side, lambda i: uq.uniql_w4_embedding(emb, ids, out=outs[i % 4]), 8)
+        nb = T * (spec.K // 2 + spec.K // 128 * 2.5 + 4 + 2 * spec.K)
+        rep[f"embedding_llama3_T{T}"] = {"MB": round(nb / 1e6, 3), "us": round(us, 2), "GBps": round(nb / us / 1e3, 1),
+                                         "frac_hbm": round(nb / us / 1e3 / HBM_PEAK_GBS, 4)}
+    del emb
+    torch.cuda.empty_cache()
     # RoPE: decode and prefill
     for name, rs in (("rope_decode_llama_p15", wl.llama3_8b_rope(15, T=1)), ("rope_prefill_llama_p15", wl.prefill_rope(15, 4096))):
         r = wl.gen_rope_inputs(wl.rng_for(4, 7), rs)

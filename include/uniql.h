@@ -36,7 +36,8 @@ enum {
   UNIQL_E_SHAPE = -2, /* impossible size: group != 128, K_total % 128, M < 1, ld < dim */
   UNIQL_E_KEEP = -3,  /* kept dims inconsistent with totals / segment rule / heads     */
   UNIQL_E_ALIGN = -4, /* qweight not 16-byte, scales / x / y / q / k not 2-byte,
-                         positions / kept_idx not 4-byte aligned                       */
+                         positions / kept_idx / ids not 4-byte aligned, embedding
+                         output not 16-byte aligned or its ld not a multiple of 8     */
   UNIQL_E_ARCH = -5,  /* current device is not gfx950                                  */
   UNIQL_E_HIP = -6    /* HIP runtime / launch error; see uniql_last_hip_error()        */
 };
@@ -124,6 +125,17 @@ int uniql_w4_linear_multi(int32_t n, const uniql_w4_t* W, const uniql_keep_t* ke
  * Errors: as uniql_w4_linear.
  */
 int uniql_w4_dequant(const uniql_w4_t* W, const uniql_keep_t* keep, void* w_f16, void* hip_stream);
+
+/*
+ * Rows of a quantised table gathered by token id (Sec. 3.4: the embedding layer is quantised like
+ * the linears; the hidden dimension is never pruned, so rows are K_total wide):
+ *   out[i][k] = RN_fp16((q - z) * s) of row ids[i], k < K_total
+ *   ids     : device int32 [n], entries in [0, N_total) (not checked: see the general rules)
+ *   out_f16 : device fp16 [n][ld], ld >= K_total; 16-byte aligned, ld a multiple of 8
+ * Bit-exact like uniql_w4_dequant.  Errors: E_NULL, E_SHAPE (n < 1, ld < K_total), E_ALIGN, E_ARCH, E_HIP.
+ */
+int uniql_w4_embedding(const uniql_w4_t* W, const int32_t* ids, int32_t n, void* out_f16, int64_t ld,
+                       void* hip_stream);
 
 /*
  * Fused rotary embedding on pruned heads, in place (Sec. 3.2 MHSA paragraph,

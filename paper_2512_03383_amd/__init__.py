@@ -74,6 +74,8 @@ def lib():
                                         i32, i32, i32, i32, i32, C.c_double, vp]
         L.uniql_w4_gate_up_silu.restype = C.c_int
         L.uniql_w4_gate_up_silu.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, vp, vp]
+        L.uniql_w4_embedding.restype = C.c_int
+        L.uniql_w4_embedding.argtypes = [C.POINTER(W4), vp, i32, vp, i64, vp]
         L.uniql_stream_read_probe.argtypes = [vp, i64, vp, vp]
         L.uniql_strerror.restype = C.c_char_p
         L.uniql_strerror.argtypes = [C.c_int]
@@ -211,6 +213,19 @@ def uniql_w4_dequant(W: QuantLinear, keep=None, out=None, stream=None):
     rc = lib().uniql_w4_dequant(C.byref(d), C.byref(kd) if kd is not None else None,
                                 C.c_void_p(out.data_ptr()), _stream_ptr(stream))
     _check(rc)
+    return out
+
+
+def uniql_w4_embedding(W: QuantLinear, ids, out=None, stream=None):
+    """fp16 [len(ids)][K] dequantised rows ids (int32 device tensor) of the quantised table W."""
+    import torch
+    assert ids.dtype == torch.int32 and ids.is_cuda and ids.is_contiguous() and ids.dim() == 1
+    if out is None:
+        out = torch.empty((ids.shape[0], W.K), dtype=torch.float16, device=ids.device)
+    assert out.dtype == torch.float16 and out.stride(1) == 1 and out.shape == (ids.shape[0], W.K)
+    d = W.desc()
+    _check(lib().uniql_w4_embedding(C.byref(d), C.c_void_p(ids.data_ptr()), ids.shape[0], C.c_void_p(out.data_ptr()),
+                                    out.stride(0), _stream_ptr(stream)))
     return out
 
 

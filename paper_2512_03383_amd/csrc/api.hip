@@ -160,6 +160,23 @@ extern "C" int uniql_w4_dequant(const uniql_w4_t* W, const uniql_keep_t* keep, v
   return e == hipSuccess ? UNIQL_OK : hip_fail(e);
 }
 
+extern "C" int uniql_w4_embedding(const uniql_w4_t* W, const int32_t* ids, int32_t n, void* out_f16, int64_t ld,
+                                  void* hip_stream) {
+  KeepMap km;
+  int rc = make_keepmap(W, nullptr, &km);
+  if (rc) return rc;
+  if (!ids || !out_f16) return UNIQL_E_NULL;
+  if (n < 1 || ld < W->K_total) return UNIQL_E_SHAPE;
+  // every lane writes 64-byte pieces with 128-bit stores
+  if (!aligned(ids, 4) || !aligned(out_f16, 16) || ld % 8) return UNIQL_E_ALIGN;
+  rc = check_arch();
+  if (rc) return rc;
+  hipError_t e = launch_w4_embedding(W->qweight, W->scales, W->zeros, W->K_total, ids, n, (half_t*)out_f16, ld,
+                                     (hipStream_t)hip_stream);
+  if (e == hipErrorInvalidValue) return UNIQL_E_SHAPE;
+  return e == hipSuccess ? UNIQL_OK : hip_fail(e);
+}
+
 extern "C" int uniql_pruned_rope(void* q_f16, void* k_f16, const int32_t* positions, const int32_t* kept_idx,
                                  int32_t T, int32_t Hq, int32_t Hkv, int32_t H_tab, int32_t D_full,
                                  int32_t D_keep, double theta, void* hip_stream) {

@@ -162,6 +162,8 @@ hipError_t launch_w4_qkv_rope(const LinearArgs* probs, const RopeFuse& rf, hipSt
 hipError_t launch_w4_gate_up_silu(const LinearArgs* probs, hipStream_t stream, bool* fused);
 hipError_t launch_w4_gemm(const LinearArgs& a, hipStream_t stream);
 hipError_t launch_w4_dequant(const LinearArgs& a, hipStream_t stream);
+hipError_t launch_w4_embedding(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros, int K_total,
+                               const int32_t* ids, int n, half_t* out, long long ld, hipStream_t stream);
 
 struct RopeArgs {
   half_t* q;

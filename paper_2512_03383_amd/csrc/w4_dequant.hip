@@ -42,4 +42,46 @@ hipError_t launch_w4_dequant(const LinearArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
+// Rows of a quantised table gathered by token id: out[i][:] = dequantised row ids[i].
+// A wave handles one (token, 2048-column chunk): a lane reads 16 bytes of codes and the scale and
+// zero point of its group, dequantises with the packed path of the GEMV, puts the 32 halves back
+// into column order and writes 64 contiguous bytes.  Rows are K_total wide (the hidden dimension
+// is never pruned).
+__global__ __launch_bounds__(256) void w4_embedding_kernel(const uint32_t* qweight, const uint16_t* scales,
+                                                           const uint8_t* zeros, int K_total, const int32_t* ids,
+                                                           int n, half_t* out, long long ld) {
+  const int lane = threadIdx.x & 63;
+  const int chunks = (K_total + 2047) / 2048;
+  const long long item = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);   // (token, chunk)
+  if (item >= (long long)n * chunks) return;
+  const int tok = (int)(item / chunks), c = (int)(item - (long long)tok * chunks);
+  const int k0 = c * 2048 + lane * 32;
+  if (k0 >= K_total) return;                      // K_total is a multiple of 128: a lane's 32 columns are all in or all out
+  const size_t row = (size_t)ids[tok];
+  const uint4 w = *reinterpret_cast<const uint4*>(qweight + row * (size_t)(K_total >> 3) + (k0 >> 3));
+  const size_t g = row * (size_t)(K_total / kGroup) + (k0 >> 7);
+  const GroupQ gq = make_groupq(scales[g], zeros[g]);
+  const Magic mg = make_magic();
+  const uint32_t words[4] = {w.x, w.y, w.z, w.w};
+  uint4* dst = reinterpret_cast<uint4*>(out + (size_t)tok * ld + k0);   // 16-byte aligned: checked by the host
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    half2_t d[4];
+    dequant_word(words[q], gq, mg, d);            // (w0,w4) (w1,w5) (w2,w6) (w3,w7)
+    const uint32_t a = as_u32(d[0]), b = as_u32(d[1]), cc = as_u32(d[2]), e = as_u32(d[3]);
+    dst[q] = make_uint4(__builtin_amdgcn_perm(b, a, 0x05040100u), __builtin_amdgcn_perm(e, cc, 0x05040100u),
+                        __builtin_amdgcn_perm(b, a, 0x07060302u), __builtin_amdgcn_perm(e, cc, 0x07060302u));
+  }
+}
+
+hipError_t launch_w4_embedding(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros, int K_total,
+                               const int32_t* ids, int n, half_t* out, long long ld, hipStream_t stream) {
+  const long long items = (long long)n * ((K_total + 2047) / 2048);
+  const long long blocks = (items + 3) / 4;
+  if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(w4_embedding_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, qweight, scales, zeros, K_total,
+                     ids, n, out, ld);
+  return hipGetLastError();
+}
+
 }  // namespace uniql

@@ -180,6 +180,23 @@ def test_gate_up_silu_rejects_bad_arguments():
     assert _glu(keeps=[KeepDesc(col_seg_stride=128, col_seg_keep=64), KeepDesc(k_keep=256)]) == uq.UNIQL_E_KEEP
 
 
+def _emb(w=None, ids=P, n=4, out=P, ld=512):
+    w = w if w is not None else _w()
+    return uq.lib().uniql_w4_embedding(C.byref(w), C.c_void_p(ids), n, C.c_void_p(out), ld, None)
+
+
+def test_embedding_rejects_bad_arguments():
+    assert uq.lib().uniql_w4_embedding(None, C.c_void_p(P), 1, C.c_void_p(P), 512, None) == uq.UNIQL_E_NULL
+    assert _emb(ids=0) == uq.UNIQL_E_NULL
+    assert _emb(out=0) == uq.UNIQL_E_NULL
+    assert _emb(n=0) == uq.UNIQL_E_SHAPE
+    assert _emb(ld=504) == uq.UNIQL_E_SHAPE
+    assert _emb(w=_w(group=64)) == uq.UNIQL_E_SHAPE
+    assert _emb(ld=516) == uq.UNIQL_E_ALIGN
+    assert _emb(out=P + 8) == uq.UNIQL_E_ALIGN
+    assert _emb(ids=P + 2) == uq.UNIQL_E_ALIGN
+
+
 def test_valid_arguments_without_gfx950_fail_loudly():
     """On a box without an MI355X a valid call must report E_HIP / E_ARCH, never pretend to work."""
     import torch
@@ -190,3 +207,4 @@ def test_valid_arguments_without_gfx950_fail_loudly():
     assert _multi() in (uq.UNIQL_E_HIP, uq.UNIQL_E_ARCH)
     assert _qkv() in (uq.UNIQL_E_HIP, uq.UNIQL_E_ARCH)
     assert _glu() in (uq.UNIQL_E_HIP, uq.UNIQL_E_ARCH)
+    assert _emb() in (uq.UNIQL_E_HIP, uq.UNIQL_E_ARCH)

@@ -593,3 +593,22 @@ def test_gate_up_silu_refuses_what_it_cannot_fuse(env):
     q = uq.QuantLinear.from_numpy(w)
     with pytest.raises(Exception):
         uq.uniql_w4_gate_up_silu([q, q], [None, None], torch.zeros(256, dtype=torch.float16, device="cuda"))
+
+
+# ------------------------------------------------- 4-bit embedding rows gathered by token id
+@pytest.mark.parametrize("N,K,n,pad", [(50, 384, 5, 0), (1000, 4096, 300, 8), (3000, 2176, 1, 0), (4096, 14336, 33, 16)])
+def test_embedding_gather_bit_exact(env, uref, N, K, n, pad):
+    uq, torch = env
+    rng = wl.rng_for(9, N + K + n)
+    w = wl.gen_linear(rng, N, K)
+    ids = rng.integers(0, N, n).astype(np.int32)
+    ids[0], ids[-1] = N - 1, 0
+    ref = uref.w4_embedding(w["qweight"], w["scales"], w["zeros"], ids)
+    buf = torch.full((n, K + pad), -3.0, dtype=torch.float16, device="cuda")
+    out = uq.uniql_w4_embedding(uq.QuantLinear.from_numpy(w), to_dev(torch, ids), out=buf[:, :K])
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    # sign of an exact zero under a negative scale is unspecified (scales are positive here anyway)
+    assert np.array_equal(got.view(np.uint16), ref.view(np.uint16))
+    if pad:
+        assert torch.all(buf[:, K:] == -3.0), "wrote past K"
