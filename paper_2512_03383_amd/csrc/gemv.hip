@@ -201,23 +201,33 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
     }
   };
   const Magic mg = make_magic();
-  auto consume = [&](const Tile& t, const uint4 (&xr)[4], float& acc, const Picked& pk) {
+  // The 8-element dot products of a word run on the matrix pipe, beside the VALU that dequantises:
+  // with A = the lane's x values and B = its weights, v_mfma_f32_16x16x32_f16 forms D[i][n] =
+  // sum over the four lanes {n, n+16, n+32, n+48} of dot(x of lane i + 16 ks, w of lane n + 16 ks);
+  // its diagonal D[n][n] is the partial sum wanted, the rest is ignored.  Lane l holds D[4 (l / 16) + v][l % 16]
+  // in register v, so the diagonal sits in lanes 5 m + 16 (m / 4) .. (one of every four), register l % 4.
+  auto consume = [&](const Tile& t, const uint4 (&xr)[4], float4_t& acc, const Picked& pk) {
     const GroupQ g = presz ? groupq_of(pk) : make_groupq(t.sbits, t.z);
     const uint32_t wv[4] = {t.w.x, t.w.y, t.w.z, t.w.w};
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       half2_t d[4];
       dequant_word(wv[q], g, mg, d);
-      acc = __builtin_amdgcn_fdot2(d[0], as_half2(xr[q].x), acc, false);
-      acc = __builtin_amdgcn_fdot2(d[1], as_half2(xr[q].y), acc, false);
-      acc = __builtin_amdgcn_fdot2(d[2], as_half2(xr[q].z), acc, false);
-      acc = __builtin_amdgcn_fdot2(d[3], as_half2(xr[q].w), acc, false);
+      const uint4 wq = make_uint4(as_u32(d[0]), as_u32(d[1]), as_u32(d[2]), as_u32(d[3]));
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, xr[q]), __builtin_bit_cast(half8_t, wq), acc, 0, 0, 0);
     }
   };
 
-  float acc[R];
+  float4_t acc[R];
 #pragma unroll
-  for (int r = 0; r < R; ++r) acc[r] = 0.f;
+  for (int r = 0; r < R; ++r) acc[r] = float4_t{0.f, 0.f, 0.f, 0.f};
+  // the lane's diagonal element of an accumulator (zero in the lanes that hold none), summed over the wave
+  const bool on_diag = (lane >> 4) == ((lane & 15) >> 2);
+  auto row_sum = [&](const float4_t& c) {
+    const int v = lane & 3;
+    float d = v == 0 ? c[0] : (v == 1 ? c[1] : (v == 2 ? c[2] : c[3]));
+    return dpp_xor_reduce(on_diag ? d : 0.f);
+  };
   float rope_sn = 0.f, rope_cs = 1.f;
 
   const ColMap cm = make_colmap(km);
@@ -326,7 +336,7 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
       // arithmetic (which would make the wave wait for loads that were issued later).
       Tile& tl = ring[t % D];
       asm volatile("" : "+v"(tl.w.x), "+v"(tl.w.y), "+v"(tl.w.z), "+v"(tl.w.w), "+v"(tl.sbits), "+v"(tl.z),
-                        "+v"(acc[(t + R - 1) % R]));
+                        "+v"(acc[(t + R - 1) % R][0]));
       consume(tl, xr, acc[r], pk);
       if (t + D < T) load_tile((t + D) / R, (t + D) % R, tl);
     }
@@ -365,7 +375,7 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
 
   if (ROPE && rope_heads > 0) {
     __shared__ float pair_sum[kGemvWaves];
-    const float v = dpp_xor_reduce(acc[0]);
+    const float v = row_sum(acc[0]);
     if (lane == 0) pair_sum[wave] = v;
     __syncthreads();
     const float x1 = pair_sum[wave & 3], x2 = pair_sum[(wave & 3) + 4];
@@ -377,7 +387,7 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
     __shared__ float glu_sum[kGemvWaves][R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      const float v = dpp_xor_reduce(acc[r]);
+      const float v = row_sum(acc[r]);
       if (lane == 0) glu_sum[wave][r] = v;
     }
     __syncthreads();
@@ -391,7 +401,7 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
   }
 #pragma unroll
   for (int r = 0; r < R; ++r) {
-    const float v = dpp_xor_reduce(acc[r]);
+    const float v = row_sum(acc[r]);
     const int rc = rg * R + r;
     if (lane == 0 && rc < km.n_keep) a.y[(size_t)m * a.ldy + rc] = (half_t)v;
   }
