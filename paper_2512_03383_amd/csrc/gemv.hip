@@ -10,7 +10,8 @@
 //
 // Per 32-bit word (8 weights): 1 shift + 4 and-or build exact fp16 codes, 4
 // packed subtracts and 4 packed multiplies give the canonical fp16 weights
-// RN16((q - z) s), and 4 two-way dot instructions accumulate in fp32.
+// RN16((q - z) s); the word's 8-element dot product with the lane's activations is
+// taken from the diagonal of one matrix instruction (see consume below), fp32.
 //
 // The kernel is fully unrolled over the row's 2048-column chunks (template NCH):
 // a wave's tiles (row, chunk) are loaded a few tiles ahead (DW in the kernel) and consumed in issue
