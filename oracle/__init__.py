@@ -46,6 +46,8 @@ def lib():
         L.uref_w4_embedding.argtypes = [vp, vp, vp, i32, i32, i32, vp, i32, vp]
         L.uref_pruned_rope.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, dbl, vp, vp]
         L.uref_pruned_rope_f64.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, dbl]
+        L.uref_w4_repack_plan.argtypes = [i32, i32, i32, vp, vp]
+        L.uref_w4_repack.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp]
         L.uref_quantize_sym.argtypes = [vp, i32, i32, i32, vp, vp, vp]
         L.uref_quantize_asym.argtypes = [vp, i32, i32, i32, vp, vp, vp]
         _lib = L
@@ -190,6 +192,30 @@ def gate_up_silu(wg, keep_g, wu, keep_u, x):
     g = w4_linear(wg["qweight"], wg["scales"], wg["zeros"], x, keep_g)
     u = w4_linear(wu["qweight"], wu["scales"], wu["zeros"], x, keep_u)
     return g / (1.0 + np.exp(-g)) * u
+
+
+def w4_repack_plan(N_total: int, K_total: int, keep=None, group: int = 128):
+    """(N_out, K_out, keep_out) of the compact matrix: keep_out is the 7-tuple to use with it."""
+    plan = np.zeros(9, dtype=np.int32)
+    rc = lib().uref_w4_repack_plan(N_total, K_total, group, _p(_keep_arr(keep)), _p(plan))
+    assert rc == 0
+    return int(plan[0]), int(plan[1]), tuple(int(v) for v in plan[2:])
+
+
+def w4_repack(qweight, scales, zeros, keep=None, group: int = 128):
+    """The compact quantised matrix of the kept channels (Sec. 3.4: unpack, prune, pack again):
+    (qweight', scales', zeros', keep') with y(W', keep') == y(W, keep)."""
+    N, K8 = qweight.shape
+    K = K8 * 8
+    _chk(qweight, np.uint32, "qweight"); _chk(scales, np.float16, "scales"); _chk(zeros, np.uint8, "zeros")
+    n_out, k_out, keep_out = w4_repack_plan(N, K, keep, group)
+    q2 = np.zeros((n_out, k_out // 8), dtype=np.uint32)
+    s2 = np.zeros((n_out, k_out // group), dtype=np.float16)
+    z2 = np.zeros((n_out, k_out // group), dtype=np.uint8)
+    rc = lib().uref_w4_repack(_p(qweight), _p(scales), _p(zeros), N, K, group, _p(_keep_arr(keep)),
+                              _p(q2), _p(s2), _p(z2))
+    assert rc == 0
+    return q2, s2, z2, keep_out
 
 
 def _quantize(fn, w: np.ndarray, group: int):

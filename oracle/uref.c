@@ -18,6 +18,9 @@
  *        channels dropped from D_int / D_hd while D_h stays, INT4 packed in INT32)
  *   uref_w4_embedding                  Sec. 3.4 (the embedding layer is quantised as well): rows of a
  *        quantised table gathered by token id and dequantised
+ *   uref_w4_repack_plan / uref_w4_repack   Sec. 3.4, on-device pruning of INT4 weights: unpack, drop
+ *        the pruned channels, pack again into INT32 -- here at the granularity the format can hold
+ *        (kept rows; whole quantisation groups that still hold a kept column)
  *   uref_pruned_rope                   Sec. 3.2 MHSA paragraph: RoPE(X) =
  *        cos * X + sin * R(X), R([x1,x2]) = [-x2,x1]; Alg. 2 / Alg. A1 (symmetric
  *        index vector, one half stored; one table per KV head under GQA); Fig. 4a
@@ -317,5 +320,75 @@ int uref_quantize_asym(const double* w, int N, int K, int group, uint32_t* qweig
         put_nibble(qweight, K, r, g * group + j, (int)qv);
       }
     }
+  return 0;
+}
+
+/* ---- repack: the compact matrix of the kept channels (Sec. 3.4, "unpack, prune channels, repackage") ----
+ * Rows: exactly the kept rows, in order.  Columns: a quantisation group stays whole (its scale and zero
+ * point belong to all of its columns), so the compact matrix holds, in order, every source group that
+ * still has a kept column -- when the kept columns are a prefix, or segments whose stride is a multiple
+ * of the group.  For any other column pattern the compact groups could not be described by one segment
+ * rule, and all columns stay in place.  plan[0] = N_out, plan[1] = K_out, plan[2..8] = the keep
+ * descriptor to use with the compact matrix (rows: all; columns: the same kept columns at their new
+ * positions). */
+static int cols_compactable(const int32_t* keep, int group) {
+  return keep[5] == 0 || keep[5] % group == 0;
+}
+
+static int group_carried(const int32_t* keep, int K_total, int group, int g) {
+  if (!cols_compactable(keep, group)) return 1;
+  for (int k = g * group; k < (g + 1) * group; ++k)
+    if (col_kept(keep, K_total, k)) return 1;
+  return 0;
+}
+
+int uref_w4_repack_plan(int N_total, int K_total, int group, const int32_t* keep, int32_t* plan) {
+  static const int32_t none[7] = {0, 0, 0, 0, 0, 0, 0};
+  if (!keep) keep = none;
+  int n = 0, kept_cols_total = 0, groups = 0;
+  for (int r = 0; r < N_total; ++r) n += row_kept(keep, N_total, r);
+  for (int k = 0; k < K_total; ++k) kept_cols_total += col_kept(keep, K_total, k);
+  for (int g = 0; g < K_total / group; ++g) groups += group_carried(keep, K_total, group, g);
+  plan[0] = n;
+  plan[1] = groups * group;
+  for (int i = 2; i < 9; ++i) plan[i] = 0;
+  if (keep[5] == 0) {
+    plan[3] = kept_cols_total == plan[1] ? 0 : kept_cols_total;   /* prefix (0 = all) */
+  } else {
+    int per_seg = (keep[6] + group - 1) / group * group;          /* groups that survive per segment */
+    plan[3] = kept_cols_total;
+    plan[7] = cols_compactable(keep, group) ? per_seg : keep[5];
+    plan[8] = keep[6];
+  }
+  return 0;
+}
+
+/* out_q [N_out][K_out/8], out_s / out_z [N_out][K_out/group], sizes from uref_w4_repack_plan */
+int uref_w4_repack(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
+                   int N_total, int K_total, int group, const int32_t* keep,
+                   uint32_t* out_q, uint16_t* out_s, uint8_t* out_z) {
+  static const int32_t none[7] = {0, 0, 0, 0, 0, 0, 0};
+  if (!keep) keep = none;
+  int32_t plan[9];
+  uref_w4_repack_plan(N_total, K_total, group, keep, plan);
+  const int K_out = plan[1];
+  int ro = 0;
+  for (int r = 0; r < N_total; ++r) {
+    if (!row_kept(keep, N_total, r)) continue;
+    int go = 0;
+    for (int g = 0; g < K_total / group; ++g) {
+      if (!group_carried(keep, K_total, group, g)) continue;
+      out_s[(size_t)ro * (K_out / group) + go] = scales[(size_t)r * (K_total / group) + g];
+      out_z[(size_t)ro * (K_out / group) + go] = zeros[(size_t)r * (K_total / group) + g];
+      for (int j = 0; j < group; ++j) {
+        int k = g * group + j;
+        uint32_t word = qweight[(size_t)r * (K_total / 8) + k / 8];
+        int q = (int)((word >> (4 * (k % 8))) & 15u);                 /* unpack */
+        put_nibble(out_q, K_out, ro, go * group + j, q);              /* pack at the compact position */
+      }
+      ++go;
+    }
+    ++ro;
+  }
   return 0;
 }
