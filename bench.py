@@ -296,6 +296,19 @@ def detail_report(torch, uq, side):
                                          "frac_hbm": round(nb / us / 1e3 / HBM_PEAK_GBS, 4)}
     del emb
     torch.cuda.empty_cache()
+    # on-device repack of the kept channels (Llama gate_proj: rows; down_proj: column prefix), 15 %
+    for spec in wl.prefill_linears(15):
+        if spec.name not in ("gate_up_proj", "gate_proj", "down_proj"):
+            continue
+        src = pool_for(spec, min_bytes=1.2e8, max_copies=4)
+        outs = [uq.uniql_w4_repack(src[0], spec.keep)[0] for _ in range(4)]
+        us = graph_time_us(torch, side, lambda i: uq.uniql_w4_repack(src[i % len(src)], spec.keep, out=outs[i % 4]), 8)
+        n_out, k_out = outs[0].N, outs[0].K
+        nb = 2 * n_out * (k_out // 2 + k_out // 128 * 3)       # codes, scale and zero point: read once, written once
+        rep[f"repack_{spec.name}_p15"] = {"MB": round(nb / 1e6, 3), "us": round(us, 2), "GBps": round(nb / us / 1e3, 1),
+                                          "frac_hbm": round(nb / us / 1e3 / HBM_PEAK_GBS, 4)}
+        del src, outs
+        torch.cuda.empty_cache()
     # RoPE: decode and prefill
     for name, rs in (("rope_decode_llama_p15", wl.llama3_8b_rope(15, T=1)), ("rope_prefill_llama_p15", wl.prefill_rope(15, 4096))):
         r = wl.gen_rope_inputs(wl.rng_for(4, 7), rs)

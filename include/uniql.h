@@ -127,6 +127,30 @@ int uniql_w4_linear_multi(int32_t n, const uniql_w4_t* W, const uniql_keep_t* ke
 int uniql_w4_dequant(const uniql_w4_t* W, const uniql_keep_t* keep, void* w_f16, void* hip_stream);
 
 /*
+ * On-device repack (Sec. 3.4: INT4 weights are unpacked, the pruned channels dropped and the rest packed
+ * again into INT32).  Nothing in this library needs it -- every call takes the pruning as an argument --
+ * but a deployment that settles on a rate can reclaim the memory of the pruned channels.  The compact
+ * matrix has the format of uniql_w4_t (group 128), which fixes the granularity:
+ *   rows    : exactly the kept rows, in order (N_out = n_keep)
+ *   columns : a quantisation group is carried whole (its scale and zero point serve all of its
+ *             columns).  Column prefix: the ceil(k_keep / 128) leading groups.  Column segments whose
+ *             stride is a multiple of 128: the leading ceil(col_seg_keep / 128) groups of every segment.
+ *             Any other column segments (e.g. o_proj, where a head is one group): all columns stay.
+ * keep_out is the descriptor to pass with the compact matrix: all rows kept, the same kept columns at
+ * their new positions; every entry point then returns exactly what it returns for (W, keep).
+ *
+ * uniql_w4_repack_plan: host arithmetic only, no GPU needed; only the sizes of W are read (its data
+ *   pointers may be NULL).  Errors: E_NULL, E_SHAPE, E_KEEP.
+ * uniql_w4_repack: out_qweight [N_out][K_out/8] (16-byte aligned), out_scales / out_zeros
+ *   [N_out][K_out/128], device, caller-allocated with the sizes of the plan (E_SHAPE if N_out / K_out
+ *   differ from it); must not overlap the source.  Bit-exact.  Errors: as uniql_w4_dequant.
+ */
+int uniql_w4_repack_plan(const uniql_w4_t* W, const uniql_keep_t* keep, int32_t* N_out, int32_t* K_out,
+                         uniql_keep_t* keep_out);
+int uniql_w4_repack(const uniql_w4_t* W, const uniql_keep_t* keep, uint32_t* out_qweight, uint16_t* out_scales,
+                    uint8_t* out_zeros, int32_t N_out, int32_t K_out, void* hip_stream);
+
+/*
  * Rows of a quantised table gathered by token id (Sec. 3.4: the embedding layer is quantised like
  * the linears; the hidden dimension is never pruned, so rows are K_total wide):
  *   out[i][k] = RN_fp16((q - z) * s) of row ids[i], k < K_total

@@ -76,6 +76,11 @@ def lib():
         L.uniql_w4_gate_up_silu.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, vp, vp]
         L.uniql_w4_embedding.restype = C.c_int
         L.uniql_w4_embedding.argtypes = [C.POINTER(W4), vp, i32, vp, i64, vp]
+        L.uniql_w4_repack_plan.restype = C.c_int
+        L.uniql_w4_repack_plan.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), C.POINTER(i32), C.POINTER(i32),
+                                           C.POINTER(KeepDesc)]
+        L.uniql_w4_repack.restype = C.c_int
+        L.uniql_w4_repack.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, vp, vp, i32, i32, vp]
         L.uniql_stream_read_probe.argtypes = [vp, i64, vp, vp]
         L.uniql_strerror.restype = C.c_char_p
         L.uniql_strerror.argtypes = [C.c_int]
@@ -214,6 +219,36 @@ def uniql_w4_dequant(W: QuantLinear, keep=None, out=None, stream=None):
                                 C.c_void_p(out.data_ptr()), _stream_ptr(stream))
     _check(rc)
     return out
+
+
+def uniql_w4_repack_plan(N_total: int, K_total: int, keep=None):
+    """(N_out, K_out, keep_out) of the compact matrix uniql_w4_repack writes (host only, no GPU)."""
+    d = W4(None, None, None, int(N_total), int(K_total), 128)
+    kd = _keep_desc(keep)
+    n, k, ko = C.c_int32(0), C.c_int32(0), KeepDesc()
+    _check(lib().uniql_w4_repack_plan(C.byref(d), C.byref(kd) if kd is not None else None, C.byref(n), C.byref(k),
+                                      C.byref(ko)))
+    return n.value, k.value, ko
+
+
+def uniql_w4_repack(W: QuantLinear, keep=None, out: Optional[QuantLinear] = None, stream=None):
+    """Compact copy of the kept channels: returns (QuantLinear, KeepDesc to use with it).  `out` may
+    bring tensors of the plan's sizes (contiguous); otherwise they are allocated."""
+    import torch
+    n_out, k_out, ko = uniql_w4_repack_plan(W.N, W.K, keep)
+    dev = W.qweight.device
+    if out is None:
+        out = QuantLinear(torch.empty((n_out, k_out // 8), dtype=torch.int32, device=dev),
+                          torch.empty((n_out, k_out // 128), dtype=torch.float16, device=dev),
+                          torch.empty((n_out, k_out // 128), dtype=torch.uint8, device=dev))
+    assert out.qweight.shape == (n_out, k_out // 8) and out.scales.shape == (n_out, k_out // 128) \
+        and out.zeros.shape == out.scales.shape
+    assert out.qweight.is_contiguous() and out.scales.is_contiguous() and out.zeros.is_contiguous()
+    d, kd = W.desc(), _keep_desc(keep)
+    _check(lib().uniql_w4_repack(C.byref(d), C.byref(kd) if kd is not None else None,
+                                 C.c_void_p(out.qweight.data_ptr()), C.c_void_p(out.scales.data_ptr()),
+                                 C.c_void_p(out.zeros.data_ptr()), n_out, k_out, _stream_ptr(stream)))
+    return out, ko
 
 
 def uniql_w4_embedding(W: QuantLinear, ids, out=None, stream=None):

@@ -160,6 +160,85 @@ extern "C" int uniql_w4_dequant(const uniql_w4_t* W, const uniql_keep_t* keep, v
   return e == hipSuccess ? UNIQL_OK : hip_fail(e);
 }
 
+// Sizes, group mapping and keep descriptor of the compact matrix.  Host arithmetic only.
+struct RepackPlan {
+  int N_out, K_out, gps_src, gps_out;
+  uniql_keep_t keep_out;
+};
+static int make_repack_plan(const uniql_w4_t* W, const uniql_keep_t* keep, KeepMap* km, RepackPlan* p) {
+  int rc = make_keepmap(W, keep, km);
+  if (rc) return rc;
+  memset(p, 0, sizeof(*p));
+  p->N_out = km->n_keep;
+  const int K = W->K_total;
+  if (km->cs_stride == 0) {
+    // column prefix: the groups that reach into it, whole
+    p->K_out = (km->k_keep + kGroup - 1) / kGroup * kGroup;
+    p->keep_out.k_keep = km->k_keep == p->K_out ? 0 : km->k_keep;
+  } else if (km->cs_stride % kGroup == 0) {
+    // segments made of whole groups: the leading groups of each segment that hold kept columns
+    p->gps_src = km->cs_stride / kGroup;
+    p->gps_out = (km->cs_keep + kGroup - 1) / kGroup;
+    p->K_out = (K / km->cs_stride) * p->gps_out * kGroup;
+    p->keep_out.k_keep = km->k_keep;
+    p->keep_out.col_seg_stride = p->gps_out * kGroup;
+    p->keep_out.col_seg_keep = km->cs_keep;
+  } else {
+    // groups straddle segments: every group still holds kept columns or could not be described; columns stay
+    p->K_out = K;
+    p->keep_out.k_keep = km->k_keep;
+    p->keep_out.col_seg_stride = km->cs_stride;
+    p->keep_out.col_seg_keep = km->cs_keep;
+  }
+  return UNIQL_OK;
+}
+
+extern "C" int uniql_w4_repack_plan(const uniql_w4_t* W, const uniql_keep_t* keep, int32_t* N_out, int32_t* K_out,
+                                    uniql_keep_t* keep_out) {
+  if (!N_out || !K_out || !keep_out) return UNIQL_E_NULL;
+  KeepMap km;
+  RepackPlan p;
+  // the plan needs the sizes only: the data pointers of W may be NULL here
+  if (!W) return UNIQL_E_NULL;
+  uniql_w4_t shape = *W;
+  static const uint32_t dummy[4] __attribute__((aligned(16))) = {0, 0, 0, 0};
+  shape.qweight = dummy;
+  shape.scales = reinterpret_cast<const uint16_t*>(dummy);
+  shape.zeros = reinterpret_cast<const uint8_t*>(dummy);
+  int rc = make_repack_plan(&shape, keep, &km, &p);
+  if (rc) return rc;
+  *N_out = p.N_out;
+  *K_out = p.K_out;
+  *keep_out = p.keep_out;
+  return UNIQL_OK;
+}
+
+extern "C" int uniql_w4_repack(const uniql_w4_t* W, const uniql_keep_t* keep, uint32_t* out_qweight,
+                               uint16_t* out_scales, uint8_t* out_zeros, int32_t N_out, int32_t K_out,
+                               void* hip_stream) {
+  RepackArgs a;
+  RepackPlan p;
+  int rc = make_repack_plan(W, keep, &a.km, &p);
+  if (rc) return rc;
+  if (!out_qweight || !out_scales || !out_zeros) return UNIQL_E_NULL;
+  if (N_out != p.N_out || K_out != p.K_out) return UNIQL_E_SHAPE;
+  if (!aligned(out_qweight, 16) || !aligned(out_scales, 2)) return UNIQL_E_ALIGN;
+  rc = check_arch();
+  if (rc) return rc;
+  a.qweight = W->qweight;
+  a.scales = W->scales;
+  a.zeros = W->zeros;
+  a.out_qweight = out_qweight;
+  a.out_scales = out_scales;
+  a.out_zeros = out_zeros;
+  a.K_total = W->K_total;
+  a.K_out = p.K_out;
+  a.gps_src = p.gps_src;
+  a.gps_out = p.gps_out;
+  hipError_t e = launch_w4_repack(a, (hipStream_t)hip_stream);
+  return e == hipSuccess ? UNIQL_OK : hip_fail(e);
+}
+
 extern "C" int uniql_w4_embedding(const uniql_w4_t* W, const int32_t* ids, int32_t n, void* out_f16, int64_t ld,
                                   void* hip_stream) {
   KeepMap km;

@@ -165,6 +165,20 @@ hipError_t launch_w4_dequant(const LinearArgs& a, hipStream_t stream);
 hipError_t launch_w4_embedding(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros, int K_total,
                                const int32_t* ids, int n, half_t* out, long long ld, hipStream_t stream);
 
+// Compact copy of the kept channels of a quantised matrix (host fills it from the repack plan).
+struct RepackArgs {
+  const uint32_t* qweight;
+  const uint16_t* scales;
+  const uint8_t* zeros;
+  uint32_t* out_qweight;
+  uint16_t* out_scales;
+  uint8_t* out_zeros;
+  int K_total, K_out;
+  int gps_src, gps_out;   // groups per column segment in the source / carried to the output (gps_out = 0: all groups stay)
+  KeepMap km;             // rows only
+};
+hipError_t launch_w4_repack(const RepackArgs& a, hipStream_t stream);
+
 struct RopeArgs {
   half_t* q;
   half_t* k;

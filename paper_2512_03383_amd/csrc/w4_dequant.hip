@@ -84,4 +84,38 @@ hipError_t launch_w4_embedding(const uint32_t* qweight, const uint16_t* scales, 
   return hipGetLastError();
 }
 
+// Compact copy of the kept channels.  Output row r' is stored row stored_row(r'); output group g' is source
+// group (g' / gps_out) * gps_src + g' % gps_out (gps_out = 0: groups stay in place).  A thread moves one
+// 16-byte unit (32 codes, a quarter of a group); the thread of a group's first unit also moves the
+// group's scale and zero point.  Rows are contiguous on both sides, so the copy streams.
+__global__ __launch_bounds__(256) void w4_repack_kernel(RepackArgs a) {
+  const int units_out = a.K_out >> 5;
+  const long long total = (long long)a.km.n_keep * units_out;
+  const int units_src = a.K_total >> 5;
+  const int groups_src = a.K_total / kGroup, groups_out = a.K_out / kGroup;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (long long)gridDim.x * blockDim.x) {
+    const int rc = (int)(i / units_out);
+    const int u = (int)(i - (long long)rc * units_out);
+    const int go = u >> 2;
+    const int g = a.gps_out ? (go / a.gps_out) * a.gps_src + go % a.gps_out : go;
+    const size_t row = (size_t)stored_row(a.km, rc);
+    const uint4* src = reinterpret_cast<const uint4*>(a.qweight) + row * units_src + (size_t)g * 4 + (u & 3);
+    reinterpret_cast<uint4*>(a.out_qweight)[(size_t)rc * units_out + u] = *src;
+    if ((u & 3) == 0) {
+      a.out_scales[(size_t)rc * groups_out + go] = a.scales[row * groups_src + g];
+      a.out_zeros[(size_t)rc * groups_out + go] = a.zeros[row * groups_src + g];
+    }
+  }
+}
+
+hipError_t launch_w4_repack(const RepackArgs& a, hipStream_t stream) {
+  const long long total = (long long)a.km.n_keep * (a.K_out >> 5);
+  long long blocks = (total + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(w4_repack_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
 }  // namespace uniql

@@ -197,6 +197,64 @@ def test_embedding_rejects_bad_arguments():
     assert _emb(ids=P + 2) == uq.UNIQL_E_ALIGN
 
 
+def _repack(w=None, keep=None, oq=P, os_=P, oz=P, N_out=256, K_out=512):
+    w = w if w is not None else _w()
+    kd = C.byref(keep) if keep is not None else None
+    return uq.lib().uniql_w4_repack(C.byref(w), kd, C.c_void_p(oq), C.c_void_p(os_), C.c_void_p(oz), N_out, K_out, None)
+
+
+def test_repack_rejects_bad_arguments():
+    assert uq.lib().uniql_w4_repack(None, None, C.c_void_p(P), C.c_void_p(P), C.c_void_p(P), 256, 512, None) == uq.UNIQL_E_NULL
+    assert _repack(oq=0) == uq.UNIQL_E_NULL
+    assert _repack(os_=0) == uq.UNIQL_E_NULL
+    assert _repack(oz=0) == uq.UNIQL_E_NULL
+    assert _repack(w=_w(group=64)) == uq.UNIQL_E_SHAPE
+    assert _repack(N_out=255) == uq.UNIQL_E_SHAPE                        # not the size of the plan
+    assert _repack(keep=KeepDesc(k_keep=300), K_out=512) == uq.UNIQL_E_SHAPE   # the plan says 384
+    assert _repack(keep=KeepDesc(n_keep=300)) == uq.UNIQL_E_KEEP
+    assert _repack(oq=P + 8) == uq.UNIQL_E_ALIGN
+    assert _repack(os_=P + 1) == uq.UNIQL_E_ALIGN
+    n, k, ko = C.c_int32(), C.c_int32(), KeepDesc()
+    w = _w()
+    assert uq.lib().uniql_w4_repack_plan(C.byref(w), None, None, C.byref(k), C.byref(ko)) == uq.UNIQL_E_NULL
+    assert uq.lib().uniql_w4_repack_plan(None, None, C.byref(n), C.byref(k), C.byref(ko)) == uq.UNIQL_E_NULL
+    bad = KeepDesc(col_seg_stride=96, col_seg_keep=200)
+    assert uq.lib().uniql_w4_repack_plan(C.byref(w), C.byref(bad), C.byref(n), C.byref(k), C.byref(ko)) == uq.UNIQL_E_KEEP
+
+
+def test_repack_plan_matches_the_oracle(uref):
+    """The plan is host arithmetic (closed forms); the oracle derives it by scanning rows, columns and
+    groups one by one."""
+    rng = np.random.default_rng(11)
+    cases = [(1024, 1024, (870, 0, 0, 0, 0, 0, 0)), (4096, 14336, (0, 12185, 0, 0, 0, 0, 0)),
+             (4096, 4096, (0, 0, 0, 0, 0, 128, 108)), (4096, 4096, (3456, 0, 64, 54, 4096, 0, 0)),
+             (10576, 2560, (9040, 0, 5120, 4352, 10240, 0, 0)), (64, 1024, (0, 768, 0, 0, 0, 0, 0)),
+             (64, 1024, None), (16, 2048, (0, 0, 0, 0, 0, 512, 200)), (16, 2048, (0, 0, 0, 0, 0, 256, 256)),
+             (16, 768, (0, 0, 0, 0, 0, 192, 10)), (16, 512, (0, 0, 0, 0, 0, 64, 54)), (8, 512, (0, 3, 0, 0, 0, 0, 0))]
+    for _ in range(60):
+        K = 128 * int(rng.integers(1, 24))
+        N = int(rng.integers(1, 300))
+        kind = int(rng.integers(0, 3))
+        keep = [0] * 7
+        if rng.integers(0, 2):
+            keep[0] = int(rng.integers(1, N + 1))
+        if kind == 1:
+            keep[1] = int(rng.integers(1, K + 1))
+        elif kind == 2:
+            divs = [d for d in range(8, K + 1) if K % d == 0]
+            keep[5] = int(rng.choice(divs))
+            keep[6] = int(rng.integers(1, keep[5] + 1))
+        cases.append((N, K, tuple(keep)))
+    for N, K, keep in cases:
+        n, k, ko = uq.uniql_w4_repack_plan(N, K, keep)
+        en, ek, eko = uref.w4_repack_plan(N, K, keep)
+        got = (ko.n_keep, ko.k_keep, ko.row_seg_stride, ko.row_seg_keep, ko.row_seg_limit, ko.col_seg_stride, ko.col_seg_keep)
+        # k_keep = 0 and k_keep = the full count name the same columns
+        norm = lambda t, kk: tuple(t[:1]) + ((0,) if t[1] in (0, kk) and t[5] == 0 else (t[1],)) + tuple(t[2:])
+        assert (n, k) == (en, ek), (N, K, keep)
+        assert norm(got, k) == norm(eko, ek), (N, K, keep, got, eko)
+
+
 def test_valid_arguments_without_gfx950_fail_loudly():
     """On a box without an MI355X a valid call must report E_HIP / E_ARCH, never pretend to work."""
     import torch
@@ -208,3 +266,4 @@ def test_valid_arguments_without_gfx950_fail_loudly():
     assert _qkv() in (uq.UNIQL_E_HIP, uq.UNIQL_E_ARCH)
     assert _glu() in (uq.UNIQL_E_HIP, uq.UNIQL_E_ARCH)
     assert _emb() in (uq.UNIQL_E_HIP, uq.UNIQL_E_ARCH)
+    assert _repack() in (uq.UNIQL_E_HIP, uq.UNIQL_E_ARCH)

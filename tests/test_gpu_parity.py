@@ -612,3 +612,46 @@ def test_embedding_gather_bit_exact(env, uref, N, K, n, pad):
     assert np.array_equal(got.view(np.uint16), ref.view(np.uint16))
     if pad:
         assert torch.all(buf[:, K:] == -3.0), "wrote past K"
+
+
+# ------------------------------------------------- on-device repack of the kept channels
+def _repack_cases():
+    ll = {s.name: s for s in wl.llama3_8b_layer(15)}
+    mb = {s.name: s for s in wl.mamba2_2p7b_layer(15)}
+    c0 = wl.small_case()
+    return [("config0", c0.N, c0.K, c0.keep),
+            ("llama_q_proj", ll["q_proj"].N, ll["q_proj"].K, ll["q_proj"].keep),
+            ("llama_o_proj", ll["o_proj"].N, ll["o_proj"].K, ll["o_proj"].keep),
+            ("llama_gate_proj", ll["gate_proj"].N, ll["gate_proj"].K, ll["gate_proj"].keep),
+            ("llama_down_proj", ll["down_proj"].N, ll["down_proj"].K, ll["down_proj"].keep),
+            ("mamba_in_proj", mb["in_proj"].N, mb["in_proj"].K, mb["in_proj"].keep),
+            ("unpruned_ragged_rows", 77, 384, Keep()),
+            ("col_segments_of_groups", 100, 2048, Keep(k_keep=4 * 200, col_seg_stride=512, col_seg_keep=200)),
+            ("rows_and_col_prefix", 333, 1152, Keep(n_keep=250, k_keep=515)),
+            ("col_prefix_tiny", 9, 512, Keep(k_keep=3))]
+
+
+@pytest.mark.parametrize("name,N,K,keep", _repack_cases(), ids=[c[0] for c in _repack_cases()])
+def test_repack_bit_exact_and_equivalent(env, uref, name, N, K, keep):
+    """The compact matrix equals the oracle's bit for bit, and the GEMV on it (with the descriptor of the
+    plan) returns what the GEMV returns on the source with the original descriptor."""
+    uq, torch = env
+    rng = wl.rng_for(10, N + K)
+    w = wl.gen_linear(rng, N, K)
+    q2, s2, z2, keep2 = uref.w4_repack(w["qweight"], w["scales"], w["zeros"], keep)
+    src = uq.QuantLinear.from_numpy(w)
+    out, ko = uq.uniql_w4_repack(src, keep)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.qweight.cpu().numpy().view(np.uint32), q2)
+    assert np.array_equal(out.scales.cpu().numpy().view(np.uint16), s2.view(np.uint16))
+    assert np.array_equal(out.zeros.cpu().numpy(), z2)
+    nk, kk = uref.count_kept(N, K, keep)
+    assert uq.kept_dims(out, ko) == (nk, kk)
+    x = wl.gen_activations(rng, 1, kk)
+    y_src = run_linear(uq, torch, w, src, keep, x)
+    y_cmp = run_linear(uq, torch, None, out, ko, x)
+    rows = _sample_rows(nk, rng)
+    ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], x, keep, rows=rows)
+    assert linear_err(y_cmp[:, rows], ref) <= TOL
+    # same numbers summed in the same order: a chunk count that shrinks only drops zero terms
+    assert np.array_equal(y_src.view(np.uint16), y_cmp.view(np.uint16))
