@@ -64,6 +64,12 @@ def _chk(a: np.ndarray, dtype, name: str) -> np.ndarray:
     return a
 
 
+def _chkz(zeros) -> None:
+    """zeros may be None: the symmetric scheme, every zero point 8."""
+    if zeros is not None:
+        _chk(zeros, np.uint8, "zeros")
+
+
 def _keep_arr(keep) -> np.ndarray:
     if keep is None:
         return np.zeros(7, dtype=np.int32)
@@ -99,8 +105,8 @@ def w4_dequant(qweight, scales, zeros, keep=None, group: int = 128) -> np.ndarra
     """fp16 [n_keep][k_keep] dequantised weights, RN16((q - z) * s)."""
     N, K8 = qweight.shape
     K = K8 * 8
-    _chk(qweight, np.uint32, "qweight"); _chk(scales, np.float16, "scales"); _chk(zeros, np.uint8, "zeros")
-    assert scales.shape == (N, K // group) and zeros.shape == (N, K // group)
+    _chk(qweight, np.uint32, "qweight"); _chk(scales, np.float16, "scales"); _chkz(zeros)
+    assert scales.shape == (N, K // group) and (zeros is None or zeros.shape == (N, K // group))
     ka = _keep_arr(keep)
     nk, kk = count_kept(N, K, ka)
     out = np.empty((nk, kk), dtype=np.float16)
@@ -113,7 +119,7 @@ def w4_embedding(qweight, scales, zeros, ids, group: int = 128) -> np.ndarray:
     """fp16 [len(ids)][K] dequantised rows ids of a quantised table."""
     N, K8 = qweight.shape
     K = K8 * 8
-    _chk(qweight, np.uint32, "qweight"); _chk(scales, np.float16, "scales"); _chk(zeros, np.uint8, "zeros")
+    _chk(qweight, np.uint32, "qweight"); _chk(scales, np.float16, "scales"); _chkz(zeros)
     _chk(ids, np.int32, "ids")
     out = np.empty((ids.shape[0], K), dtype=np.float16)
     rc = lib().uref_w4_embedding(_p(qweight), _p(scales), _p(zeros), N, K, group, _p(ids), ids.shape[0], _p(out))
@@ -126,7 +132,7 @@ def w4_linear(qweight, scales, zeros, x, keep=None, group: int = 128,
     """fp64 y [M][n_keep] (or [M][len(rows)] for sampled compact rows)."""
     N, K8 = qweight.shape
     K = K8 * 8
-    _chk(qweight, np.uint32, "qweight"); _chk(scales, np.float16, "scales"); _chk(zeros, np.uint8, "zeros")
+    _chk(qweight, np.uint32, "qweight"); _chk(scales, np.float16, "scales"); _chkz(zeros)
     _chk(x, np.float16, "x")
     ka = _keep_arr(keep)
     nk, kk = count_kept(N, K, ka)
@@ -207,11 +213,11 @@ def w4_repack(qweight, scales, zeros, keep=None, group: int = 128):
     (qweight', scales', zeros', keep') with y(W', keep') == y(W, keep)."""
     N, K8 = qweight.shape
     K = K8 * 8
-    _chk(qweight, np.uint32, "qweight"); _chk(scales, np.float16, "scales"); _chk(zeros, np.uint8, "zeros")
+    _chk(qweight, np.uint32, "qweight"); _chk(scales, np.float16, "scales"); _chkz(zeros)
     n_out, k_out, keep_out = w4_repack_plan(N, K, keep, group)
     q2 = np.zeros((n_out, k_out // 8), dtype=np.uint32)
     s2 = np.zeros((n_out, k_out // group), dtype=np.float16)
-    z2 = np.zeros((n_out, k_out // group), dtype=np.uint8)
+    z2 = None if zeros is None else np.zeros((n_out, k_out // group), dtype=np.uint8)
     rc = lib().uref_w4_repack(_p(qweight), _p(scales), _p(zeros), N, K, group, _p(_keep_arr(keep)),
                               _p(q2), _p(s2), _p(z2))
     assert rc == 0

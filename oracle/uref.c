@@ -34,7 +34,8 @@
  * Storage convention (the paper only says INT4 is repacked into INT32):
  *   qweight uint32 [N_total][K_total/8]; nibble j (bits 4j..4j+3) of word w of a
  *   row is input column 8w+j.  scales fp16 bits [N_total][K_total/group]; zeros
- *   uint8 0..15, same shape.  Groups are those of the unpruned matrix.
+ *   uint8 0..15, same shape, or NULL: every zero point is 8, i.e. the stored code is Eq. 3's signed
+ *   code + 8 (the paper's own, symmetric, scheme).  Groups are those of the unpruned matrix.
  *
  * keep[7] = { n_keep, k_keep, row_seg_stride, row_seg_keep, row_seg_limit,
  *             col_seg_stride, col_seg_keep }:
@@ -142,7 +143,7 @@ static uint16_t dequant_one(const uint32_t* qweight, const uint16_t* scales, con
   uint32_t word = qweight[(size_t)r * (K_total / 8) + k / 8];
   int q = (int)((word >> (4 * (k % 8))) & 15u);
   size_t g = (size_t)r * (K_total / group) + k / group;
-  int z = zeros[g];
+  int z = zeros ? zeros[g] : 8;   /* no zero points: the symmetric codes of Eq. 3, stored as signed code + 8 */
   double s = uref_half_to_double(scales[g]);
   return uref_double_to_half((double)(q - z) * s);
 }
@@ -379,7 +380,7 @@ int uref_w4_repack(const uint32_t* qweight, const uint16_t* scales, const uint8_
     for (int g = 0; g < K_total / group; ++g) {
       if (!group_carried(keep, K_total, group, g)) continue;
       out_s[(size_t)ro * (K_out / group) + go] = scales[(size_t)r * (K_total / group) + g];
-      out_z[(size_t)ro * (K_out / group) + go] = zeros[(size_t)r * (K_total / group) + g];
+      if (zeros) out_z[(size_t)ro * (K_out / group) + go] = zeros[(size_t)r * (K_total / group) + g];
       for (int j = 0; j < group; ++j) {
         int k = g * group + j;
         uint32_t word = qweight[(size_t)r * (K_total / 8) + k / 8];

@@ -304,6 +304,40 @@ def test_symmetric_is_the_zero_8_case(uref):
     assert np.array_equal(Wd, exp)
 
 
+def test_no_zero_points_is_the_signed_code_scheme_of_eq3(uref):
+    """zeros = None: the stored nibble is Eq. 3's signed code + 8, so the weight is (nibble - 8) * s.
+    Checked against the signed codes read back by numpy -- for random nibbles, for the output of the
+    symmetric quantiser, and through the linear (numpy matmul on the dense signed matrix), the
+    embedding gather and the repack."""
+    rng = np.random.default_rng(81)
+    N, K = 24, 384
+    w = wl.gen_linear(rng, N, K)
+    sh = (4 * np.arange(8, dtype=np.uint32))[None, None, :]
+    signed = ((w["qweight"][:, :, None] >> sh) & np.uint32(15)).reshape(N, K).astype(np.int64) - 8
+    s = np.repeat(w["scales"].astype(np.float64), 128, axis=1)
+    dense = (signed * s).astype(np.float16)
+    got = uref.w4_dequant(w["qweight"], w["scales"], None)
+    assert np.array_equal(got.view(np.uint16), dense.view(np.uint16))
+    # a stored zero-point array is ignored only when it is absent: random zeros give something else
+    assert not np.array_equal(uref.w4_dequant(w["qweight"], w["scales"], w["zeros"]).view(np.uint16), dense.view(np.uint16))
+    keep = Keep(n_keep=17, k_keep=300)
+    x = wl.gen_activations(rng, 2, 300)
+    y = uref.w4_linear(w["qweight"], w["scales"], None, x, keep)
+    ref = x.astype(np.float64) @ dense.astype(np.float64)[:17, :300].T
+    assert np.allclose(y, ref, rtol=1e-12, atol=1e-12)
+    ids = np.array([5, 0, 23], dtype=np.int32)
+    assert np.array_equal(uref.w4_embedding(w["qweight"], w["scales"], None, ids).view(np.uint16), dense[ids].view(np.uint16))
+    q2, s2, z2, keep2 = uref.w4_repack(w["qweight"], w["scales"], None, keep)
+    assert z2 is None
+    assert np.array_equal(uref.w4_dequant(q2, s2, None, Keep(*keep2)).view(np.uint16), dense[:17, :300].view(np.uint16))
+    # Eq. 3 end to end: quantise real weights, drop the (all 8) zero points, dequantise
+    wf = rng.standard_normal((4, 256))
+    qw, sc, zr = uref.quantize_sym(wf)
+    exp = (np.clip(np.rint(wf / np.repeat(sc.astype(np.float64), 128, axis=1)), -8, 7)
+           * np.repeat(sc.astype(np.float64), 128, axis=1)).astype(np.float16)
+    assert np.array_equal(uref.w4_dequant(qw, sc, None).view(np.uint16), exp.view(np.uint16))
+
+
 def test_gate_up_silu_is_numpy_matmul_then_silu(uref):
     """h = SiLU(x Wg) * (x Wu) (Eq. 1) against an independently unpacked dense weight, numpy matmul and
     the textbook SiLU written with tanh: x * (1 + tanh(x / 2)) / 2."""
