@@ -43,7 +43,7 @@ def log(*a):
 class Layer:
     """Device tensors and buffers of one decoder layer at one pruning rate."""
 
-    def __init__(self, torch, uq, specs, rope, layer_index, rate, host_first=True):
+    def __init__(self, torch, uq, specs, rope, layer_index, rate, host_first=True, symmetric=False):
         self.specs = specs
         self.rope = rope
         self.lin = {}
@@ -52,6 +52,8 @@ class Layer:
         for si, s in enumerate(specs):
             if layer_index == 0 and host_first:
                 w = wl.gen_linear(wl.rng_for(1, 100 * rate + si), s.N, s.K)
+                if symmetric:
+                    w["zeros"] = None
                 self.lin[s.name] = uq.QuantLinear.from_numpy(w)
                 if not hasattr(self, "host"):
                     self.host = {}
@@ -61,7 +63,7 @@ class Layer:
                       - 2 ** 31).to(torch.int32)
                 sc = (torch.rand((s.N, s.K // 128), device="cuda", generator=gen) * 0.015 + 0.005).to(torch.float16)
                 zr = torch.randint(0, 16, (s.N, s.K // 128), dtype=torch.uint8, device="cuda", generator=gen)
-                self.lin[s.name] = uq.QuantLinear(qw, sc, zr)
+                self.lin[s.name] = uq.QuantLinear(qw, sc, None if symmetric else zr)
 
 
 class DecodeStep:
@@ -338,6 +340,9 @@ def main():
     ap.add_argument("--pmc-calib", action="store_true",
                     help="also launch a plain 256 MiB elementwise copy four times: the kernel of known size that "
                          "scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
+    ap.add_argument("--symmetric", action="store_true",
+                    help="matrices without zero points (Eq. 3's symmetric scheme, every z = 8): no zero point is stored or "
+                         "read; not the benchmark configuration, which is asymmetric")
     ap.add_argument("--detail", action="store_true", help="also time the other benchmark configurations (three rates, Qwen / Mamba shapes, prefill GEMM, RoPE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -353,9 +358,10 @@ def main():
     rate = args.prune
     specs = wl.llama3_8b_layer(rate)
     rope = wl.llama3_8b_rope(rate, T=M)
-    layers = [Layer(torch, uq, specs, rope, i, rate) for i in range(args.layers)]
+    layers = [Layer(torch, uq, specs, rope, i, rate, symmetric=args.symmetric) for i in range(args.layers)]
     step = DecodeStep(torch, uq, specs, rope, M)
-    lin_bytes = {s.name: s.algorithmic_bytes(M) for s in specs}
+    # without zero points a touched group costs its 2-byte scale only
+    lin_bytes = {s.name: s.algorithmic_bytes(M) - (s.n_keep * s.groups_touched() // 2 if args.symmetric else 0) for s in specs}
     step_bytes = sum(lin_bytes.values()) + rope.algorithmic_bytes()
     pool_gb = sum(s.N * s.K / 2 for s in specs) * args.layers / 1e9
     log(f"pool: {args.layers} layers, {pool_gb:.2f} GB of packed weights; step = {step_bytes / 1e6:.2f} MB algorithmic")
@@ -479,7 +485,7 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 6),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
         "data": "synthetic",
-        "config": {"workload": f"Llama-3-8B shaped decode layer, batch 1, int4 group-128 weights, "
+        "config": {"workload": f"Llama-3-8B shaped decode layer, batch 1, int4 group-128 weights{' without zero points (symmetric)' if args.symmetric else ''}, "
                                f"pruning {rate}% (q+k+v{' with the pruned RoPE as epilogue' if fuse_rope else ', pruned RoPE'}, "
                                f"o, gate+up with SiLU(gate)*up as epilogue, down: W4A16 GEMV launches), "
                                f"{args.layers}-layer weight pool streamed from HBM",
@@ -488,7 +494,7 @@ def main():
         "us_per_step_gpu_events": round(ms_per_step_gpu * 1e3, 3),
         "per_linear": per_linear,
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": PMC_TRAFFIC_BYTES.get(rate),
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None if args.symmetric else PMC_TRAFFIC_BYTES.get(rate),
                      "traffic_unit": "bytes per launch (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, copy-kernel scaled)",
                      "kernel": "w4_gemv_kernel<4,true,2,2> (gate_proj + up_proj + SiLU(gate)*up in one launch)",
                      "bytes_per_launch": int(dom_bytes), "us_per_launch": round(dom_us, 3),

@@ -51,15 +51,16 @@ enum {
  *   qweight [N_total][K_total/8] : nibble j (bits 4j..4j+3) of word w of a row is
  *                                  the code q of input column 8w+j, 0..15
  *   scales  [N_total][K_total/128]: fp16 bits, scale s of the group
- *   zeros   [N_total][K_total/128]: zero point z, 0..15 (Eq. 3's symmetric scheme
- *                                  is z = 8 with stored code = signed code + 8)
+ *   zeros   [N_total][K_total/128]: zero point z, 0..15; or NULL: every zero point is 8,
+ *                                  which is Eq. 3's symmetric scheme with stored code =
+ *                                  signed code + 8 (no zero point is read at all)
  * The dequantised weight is the fp16 number nearest (ties to even) to (q - z) * s.
  * Groups are those of the unpruned matrix (quantisation precedes pruning).
  */
 typedef struct uniql_w4 {
   const uint32_t* qweight; /* device, 16-byte aligned */
   const uint16_t* scales;  /* device */
-  const uint8_t* zeros;    /* device */
+  const uint8_t* zeros;    /* device, or NULL (symmetric) */
   int32_t N_total, K_total, group;
 } uniql_w4_t;
 
@@ -142,7 +143,8 @@ int uniql_w4_dequant(const uniql_w4_t* W, const uniql_keep_t* keep, void* w_f16,
  * uniql_w4_repack_plan: host arithmetic only, no GPU needed; only the sizes of W are read (its data
  *   pointers may be NULL).  Errors: E_NULL, E_SHAPE, E_KEEP.
  * uniql_w4_repack: out_qweight [N_out][K_out/8] (16-byte aligned), out_scales / out_zeros
- *   [N_out][K_out/128], device, caller-allocated with the sizes of the plan (E_SHAPE if N_out / K_out
+ *   [N_out][K_out/128] (out_zeros is not written, and may be NULL, when W has no zero points),
+ *   device, caller-allocated with the sizes of the plan (E_SHAPE if N_out / K_out
  *   differ from it); must not overlap the source.  Bit-exact.  Errors: as uniql_w4_dequant.
  */
 int uniql_w4_repack_plan(const uniql_w4_t* W, const uniql_keep_t* keep, int32_t* N_out, int32_t* K_out,

@@ -122,7 +122,7 @@ class QuantLinear:
     """Device tensors of one quantised linear (torch owns the memory)."""
     qweight: "torch.Tensor"   # int32 [N][K/8] (bit pattern of the uint32 words)
     scales: "torch.Tensor"    # float16 [N][K/128]
-    zeros: "torch.Tensor"     # uint8 [N][K/128]
+    zeros: "Optional[torch.Tensor]"     # uint8 [N][K/128], or None: symmetric scheme, every zero point 8
 
     @property
     def N(self) -> int:
@@ -133,7 +133,8 @@ class QuantLinear:
         return self.qweight.shape[1] * 8
 
     def desc(self) -> W4:
-        return W4(self.qweight.data_ptr(), self.scales.data_ptr(), self.zeros.data_ptr(), self.N, self.K, 128)
+        return W4(self.qweight.data_ptr(), self.scales.data_ptr(),
+                  self.zeros.data_ptr() if self.zeros is not None else None, self.N, self.K, 128)
 
     @staticmethod
     def from_numpy(w: dict, device="cuda") -> "QuantLinear":
@@ -141,7 +142,7 @@ class QuantLinear:
         import torch
         return QuantLinear(torch.from_numpy(w["qweight"].view(np.int32)).to(device),
                            torch.from_numpy(w["scales"]).to(device),
-                           torch.from_numpy(w["zeros"]).to(device))
+                           torch.from_numpy(w["zeros"]).to(device) if w.get("zeros") is not None else None)
 
 
 def kept_dims(W: QuantLinear, keep) -> tuple:
@@ -240,14 +241,15 @@ def uniql_w4_repack(W: QuantLinear, keep=None, out: Optional[QuantLinear] = None
     if out is None:
         out = QuantLinear(torch.empty((n_out, k_out // 8), dtype=torch.int32, device=dev),
                           torch.empty((n_out, k_out // 128), dtype=torch.float16, device=dev),
-                          torch.empty((n_out, k_out // 128), dtype=torch.uint8, device=dev))
+                          torch.empty((n_out, k_out // 128), dtype=torch.uint8, device=dev) if W.zeros is not None else None)
     assert out.qweight.shape == (n_out, k_out // 8) and out.scales.shape == (n_out, k_out // 128) \
-        and out.zeros.shape == out.scales.shape
-    assert out.qweight.is_contiguous() and out.scales.is_contiguous() and out.zeros.is_contiguous()
+        and (W.zeros is None or out.zeros.shape == out.scales.shape)
+    assert out.qweight.is_contiguous() and out.scales.is_contiguous() and (W.zeros is None or out.zeros.is_contiguous())
     d, kd = W.desc(), _keep_desc(keep)
     _check(lib().uniql_w4_repack(C.byref(d), C.byref(kd) if kd is not None else None,
                                  C.c_void_p(out.qweight.data_ptr()), C.c_void_p(out.scales.data_ptr()),
-                                 C.c_void_p(out.zeros.data_ptr()), n_out, k_out, _stream_ptr(stream)))
+                                 C.c_void_p(out.zeros.data_ptr()) if W.zeros is not None else None, n_out, k_out,
+                                 _stream_ptr(stream)))
     return out, ko
 
 

@@ -35,7 +35,7 @@ static bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)
 
 // Validate W / keep and normalise the keep rule.  Pure host arithmetic.
 static int make_keepmap(const uniql_w4_t* W, const uniql_keep_t* keep, KeepMap* km) {
-  if (!W || !W->qweight || !W->scales || !W->zeros) return UNIQL_E_NULL;
+  if (!W || !W->qweight || !W->scales) return UNIQL_E_NULL;   // zeros may be NULL: every zero point is 8
   if (W->group != kGroup || W->N_total < 1 || W->K_total < kGroup || W->K_total % kGroup) return UNIQL_E_SHAPE;
   if (!aligned(W->qweight, 16) || !aligned(W->scales, 2)) return UNIQL_E_ALIGN;
   uniql_keep_t none;
@@ -220,7 +220,7 @@ extern "C" int uniql_w4_repack(const uniql_w4_t* W, const uniql_keep_t* keep, ui
   RepackPlan p;
   int rc = make_repack_plan(W, keep, &a.km, &p);
   if (rc) return rc;
-  if (!out_qweight || !out_scales || !out_zeros) return UNIQL_E_NULL;
+  if (!out_qweight || !out_scales || (W->zeros && !out_zeros)) return UNIQL_E_NULL;
   if (N_out != p.N_out || K_out != p.K_out) return UNIQL_E_SHAPE;
   if (!aligned(out_qweight, 16) || !aligned(out_scales, 2)) return UNIQL_E_ALIGN;
   rc = check_arch();

@@ -160,6 +160,11 @@ hipError_t launch_w4_gemv_batch(const LinearArgs* probs, int n, hipStream_t stre
 hipError_t launch_w4_qkv_rope(const LinearArgs* probs, const RopeFuse& rf, hipStream_t stream, bool* fused);
 // gate and up of one token (probs[0], probs[1], same x) with h = SiLU(gate) * up written to probs[0].y
 hipError_t launch_w4_gate_up_silu(const LinearArgs* probs, hipStream_t stream, bool* fused);
+// the same four for matrices without zero points (a translation unit of their own)
+hipError_t launch_w4_gemv_sym(const LinearArgs& a, hipStream_t stream);
+hipError_t launch_w4_gemv_batch_sym(const LinearArgs* probs, int n, hipStream_t stream);
+hipError_t launch_w4_qkv_rope_sym(const LinearArgs* probs, const RopeFuse& rf, hipStream_t stream, bool* fused);
+hipError_t launch_w4_gate_up_silu_sym(const LinearArgs* probs, hipStream_t stream, bool* fused);
 hipError_t launch_w4_gemm(const LinearArgs& a, hipStream_t stream);
 hipError_t launch_w4_dequant(const LinearArgs& a, hipStream_t stream);
 hipError_t launch_w4_embedding(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros, int K_total,

@@ -100,7 +100,7 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
     int g = it * NG + tid % NG;
     g = g < ngroups ? g : ngroups - 1;
     sbits = a.scales[sz_row + g];
-    z = a.zeros[sz_row + g];
+    z = a.zeros ? a.zeros[sz_row + g] : 8u;   // no zero points: the symmetric scheme, z = 8
   };
 
   // x slab staging: unit u of a slab = token (u / NCH), 8-column chunk (u % NCH).
@@ -301,7 +301,7 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
         const uint32_t word = a.qweight[wrow[bf] * words_per_row + (kv >> 3)];
         const size_t gi = wrow[bf] * groups_per_row + (kv >> 7);
         const float sf = (float)__builtin_bit_cast(half_t, a.scales[gi]);
-        const int z = a.zeros[gi];
+        const int z = a.zeros ? a.zeros[gi] : 8;
         for (int j = 0; kv + j < km.k_keep; ++j) {
           const int q = (int)((word >> (4 * j)) & 15u);
           const float w = (float)(half_t)((float)(q - z) * sf);   // the canonical fp16 weight
@@ -342,7 +342,8 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
 // second MFMA by the LDS read that refills the activation fragment it just consumed.
 // Column prefix only (XVEC staging); weights and activations are addressed as a uniform base plus
 // a 32-bit per-lane offset, which the host checks for.
-template <bool DUMMY>
+// ZP = false: the matrix has no zero points (every z = 8, the symmetric scheme) and none is loaded.
+template <bool ZP>
 __global__ __launch_bounds__(512) void w4_mfma_prefill_kernel(LinearArgs a) {
   constexpr int AF = 8, BF = 2, WN = 8, NT = WN * 64, BM = 16 * AF, BN = WN * BF * 16, SC = 128, NCH = 16;
   constexpr int UPT = BM * NCH / NT;          // 16-byte staging units per thread and slab
@@ -407,8 +408,12 @@ __global__ __launch_bounds__(512) void w4_mfma_prefill_kernel(LinearArgs a) {
 #pragma unroll
     for (int bf = 0; bf < BF; ++bf) {
       sc[bf] = load_u4_unaligned(reinterpret_cast<const half_t*>(sbase + ((size_t)start + zoff[bf]) * 2));
-      const uint32_t* zp = reinterpret_cast<const uint32_t*>(zbase + (size_t)start + zoff[bf]);
-      zz[bf] = make_uint2(load_u32_unaligned(zp), load_u32_unaligned(zp + 1));
+      if constexpr (ZP) {
+        const uint32_t* zp = reinterpret_cast<const uint32_t*>(zbase + (size_t)start + zoff[bf]);
+        zz[bf] = make_uint2(load_u32_unaligned(zp), load_u32_unaligned(zp + 1));
+      } else {
+        zz[bf] = make_uint2(0x08080808u, 0x08080808u);
+      }
     }
     for (int i = start; i < g0; ++i) {   // only the last set of a row whose group count is not a multiple of 8
 #pragma unroll
@@ -573,7 +578,7 @@ __global__ __launch_bounds__(512) void w4_mfma_prefill_kernel(LinearArgs a) {
       const uint32_t word = a.qweight[wr * words_per_row + (kv >> 3)];
       const size_t gi = wr * groups_per_row + (kv >> 7);
       const float sf = (float)__builtin_bit_cast(half_t, a.scales[gi]);
-      const int z = a.zeros[gi];
+      const int z = a.zeros ? a.zeros[gi] : 8;
       for (int j = 0; kv + j < km.k_keep; ++j) {
         const int q = (int)((word >> (4 * j)) & 15u);
         const float w = (float)(half_t)((float)(q - z) * sf);   // the canonical fp16 weight
@@ -604,7 +609,7 @@ __global__ __launch_bounds__(512) void w4_mfma_prefill_kernel(LinearArgs a) {
 static hipError_t launch_prefill(const LinearArgs& a, hipStream_t stream) {
   constexpr int BM = 128, BN = 256;
   const size_t smem = (size_t)2 * BM * 128 * sizeof(half_t);
-  auto kern = w4_mfma_prefill_kernel<true>;
+  auto kern = a.zeros ? w4_mfma_prefill_kernel<true> : w4_mfma_prefill_kernel<false>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (e != hipSuccess) return e;
   dim3 grid((a.km.n_keep + BN - 1) / BN, (a.M + BM - 1) / BM);

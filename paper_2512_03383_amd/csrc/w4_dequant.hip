@@ -21,7 +21,7 @@ __global__ __launch_bounds__(256) void w4_dequant_kernel(LinearArgs a) {
     const uint32_t word = a.qweight[row * words_per_row + w];
     const size_t g = row * groups_per_row + (w >> 4);
     const float s = (float)__builtin_bit_cast(half_t, a.scales[g]);
-    const int z = a.zeros[g];
+    const int z = a.zeros ? a.zeros[g] : 8;   // no zero points: the symmetric scheme
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const int kc = compact_col(km, w * 8 + j);
@@ -60,7 +60,7 @@ __global__ __launch_bounds__(256) void w4_embedding_kernel(const uint32_t* qweig
   const size_t row = (size_t)ids[tok];
   const uint4 w = *reinterpret_cast<const uint4*>(qweight + row * (size_t)(K_total >> 3) + (k0 >> 3));
   const size_t g = row * (size_t)(K_total / kGroup) + (k0 >> 7);
-  const GroupQ gq = make_groupq(scales[g], zeros[g]);
+  const GroupQ gq = make_groupq(scales[g], zeros ? zeros[g] : 8u);
   const Magic mg = make_magic();
   const uint32_t words[4] = {w.x, w.y, w.z, w.w};
   uint4* dst = reinterpret_cast<uint4*>(out + (size_t)tok * ld + k0);   // 16-byte aligned: checked by the host
@@ -104,7 +104,7 @@ __global__ __launch_bounds__(256) void w4_repack_kernel(RepackArgs a) {
     reinterpret_cast<uint4*>(a.out_qweight)[(size_t)rc * units_out + u] = *src;
     if ((u & 3) == 0) {
       a.out_scales[(size_t)rc * groups_out + go] = a.scales[row * groups_src + g];
-      a.out_zeros[(size_t)rc * groups_out + go] = a.zeros[row * groups_src + g];
+      if (a.zeros) a.out_zeros[(size_t)rc * groups_out + go] = a.zeros[row * groups_src + g];
     }
   }
 }

@@ -82,6 +82,15 @@ def test_linear_rejects_null_shape_keep_align():
     assert _lin(_w(), KeepDesc(k_keep=7, col_seg_stride=128, col_seg_keep=64)) == L.UNIQL_E_KEEP
 
 
+def test_matrix_without_zero_points_is_accepted():
+    """zeros = NULL is the symmetric scheme, not an error: validation passes it on to the device check."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present; covered by the gpu tests")
+    assert _lin(_w(z=0), None) in (uq.UNIQL_E_HIP, uq.UNIQL_E_ARCH)
+    assert _lin(_w(z=0), KeepDesc(n_keep=300)) == uq.UNIQL_E_KEEP
+
+
 def test_dequant_rejects_bad_arguments():
     L = uq.lib()
     w = _w()

@@ -655,3 +655,83 @@ def test_repack_bit_exact_and_equivalent(env, uref, name, N, K, keep):
     assert linear_err(y_cmp[:, rows], ref) <= TOL
     # same numbers summed in the same order: a chunk count that shrinks only drops zero terms
     assert np.array_equal(y_src.view(np.uint16), y_cmp.view(np.uint16))
+
+
+# ------------------------------------------------- matrices without zero points (Eq. 3's symmetric scheme)
+def _drop_zeros(w):
+    return {"qweight": w["qweight"], "scales": w["scales"], "zeros": None}
+
+
+@pytest.mark.parametrize("N,K,keep,M", [
+    (1024, 1024, Keep(n_keep=870), 1),                    # one row per wave, wide scale loads
+    (14336, 4096, Keep(n_keep=12185), 1),                 # two rows per wave
+    (20000, 2048, Keep(), 1),                             # four rows per wave, per-tile scale loads
+    (640, 1280, Keep(k_keep=1000), 1),                    # ten groups per row: run-time chunk loop
+    (4096, 4096, Keep(k_keep=32 * 108, col_seg_stride=128, col_seg_keep=108), 1),
+    (3584, 4096, Keep(n_keep=3000, k_keep=4003), 8),      # K split over waves, tail columns in fp32
+    (512, 1024, Keep(k_keep=8 * 108, col_seg_stride=128, col_seg_keep=108), 16),
+    (1000, 2048, Keep(k_keep=1999), 48),
+    (14336, 4096, Keep(n_keep=12185), 1024),              # hand-scheduled prefill kernel
+    (4096, 14336, Keep(k_keep=12185), 333),               # prefill kernel, column prefix, ragged tokens
+])
+def test_linear_without_zero_points(env, uref, N, K, keep, M):
+    """zeros = NULL: parity with the oracle's symmetric reading, and the same bits as the same call
+    with an explicit array of 8s."""
+    uq, torch = env
+    rng = wl.rng_for(11, N + K + M)
+    w = wl.gen_linear(rng, N, K, sym_zero=True)
+    q_sym, q_z8 = uq.QuantLinear.from_numpy(_drop_zeros(w)), uq.QuantLinear.from_numpy(w)
+    assert q_sym.zeros is None
+    nk, kk = uref.count_kept(N, K, keep)
+    x = wl.gen_activations(rng, M, kk)
+    y = run_linear(uq, torch, w, q_sym, keep, x)
+    y8 = run_linear(uq, torch, w, q_z8, keep, x)
+    assert np.array_equal(y.view(np.uint16), y8.view(np.uint16))
+    rows = _sample_rows(nk, rng, 96 if M > 64 else 192)
+    toks = np.unique(np.concatenate([[0, M - 1], rng.integers(0, M, 6)]))
+    ref = uref.w4_linear(w["qweight"], w["scales"], None, np.ascontiguousarray(x[toks]), keep, rows=rows)
+    assert linear_err(y[np.ix_(toks, rows)], ref) <= TOL
+
+
+def test_fused_launches_dequant_embedding_repack_without_zero_points(env, uref):
+    uq, torch = env
+    rng = wl.rng_for(11, 5)
+    # gate + up + SiLU
+    N, K, keep = 14336, 4096, Keep(n_keep=12185)
+    wg, wu = _drop_zeros(wl.gen_linear(rng, N, K)), _drop_zeros(wl.gen_linear(rng, N, K))
+    x = wl.gen_activations(rng, 1, K)
+    h = uq.uniql_w4_gate_up_silu([uq.QuantLinear.from_numpy(wg), uq.QuantLinear.from_numpy(wu)], [keep, keep], to_dev(torch, x[0]))
+    torch.cuda.synchronize()
+    assert linear_err(h.cpu().numpy().reshape(1, -1), uref.gate_up_silu(wg, keep, wu, keep, x)) <= TOL
+    # q / k / v + RoPE on a small attention block
+    specs = {s.name: s for s in wl.attention_mlp_layer(512, 1024, 8, 2, 64, 15)}
+    rope = wl.RopeSpec(T=1, Hq=8, Hkv=2, H_tab=2, D_full=64, D_keep=specs["q_proj"].n_keep // 8, theta=10000.0, pos_max=4096)
+    ws = {n: _drop_zeros(wl.gen_linear(rng, specs[n].N, specs[n].K)) for n in ("q_proj", "k_proj", "v_proj")}
+    r = wl.gen_rope_inputs(rng, rope)
+    xq = wl.gen_activations(rng, 1, 512)
+    q, k, v = uq.uniql_w4_qkv_rope([uq.QuantLinear.from_numpy(ws[n]) for n in ("q_proj", "k_proj", "v_proj")],
+                                   [specs[n].keep for n in ("q_proj", "k_proj", "v_proj")], to_dev(torch, xq[0]),
+                                   to_dev(torch, r["positions"]), to_dev(torch, r["kept_idx"]), 8, 2, 64, rope.D_keep, rope.theta)
+    torch.cuda.synchronize()
+    rq, rk, rv = uref.qkv_rope(ws["q_proj"], specs["q_proj"].keep, ws["k_proj"], specs["k_proj"].keep, ws["v_proj"],
+                               specs["v_proj"].keep, xq, r["positions"], r["kept_idx"], 8, 2, 64, rope.D_keep, rope.theta)
+    assert linear_err(q.cpu().numpy().reshape(1, -1), rq.reshape(1, -1)) <= TOL
+    assert linear_err(k.cpu().numpy().reshape(1, -1), rk.reshape(1, -1)) <= TOL
+    assert linear_err(v.cpu().numpy().reshape(1, -1), rv) <= TOL
+    # dequant export, embedding gather, repack: bit-exact
+    w = _drop_zeros(wl.gen_linear(rng, 300, 1152))
+    qw = uq.QuantLinear.from_numpy(w)
+    kp = Keep(n_keep=250, k_keep=515)
+    got = uq.uniql_w4_dequant(qw, kp)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy().view(np.uint16), uref.w4_dequant(w["qweight"], w["scales"], None, kp).view(np.uint16))
+    ids = np.array([0, 299, 17, 17], dtype=np.int32)
+    emb = uq.uniql_w4_embedding(qw, to_dev(torch, ids))
+    torch.cuda.synchronize()
+    assert np.array_equal(emb.cpu().numpy().view(np.uint16), uref.w4_embedding(w["qweight"], w["scales"], None, ids).view(np.uint16))
+    out, ko = uq.uniql_w4_repack(qw, kp)
+    torch.cuda.synchronize()
+    q2, s2, z2, keep2 = uref.w4_repack(w["qweight"], w["scales"], None, kp)
+    assert out.zeros is None and z2 is None
+    assert np.array_equal(out.qweight.cpu().numpy().view(np.uint32), q2)
+    assert np.array_equal(out.scales.cpu().numpy().view(np.uint16), s2.view(np.uint16))
