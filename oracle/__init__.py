@@ -72,10 +72,10 @@ def _chkz(zeros) -> None:
 
 def _keep_arr(keep) -> np.ndarray:
     if keep is None:
-        return np.zeros(7, dtype=np.int32)
+        return np.zeros(10, dtype=np.int32)
     t = keep.as_tuple() if hasattr(keep, "as_tuple") else tuple(keep)
-    assert len(t) == 7
-    return np.asarray(t, dtype=np.int32)
+    assert len(t) in (7, 10)      # the second row-segment family is optional
+    return np.asarray(tuple(t) + (0,) * (10 - len(t)), dtype=np.int32)
 
 
 def set_threads(n: int) -> None:

@@ -37,10 +37,17 @@
  *   uint8 0..15, same shape, or NULL: every zero point is 8, i.e. the stored code is Eq. 3's signed
  *   code + 8 (the paper's own, symmetric, scheme).  Groups are those of the unpruned matrix.
  *
- * keep[7] = { n_keep, k_keep, row_seg_stride, row_seg_keep, row_seg_limit,
- *             col_seg_stride, col_seg_keep }:
+ * keep[10] = { n_keep, k_keep, row_seg_stride, row_seg_keep, row_seg_limit,
+ *              col_seg_stride, col_seg_keep, row_seg2_stride, row_seg2_keep, row_seg2_limit }:
  *   stored row r is kept iff  row_seg_stride == 0 ? r < n_keep
- *                           : (r >= row_seg_limit || r % row_seg_stride < row_seg_keep)
+ *                           : r < row_seg_limit ? r % row_seg_stride < row_seg_keep
+ *                           : (row_seg2_stride != 0 && r < row_seg2_limit)
+ *                                 ? (r - row_seg_limit) % row_seg2_stride < row_seg2_keep
+ *                           : 1
+ *   (the second family of segments serves the Mamba block's in_proj, Sec. 3.4: besides the head
+ *   dimension of the z and x parts, the state dimension D_s is pruned, i.e. the leading D_s' rows of
+ *   every SSM group of the B and of the C part survive, in the order Alg. 4 sorted them; the
+ *   step-size rows behind them are kept whole)
  *   stored col k is kept iff  col_seg_stride == 0 ? k < k_keep
  *                           : (k % col_seg_stride < col_seg_keep)
  *   n_keep == 0 / k_keep == 0 with stride 0 mean "all".  Kept rows and columns
@@ -103,7 +110,9 @@ uint16_t uref_double_to_half(double x) {
 
 static int row_kept(const int32_t* keep, int N_total, int r) {
   if (keep[2] == 0) return r < (keep[0] ? keep[0] : N_total);
-  return r >= keep[4] || (r % keep[2]) < keep[3];
+  if (r < keep[4]) return (r % keep[2]) < keep[3];
+  if (keep[7] != 0 && r < keep[9]) return ((r - keep[4]) % keep[7]) < keep[8];
+  return 1;
 }
 
 static int col_kept(const int32_t* keep, int K_total, int k) {
@@ -127,7 +136,7 @@ static int kept_cols(const int32_t* keep, int K_total, int32_t* list) {
 }
 
 int uref_count_kept(int N_total, int K_total, const int32_t* keep, int32_t* n_out, int32_t* k_out) {
-  static const int32_t none[7] = {0, 0, 0, 0, 0, 0, 0};
+  static const int32_t none[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   if (!keep) keep = none;
   int32_t* tmp = (int32_t*)malloc(sizeof(int32_t) * (size_t)(N_total > K_total ? N_total : K_total));
   if (!tmp) return -1;
@@ -151,7 +160,7 @@ static uint16_t dequant_one(const uint32_t* qweight, const uint16_t* scales, con
 /* w_f16: [n_keep][k_keep] compact, fp16 bits */
 int uref_w4_dequant(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
                     int N_total, int K_total, int group, const int32_t* keep, uint16_t* w_f16) {
-  static const int32_t none[7] = {0, 0, 0, 0, 0, 0, 0};
+  static const int32_t none[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   if (!keep) keep = none;
   int32_t* rows = (int32_t*)malloc(sizeof(int32_t) * (size_t)N_total);
   int32_t* cols = (int32_t*)malloc(sizeof(int32_t) * (size_t)K_total);
@@ -185,7 +194,7 @@ int uref_w4_linear(const uint32_t* qweight, const uint16_t* scales, const uint8_
                    int N_total, int K_total, int group, const int32_t* keep,
                    const uint16_t* x, int64_t ldx, double* y, int64_t ldy, int M,
                    const int32_t* row_list, int n_list) {
-  static const int32_t none[7] = {0, 0, 0, 0, 0, 0, 0};
+  static const int32_t none[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   if (!keep) keep = none;
   int32_t* rows = (int32_t*)malloc(sizeof(int32_t) * (size_t)N_total);
   int32_t* cols = (int32_t*)malloc(sizeof(int32_t) * (size_t)K_total);
@@ -344,7 +353,7 @@ static int group_carried(const int32_t* keep, int K_total, int group, int g) {
 }
 
 int uref_w4_repack_plan(int N_total, int K_total, int group, const int32_t* keep, int32_t* plan) {
-  static const int32_t none[7] = {0, 0, 0, 0, 0, 0, 0};
+  static const int32_t none[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   if (!keep) keep = none;
   int n = 0, kept_cols_total = 0, groups = 0;
   for (int r = 0; r < N_total; ++r) n += row_kept(keep, N_total, r);
@@ -368,7 +377,7 @@ int uref_w4_repack_plan(int N_total, int K_total, int group, const int32_t* keep
 int uref_w4_repack(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
                    int N_total, int K_total, int group, const int32_t* keep,
                    uint32_t* out_q, uint16_t* out_s, uint8_t* out_z) {
-  static const int32_t none[7] = {0, 0, 0, 0, 0, 0, 0};
+  static const int32_t none[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   if (!keep) keep = none;
   int32_t plan[9];
   uref_w4_repack_plan(N_total, K_total, group, keep, plan);

@@ -56,7 +56,13 @@ def kept_lists(N, K, keep: Keep):
     r = np.arange(N)
     k = np.arange(K)
     if keep.row_seg_stride:
-        rows = r[(r >= keep.row_seg_limit) | (r % keep.row_seg_stride < keep.row_seg_keep)]
+        first = (r < keep.row_seg_limit) & (r % keep.row_seg_stride < keep.row_seg_keep)
+        if keep.row_seg2_stride:
+            second = ((r >= keep.row_seg_limit) & (r < keep.row_seg2_limit)
+                      & ((r - keep.row_seg_limit) % keep.row_seg2_stride < keep.row_seg2_keep))
+            rows = r[first | second | (r >= keep.row_seg2_limit)]
+        else:
+            rows = r[first | (r >= keep.row_seg_limit)]
     else:
         rows = r[: keep.n_keep or N]
     if keep.col_seg_stride:
@@ -129,6 +135,12 @@ KEEPS = [
     Keep(k_keep=8 * 108, col_seg_stride=128, col_seg_keep=108),  # o_proj style
     Keep(n_keep=2 * 300 + 224, row_seg_stride=400, row_seg_keep=300, row_seg_limit=800),   # in_proj style + tail
     Keep(n_keep=8 * 82, k_keep=16 * 41, row_seg_stride=128, row_seg_keep=82, col_seg_stride=64, col_seg_keep=41),
+    # Mamba in_proj with head and state dimension pruned: z | x heads of 64 keep 54, B | C groups of 128 keep 109, dt whole
+    Keep(n_keep=10 * 54 + 2 * 109 + 128, row_seg_stride=64, row_seg_keep=54, row_seg_limit=640,
+         row_seg2_stride=128, row_seg2_keep=109, row_seg2_limit=896),
+    # second family running to the last row (no whole-kept tail), first family one segment
+    Keep(n_keep=500 + 4 * 100, row_seg_stride=512, row_seg_keep=500, row_seg_limit=512,
+         row_seg2_stride=128, row_seg2_keep=100, row_seg2_limit=1024),
 ]
 
 
@@ -147,6 +159,29 @@ def test_linear_matches_numpy_matmul(uref, keep):
     ref = x.astype(np.float64) @ Wd[np.ix_(rows, cols)].astype(np.float64).T
     assert y.shape == ref.shape
     assert np.max(np.abs(y - ref)) <= 1e-11
+
+
+def test_mamba_in_proj_rows_by_part(uref):
+    """The head- and state-pruned in_proj keeps, part by part, what Alg. 5 / Alg. 4 and Sec. 3.4 say: the
+    leading channels of every head of z and of x, the leading state channels of the group in B and in C,
+    every step-size row -- written here as explicit slices of the full output, not through the rule."""
+    spec = wl.mamba2_2p7b_layer_heads_and_state(15)[0]
+    H, D, Ds = 80, 64, 128
+    Dk, Sk = wl.kept_head_dim(D, 15), wl.kept_dim(Ds, 15)
+    assert (Dk, Sk) == (54, 108) and spec.N == 2 * H * D + 2 * Ds + H
+    rng = wl.rng_for(3, 77)
+    # a narrow stand-in for the 2560 input columns keeps the test fast; the rows are the real ones
+    w = wl.gen_linear(rng, spec.N, 256)
+    x = wl.gen_activations(rng, 1, 256)
+    full = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], x, None)[0]
+    y = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], x, spec.keep)[0]
+    z_part = full[: H * D].reshape(H, D)[:, :Dk].reshape(-1)
+    x_part = full[H * D: 2 * H * D].reshape(H, D)[:, :Dk].reshape(-1)
+    b_part = full[2 * H * D: 2 * H * D + Ds][:Sk]
+    c_part = full[2 * H * D + Ds: 2 * H * D + 2 * Ds][:Sk]
+    dt_part = full[2 * H * D + 2 * Ds:]
+    assert np.array_equal(y, np.concatenate([z_part, x_part, b_part, c_part, dt_part]))
+    assert y.size == spec.n_keep
 
 
 # ------------------------------------------------------ P1 / P2 invariants

@@ -44,8 +44,11 @@ class Keep:
     """Which stored rows / columns of a linear survive (all zero = unpruned).
 
     rows: if row_seg_stride == 0 the first n_keep stored rows are kept.
-          Otherwise stored row r is kept iff r >= row_seg_limit or
-          (r % row_seg_stride) < row_seg_keep; n_keep is the resulting count.
+          Otherwise stored row r below row_seg_limit is kept iff
+          (r % row_seg_stride) < row_seg_keep; a row from row_seg_limit up to
+          row_seg2_limit iff ((r - row_seg_limit) % row_seg2_stride) < row_seg2_keep
+          (when row_seg2_stride > 0); every row behind that is kept.  n_keep is the
+          resulting count.
     cols: if col_seg_stride == 0 the first k_keep stored columns are kept,
           otherwise column k is kept iff (k % col_seg_stride) < col_seg_keep.
     Kept rows / columns appear in the compact y / x in increasing stored order.
@@ -57,10 +60,14 @@ class Keep:
     row_seg_limit: int = 0
     col_seg_stride: int = 0
     col_seg_keep: int = 0
+    row_seg2_stride: int = 0
+    row_seg2_keep: int = 0
+    row_seg2_limit: int = 0
 
     def as_tuple(self):
         return (self.n_keep, self.k_keep, self.row_seg_stride, self.row_seg_keep,
-                self.row_seg_limit, self.col_seg_stride, self.col_seg_keep)
+                self.row_seg_limit, self.col_seg_stride, self.col_seg_keep,
+                self.row_seg2_stride, self.row_seg2_keep, self.row_seg2_limit)
 
 
 @dataclass(frozen=True)
@@ -192,6 +199,22 @@ def mamba2_2p7b_layer(rate_pct: int = 15) -> List[LinearSpec]:
     return [LinearSpec("in_proj", 2560, 2 * d_inner + tail,
                        _rows_seg(2 * d_inner + tail, d_inner, kd, limit=2 * d_inner)),
             LinearSpec("out_proj", d_inner, 2560, _cols_prefix(kd))]
+
+
+def mamba2_2p7b_layer_heads_and_state(rate_pct: int = 15) -> List[LinearSpec]:
+    """The same block pruned the way Alg. 4 and Alg. 5 sort it: every one of the 80 SSM heads (64
+    channels) keeps its leading channels in the z and x parts, and the single SSM group keeps the
+    leading state channels of its 128 in the B and in the C part (Sec. 3.4 prunes both the head and the
+    state dimension of a Mamba layer); the 80 step-size rows stay.  out_proj keeps the matching columns
+    of every head."""
+    H, D, Ds, G = 80, 64, 128, 1
+    d_inner = H * D
+    Dk, Sk = kept_head_dim(D, rate_pct), kept_dim(Ds, rate_pct)
+    N = 2 * d_inner + 2 * G * Ds + H
+    keep = Keep(n_keep=2 * H * Dk + 2 * G * Sk + H, row_seg_stride=D, row_seg_keep=Dk, row_seg_limit=2 * d_inner,
+                row_seg2_stride=Ds, row_seg2_keep=Sk, row_seg2_limit=2 * d_inner + 2 * G * Ds)
+    return [LinearSpec("in_proj", 2560, N, keep),
+            LinearSpec("out_proj", d_inner, 2560, _cols_seg(d_inner, D, Dk))]
 
 
 def lm_head_llama3() -> LinearSpec:
