@@ -282,6 +282,9 @@ def detail_report(torch, uq, side):
     # Mamba2-2.7B shapes, 15 %
     for spec in wl.mamba2_2p7b_layer(15):
         rep[f"mamba2_2p7b_p15_{spec.name}"] = time_linear(spec, 1, pool_for(spec))
+    # the same block with every SSM head cut to 54 of 64 channels and the B / C parts to 108 of 128 state channels
+    for spec in wl.mamba2_2p7b_layer_heads_and_state(15):
+        rep[f"mamba2_2p7b_heads_state_p15_{spec.name}"] = time_linear(spec, 1, pool_for(spec))
     torch.cuda.empty_cache()
     # the 4-bit output head (128256 x 4096), M = 1: the same GEMV at a size where launch latency is small
     spec = wl.lm_head_llama3()

@@ -69,14 +69,20 @@ typedef struct uniql_w4 {
  * all-zero struct (or a NULL pointer) means unpruned.
  *
  * rows: row_seg_stride == 0 : the first n_keep rows (n_keep == 0 -> all)
- *       row_seg_stride  > 0 : row r is kept iff r >= row_seg_limit or
- *                             (r % row_seg_stride) < row_seg_keep.  row_seg_limit
- *                             must be a multiple of the stride; n_keep must be 0
- *                             or the resulting count.
+ *       row_seg_stride  > 0 : row r < row_seg_limit is kept iff
+ *                             (r % row_seg_stride) < row_seg_keep; row_seg_limit must
+ *                             be a multiple of the stride.  With row_seg2_stride > 0 a
+ *                             second family follows: row_seg_limit <= r < row_seg2_limit
+ *                             is kept iff ((r - row_seg_limit) % row_seg2_stride) <
+ *                             row_seg2_keep (row_seg2_limit - row_seg_limit a multiple
+ *                             of that stride).  Every row behind the last family is
+ *                             kept.  n_keep must be 0 or the resulting count.
  *       (MLP gate/up: prefix of D_int.  Q/K heads: stride D_hd/2, keep D'_hd/2 —
  *        the leading channels of each half, Alg. 2.  V heads: stride D_hd, keep
- *        D'_hd.  Mamba in_proj: stride d_inner over the z and x segments with the
- *        B/C/dt rows above row_seg_limit kept whole, Alg. 5.)
+ *        D'_hd.  Mamba in_proj [z | x | B | C | dt]: first family over the z and x
+ *        parts (per head, Alg. 5: stride D_hd, keep D'_hd), second family over the B and
+ *        C parts when the state dimension is pruned too (per SSM group, Alg. 4: stride
+ *        D_s, keep D'_s), the step-size rows behind them kept whole.)
  * cols: col_seg_stride == 0 : the first k_keep columns (k_keep == 0 -> all)
  *       col_seg_stride  > 0 : column k is kept iff (k % col_seg_stride) <
  *                             col_seg_keep; the stride is at least 8 and divides
@@ -88,6 +94,7 @@ typedef struct uniql_keep {
   int32_t n_keep, k_keep;
   int32_t row_seg_stride, row_seg_keep, row_seg_limit;
   int32_t col_seg_stride, col_seg_keep;
+  int32_t row_seg2_stride, row_seg2_keep, row_seg2_limit;
 } uniql_keep_t;
 
 /*

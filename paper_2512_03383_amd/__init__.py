@@ -36,7 +36,8 @@ class KeepDesc(C.Structure):
     """uniql_keep_t"""
     _fields_ = [("n_keep", C.c_int32), ("k_keep", C.c_int32),
                 ("row_seg_stride", C.c_int32), ("row_seg_keep", C.c_int32), ("row_seg_limit", C.c_int32),
-                ("col_seg_stride", C.c_int32), ("col_seg_keep", C.c_int32)]
+                ("col_seg_stride", C.c_int32), ("col_seg_keep", C.c_int32),
+                ("row_seg2_stride", C.c_int32), ("row_seg2_keep", C.c_int32), ("row_seg2_limit", C.c_int32)]
 
 
 _lib = None
@@ -149,7 +150,12 @@ def kept_dims(W: QuantLinear, keep) -> tuple:
     """(n_keep, k_keep) the descriptor yields (same rule as the C ABI)."""
     kd = _keep_desc(keep) or KeepDesc()
     if kd.row_seg_stride:
-        n = (kd.row_seg_limit // kd.row_seg_stride) * kd.row_seg_keep + (W.N - kd.row_seg_limit)
+        n = (kd.row_seg_limit // kd.row_seg_stride) * kd.row_seg_keep
+        tail_from = kd.row_seg_limit
+        if kd.row_seg2_stride:
+            n += ((kd.row_seg2_limit - kd.row_seg_limit) // kd.row_seg2_stride) * kd.row_seg2_keep
+            tail_from = kd.row_seg2_limit
+        n += W.N - tail_from
     else:
         n = kd.n_keep or W.N
     if kd.col_seg_stride:

@@ -46,6 +46,8 @@ static int make_keepmap(const uniql_w4_t* W, const uniql_keep_t* keep, KeepMap* 
 
   km->rs_stride = keep->row_seg_stride;
   km->rs_keep = km->rs_limit = km->rs_segrows = 0;
+  km->rs2_stride = km->rs2_keep = km->rs2_limit = km->rs2_segrows = 0;
+  if (keep->row_seg2_stride < 0 || (keep->row_seg2_stride > 0 && keep->row_seg_stride == 0)) return UNIQL_E_KEEP;
   if (keep->row_seg_stride == 0) {
     if (keep->n_keep > N) return UNIQL_E_KEEP;
     km->n_keep = keep->n_keep ? keep->n_keep : N;
@@ -55,7 +57,17 @@ static int make_keepmap(const uniql_w4_t* W, const uniql_keep_t* keep, KeepMap* 
     km->rs_keep = keep->row_seg_keep;
     km->rs_limit = keep->row_seg_limit;
     km->rs_segrows = (keep->row_seg_limit / keep->row_seg_stride) * keep->row_seg_keep;
-    km->n_keep = km->rs_segrows + (N - keep->row_seg_limit);
+    km->rs2_limit = keep->row_seg_limit;
+    if (keep->row_seg2_stride > 0) {
+      const int span = keep->row_seg2_limit - keep->row_seg_limit;
+      if (keep->row_seg2_keep < 1 || keep->row_seg2_keep > keep->row_seg2_stride) return UNIQL_E_KEEP;
+      if (span < 0 || keep->row_seg2_limit > N || span % keep->row_seg2_stride) return UNIQL_E_KEEP;
+      km->rs2_stride = keep->row_seg2_stride;
+      km->rs2_keep = keep->row_seg2_keep;
+      km->rs2_limit = keep->row_seg2_limit;
+      km->rs2_segrows = (span / keep->row_seg2_stride) * keep->row_seg2_keep;
+    }
+    km->n_keep = km->rs_segrows + km->rs2_segrows + (N - km->rs2_limit);
     if (keep->n_keep && keep->n_keep != km->n_keep) return UNIQL_E_KEEP;
   }
 

@@ -23,7 +23,11 @@ struct KeepMap {
   int rs_stride;    // 0 = row prefix
   int rs_keep;
   int rs_limit;
-  int rs_segrows;   // compact rows that come from the segmented part
+  int rs_segrows;   // compact rows that come from the (first) segmented part
+  int rs2_stride;   // second family of segments, stored rows [rs_limit, rs2_limit); 0 = none
+  int rs2_keep;
+  int rs2_limit;    // rows from here on are kept whole (= rs_limit without a second family)
+  int rs2_segrows;  // compact rows that come from the second family
   int cs_stride;    // 0 = column prefix
   int cs_keep;
   int k_span;       // stored columns [0, k_span) contain every kept column
@@ -62,9 +66,16 @@ struct GemvBatch {
 // compact output row -> stored row
 __device__ __forceinline__ int stored_row(const KeepMap& km, int rc) {
   if (km.rs_stride == 0) return rc;
-  if (rc >= km.rs_segrows) return km.rs_limit + (rc - km.rs_segrows);
-  int seg = rc / km.rs_keep;
-  return seg * km.rs_stride + (rc - seg * km.rs_keep);
+  if (rc < km.rs_segrows) {
+    int seg = rc / km.rs_keep;
+    return seg * km.rs_stride + (rc - seg * km.rs_keep);
+  }
+  rc -= km.rs_segrows;
+  if (rc < km.rs2_segrows) {
+    int seg = rc / km.rs2_keep;
+    return km.rs_limit + seg * km.rs2_stride + (rc - seg * km.rs2_keep);
+  }
+  return km.rs2_limit + (rc - km.rs2_segrows);
 }
 
 // stored column -> compact column, or -1 when the column is pruned

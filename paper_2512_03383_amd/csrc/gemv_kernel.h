@@ -127,35 +127,55 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
     rope_j = batch.rf.kept_idx[(size_t)(head / (rope_heads / batch.rf.H_tab)) * hk + i];
     rope_pos = batch.rf.positions[0];
   } else {
-    // R consecutive compact rows: one division for the first, the others step through the segment
+    // R consecutive compact rows: one division for the first, the others step through their zone.
+    // Zones in compact order: first family of segments [0, rs_segrows), second family
+    // [rs_segrows, rs_segrows + rs2_segrows), whole-kept tail; a prefix is one contiguous zone.
     int rc = rg * R;
     rc = rc < km.n_keep ? rc : km.n_keep - 1;
-    const int seg_room = km.rs_stride ? km.rs_stride - km.rs_keep : 0;   // stored rows skipped at a segment end
-    int off = 0;                                                          // position inside the segment
+    const int z1 = km.rs_segrows, z2 = km.rs_segrows + km.rs2_segrows;   // compact starts of the second family and the tail
+    int off = 0, len = 1 << 30, gap = 0;   // position in the segment, kept rows per segment, stored rows skipped at its end
     if (km.rs_stride == 0) {
       srow[0] = rc;
-    } else if (rc >= km.rs_segrows) {
-      srow[0] = km.rs_limit + (rc - km.rs_segrows);
-    } else {
+    } else if (rc < z1) {
       const int seg = rc / km.rs_keep;
       off = rc - seg * km.rs_keep;
       srow[0] = seg * km.rs_stride + off;
+      len = km.rs_keep;
+      gap = km.rs_stride - km.rs_keep;
+    } else if (rc < z2) {
+      const int t = rc - z1;
+      const int seg = t / km.rs2_keep;
+      off = t - seg * km.rs2_keep;
+      srow[0] = km.rs_limit + seg * km.rs2_stride + off;
+      len = km.rs2_keep;
+      gap = km.rs2_stride - km.rs2_keep;
+    } else {
+      srow[0] = km.rs2_limit + (rc - z2);
     }
 #pragma unroll
     for (int r = 1; r < R; ++r) {
-      const bool more = rc + 1 < km.n_keep;            // past the last kept row: repeat it
-      int step = more ? 1 : 0;
-      if (km.rs_stride && more && rc < km.rs_segrows) {
-        // last row of a segment: jump to the next segment, or to the whole-kept tail (rs_limit)
-        if (off + 1 == km.rs_keep) {
-          step += (rc + 1 < km.rs_segrows) ? seg_room : km.rs_limit - (srow[r - 1] + 1);
-          off = 0;
-        } else {
-          off += 1;
-        }
+      if (rc + 1 >= km.n_keep) {            // past the last kept row: repeat it
+        srow[r] = srow[r - 1];
+        continue;
       }
-      rc += more ? 1 : 0;
-      srow[r] = srow[r - 1] + step;
+      rc += 1;
+      if (km.rs_stride != 0 && rc == z2) {          // enters the whole-kept tail (also when there is no second family)
+        srow[r] = km.rs2_limit;
+        off = 0;
+        len = 1 << 30;
+        gap = 0;
+      } else if (km.rs_stride != 0 && rc == z1) {   // enters the second family
+        srow[r] = km.rs_limit;
+        off = 0;
+        len = km.rs2_keep;
+        gap = km.rs2_stride - km.rs2_keep;
+      } else if (off + 1 == len) {                  // next segment of the same family
+        srow[r] = srow[r - 1] + 1 + gap;
+        off = 0;
+      } else {
+        srow[r] = srow[r - 1] + 1;
+        off += 1;
+      }
     }
   }
 

@@ -28,9 +28,9 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_layout_matches_header():
     assert C.sizeof(W4) == 3 * 8 + 3 * 4 + 4      # three pointers, three int32, tail padding
-    assert C.sizeof(KeepDesc) == 7 * 4
+    assert C.sizeof(KeepDesc) == 10 * 4
     assert W4.N_total.offset == 24 and W4.group.offset == 32
-    assert KeepDesc.col_seg_keep.offset == 24
+    assert KeepDesc.col_seg_keep.offset == 24 and KeepDesc.row_seg2_limit.offset == 36
 
 
 def test_strerror_covers_all_codes():
@@ -77,6 +77,13 @@ def test_linear_rejects_null_shape_keep_align():
     assert _lin(_w(), KeepDesc(row_seg_stride=64, row_seg_keep=32, row_seg_limit=100)) == L.UNIQL_E_KEEP
     assert _lin(_w(), KeepDesc(row_seg_stride=64, row_seg_keep=32, row_seg_limit=320)) == L.UNIQL_E_KEEP
     assert _lin(_w(), KeepDesc(n_keep=100, row_seg_stride=64, row_seg_keep=32, row_seg_limit=256)) == L.UNIQL_E_KEEP
+    # second family of row segments (N = 256): needs the first, keep within stride, span a multiple of the stride, inside the matrix
+    assert _lin(_w(), KeepDesc(row_seg2_stride=32, row_seg2_keep=8, row_seg2_limit=64)) == L.UNIQL_E_KEEP
+    assert _lin(_w(), KeepDesc(row_seg_stride=64, row_seg_keep=32, row_seg_limit=128, row_seg2_stride=32, row_seg2_keep=33, row_seg2_limit=192)) == L.UNIQL_E_KEEP
+    assert _lin(_w(), KeepDesc(row_seg_stride=64, row_seg_keep=32, row_seg_limit=128, row_seg2_stride=32, row_seg2_keep=8, row_seg2_limit=200)) == L.UNIQL_E_KEEP
+    assert _lin(_w(), KeepDesc(row_seg_stride=64, row_seg_keep=32, row_seg_limit=128, row_seg2_stride=32, row_seg2_keep=8, row_seg2_limit=288)) == L.UNIQL_E_KEEP
+    assert _lin(_w(), KeepDesc(row_seg_stride=64, row_seg_keep=32, row_seg_limit=128, row_seg2_stride=32, row_seg2_keep=8, row_seg2_limit=96)) == L.UNIQL_E_KEEP
+    assert _lin(_w(), KeepDesc(n_keep=64 + 16 + 65, row_seg_stride=64, row_seg_keep=32, row_seg_limit=128, row_seg2_stride=32, row_seg2_keep=8, row_seg2_limit=192)) == L.UNIQL_E_KEEP
     assert _lin(_w(), KeepDesc(col_seg_stride=100, col_seg_keep=50)) == L.UNIQL_E_KEEP
     assert _lin(_w(), KeepDesc(col_seg_stride=128, col_seg_keep=129)) == L.UNIQL_E_KEEP
     assert _lin(_w(), KeepDesc(k_keep=7, col_seg_stride=128, col_seg_keep=64)) == L.UNIQL_E_KEEP

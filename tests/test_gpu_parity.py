@@ -91,6 +91,11 @@ KEEPS = [
     Keep(n_keep=2 * 300 + 224, row_seg_stride=400, row_seg_keep=300, row_seg_limit=800),
     Keep(n_keep=8 * 82, k_keep=16 * 41, row_seg_stride=128, row_seg_keep=82, row_seg_limit=1024,
          col_seg_stride=64, col_seg_keep=41),
+    # two families of row segments and a whole-kept tail (Mamba in_proj with head and state dimension pruned)
+    Keep(n_keep=10 * 54 + 2 * 109 + 128, row_seg_stride=64, row_seg_keep=54, row_seg_limit=640,
+         row_seg2_stride=128, row_seg2_keep=109, row_seg2_limit=896),
+    Keep(n_keep=500 + 4 * 100, k_keep=700, row_seg_stride=512, row_seg_keep=500, row_seg_limit=512,
+         row_seg2_stride=128, row_seg2_keep=100, row_seg2_limit=1024),
 ]
 
 
@@ -251,6 +256,56 @@ def test_mamba2_shapes(env, uref):
         rms = np.sqrt(np.mean(ref ** 2))
         err = np.max(np.abs(y[:, rows].astype(np.float64) - ref) / np.maximum(np.abs(ref), 1e-2 * rms))
         assert err <= TOL, (spec.name, err)
+
+
+@pytest.mark.parametrize("M", [1, 8])
+def test_mamba2_head_and_state_dimension_pruned(env, uref, M):
+    """in_proj with the 80 heads of z and x cut to 54 of 64 channels and the B and C parts to 108 of 128
+    state channels (second family of row segments), out_proj with the matching per-head columns."""
+    uq, torch = env
+    rng = wl.rng_for(3, 5)
+    for spec in wl.mamba2_2p7b_layer_heads_and_state(15):
+        w = wl.gen_linear(rng, spec.N, spec.K)
+        qw = uq.QuantLinear.from_numpy(w)
+        assert uq.kept_dims(qw, spec.keep) == uref.count_kept(spec.N, spec.K, spec.keep) == (spec.n_keep, spec.k_keep)
+        x = wl.gen_activations(rng, M, spec.k_keep)
+        y = run_linear(uq, torch, w, qw, spec.keep, x)
+        rows = _sample_rows(spec.n_keep, rng, 128)
+        if spec.name == "in_proj":      # every zone boundary: z | x | B | C | dt in compact rows
+            zx, s = 2 * 80 * 54, 108
+            edges = [53, 54, zx - 1, zx, zx + s - 1, zx + s, zx + 2 * s - 1, zx + 2 * s, spec.n_keep - 1]
+            rows = np.unique(np.concatenate([rows, edges])).astype(np.int32)
+        ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], x, spec.keep, rows=rows)
+        assert linear_err(y[:, rows], ref) <= TOL, spec.name
+        if M == 1:
+            d = uq.uniql_w4_dequant(qw, spec.keep)
+            torch.cuda.synchronize()
+            assert np.array_equal(d.cpu().numpy().view(np.uint16),
+                                  uref.w4_dequant(w["qweight"], w["scales"], w["zeros"], spec.keep).view(np.uint16))
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_linear_random_two_segment_families(env, uref, seed):
+    """Seeded random two-family row rules (either family may be empty, the tail may be empty) at
+    token counts that reach the GEMV with one, two and four rows per wave and the MFMA kernels."""
+    uq, torch = env
+    rng = wl.rng_for(12, seed)
+    s1 = int(rng.choice([8, 24, 64, 100])); k1 = int(rng.integers(1, s1 + 1)); n1 = int(rng.integers(0, 40))
+    s2 = int(rng.choice([8, 16, 128])); k2 = int(rng.integers(1, s2 + 1)); n2 = int(rng.integers(0, 6))
+    tail = int(rng.integers(0, 90))
+    N = max(1, n1 * s1 + n2 * s2 + tail)
+    if n1 * s1 + n2 * s2 + tail == 0:
+        tail = 1
+    keep = Keep(n_keep=n1 * k1 + n2 * k2 + tail, row_seg_stride=s1, row_seg_keep=k1, row_seg_limit=n1 * s1,
+                row_seg2_stride=s2, row_seg2_keep=k2, row_seg2_limit=n1 * s1 + n2 * s2)
+    K = 128 * int(rng.choice([1, 4, 8, 20]))
+    M = int(rng.choice([1, 1, 1, 5, 16, 70]))
+    w = wl.gen_linear(rng, N, K)
+    qw = uq.QuantLinear.from_numpy(w)
+    x = wl.gen_activations(rng, M, K)
+    ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], x, keep)
+    y = run_linear(uq, torch, w, qw, keep, x)
+    assert y.shape == ref.shape and linear_err(y, ref) <= TOL, (N, K, M, keep)
 
 
 @pytest.mark.parametrize("M", [256, 1024])
