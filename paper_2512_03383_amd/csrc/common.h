@@ -176,6 +176,10 @@ hipError_t launch_w4_gemv_sym(const LinearArgs& a, hipStream_t stream);
 hipError_t launch_w4_gemv_batch_sym(const LinearArgs* probs, int n, hipStream_t stream);
 hipError_t launch_w4_qkv_rope_sym(const LinearArgs* probs, const RopeFuse& rf, hipStream_t stream, bool* fused);
 hipError_t launch_w4_gate_up_silu_sym(const LinearArgs* probs, hipStream_t stream, bool* fused);
+// persistent streaming GEMV for tall row-prefix x column-prefix matrices; *done = false (nothing launched)
+// when the shape is not one it serves
+hipError_t launch_w4_gemv_stream(const LinearArgs& a, hipStream_t stream, bool* done);
+hipError_t launch_w4_gate_up_stream(const LinearArgs* probs, hipStream_t stream, bool* done);
 hipError_t launch_w4_gemm(const LinearArgs& a, hipStream_t stream);
 hipError_t launch_w4_dequant(const LinearArgs& a, hipStream_t stream);
 hipError_t launch_w4_embedding(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros, int K_total,

@@ -17,10 +17,14 @@ static bool none_has_zeros(const LinearArgs* p, int n) {
 }
 
 hipError_t launch_w4_gemv(const LinearArgs& a, hipStream_t stream) {
+  bool done = false;
+  hipError_t e = launch_w4_gemv_stream(a, stream, &done);
+  if (done || e != hipSuccess) return e;
   return a.zeros ? gemv::gemv_one<true>(a, stream) : launch_w4_gemv_sym(a, stream);
 }
 
 hipError_t launch_w4_gemv_batch(const LinearArgs* probs, int n, hipStream_t stream) {
+  if (n == 1) return launch_w4_gemv(probs[0], stream);
   if (all_have_zeros(probs, n)) return gemv::gemv_batch<true>(probs, n, stream);
   if (none_has_zeros(probs, n)) return launch_w4_gemv_batch_sym(probs, n, stream);
   for (int i = 0; i < n; ++i) {   // mixed: no common kernel instantiation
@@ -31,6 +35,8 @@ hipError_t launch_w4_gemv_batch(const LinearArgs* probs, int n, hipStream_t stre
 }
 
 hipError_t launch_w4_gate_up_silu(const LinearArgs* probs, hipStream_t stream, bool* fused) {
+  hipError_t e = launch_w4_gate_up_stream(probs, stream, fused);
+  if (*fused || e != hipSuccess) return e;
   if (all_have_zeros(probs, 2)) return gemv::gate_up_silu<true>(probs, stream, fused);
   if (none_has_zeros(probs, 2)) return launch_w4_gate_up_silu_sym(probs, stream, fused);
   *fused = false;

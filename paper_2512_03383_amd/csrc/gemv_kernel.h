@@ -531,11 +531,11 @@ static hipError_t launch_rows(const LinearArgs* probs, int n, int r1, int m, int
   return launch_nch<ZP, 1, XVEC>(probs, n, m, nchunk, stream);
 }
 
-static int nchunk_of(const LinearArgs& a) {
+static inline int nchunk_of(const LinearArgs& a) {
   const int k_span32 = (a.km.k_span + 31) & ~31;
   return (k_span32 + kChunk - 1) / kChunk;
 }
-static bool xvec_of(const LinearArgs& a, int) {
+static inline bool xvec_of(const LinearArgs& a, int) {
   // a column prefix is fetched with 128-bit loads whatever the alignment of x (global loads may
   // start on any 2-byte boundary on this target)
   return a.km.cs_stride == 0 && a.km.k_keep >= 8;
