@@ -67,7 +67,7 @@ __device__ __forceinline__ ColMap make_colmap(const KeepMap& km) {
   return c;
 }
 
-// R rows per wave.  XVEC: the kept columns are a prefix and x is 16-byte aligned, so x is
+// R rows per wave.  XVEC: the kept columns are a prefix, or segments of a stride that is a multiple of 8, so x is
 // fetched with 128-bit loads; otherwise element by element through the column map (segment
 // strides are at least 8, so a unit of 8 columns wraps at most once).  NCH: chunks per row,
 // compile-time, 1..8 (NCH = 0: run-time chunk count for rows longer than 8 chunks).
@@ -292,7 +292,22 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
   float rope_sn = 0.f, rope_cs = 1.f;
 
   const ColMap cm = make_colmap(km);
-  const int kv = km.k_keep & ~7;   // XVEC: columns below kv come from whole 128-bit loads
+  // XVEC: a unit of 8 stored columns starting at k0 lies in one segment (the stride is a multiple of 8, or
+  // there is one segment: the prefix); pos = compact position of its first column, nk = how many of its
+  // columns are kept, counted from the first (<= 0: none, >= 8: all)
+  auto unit_map = [&](int k0, int& pos, int& nk) {
+    if (km.cs_stride == 0) {
+      pos = k0;
+      nk = km.k_keep - k0;
+    } else {
+      const int seg = k0 / km.cs_stride, off0 = k0 - seg * km.cs_stride;
+      pos = seg * km.cs_keep + off0;
+      nk = k0 < km.k_span ? km.cs_keep - off0 : 0;
+    }
+  };
+  // kept columns of the last, partly kept unit of a segment (8: the kept width is a multiple of 8)
+  const int seg_keep = km.cs_stride ? km.cs_keep : km.k_keep;
+  const int nk_tail = seg_keep - ((seg_keep - 1) & ~7);
   const int units = nchunk * 256;
 
   if constexpr (NCH > 0) {
@@ -311,8 +326,12 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
       const int k0 = unit_k0(uraw < NCH * 256 ? uraw : NCH * 256 - 1);   // past the end: a redundant, valid load
       okmask[i] = 0;
       if constexpr (XVEC) {
-        const int k0c = k0 + 8 <= kv ? k0 : kv - 8;   // the host selects XVEC only when k_keep >= 8
-        rawv[i] = load_u4_unaligned(xrow + k0c);
+        int pos, nk;
+        unit_map(k0, pos, nk);
+        // a unit wholly inside x is fetched where it lies (a partly kept unit of an inner segment reads on
+        // into the next segment's values, masked later); anything else fetches a valid, unused address
+        const int pc = (nk > 0 && pos + 8 <= km.k_keep) ? pos : km.k_keep - 8;   // the host selects XVEC only when k_keep >= 8
+        rawv[i] = load_u4_unaligned(xrow + pc);
       } else {
         const int seg0 = k0 / cm.stride, off0 = k0 - seg0 * cm.stride;
 #pragma unroll
@@ -328,9 +347,9 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
     if constexpr (XVEC) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) tailv[j] = 0;
-      if (kv < km.k_keep) {   // uniform: only a kept width that is not a multiple of 8 has a tail
+      if (nk_tail < 8) {   // uniform: only a kept width that is not a multiple of 8 has a tail
 #pragma unroll
-        for (int j = 0; j < 8; ++j) tailv[j] = xbits[kv + j < km.k_keep ? kv + j : km.k_keep - 1];
+        for (int j = 0; j < 8; ++j) tailv[j] = xbits[km.k_keep - nk_tail + (j < nk_tail ? j : 0)];
       }
     }
 
@@ -352,13 +371,16 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
       const int k0 = unit_k0(u);
       uint32_t e[8];
       if constexpr (XVEC) {
-        // a unit is wholly kept (k0 + 8 <= kv), the one that starts at kv (tail values), or pruned
+        // the unit's first nk columns are kept (8 or more: all of it; none: pruned); the partly kept unit
+        // that ends x takes the tail values, any other its own load
         const uint4 r = rawv[i];
         const uint32_t full[8] = {r.x & 0xffffu, r.x >> 16, r.y & 0xffffu, r.y >> 16,
                                   r.z & 0xffffu, r.z >> 16, r.w & 0xffffu, r.w >> 16};
-        const bool whole = k0 + 8 <= kv, tail = k0 == kv;
+        int pos, nk;
+        unit_map(k0, pos, nk);
+        const bool tail = nk < 8 && pos + nk == km.k_keep;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) e[j] = whole ? full[j] : ((tail && kv + j < km.k_keep) ? tailv[j] : 0u);
+        for (int j = 0; j < 8; ++j) e[j] = j < nk ? (tail ? tailv[j] : full[j]) : 0u;
       } else {
 #pragma unroll
         for (int j = 0; j < 8; ++j) e[j] = (okmask[i] >> j) & 1u ? rawe[i][j] : 0u;
@@ -538,7 +560,11 @@ static inline int nchunk_of(const LinearArgs& a) {
 static inline bool xvec_of(const LinearArgs& a, int) {
   // a column prefix is fetched with 128-bit loads whatever the alignment of x (global loads may
   // start on any 2-byte boundary on this target)
-  return a.km.cs_stride == 0 && a.km.k_keep >= 8;
+  // ... and so are column segments whose stride is a multiple of 8: a unit of 8 stored columns then lies in
+  // one segment and its kept columns are contiguous in x
+  // (with at least 8 kept columns per segment, so that a partly kept unit of an inner segment can read 16 bytes
+  // without leaving x)
+  return (a.km.cs_stride == 0 || (a.km.cs_stride % 8 == 0 && a.km.cs_keep >= 8)) && a.km.k_keep >= 8;
 }
 
 template <bool ZP>
