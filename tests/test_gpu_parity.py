@@ -790,3 +790,53 @@ def test_fused_launches_dequant_embedding_repack_without_zero_points(env, uref):
     assert out.zeros is None and z2 is None
     assert np.array_equal(out.qweight.cpu().numpy().view(np.uint32), q2)
     assert np.array_equal(out.scales.cpu().numpy().view(np.uint16), s2.view(np.uint16))
+
+
+# ------------------------------------------------- persistent streaming GEMV (tall row-prefix x column-prefix matrices)
+@pytest.mark.parametrize("N,K,keep", [
+    (8192, 128, Keep()),                                   # one chunk, a single group per row, exactly the row threshold
+    (9001, 1024, Keep(k_keep=1001)),                       # ragged rows, column prefix with a tail of one
+    (12000, 2304, Keep(n_keep=8193, k_keep=2055)),         # two chunks, 18 groups per row, tail of seven
+    (8200, 4096, Keep(n_keep=8197, k_keep=8)),             # the narrowest prefix the vector staging takes
+    (8300, 6144, Keep(k_keep=6100)),                       # three chunks: activations read from LDS per tile
+    (8192, 8192, Keep(n_keep=8191)),                       # four chunks
+    (8448, 10240, Keep(k_keep=9999)),                      # five
+    (8200, 14336, Keep(k_keep=12185)),                     # six (a tall down_proj)
+    (8200, 16384, Keep(k_keep=16383)),                     # eight chunks, the longest row the kernel takes
+])
+@pytest.mark.parametrize("sym", [False, True])
+def test_streaming_gemv_shapes(env, uref, N, K, keep, sym):
+    uq, torch = env
+    rng = wl.rng_for(13, N + K)
+    w = wl.gen_linear(rng, N, K)
+    if sym:
+        w["zeros"] = None
+    qw = uq.QuantLinear.from_numpy(w)
+    nk, kk = uref.count_kept(N, K, keep)
+    x = wl.gen_activations(rng, 1, kk)
+    y = run_linear(uq, torch, w, qw, keep, x, pad=3)
+    # every row against the oracle: the walk must reach each one exactly once
+    ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], x, keep)
+    assert y.shape == ref.shape and linear_err(y, ref) <= TOL
+
+
+@pytest.mark.parametrize("N,K,keep", [
+    (4096, 128, Keep()),                                   # exactly the row threshold of the fused launch, one chunk
+    (5000, 2048, Keep(n_keep=4097, k_keep=2047)),
+    (6000, 6144, Keep(n_keep=4500, k_keep=6001)),          # three chunks
+    (4200, 8192, Keep(k_keep=8191)),                       # four chunks, the longest row of the fused walk
+])
+@pytest.mark.parametrize("sym", [False, True])
+def test_streaming_gate_up_silu_shapes(env, uref, N, K, keep, sym):
+    uq, torch = env
+    rng = wl.rng_for(14, N + K)
+    wg, wu = wl.gen_linear(rng, N, K), wl.gen_linear(rng, N, K)
+    if sym:
+        wg["zeros"] = wu["zeros"] = None
+    nk, kk = uref.count_kept(N, K, keep)
+    x = wl.gen_activations(rng, 1, kk)
+    h = uq.uniql_w4_gate_up_silu([uq.QuantLinear.from_numpy(wg), uq.QuantLinear.from_numpy(wu)], [keep, keep], to_dev(torch, x[0]))
+    torch.cuda.synchronize()
+    ref = uref.gate_up_silu(wg, keep, wu, keep, x)      # every row
+    assert h.shape == (nk,)
+    assert linear_err(h.cpu().numpy().reshape(1, -1), ref) <= TOL
