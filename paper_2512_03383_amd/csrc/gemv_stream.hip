@@ -1,7 +1,7 @@
 // Persistent streaming GEMV for tall matrices (one token): row prefix x column prefix, at least a row
 // or two per wave of the whole chip -- gate / up / output-head shaped linears.
 //
-// The launch fills the chip once (a fixed number of blocks per CU) and every wave walks its own rows,
+// The launch fills the chip once (one or two blocks per CU) and every wave walks its own rows,
 // row r of the wave being compact row wave_id + r * total_waves, so that at any moment the chip reads
 // one contiguous window of the matrix and every CU ends up with the same number of rows whatever
 // the pruning rate.  The activations are staged once per block (LDS, stored column positions, zeros
@@ -19,7 +19,7 @@
 namespace uniql {
 namespace gemv {
 
-constexpr int kStreamThreads = 256;
+constexpr int kStreamThreads = 512;
 constexpr int kStreamWaves = kStreamThreads / kWave;
 
 struct StreamArgs {
@@ -211,22 +211,24 @@ template <int NCH, int NM, bool ZP>
 static hipError_t stream_launch(const StreamArgs& a, hipStream_t stream) {
   auto kern = w4_gemv_stream_kernel<NCH, NM, ZP>;
   const size_t smem = (size_t)NCH * 4096;
-  static int grid_cap[64];   // per device ordinal
+  static int cu_count[64], occupancy[64];   // per device ordinal
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
-  int cap = (dev >= 0 && dev < 64) ? grid_cap[dev] : 0;
-  if (cap == 0) {
-    int per_cu = 0, cus = 0;
+  int cus = (dev >= 0 && dev < 64) ? cu_count[dev] : 0, per_cu = (dev >= 0 && dev < 64) ? occupancy[dev] : 0;
+  if (cus == 0) {
     e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(kern), kStreamThreads, smem);
     if (e != hipSuccess) return e;
     e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e != hipSuccess) return e;
     if (per_cu < 1) per_cu = 1;
-    if (per_cu > 4) per_cu = 4;      // 16 waves per CU, four tiles each, keep more than enough loads in flight
-    cap = per_cu * cus;
-    if (dev >= 0 && dev < 64) grid_cap[dev] = cap;
+    if (dev >= 0 && dev < 64) { cu_count[dev] = cus; occupancy[dev] = per_cu; }
   }
+  // One block (8 waves, four tiles in flight each) per CU measured fastest up to the size of a gated MLP
+  // (more waves only add start-up work); an output-head sized stream needs two to keep enough loads in flight.
+  const long long bytes = (long long)NM * a.n_keep * (a.k_keep / 2);
+  const int want = bytes >= 100000000ll ? 2 : 1;
+  const int cap = cus * (want < per_cu ? want : per_cu);
   int blocks = (a.n_keep + kStreamWaves - 1) / kStreamWaves;
   if (blocks > cap) blocks = cap;
   hipLaunchKernelGGL(kern, dim3(blocks), dim3(kStreamThreads), smem, stream, a);
