@@ -33,7 +33,7 @@ MFMA_F16_PEAK_TFLOPS = 2500.0
 # HBM bytes per gate+up+SiLU GEMV launch at pruning 15 %, from the two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE)
 # summarised in profiles/w4_gemv_llama3_8b_decode_p15.md: 25713.1 x 2.000 KiB read + 23.8 x 1.000 KiB written, each
 # scaled by what the counter reads for a 256 MiB elementwise copy (--pmc-calib).  Other rates were not measured.
-PMC_TRAFFIC_BYTES = {15: int(25720.0 * 1024 * (262144 / 131086)) + int(23.8 * 1024)}
+PMC_TRAFFIC_BYTES = {15: int(25600.9 * 1024 * (262144 / 131086)) + int(51.7 * 1024)}
 
 
 def log(*a):
@@ -499,7 +499,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None if args.symmetric else PMC_TRAFFIC_BYTES.get(rate),
                      "traffic_unit": "bytes per launch (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, copy-kernel scaled)",
-                     "kernel": "w4_gemv_kernel<4,true,2,2> (gate_proj + up_proj + SiLU(gate)*up in one launch)",
+                     "kernel": "w4_gemv_stream_kernel<2,2,true> (gate_proj + up_proj + SiLU(gate)*up in one launch)",
                      "bytes_per_launch": int(dom_bytes), "us_per_launch": round(dom_us, 3),
                      "stream_ceiling_GBps": round(ceil_gbs, 1),
                      "frac_of_stream_ceiling": round(achieved / ceil_gbs, 4),
