@@ -259,8 +259,10 @@ static hipError_t stream_nch(const StreamArgs& a, int nchunk, hipStream_t stream
 }  // namespace gemv
 
 // Rows below which the kernels of gemv_kernel.h are used: the walk pays off once every wave of the
-// persistent grid has more than a row or two.
+// persistent grid has more than a row or two.  Rows of up to four chunks (short tile rings, activations in
+// registers or few LDS reads) already gain from one row per wave.
 constexpr int kStreamMinRows = 8192;
+constexpr int kStreamMinRowsShort = 2048;
 
 static bool stream_shape(const LinearArgs& a, int max_chunks) {
   const KeepMap& km = a.km;
@@ -272,7 +274,8 @@ static bool stream_shape(const LinearArgs& a, int max_chunks) {
 
 // One linear: *done = false (nothing launched) when the shape is not one this kernel serves.
 hipError_t launch_w4_gemv_stream(const LinearArgs& a, hipStream_t stream, bool* done) {
-  *done = stream_shape(a, 8) && a.km.n_keep >= kStreamMinRows;
+  const int nchunks = ((a.km.k_keep + 31) / 32 * 32 + gemv::kChunk - 1) / gemv::kChunk;
+  *done = stream_shape(a, 8) && a.km.n_keep >= (nchunks <= 4 ? kStreamMinRowsShort : kStreamMinRows);
   if (!*done) return hipSuccess;
   gemv::StreamArgs s;
   s.qweight[0] = s.qweight[1] = a.qweight;

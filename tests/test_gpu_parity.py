@@ -794,7 +794,10 @@ def test_fused_launches_dequant_embedding_repack_without_zero_points(env, uref):
 
 # ------------------------------------------------- persistent streaming GEMV (tall row-prefix x column-prefix matrices)
 @pytest.mark.parametrize("N,K,keep", [
-    (8192, 128, Keep()),                                   # one chunk, a single group per row, exactly the row threshold
+    (2048, 128, Keep()),                                   # one chunk, a single group per row, exactly the row threshold of short rows
+    (2047, 1024, Keep()),                                  # one row below it: the block-per-rows kernel
+    (2560, 5120, Keep(k_keep=4352)),                       # Mamba2 out_proj: three chunks
+    (8192, 10240, Keep()),                                 # exactly the row threshold of long rows
     (9001, 1024, Keep(k_keep=1001)),                       # ragged rows, column prefix with a tail of one
     (12000, 2304, Keep(n_keep=8193, k_keep=2055)),         # two chunks, 18 groups per row, tail of seven
     (8200, 4096, Keep(n_keep=8197, k_keep=8)),             # the narrowest prefix the vector staging takes
