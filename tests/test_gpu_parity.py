@@ -843,3 +843,29 @@ def test_streaming_gate_up_silu_shapes(env, uref, N, K, keep, sym):
     ref = uref.gate_up_silu(wg, keep, wu, keep, x)      # every row
     assert h.shape == (nk,)
     assert linear_err(h.cpu().numpy().reshape(1, -1), ref) <= TOL
+
+
+@pytest.mark.parametrize("N,K,keep,M", [
+    (2048, 128, Keep(), 2),                                # one chunk, the row threshold, two tokens
+    (3000, 1024, Keep(n_keep=2500, k_keep=1000), 3),       # padded to four tokens; kept width a multiple of 8
+    (14208 + 37, 3584, Keep(n_keep=14208), 8),             # Qwen2.5-7B gate / up at 25 %, eight tokens
+    (9000, 4096, Keep(), 5),                               # padded to eight tokens
+    (4100, 6144, Keep(k_keep=6016), 4),                    # three chunks
+    (2500, 8192, Keep(n_keep=2049, k_keep=8184), 8),       # four chunks, 128 KB of activations
+    (2100, 8192, Keep(), 7),
+])
+@pytest.mark.parametrize("sym", [False, True])
+def test_decode_batches_on_tall_matrices(env, uref, N, K, keep, M, sym):
+    """2..8 tokens on tall row-prefix x column-prefix matrices (small decode batches on gate / up shaped
+    linears), every output against the oracle."""
+    uq, torch = env
+    rng = wl.rng_for(15, N + K + M)
+    w = wl.gen_linear(rng, N, K)
+    if sym:
+        w["zeros"] = None
+    qw = uq.QuantLinear.from_numpy(w)
+    nk, kk = uref.count_kept(N, K, keep)
+    x = wl.gen_activations(rng, M, kk)
+    y = run_linear(uq, torch, w, qw, keep, x, pad=5)
+    ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], x, keep)
+    assert y.shape == ref.shape and linear_err(y, ref) <= TOL
