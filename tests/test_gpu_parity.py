@@ -869,3 +869,29 @@ def test_decode_batches_on_tall_matrices(env, uref, N, K, keep, M, sym):
     y = run_linear(uq, torch, w, qw, keep, x, pad=5)
     ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], x, keep)
     assert y.shape == ref.shape and linear_err(y, ref) <= TOL
+
+
+# ------------------------------------------------- prompt-sized RoPE calls
+@pytest.mark.parametrize("spec", [
+    wl.RopeSpec(T=64, Hq=32, Hkv=8, H_tab=8, D_full=128, D_keep=108, theta=5.0e5, pos_max=8192),     # 64 tokens
+    wl.RopeSpec(T=1027, Hq=32, Hkv=8, H_tab=8, D_full=128, D_keep=108, theta=5.0e5, pos_max=-1),     # odd token count
+    wl.RopeSpec(T=4099, Hq=28, Hkv=4, H_tab=4, D_full=128, D_keep=96, theta=1.0e6, pos_max=131072),  # Qwen heads
+    wl.RopeSpec(T=300, Hq=8, Hkv=8, H_tab=8, D_full=64, D_keep=64, theta=1.0e4, pos_max=4096),       # one table row per head, unpruned
+    wl.RopeSpec(T=257, Hq=6, Hkv=0, H_tab=2, D_full=256, D_keep=200, theta=1.0e4, pos_max=4096),     # no K tensor
+    wl.RopeSpec(T=128, Hq=2, Hkv=2, H_tab=1, D_full=32, D_keep=4, theta=1.0e4, pos_max=100),         # one word per half head
+    wl.RopeSpec(T=96, Hq=3, Hkv=1, H_tab=1, D_full=64, D_keep=44, theta=1.0e4, pos_max=100),         # token rows not a multiple of 16 bytes
+    wl.RopeSpec(T=70, Hq=4, Hkv=4, H_tab=4, D_full=64, D_keep=54, theta=1.0e4, pos_max=100),         # odd pair count: 2-byte accesses
+])
+def test_rope_prompt_sized_calls(env, uref, spec):
+    uq, torch = env
+    r = wl.gen_rope_inputs(wl.rng_for(16, spec.T + spec.D_keep), spec)
+    qo, ko = uref.pruned_rope(r["q"], r["k"], r["positions"], r["kept_idx"], spec.D_full, spec.theta)
+    gq, gk = run_rope(uq, torch, r, spec)
+    assert rope_err(gq, qo) <= TOL
+    if ko is not None:
+        assert rope_err(gk, ko) <= TOL
+    # pair norms survive the rotation (to fp16 rounding)
+    hk = spec.D_keep // 2
+    n_in = r["q"][..., :hk].astype(np.float64) ** 2 + r["q"][..., hk:].astype(np.float64) ** 2
+    n_out = gq[..., :hk].astype(np.float64) ** 2 + gq[..., hk:].astype(np.float64) ** 2
+    assert np.max(np.abs(n_out - n_in) / np.maximum(n_in, 1e-3)) < 5e-3
