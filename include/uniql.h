@@ -229,8 +229,10 @@ int uniql_w4_qkv_rope(const uniql_w4_t* W, const uniql_keep_t* keep, const void*
  *             rows and the same columns (they read one x and fill one h).
  *   x_f16   : device fp16 [k_keep], one token;  h_f16 : device fp16 [n_keep]
  * The library has no scratch memory for separate gate and up vectors, so shapes that cannot share one
- * launch are refused: rows longer than 16384 kept columns, or a group count per row that is not a
- * multiple of 4 (E_SHAPE; run uniql_w4_linear_multi and the activation yourself).
+ * launch are refused (E_SHAPE; run uniql_w4_linear_multi and the activation yourself): rows longer than
+ * 16384 kept columns; with fewer than 4096 kept rows (or more than 8192 kept columns, or pruned rows that
+ * are not a prefix, or pruned columns that are not a prefix) also a group count per row that is not a
+ * multiple of 4, and two members of which only one has zero points.
  * Errors: as uniql_w4_linear; E_KEEP when the two members keep different rows in number or different
  * columns; E_SHAPE as above.
  */
