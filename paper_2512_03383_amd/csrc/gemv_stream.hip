@@ -1,5 +1,5 @@
-// Persistent streaming GEMV for tall matrices (one token): row prefix x column prefix, at least a row
-// or two per wave of the whole chip -- gate / up / output-head shaped linears.
+// Persistent streaming GEMV for tall matrices (one token): any row rule x column prefix, at least a row
+// or two per wave of the whole chip -- gate / up / output-head / in_proj shaped linears.
 //
 // The launch fills the chip once (one or two blocks per CU) and every wave walks its own rows,
 // row r of the wave being compact row wave_id + r * total_waves, so that at any moment the chip reads
@@ -29,6 +29,8 @@ struct StreamArgs {
   const half_t* x;
   half_t* y;
   int n_keep, k_keep, K_total;
+  int N_total;           // stored rows (extent of the buffer resources)
+  KeepMap km;            // row map (rows only; the kept columns are a prefix)
 };
 
 template <int NCH, int NM, bool ZP>
@@ -84,14 +86,15 @@ __global__ __launch_bounds__(kStreamThreads) void w4_gemv_stream_kernel(StreamAr
   __amdgpu_buffer_rsrc_t rq[NM], rs[NM], rz[NM];
 #pragma unroll
   for (int m = 0; m < NM; ++m) {
-    rq[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(a.qweight[m]), 0, a.n_keep * words_per_row * 4, kRsrcWord3);
-    rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.scales[m]), 0, a.n_keep * groups_per_row * 2, kRsrcWord3);
+    rq[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(a.qweight[m]), 0, a.N_total * words_per_row * 4, kRsrcWord3);
+    rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.scales[m]), 0, a.N_total * groups_per_row * 2, kRsrcWord3);
     if constexpr (ZP)
-      rz[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(a.zeros[m]), 0, a.n_keep * groups_per_row, kRsrcWord3);
+      rz[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(a.zeros[m]), 0, a.N_total * groups_per_row, kRsrcWord3);
   }
   typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-  auto load_tile = [&](int rc, int m, int c, Tile& t) {   // rc: compact (= stored) row, clamped by the caller
-    const int row_q = rc * words_per_row * 4, row_g = rc * groups_per_row;   // scalar byte offsets of the row
+  auto load_tile = [&](int rc, int m, int c, Tile& t) {   // rc: compact row, clamped by the caller
+    const int sr = a.km.rs_stride ? stored_row(a.km, rc) : rc;              // uniform: scalar arithmetic
+    const int row_q = sr * words_per_row * 4, row_g = sr * groups_per_row;   // scalar byte offsets of the row
     const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rq[m], (int)woff[c], row_q, 0);
     t.w = make_uint4(v.x, v.y, v.z, v.w);
     t.sbits = __builtin_amdgcn_raw_buffer_load_b16(rs[m], (int)(2u * goff[c]), 2 * row_g, 0);
@@ -268,14 +271,15 @@ static bool stream_shape(const LinearArgs& a, int max_chunks) {
   const KeepMap& km = a.km;
   const int nch = ((km.k_keep + 31) / 32 * 32 + gemv::kChunk - 1) / gemv::kChunk;
   // row offsets inside the buffer resources are signed 32-bit byte counts
-  const bool fits = (long long)km.n_keep * (a.K_total / 2) < (1ll << 31);
-  return a.M == 1 && km.rs_stride == 0 && km.cs_stride == 0 && km.k_keep >= 8 && nch <= max_chunks && fits;
+  const bool fits = (long long)a.N_total * (a.K_total / 2) < (1ll << 31);
+  return a.M == 1 && km.cs_stride == 0 && km.k_keep >= 8 && nch <= max_chunks && fits;
 }
 
 // One linear: *done = false (nothing launched) when the shape is not one this kernel serves.
 hipError_t launch_w4_gemv_stream(const LinearArgs& a, hipStream_t stream, bool* done) {
   const int nchunks = ((a.km.k_keep + 31) / 32 * 32 + gemv::kChunk - 1) / gemv::kChunk;
-  *done = stream_shape(a, 8) && a.km.n_keep >= (nchunks <= 4 ? kStreamMinRowsShort : kStreamMinRows);
+  // (segmented row rules, one division per row, only from the higher threshold: q_proj sized launches measured slower)
+  *done = stream_shape(a, 8) && a.km.n_keep >= (nchunks <= 4 && a.km.rs_stride == 0 ? kStreamMinRowsShort : kStreamMinRows);
   if (!*done) return hipSuccess;
   gemv::StreamArgs s;
   s.qweight[0] = s.qweight[1] = a.qweight;
@@ -286,6 +290,8 @@ hipError_t launch_w4_gemv_stream(const LinearArgs& a, hipStream_t stream, bool* 
   s.n_keep = a.km.n_keep;
   s.k_keep = a.km.k_keep;
   s.K_total = a.K_total;
+  s.N_total = a.N_total;
+  s.km = a.km;
   const int nch = ((a.km.k_keep + 31) / 32 * 32 + gemv::kChunk - 1) / gemv::kChunk;
   return a.zeros ? gemv::stream_nch<1, true>(s, nch, stream) : gemv::stream_nch<1, false>(s, nch, stream);
 }
@@ -294,7 +300,9 @@ hipError_t launch_w4_gemv_stream(const LinearArgs& a, hipStream_t stream, bool* 
 hipError_t launch_w4_gate_up_stream(const LinearArgs* p, hipStream_t stream, bool* done) {
   *done = stream_shape(p[0], 4) && stream_shape(p[1], 4) && p[0].km.n_keep >= kStreamMinRows / 2 &&
           p[0].km.n_keep == p[1].km.n_keep && p[0].km.k_keep == p[1].km.k_keep && p[0].K_total == p[1].K_total &&
-          p[0].x == p[1].x && (p[0].zeros != nullptr) == (p[1].zeros != nullptr);
+          p[0].x == p[1].x && (p[0].zeros != nullptr) == (p[1].zeros != nullptr) && p[0].N_total == p[1].N_total &&
+          p[0].km.rs_stride == p[1].km.rs_stride && p[0].km.rs_keep == p[1].km.rs_keep && p[0].km.rs_limit == p[1].km.rs_limit &&
+          p[0].km.rs2_stride == p[1].km.rs2_stride && p[0].km.rs2_keep == p[1].km.rs2_keep && p[0].km.rs2_limit == p[1].km.rs2_limit;
   if (!*done) return hipSuccess;
   gemv::StreamArgs s;
   for (int m = 0; m < 2; ++m) {
@@ -307,6 +315,8 @@ hipError_t launch_w4_gate_up_stream(const LinearArgs* p, hipStream_t stream, boo
   s.n_keep = p[0].km.n_keep;
   s.k_keep = p[0].km.k_keep;
   s.K_total = p[0].K_total;
+  s.N_total = p[0].N_total;
+  s.km = p[0].km;
   const int nch = ((s.k_keep + 31) / 32 * 32 + gemv::kChunk - 1) / gemv::kChunk;
   return p[0].zeros ? gemv::stream_nch<2, true>(s, nch, stream) : gemv::stream_nch<2, false>(s, nch, stream);
 }
