@@ -33,7 +33,7 @@ MFMA_F16_PEAK_TFLOPS = 2500.0
 # HBM bytes per gate+up+SiLU GEMV launch at pruning 15 %, from the two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE)
 # summarised in profiles/w4_gemv_llama3_8b_decode_p15.md: 25713.1 x 2.000 KiB read + 23.8 x 1.000 KiB written, each
 # scaled by what the counter reads for a 256 MiB elementwise copy (--pmc-calib).  Other rates were not measured.
-PMC_TRAFFIC_BYTES = {15: int(25600.9 * 1024 * (262144 / 131086)) + int(51.7 * 1024)}
+PMC_TRAFFIC_BYTES = {15: int(25619.4 * 1024 * (262144 / 131086)) + int(50.0 * 1024)}
 
 
 def log(*a):
