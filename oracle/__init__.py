@@ -38,6 +38,14 @@ def lib():
         L.uref_half_to_double.argtypes = [C.c_uint16]
         L.uref_double_to_half.restype = C.c_uint16
         L.uref_double_to_half.argtypes = [dbl]
+        L.uref_bf16_to_double.restype = dbl
+        L.uref_bf16_to_double.argtypes = [C.c_uint16]
+        L.uref_double_to_bf16.restype = C.c_uint16
+        L.uref_double_to_bf16.argtypes = [dbl]
+        L.uref_w4_dequant_fmt.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, i32]
+        L.uref_w4_linear_fmt.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, i64, vp, i64, i32, vp, i32, i32]
+        L.uref_w4_embedding_fmt.argtypes = [vp, vp, vp, i32, i32, i32, vp, i32, vp, i32]
+        L.uref_pruned_rope_fmt.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, dbl, vp, vp, i32]
         L.uref_set_threads.argtypes = [i32]
         L.uref_get_max_threads.restype = i32
         L.uref_count_kept.argtypes = [i32, i32, vp, vp, vp]
@@ -62,6 +70,15 @@ def _chk(a: np.ndarray, dtype, name: str) -> np.ndarray:
     if a.dtype != dtype or not a.flags["C_CONTIGUOUS"]:
         raise TypeError(f"{name}: expected C-contiguous {np.dtype(dtype)}, got {a.dtype}")
     return a
+
+
+FMTS = {"f16": 0, "bf16": 1}
+
+
+def _f16_dtype(fmt: str):
+    """numpy type of 16-bit float arrays: float16 for "f16"; "bf16" arrays are uint16 bit patterns
+    (numpy has no bfloat16)."""
+    return np.float16 if FMTS[fmt] == 0 else np.uint16
 
 
 def _chkz(zeros) -> None:
@@ -94,6 +111,14 @@ def double_to_half(x: float) -> int:
     return int(lib().uref_double_to_half(float(x)))
 
 
+def bf16_to_double(bits: int) -> float:
+    return float(lib().uref_bf16_to_double(int(bits)))
+
+
+def double_to_bf16(x: float) -> int:
+    return int(lib().uref_double_to_bf16(float(x)))
+
+
 def count_kept(N_total: int, K_total: int, keep) -> tuple:
     n, k = C.c_int32(0), C.c_int32(0)
     ka = _keep_arr(keep)
@@ -101,39 +126,43 @@ def count_kept(N_total: int, K_total: int, keep) -> tuple:
     return n.value, k.value
 
 
-def w4_dequant(qweight, scales, zeros, keep=None, group: int = 128) -> np.ndarray:
-    """fp16 [n_keep][k_keep] dequantised weights, RN16((q - z) * s)."""
+def w4_dequant(qweight, scales, zeros, keep=None, group: int = 128, fmt: str = "f16") -> np.ndarray:
+    """[n_keep][k_keep] dequantised weights, RN16((q - z) * s), in the format of the scales."""
     N, K8 = qweight.shape
     K = K8 * 8
-    _chk(qweight, np.uint32, "qweight"); _chk(scales, np.float16, "scales"); _chkz(zeros)
+    ft = _f16_dtype(fmt)
+    _chk(qweight, np.uint32, "qweight"); _chk(scales, ft, "scales"); _chkz(zeros)
     assert scales.shape == (N, K // group) and (zeros is None or zeros.shape == (N, K // group))
     ka = _keep_arr(keep)
     nk, kk = count_kept(N, K, ka)
-    out = np.empty((nk, kk), dtype=np.float16)
-    rc = lib().uref_w4_dequant(_p(qweight), _p(scales), _p(zeros), N, K, group, _p(ka), _p(out))
+    out = np.empty((nk, kk), dtype=ft)
+    rc = lib().uref_w4_dequant_fmt(_p(qweight), _p(scales), _p(zeros), N, K, group, _p(ka), _p(out), FMTS[fmt])
     assert rc == 0
     return out
 
 
-def w4_embedding(qweight, scales, zeros, ids, group: int = 128) -> np.ndarray:
-    """fp16 [len(ids)][K] dequantised rows ids of a quantised table."""
+def w4_embedding(qweight, scales, zeros, ids, group: int = 128, fmt: str = "f16") -> np.ndarray:
+    """[len(ids)][K] dequantised rows ids of a quantised table, in the format of the scales."""
     N, K8 = qweight.shape
     K = K8 * 8
-    _chk(qweight, np.uint32, "qweight"); _chk(scales, np.float16, "scales"); _chkz(zeros)
+    ft = _f16_dtype(fmt)
+    _chk(qweight, np.uint32, "qweight"); _chk(scales, ft, "scales"); _chkz(zeros)
     _chk(ids, np.int32, "ids")
-    out = np.empty((ids.shape[0], K), dtype=np.float16)
-    rc = lib().uref_w4_embedding(_p(qweight), _p(scales), _p(zeros), N, K, group, _p(ids), ids.shape[0], _p(out))
+    out = np.empty((ids.shape[0], K), dtype=ft)
+    rc = lib().uref_w4_embedding_fmt(_p(qweight), _p(scales), _p(zeros), N, K, group, _p(ids), ids.shape[0],
+                                     _p(out), FMTS[fmt])
     assert rc == 0, rc
     return out
 
 
 def w4_linear(qweight, scales, zeros, x, keep=None, group: int = 128,
-              rows: Optional[Sequence[int]] = None) -> np.ndarray:
-    """fp64 y [M][n_keep] (or [M][len(rows)] for sampled compact rows)."""
+              rows: Optional[Sequence[int]] = None, fmt: str = "f16") -> np.ndarray:
+    """fp64 y [M][n_keep] (or [M][len(rows)] for sampled compact rows); scales and x in format fmt."""
     N, K8 = qweight.shape
     K = K8 * 8
-    _chk(qweight, np.uint32, "qweight"); _chk(scales, np.float16, "scales"); _chkz(zeros)
-    _chk(x, np.float16, "x")
+    ft = _f16_dtype(fmt)
+    _chk(qweight, np.uint32, "qweight"); _chk(scales, ft, "scales"); _chkz(zeros)
+    _chk(x, ft, "x")
     ka = _keep_arr(keep)
     nk, kk = count_kept(N, K, ka)
     M = x.shape[0]
@@ -141,27 +170,28 @@ def w4_linear(qweight, scales, zeros, x, keep=None, group: int = 128,
     rl = None if rows is None else np.ascontiguousarray(rows, dtype=np.int32)
     n_out = nk if rl is None else rl.size
     y = np.empty((M, n_out), dtype=np.float64)
-    rc = lib().uref_w4_linear(_p(qweight), _p(scales), _p(zeros), N, K, group, _p(ka),
-                              _p(x), kk, _p(y), n_out, M, _p(rl), 0 if rl is None else rl.size)
+    rc = lib().uref_w4_linear_fmt(_p(qweight), _p(scales), _p(zeros), N, K, group, _p(ka),
+                                  _p(x), kk, _p(y), n_out, M, _p(rl), 0 if rl is None else rl.size, FMTS[fmt])
     assert rc == 0, rc
     return y
 
 
-def pruned_rope(q, k, positions, kept_idx, D_full: int, theta: float):
-    """fp64 rotated copies of q [T][Hq][D_keep] and k [T][Hkv][D_keep] (k may be None)."""
-    _chk(q, np.float16, "q"); _chk(positions, np.int32, "positions"); _chk(kept_idx, np.int32, "kept_idx")
+def pruned_rope(q, k, positions, kept_idx, D_full: int, theta: float, fmt: str = "f16"):
+    """fp64 rotated copies of q [T][Hq][D_keep] and k [T][Hkv][D_keep] (k may be None), inputs in format fmt."""
+    ft = _f16_dtype(fmt)
+    _chk(q, ft, "q"); _chk(positions, np.int32, "positions"); _chk(kept_idx, np.int32, "kept_idx")
     T, Hq, Dk = q.shape
     H_tab = kept_idx.shape[0]
     assert kept_idx.shape == (H_tab, Dk // 2) and positions.shape == (T,)
     q_out = np.empty(q.shape, dtype=np.float64)
     Hkv, k_out = 0, None
     if k is not None:
-        _chk(k, np.float16, "k")
+        _chk(k, ft, "k")
         assert k.shape[0] == T and k.shape[2] == Dk
         Hkv = k.shape[1]
         k_out = np.empty(k.shape, dtype=np.float64)
-    rc = lib().uref_pruned_rope(_p(q), _p(k), _p(positions), _p(kept_idx), T, Hq, Hkv, H_tab,
-                                D_full, Dk, float(theta), _p(q_out), _p(k_out))
+    rc = lib().uref_pruned_rope_fmt(_p(q), _p(k), _p(positions), _p(kept_idx), T, Hq, Hkv, H_tab,
+                                    D_full, Dk, float(theta), _p(q_out), _p(k_out), FMTS[fmt])
     assert rc == 0, rc
     return q_out, k_out
 
@@ -180,23 +210,23 @@ def pruned_rope_f64(x, positions, kept_idx, D_full: int, theta: float):
 
 
 def qkv_rope(wq, keep_q, wk, keep_k, wv, keep_v, x, positions, kept_idx, Hq: int, Hkv: int, D_full: int,
-             D_keep: int, theta: float):
+             D_keep: int, theta: float, fmt: str = "f16"):
     """The fused decode step y = RoPE(x W) for the q and k projections and y = x W for v, all fp64:
     each w* is a dict(qweight, scales, zeros); x is fp16 [T][k_keep].  Returns q [T][Hq][D_keep],
     k [T][Hkv][D_keep], v [T][n_keep_v]."""
     T = x.shape[0]
-    q = w4_linear(wq["qweight"], wq["scales"], wq["zeros"], x, keep_q).reshape(T, Hq, D_keep)
-    k = w4_linear(wk["qweight"], wk["scales"], wk["zeros"], x, keep_k).reshape(T, Hkv, D_keep)
-    v = w4_linear(wv["qweight"], wv["scales"], wv["zeros"], x, keep_v)
+    q = w4_linear(wq["qweight"], wq["scales"], wq["zeros"], x, keep_q, fmt=fmt).reshape(T, Hq, D_keep)
+    k = w4_linear(wk["qweight"], wk["scales"], wk["zeros"], x, keep_k, fmt=fmt).reshape(T, Hkv, D_keep)
+    v = w4_linear(wv["qweight"], wv["scales"], wv["zeros"], x, keep_v, fmt=fmt)
     return (pruned_rope_f64(q, positions, kept_idx, D_full, theta),
             pruned_rope_f64(k, positions, kept_idx, D_full, theta), v)
 
 
-def gate_up_silu(wg, keep_g, wu, keep_u, x):
+def gate_up_silu(wg, keep_g, wu, keep_u, x, fmt: str = "f16"):
     """The gated MLP's hidden vector h = sigma(x W_gate) * (x W_up) of Eq. 1 with sigma = SiLU
     (g / (1 + exp(-g))), fp64: each w* is a dict(qweight, scales, zeros); x is fp16 [T][k_keep]."""
-    g = w4_linear(wg["qweight"], wg["scales"], wg["zeros"], x, keep_g)
-    u = w4_linear(wu["qweight"], wu["scales"], wu["zeros"], x, keep_u)
+    g = w4_linear(wg["qweight"], wg["scales"], wg["zeros"], x, keep_g, fmt=fmt)
+    u = w4_linear(wu["qweight"], wu["scales"], wu["zeros"], x, keep_u, fmt=fmt)
     return g / (1.0 + np.exp(-g)) * u
 
 
@@ -213,10 +243,12 @@ def w4_repack(qweight, scales, zeros, keep=None, group: int = 128):
     (qweight', scales', zeros', keep') with y(W', keep') == y(W, keep)."""
     N, K8 = qweight.shape
     K = K8 * 8
-    _chk(qweight, np.uint32, "qweight"); _chk(scales, np.float16, "scales"); _chkz(zeros)
+    _chk(qweight, np.uint32, "qweight"); _chkz(zeros)
+    if scales.dtype != np.uint16:     # scales are carried as they are stored: fp16, or bfloat16 bit patterns
+        _chk(scales, np.float16, "scales")
     n_out, k_out, keep_out = w4_repack_plan(N, K, keep, group)
     q2 = np.zeros((n_out, k_out // 8), dtype=np.uint32)
-    s2 = np.zeros((n_out, k_out // group), dtype=np.float16)
+    s2 = np.zeros((n_out, k_out // group), dtype=scales.dtype)
     z2 = None if zeros is None else np.zeros((n_out, k_out // group), dtype=np.uint8)
     rc = lib().uref_w4_repack(_p(qweight), _p(scales), _p(zeros), N, K, group, _p(_keep_arr(keep)),
                               _p(q2), _p(s2), _p(z2))

@@ -12,6 +12,12 @@
  * 11-bit significand).  Sums run in index order; the only parallelism is an
  * OpenMP loop over independent output rows / tokens, which reorders no sum.
  *
+ * The *_fmt functions take the 16-bit floating-point format of scales, activations and dequantised
+ * weights as an argument: fmt 0 = IEEE binary16 (the functions without the suffix), fmt 1 = bfloat16
+ * (Sec. 4.1 names BF16 as the compute type of the paper's kernels): 1 sign, 8 exponent and 7 fraction
+ * bits, i.e. the upper half of a binary32.  Nothing else changes: a weight is the bfloat16 nearest
+ * (ties to even) to (q - z) * s, sums are fp64.
+ *
  * What each function follows in the paper (UniQL, arxiv 2512.03383):
  *   uref_w4_dequant / uref_w4_linear   Sec. 3.1 (Y = X W), Eq. 1 / Eq. 2 (where
  *        the linears sit), Sec. 3.4 (group-wise 4-bit weights, group 128, pruned
@@ -106,6 +112,44 @@ uint16_t uref_double_to_half(double x) {
   return sign | (uint16_t)(((e + 15) << 10) | ((int)m - 1024));
 }
 
+/* ---- bfloat16 <-> fp64, from the format's definition: sign, 8 exponent bits (bias 127), 7 fraction
+ * bits; exponent 0 = zero and subnormals (multiples of 2^-133), exponent 255 = inf / nan ---- */
+
+double uref_bf16_to_double(uint16_t h) {
+  int sign = h >> 15, e = (h >> 7) & 255, m = h & 127;
+  double v;
+  if (e == 0)
+    v = ldexp((double)m, -133);
+  else if (e == 255)
+    v = m ? NAN : INFINITY;
+  else
+    v = ldexp((double)(128 + m), e - 134); /* (1 + m/128) * 2^(e-127) */
+  return sign ? -v : v;
+}
+
+uint16_t uref_double_to_bf16(double x) {
+  uint16_t sign = signbit(x) ? 0x8000 : 0;
+  double a = fabs(x);
+  if (isnan(x)) return 0x7fc0;
+  if (a == 0.0) return sign;
+  if (isinf(x)) return sign | 0x7f80;
+  int e;
+  (void)frexp(a, &e);
+  e -= 1; /* floor(log2 a) */
+  if (e > 127) return sign | 0x7f80;
+  if (e < -126) { /* subnormal range: multiples of 2^-133 */
+    double m = rint(ldexp(a, 133));
+    return sign | (uint16_t)m; /* m == 128 is the smallest normal, same bits */
+  }
+  double m = rint(ldexp(a, 7 - e)); /* in [128, 256] */
+  if (m == 256.0) { m = 128.0; e += 1; }
+  if (e > 127) return sign | 0x7f80; /* the largest finite value plus half an ulp rounds up to inf */
+  return sign | (uint16_t)(((e + 127) << 7) | ((int)m - 128));
+}
+
+static double f16_to_double(uint16_t h, int fmt) { return fmt ? uref_bf16_to_double(h) : uref_half_to_double(h); }
+static uint16_t double_to_f16(double x, int fmt) { return fmt ? uref_double_to_bf16(x) : uref_double_to_half(x); }
+
 /* ---- kept rows / columns: the definition, written as a scan ---- */
 
 static int row_kept(const int32_t* keep, int N_total, int r) {
@@ -146,20 +190,20 @@ int uref_count_kept(int N_total, int K_total, const int32_t* keep, int32_t* n_ou
   return 0;
 }
 
-/* one dequantised weight as fp16 bits: RN16((q - z) * s) */
+/* one dequantised weight as 16-bit float bits of format fmt: RN16((q - z) * s) */
 static uint16_t dequant_one(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
-                            int K_total, int group, int r, int k) {
+                            int K_total, int group, int r, int k, int fmt) {
   uint32_t word = qweight[(size_t)r * (K_total / 8) + k / 8];
   int q = (int)((word >> (4 * (k % 8))) & 15u);
   size_t g = (size_t)r * (K_total / group) + k / group;
   int z = zeros ? zeros[g] : 8;   /* no zero points: the symmetric codes of Eq. 3, stored as signed code + 8 */
-  double s = uref_half_to_double(scales[g]);
-  return uref_double_to_half((double)(q - z) * s);
+  double s = f16_to_double(scales[g], fmt);
+  return double_to_f16((double)(q - z) * s, fmt);
 }
 
-/* w_f16: [n_keep][k_keep] compact, fp16 bits */
-int uref_w4_dequant(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
-                    int N_total, int K_total, int group, const int32_t* keep, uint16_t* w_f16) {
+/* w_f16: [n_keep][k_keep] compact, 16-bit float bits */
+int uref_w4_dequant_fmt(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
+                        int N_total, int K_total, int group, const int32_t* keep, uint16_t* w_f16, int fmt) {
   static const int32_t none[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   if (!keep) keep = none;
   int32_t* rows = (int32_t*)malloc(sizeof(int32_t) * (size_t)N_total);
@@ -169,31 +213,41 @@ int uref_w4_dequant(const uint32_t* qweight, const uint16_t* scales, const uint8
 #pragma omp parallel for num_threads(g_threads) schedule(static)
   for (int i = 0; i < nk; ++i)
     for (int j = 0; j < kk; ++j)
-      w_f16[(size_t)i * kk + j] = dequant_one(qweight, scales, zeros, K_total, group, rows[i], cols[j]);
+      w_f16[(size_t)i * kk + j] = dequant_one(qweight, scales, zeros, K_total, group, rows[i], cols[j], fmt);
   free(rows); free(cols);
   return 0;
 }
 
+int uref_w4_dequant(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
+                    int N_total, int K_total, int group, const int32_t* keep, uint16_t* w_f16) {
+  return uref_w4_dequant_fmt(qweight, scales, zeros, N_total, K_total, group, keep, w_f16, 0);
+}
+
 /* Rows of a quantised table gathered by token id (Sec. 3.4 also quantises the embedding layer):
  * out[i][k] = RN16((q - z) * s) of row ids[i], every column; fp16 bits [n][K_total]. */
-int uref_w4_embedding(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
-                      int N_total, int K_total, int group, const int32_t* ids, int n, uint16_t* out) {
+int uref_w4_embedding_fmt(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
+                          int N_total, int K_total, int group, const int32_t* ids, int n, uint16_t* out, int fmt) {
   for (int i = 0; i < n; ++i) {
     if (ids[i] < 0 || ids[i] >= N_total) return -3;
     for (int k = 0; k < K_total; ++k)
-      out[(size_t)i * K_total + k] = dequant_one(qweight, scales, zeros, K_total, group, ids[i], k);
+      out[(size_t)i * K_total + k] = dequant_one(qweight, scales, zeros, K_total, group, ids[i], k, fmt);
   }
   return 0;
+}
+
+int uref_w4_embedding(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
+                      int N_total, int K_total, int group, const int32_t* ids, int n, uint16_t* out) {
+  return uref_w4_embedding_fmt(qweight, scales, zeros, N_total, K_total, group, ids, n, out, 0);
 }
 
 /* y[m][r'] = sum_{k'} x[m][k'] * w[row(r')][col(k')], fp64, index order.
  * x: fp16 bits [M][ldx] compact columns; y: fp64 [M][ldy] compact rows.
  * If row_list != NULL only the compact rows row_list[0..n_list) are computed,
  * and written to y[m][i] (i = position in the list) -- used to sample large cases. */
-int uref_w4_linear(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
-                   int N_total, int K_total, int group, const int32_t* keep,
-                   const uint16_t* x, int64_t ldx, double* y, int64_t ldy, int M,
-                   const int32_t* row_list, int n_list) {
+int uref_w4_linear_fmt(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
+                       int N_total, int K_total, int group, const int32_t* keep,
+                       const uint16_t* x, int64_t ldx, double* y, int64_t ldy, int M,
+                       const int32_t* row_list, int n_list, int fmt) {
   static const int32_t none[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   if (!keep) keep = none;
   int32_t* rows = (int32_t*)malloc(sizeof(int32_t) * (size_t)N_total);
@@ -210,8 +264,8 @@ int uref_w4_linear(const uint32_t* qweight, const uint16_t* scales, const uint8_
     for (int m = 0; m < M; ++m) {
       double acc = 0.0;
       for (int j = 0; j < kk; ++j) {
-        double w = uref_half_to_double(dequant_one(qweight, scales, zeros, K_total, group, r, cols[j]));
-        acc += uref_half_to_double(x[(size_t)m * ldx + j]) * w;
+        double w = f16_to_double(dequant_one(qweight, scales, zeros, K_total, group, r, cols[j], fmt), fmt);
+        acc += f16_to_double(x[(size_t)m * ldx + j], fmt) * w;
       }
       y[(size_t)m * ldy + i] = acc;
     }
@@ -220,12 +274,20 @@ int uref_w4_linear(const uint32_t* qweight, const uint16_t* scales, const uint8_
   return bad ? -2 : 0;
 }
 
+int uref_w4_linear(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
+                   int N_total, int K_total, int group, const int32_t* keep,
+                   const uint16_t* x, int64_t ldx, double* y, int64_t ldy, int M,
+                   const int32_t* row_list, int n_list) {
+  return uref_w4_linear_fmt(qweight, scales, zeros, N_total, K_total, group, keep, x, ldx, y, ldy, M,
+                            row_list, n_list, 0);
+}
+
 /* Pruned RoPE.  q: fp16 bits [T][Hq][D_keep]; k: [T][Hkv][D_keep] or NULL.
  * Kept pair i of a head is (x[i], x[i + D_keep/2]); its original pair index is
  * j = kept_idx[h_tab][i] and its angle pos * theta^(-2j/D_full).  Heads map to
  * table rows in contiguous blocks: h_tab = h / (H / H_tab).  Outputs are fp64. */
 static void rope_tensor(const uint16_t* x, double* out, const int32_t* pos, const int32_t* kept_idx,
-                        int T, int H, int H_tab, int D_full, int D_keep, double theta) {
+                        int T, int H, int H_tab, int D_full, int D_keep, double theta, int fmt) {
   int half = D_keep / 2, per = H / H_tab;
 #pragma omp parallel for num_threads(g_threads) schedule(static)
   for (int t = 0; t < T; ++t)
@@ -236,23 +298,29 @@ static void rope_tensor(const uint16_t* x, double* out, const int32_t* pos, cons
       for (int i = 0; i < half; ++i) {
         int j = tab[i];
         double phi = (double)pos[t] * pow(theta, -2.0 * (double)j / (double)D_full);
-        double a = uref_half_to_double(xv[i]), b = uref_half_to_double(xv[i + half]);
+        double a = f16_to_double(xv[i], fmt), b = f16_to_double(xv[i + half], fmt);
         ov[i] = a * cos(phi) - b * sin(phi);
         ov[i + half] = b * cos(phi) + a * sin(phi);
       }
     }
 }
 
+int uref_pruned_rope_fmt(const uint16_t* q, const uint16_t* k, const int32_t* positions,
+                         const int32_t* kept_idx, int T, int Hq, int Hkv, int H_tab, int D_full,
+                         int D_keep, double theta, double* q_out, double* k_out, int fmt) {
+  if (D_keep % 2 || D_keep > D_full || H_tab < 1 || Hq % H_tab) return -3;
+  rope_tensor(q, q_out, positions, kept_idx, T, Hq, H_tab, D_full, D_keep, theta, fmt);
+  if (k) {
+    if (Hkv % H_tab) return -3;
+    rope_tensor(k, k_out, positions, kept_idx, T, Hkv, H_tab, D_full, D_keep, theta, fmt);
+  }
+  return 0;
+}
+
 int uref_pruned_rope(const uint16_t* q, const uint16_t* k, const int32_t* positions,
                      const int32_t* kept_idx, int T, int Hq, int Hkv, int H_tab, int D_full,
                      int D_keep, double theta, double* q_out, double* k_out) {
-  if (D_keep % 2 || D_keep > D_full || H_tab < 1 || Hq % H_tab) return -3;
-  rope_tensor(q, q_out, positions, kept_idx, T, Hq, H_tab, D_full, D_keep, theta);
-  if (k) {
-    if (Hkv % H_tab) return -3;
-    rope_tensor(k, k_out, positions, kept_idx, T, Hkv, H_tab, D_full, D_keep, theta);
-  }
-  return 0;
+  return uref_pruned_rope_fmt(q, k, positions, kept_idx, T, Hq, Hkv, H_tab, D_full, D_keep, theta, q_out, k_out, 0);
 }
 
 /* The same rotation on fp64 inputs, in place: x [T][H][D_keep].  It defines the fused

@@ -251,13 +251,30 @@ def rng_for(config_index: int, stream: int = 0) -> np.random.Generator:
     return np.random.default_rng([SEED_BASE + config_index, stream])
 
 
+def to_bf16_bits(a: np.ndarray) -> np.ndarray:
+    """Storage format of generated inputs: float32 -> bfloat16 bit patterns (the upper half of the
+    binary32, rounded to nearest even) as uint16; numpy has no bfloat16 type."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """The values of bfloat16 bit patterns (exact: a bfloat16 is a binary32 with a zero lower half)."""
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32)
+
+
+def _store16(a: np.ndarray, fmt: str) -> np.ndarray:
+    return a.astype(np.float16) if fmt == "f16" else to_bf16_bits(a.astype(np.float32))
+
+
 def gen_linear(rng: np.random.Generator, N: int, K: int,
-               sym_zero: bool = False) -> Dict[str, np.ndarray]:
+               sym_zero: bool = False, fmt: str = "f16") -> Dict[str, np.ndarray]:
     """Random packed nibbles (uniform 32-bit words are eight uniform nibbles),
-    fp16 scales ~ U(0.005, 0.02) and zeros ~ U{0..15} (or all 8 when sym_zero)."""
+    scales ~ U(0.005, 0.02) stored as fp16 (fmt "f16") or as bfloat16 bit patterns (fmt "bf16", uint16)
+    and zeros ~ U{0..15} (or all 8 when sym_zero)."""
     assert K % GROUP == 0
     qweight = rng.integers(0, 2 ** 32, size=(N, K // 8), dtype=np.uint64).astype(np.uint32)
-    scales = rng.uniform(0.005, 0.02, size=(N, K // GROUP)).astype(np.float16)
+    scales = _store16(rng.uniform(0.005, 0.02, size=(N, K // GROUP)), fmt)
     if sym_zero:
         zeros = np.full((N, K // GROUP), 8, dtype=np.uint8)
     else:
@@ -265,16 +282,16 @@ def gen_linear(rng: np.random.Generator, N: int, K: int,
     return {"qweight": qweight, "scales": scales, "zeros": zeros}
 
 
-def gen_activations(rng: np.random.Generator, M: int, K: int) -> np.ndarray:
-    return rng.standard_normal((M, K)).astype(np.float16)
+def gen_activations(rng: np.random.Generator, M: int, K: int, fmt: str = "f16") -> np.ndarray:
+    return _store16(rng.standard_normal((M, K)), fmt)
 
 
-def gen_rope_inputs(rng: np.random.Generator, spec: RopeSpec) -> Dict[str, Optional[np.ndarray]]:
-    """q [T][Hq][D_keep], k [T][Hkv][D_keep] ~ N(0,1) fp16, int32 positions and a
-    kept-index table whose rows are the first D_keep/2 entries of a random
+def gen_rope_inputs(rng: np.random.Generator, spec: RopeSpec, fmt: str = "f16") -> Dict[str, Optional[np.ndarray]]:
+    """q [T][Hq][D_keep], k [T][Hkv][D_keep] ~ N(0,1) in fp16 (or bfloat16 bit patterns), int32 positions
+    and a kept-index table whose rows are the first D_keep/2 entries of a random
     permutation of 0..D_full/2-1 (importance order, not numerically sorted)."""
-    q = rng.standard_normal((spec.T, spec.Hq, spec.D_keep)).astype(np.float16)
-    k = (rng.standard_normal((spec.T, spec.Hkv, spec.D_keep)).astype(np.float16)
+    q = _store16(rng.standard_normal((spec.T, spec.Hq, spec.D_keep)), fmt)
+    k = (_store16(rng.standard_normal((spec.T, spec.Hkv, spec.D_keep)), fmt)
          if spec.Hkv else None)
     if spec.pos_max < 0:
         pos = np.arange(spec.T, dtype=np.int32)
