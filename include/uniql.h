@@ -50,18 +50,29 @@ enum {
  *
  *   qweight [N_total][K_total/8] : nibble j (bits 4j..4j+3) of word w of a row is
  *                                  the code q of input column 8w+j, 0..15
- *   scales  [N_total][K_total/128]: fp16 bits, scale s of the group
+ *   scales  [N_total][K_total/128]: scale s of the group, 16-bit float bits in the format `dtype`
  *   zeros   [N_total][K_total/128]: zero point z, 0..15; or NULL: every zero point is 8,
  *                                  which is Eq. 3's symmetric scheme with stored code =
  *                                  signed code + 8 (no zero point is read at all)
  * The dequantised weight is the fp16 number nearest (ties to even) to (q - z) * s.
  * Groups are those of the unpruned matrix (quantisation precedes pruning).
+ *
+ * dtype selects the 16-bit floating-point format of everything that goes with the matrix: its
+ * scales, the activations multiplied with it and the outputs (all the `_f16` arguments of the calls
+ * below).  UNIQL_F16 (0, so a zero-initialised field keeps its meaning) is IEEE binary16;
+ * UNIQL_BF16 is bfloat16, the compute type the paper names (Sec. 4.1): the dequantised weight is then
+ * the bfloat16 nearest (ties to even) to (q - z) * s, sums are still fp32 and rounded once.
+ * Matrices that share a call (multi, qkv_rope, gate_up_silu) must share the format, except in
+ * uniql_w4_linear_multi, which then runs them one by one.
  */
+enum { UNIQL_F16 = 0, UNIQL_BF16 = 1 };
+
 typedef struct uniql_w4 {
   const uint32_t* qweight; /* device, 16-byte aligned */
   const uint16_t* scales;  /* device */
   const uint8_t* zeros;    /* device, or NULL (symmetric) */
   int32_t N_total, K_total, group;
+  int32_t dtype;           /* UNIQL_F16 or UNIQL_BF16; anything else: E_SHAPE */
 } uniql_w4_t;
 
 /*
@@ -194,6 +205,13 @@ int uniql_w4_embedding(const uniql_w4_t* W, const int32_t* ids, int32_t n, void*
 int uniql_pruned_rope(void* q_f16, void* k_f16, const int32_t* positions, const int32_t* kept_idx,
                       int32_t T, int32_t Hq, int32_t Hkv, int32_t H_tab, int32_t D_full,
                       int32_t D_keep, double theta, void* hip_stream);
+
+/* The same rotation (Sec. 3.2, Alg. 2 / Alg. A1) of bfloat16 tensors (Sec. 4.1's compute type): every
+ * argument, layout and error as in uniql_pruned_rope; q and k hold bfloat16 and are rounded to
+ * bfloat16 (nearest even) once, after the fp32 rotation. */
+int uniql_pruned_rope_bf16(void* q_bf16, void* k_bf16, const int32_t* positions, const int32_t* kept_idx,
+                           int32_t T, int32_t Hq, int32_t Hkv, int32_t H_tab, int32_t D_full,
+                           int32_t D_keep, double theta, void* hip_stream);
 
 /*
  * Decode step of an attention block's input side in ONE launch (Eq. 2 followed by the rotary

@@ -29,7 +29,10 @@ class UniqlError(RuntimeError):
 class W4(C.Structure):
     """uniql_w4_t"""
     _fields_ = [("qweight", C.c_void_p), ("scales", C.c_void_p), ("zeros", C.c_void_p),
-                ("N_total", C.c_int32), ("K_total", C.c_int32), ("group", C.c_int32)]
+                ("N_total", C.c_int32), ("K_total", C.c_int32), ("group", C.c_int32), ("dtype", C.c_int32)]
+
+
+UNIQL_F16, UNIQL_BF16 = 0, 1
 
 
 class KeepDesc(C.Structure):
@@ -69,6 +72,8 @@ def lib():
         L.uniql_w4_dequant.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, vp]
         L.uniql_pruned_rope.restype = C.c_int
         L.uniql_pruned_rope.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, C.c_double, vp]
+        L.uniql_pruned_rope_bf16.restype = C.c_int
+        L.uniql_pruned_rope_bf16.argtypes = L.uniql_pruned_rope.argtypes
         L.uniql_stream_read_probe.restype = C.c_int
         L.uniql_w4_qkv_rope.restype = C.c_int
         L.uniql_w4_qkv_rope.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, vp, vp, vp, vp, vp,
@@ -122,7 +127,7 @@ def _stream_ptr(stream) -> Optional[int]:
 class QuantLinear:
     """Device tensors of one quantised linear (torch owns the memory)."""
     qweight: "torch.Tensor"   # int32 [N][K/8] (bit pattern of the uint32 words)
-    scales: "torch.Tensor"    # float16 [N][K/128]
+    scales: "torch.Tensor"    # float16 or bfloat16 [N][K/128]: the format of activations and outputs too
     zeros: "Optional[torch.Tensor]"     # uint8 [N][K/128], or None: symmetric scheme, every zero point 8
 
     @property
@@ -133,16 +138,28 @@ class QuantLinear:
     def K(self) -> int:
         return self.qweight.shape[1] * 8
 
+    @property
+    def ftype(self):
+        """torch dtype of the scales = of the activations and outputs that go with this matrix."""
+        import torch
+        assert self.scales.dtype in (torch.float16, torch.bfloat16)
+        return self.scales.dtype
+
     def desc(self) -> W4:
+        import torch
         return W4(self.qweight.data_ptr(), self.scales.data_ptr(),
-                  self.zeros.data_ptr() if self.zeros is not None else None, self.N, self.K, 128)
+                  self.zeros.data_ptr() if self.zeros is not None else None, self.N, self.K, 128,
+                  UNIQL_BF16 if self.ftype == torch.bfloat16 else UNIQL_F16)
 
     @staticmethod
     def from_numpy(w: dict, device="cuda") -> "QuantLinear":
         import numpy as np
         import torch
+        scales = w["scales"]      # float16, or uint16 bit patterns of bfloat16
+        scales = (torch.from_numpy(scales.view(np.int16)).view(torch.bfloat16) if scales.dtype == np.uint16
+                  else torch.from_numpy(scales))
         return QuantLinear(torch.from_numpy(w["qweight"].view(np.int32)).to(device),
-                           torch.from_numpy(w["scales"]).to(device),
+                           scales.to(device),
                            torch.from_numpy(w["zeros"]).to(device) if w.get("zeros") is not None else None)
 
 
@@ -169,11 +186,11 @@ def uniql_w4_linear(W: QuantLinear, keep, x, y=None, stream=None):
     """y[M][n_keep] = x[M][k_keep] @ W'^T on the current device; returns y."""
     import torch
     n_keep, k_keep = kept_dims(W, keep)
-    assert x.dtype == torch.float16 and x.is_cuda and x.dim() == 2 and x.stride(1) == 1
+    assert x.dtype == W.ftype and x.is_cuda and x.dim() == 2 and x.stride(1) == 1
     M = x.shape[0]
     if y is None:
-        y = torch.empty((M, n_keep), dtype=torch.float16, device=x.device)
-    assert y.dtype == torch.float16 and y.is_cuda and y.stride(1) == 1
+        y = torch.empty((M, n_keep), dtype=W.ftype, device=x.device)
+    assert y.dtype == W.ftype and y.is_cuda and y.stride(1) == 1
     d, kd = W.desc(), _keep_desc(keep)
     rc = lib().uniql_w4_linear(C.byref(d), C.byref(kd) if kd is not None else None,
                                C.c_void_p(x.data_ptr()), x.stride(0), C.c_void_p(y.data_ptr()), y.stride(0),
@@ -206,21 +223,20 @@ class MultiCall:
 
 def uniql_w4_linear_multi(Ws, keeps, xs, ys, stream=None):
     """Several independent linears with the same token count in one call; ys are written in place."""
-    import torch
-    for x, y in zip(xs, ys):
-        assert x.dtype == torch.float16 and y.dtype == torch.float16 and x.stride(1) == 1 and y.stride(1) == 1
+    for W, x, y in zip(Ws, xs, ys):
+        assert x.dtype == W.ftype and y.dtype == W.ftype and x.stride(1) == 1 and y.stride(1) == 1
         assert x.shape[0] == xs[0].shape[0]
     MultiCall(Ws, keeps, xs, ys).run(stream)
     return ys
 
 
 def uniql_w4_dequant(W: QuantLinear, keep=None, out=None, stream=None):
-    """fp16 [n_keep][k_keep] bit-exact dequantised weights."""
+    """[n_keep][k_keep] bit-exact dequantised weights, in the format of the scales."""
     import torch
     n_keep, k_keep = kept_dims(W, keep)
     if out is None:
-        out = torch.empty((n_keep, k_keep), dtype=torch.float16, device=W.qweight.device)
-    assert out.is_contiguous() and out.dtype == torch.float16
+        out = torch.empty((n_keep, k_keep), dtype=W.ftype, device=W.qweight.device)
+    assert out.is_contiguous() and out.dtype == W.ftype
     d, kd = W.desc(), _keep_desc(keep)
     rc = lib().uniql_w4_dequant(C.byref(d), C.byref(kd) if kd is not None else None,
                                 C.c_void_p(out.data_ptr()), _stream_ptr(stream))
@@ -246,11 +262,12 @@ def uniql_w4_repack(W: QuantLinear, keep=None, out: Optional[QuantLinear] = None
     dev = W.qweight.device
     if out is None:
         out = QuantLinear(torch.empty((n_out, k_out // 8), dtype=torch.int32, device=dev),
-                          torch.empty((n_out, k_out // 128), dtype=torch.float16, device=dev),
+                          torch.empty((n_out, k_out // 128), dtype=W.ftype, device=dev),
                           torch.empty((n_out, k_out // 128), dtype=torch.uint8, device=dev) if W.zeros is not None else None)
     assert out.qweight.shape == (n_out, k_out // 8) and out.scales.shape == (n_out, k_out // 128) \
         and (W.zeros is None or out.zeros.shape == out.scales.shape)
     assert out.qweight.is_contiguous() and out.scales.is_contiguous() and (W.zeros is None or out.zeros.is_contiguous())
+    assert out.scales.dtype == W.ftype
     d, kd = W.desc(), _keep_desc(keep)
     _check(lib().uniql_w4_repack(C.byref(d), C.byref(kd) if kd is not None else None,
                                  C.c_void_p(out.qweight.data_ptr()), C.c_void_p(out.scales.data_ptr()),
@@ -260,12 +277,12 @@ def uniql_w4_repack(W: QuantLinear, keep=None, out: Optional[QuantLinear] = None
 
 
 def uniql_w4_embedding(W: QuantLinear, ids, out=None, stream=None):
-    """fp16 [len(ids)][K] dequantised rows ids (int32 device tensor) of the quantised table W."""
+    """[len(ids)][K] dequantised rows ids (int32 device tensor) of the quantised table W, in the format of its scales."""
     import torch
     assert ids.dtype == torch.int32 and ids.is_cuda and ids.is_contiguous() and ids.dim() == 1
     if out is None:
-        out = torch.empty((ids.shape[0], W.K), dtype=torch.float16, device=ids.device)
-    assert out.dtype == torch.float16 and out.stride(1) == 1 and out.shape == (ids.shape[0], W.K)
+        out = torch.empty((ids.shape[0], W.K), dtype=W.ftype, device=ids.device)
+    assert out.dtype == W.ftype and out.stride(1) == 1 and out.shape == (ids.shape[0], W.K)
     d = W.desc()
     _check(lib().uniql_w4_embedding(C.byref(d), C.c_void_p(ids.data_ptr()), ids.shape[0], C.c_void_p(out.data_ptr()),
                                     out.stride(0), _stream_ptr(stream)))
@@ -273,19 +290,20 @@ def uniql_w4_embedding(W: QuantLinear, ids, out=None, stream=None):
 
 
 def uniql_pruned_rope(q, k, positions, kept_idx, D_full: int, theta: float, stream=None):
-    """Rotate q [T][Hq][D_keep] and k [T][Hkv][D_keep] (or None) in place."""
+    """Rotate q [T][Hq][D_keep] and k [T][Hkv][D_keep] (or None) in place (float16 or bfloat16 tensors)."""
     import torch
-    assert q.dtype == torch.float16 and q.is_cuda and q.is_contiguous() and q.dim() == 3
+    assert q.dtype in (torch.float16, torch.bfloat16) and q.is_cuda and q.is_contiguous() and q.dim() == 3
     T, Hq, Dk = q.shape
     Hkv = 0
     if k is not None:
-        assert k.dtype == torch.float16 and k.is_contiguous() and k.shape[0] == T and k.shape[2] == Dk
+        assert k.dtype == q.dtype and k.is_contiguous() and k.shape[0] == T and k.shape[2] == Dk
         Hkv = k.shape[1]
     assert positions.dtype == torch.int32 and positions.shape == (T,) and positions.is_contiguous()
     assert kept_idx.dtype == torch.int32 and kept_idx.is_contiguous() and kept_idx.shape[1] == Dk // 2
-    rc = lib().uniql_pruned_rope(C.c_void_p(q.data_ptr()), C.c_void_p(k.data_ptr()) if k is not None else None,
-                                 C.c_void_p(positions.data_ptr()), C.c_void_p(kept_idx.data_ptr()),
-                                 T, Hq, Hkv, kept_idx.shape[0], D_full, Dk, float(theta), _stream_ptr(stream))
+    fn = lib().uniql_pruned_rope_bf16 if q.dtype == torch.bfloat16 else lib().uniql_pruned_rope
+    rc = fn(C.c_void_p(q.data_ptr()), C.c_void_p(k.data_ptr()) if k is not None else None,
+            C.c_void_p(positions.data_ptr()), C.c_void_p(kept_idx.data_ptr()),
+            T, Hq, Hkv, kept_idx.shape[0], D_full, Dk, float(theta), _stream_ptr(stream))
     _check(rc)
     return q, k
 
@@ -298,7 +316,7 @@ class QkvRopeCall:
         import torch
         assert len(Ws) == 3 and len(keeps) == 3
         for t in (x, q, k, v):
-            assert t.dtype == torch.float16 and t.is_cuda and t.is_contiguous()
+            assert t.dtype == Ws[0].ftype and t.is_cuda and t.is_contiguous()
         assert q.dim() == 2 and k.dim() == 2 and q.shape[1] == k.shape[1], "q [Hq][D_keep], k [Hkv][D_keep]"
         assert position.dtype == torch.int32 and position.numel() == 1
         assert kept_idx.dtype == torch.int32 and kept_idx.is_contiguous() and kept_idx.shape[1] == q.shape[1] // 2
@@ -315,12 +333,12 @@ class QkvRopeCall:
 
 def uniql_w4_qkv_rope(Ws, keeps, x, position, kept_idx, Hq: int, Hkv: int, D_full: int, D_keep: int, theta: float,
                       stream=None):
-    """q = RoPE(x Wq'), k = RoPE(x Wk'), v = x Wv' for one token x [k_keep]; returns fp16 q [Hq][D_keep],
+    """q = RoPE(x Wq'), k = RoPE(x Wk'), v = x Wv' for one token x [k_keep]; returns q [Hq][D_keep],
     k [Hkv][D_keep], v [n_keep of v]."""
     import torch
-    q = torch.empty((Hq, D_keep), dtype=torch.float16, device=x.device)
-    k = torch.empty((Hkv, D_keep), dtype=torch.float16, device=x.device)
-    v = torch.empty((kept_dims(Ws[2], keeps[2])[0],), dtype=torch.float16, device=x.device)
+    q = torch.empty((Hq, D_keep), dtype=x.dtype, device=x.device)
+    k = torch.empty((Hkv, D_keep), dtype=x.dtype, device=x.device)
+    v = torch.empty((kept_dims(Ws[2], keeps[2])[0],), dtype=x.dtype, device=x.device)
     QkvRopeCall(Ws, keeps, x, q, k, v, position, kept_idx, D_full, theta).run(stream)
     return q, k, v
 
@@ -332,7 +350,7 @@ class GateUpCall:
         import torch
         assert len(Ws) == 2 and len(keeps) == 2
         for t in (x, h):
-            assert t.dtype == torch.float16 and t.is_cuda and t.is_contiguous() and t.dim() == 1
+            assert t.dtype == Ws[0].ftype and t.is_cuda and t.is_contiguous() and t.dim() == 1
         self.W = (W4 * 2)(*[w.desc() for w in Ws])
         self.keep = (KeepDesc * 2)(*[(_keep_desc(kp) or KeepDesc()) for kp in keeps])
         self.x, self.h = C.c_void_p(x.data_ptr()), C.c_void_p(h.data_ptr())
@@ -343,10 +361,10 @@ class GateUpCall:
 
 
 def uniql_w4_gate_up_silu(Ws, keeps, x, h=None, stream=None):
-    """h = SiLU(x W_gate') * (x W_up') for one token x [k_keep]; returns fp16 h [n_keep]."""
+    """h = SiLU(x W_gate') * (x W_up') for one token x [k_keep]; returns h [n_keep]."""
     import torch
     if h is None:
-        h = torch.empty((kept_dims(Ws[0], keeps[0])[0],), dtype=torch.float16, device=x.device)
+        h = torch.empty((kept_dims(Ws[0], keeps[0])[0],), dtype=x.dtype, device=x.device)
     GateUpCall(Ws, keeps, x, h).run(stream)
     return h
 

@@ -37,6 +37,7 @@ static bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)
 static int make_keepmap(const uniql_w4_t* W, const uniql_keep_t* keep, KeepMap* km) {
   if (!W || !W->qweight || !W->scales) return UNIQL_E_NULL;   // zeros may be NULL: every zero point is 8
   if (W->group != kGroup || W->N_total < 1 || W->K_total < kGroup || W->K_total % kGroup) return UNIQL_E_SHAPE;
+  if (W->dtype != UNIQL_F16 && W->dtype != UNIQL_BF16) return UNIQL_E_SHAPE;
   if (!aligned(W->qweight, 16) || !aligned(W->scales, 2)) return UNIQL_E_ALIGN;
   uniql_keep_t none;
   memset(&none, 0, sizeof(none));
@@ -106,6 +107,7 @@ static int fill_linear(const uniql_w4_t* W, const uniql_keep_t* keep, const void
   a->N_total = W->N_total;
   a->K_total = W->K_total;
   a->M = M;
+  a->bf16 = W->dtype == UNIQL_BF16;
   return UNIQL_OK;
 }
 
@@ -168,6 +170,7 @@ extern "C" int uniql_w4_dequant(const uniql_w4_t* W, const uniql_keep_t* keep, v
   a.N_total = W->N_total;
   a.K_total = W->K_total;
   a.M = 0;
+  a.bf16 = W->dtype == UNIQL_BF16;
   hipError_t e = launch_w4_dequant(a, (hipStream_t)hip_stream);
   return e == hipSuccess ? UNIQL_OK : hip_fail(e);
 }
@@ -263,14 +266,14 @@ extern "C" int uniql_w4_embedding(const uniql_w4_t* W, const int32_t* ids, int32
   rc = check_arch();
   if (rc) return rc;
   hipError_t e = launch_w4_embedding(W->qweight, W->scales, W->zeros, W->K_total, ids, n, (half_t*)out_f16, ld,
-                                     (hipStream_t)hip_stream);
+                                     W->dtype == UNIQL_BF16, (hipStream_t)hip_stream);
   if (e == hipErrorInvalidValue) return UNIQL_E_SHAPE;
   return e == hipSuccess ? UNIQL_OK : hip_fail(e);
 }
 
-extern "C" int uniql_pruned_rope(void* q_f16, void* k_f16, const int32_t* positions, const int32_t* kept_idx,
-                                 int32_t T, int32_t Hq, int32_t Hkv, int32_t H_tab, int32_t D_full,
-                                 int32_t D_keep, double theta, void* hip_stream) {
+static int pruned_rope(void* q_f16, void* k_f16, const int32_t* positions, const int32_t* kept_idx,
+                       int32_t T, int32_t Hq, int32_t Hkv, int32_t H_tab, int32_t D_full,
+                       int32_t D_keep, double theta, int bf16, void* hip_stream) {
   if (!q_f16 || !positions || !kept_idx) return UNIQL_E_NULL;
   if ((Hkv > 0) != (k_f16 != nullptr)) return Hkv > 0 ? UNIQL_E_NULL : UNIQL_E_SHAPE;
   if (T < 1 || Hq < 1 || Hkv < 0) return UNIQL_E_SHAPE;
@@ -287,8 +290,21 @@ extern "C" int uniql_pruned_rope(void* q_f16, void* k_f16, const int32_t* positi
   a.kept_idx = kept_idx;
   a.T = T; a.Hq = Hq; a.Hkv = Hkv; a.H_tab = H_tab; a.D_full = D_full; a.D_keep = D_keep;
   a.theta = theta;
+  a.bf16 = bf16;
   hipError_t e = launch_pruned_rope(a, (hipStream_t)hip_stream);
   return e == hipSuccess ? UNIQL_OK : hip_fail(e);
+}
+
+extern "C" int uniql_pruned_rope(void* q_f16, void* k_f16, const int32_t* positions, const int32_t* kept_idx,
+                                 int32_t T, int32_t Hq, int32_t Hkv, int32_t H_tab, int32_t D_full,
+                                 int32_t D_keep, double theta, void* hip_stream) {
+  return pruned_rope(q_f16, k_f16, positions, kept_idx, T, Hq, Hkv, H_tab, D_full, D_keep, theta, 0, hip_stream);
+}
+
+extern "C" int uniql_pruned_rope_bf16(void* q_bf16, void* k_bf16, const int32_t* positions, const int32_t* kept_idx,
+                                      int32_t T, int32_t Hq, int32_t Hkv, int32_t H_tab, int32_t D_full,
+                                      int32_t D_keep, double theta, void* hip_stream) {
+  return pruned_rope(q_bf16, k_bf16, positions, kept_idx, T, Hq, Hkv, H_tab, D_full, D_keep, theta, 1, hip_stream);
 }
 
 extern "C" int uniql_w4_qkv_rope(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_f16, void* q_f16,
@@ -311,6 +327,7 @@ extern "C" int uniql_w4_qkv_rope(const uniql_w4_t* W, const uniql_keep_t* keep, 
     rc = fill_linear(&W[i], keep ? &keep[i] : nullptr, x_f16, km.k_keep, y[i], km.n_keep, 1, &a[i]);
     if (rc) return rc;
     if (km.k_keep != a[0].km.k_keep) return UNIQL_E_SHAPE;   // one x for all three
+    if (a[i].bf16 != a[0].bf16) return UNIQL_E_SHAPE;        // ... in one format
   }
   // q and k come out as [heads][D_keep]
   if ((long long)a[0].km.n_keep != (long long)Hq * D_keep || (long long)a[1].km.n_keep != (long long)Hkv * D_keep) return UNIQL_E_KEEP;
@@ -339,6 +356,7 @@ extern "C" int uniql_w4_qkv_rope(const uniql_w4_t* W, const uniql_keep_t* keep, 
   r.kept_idx = kept_idx;
   r.T = 1; r.Hq = Hq; r.Hkv = Hkv; r.H_tab = H_tab; r.D_full = D_full; r.D_keep = D_keep;
   r.theta = theta;
+  r.bf16 = a[0].bf16;
   e = launch_pruned_rope(r, s);
   return e == hipSuccess ? UNIQL_OK : hip_fail(e);
 }
@@ -358,6 +376,7 @@ extern "C" int uniql_w4_gate_up_silu(const uniql_w4_t* W, const uniql_keep_t* ke
   // one x and one h: the same kept rows in number, the same rule for the kept columns
   if (a[0].km.n_keep != a[1].km.n_keep || a[0].K_total != a[1].K_total || a[0].km.k_keep != a[1].km.k_keep ||
       a[0].km.cs_stride != a[1].km.cs_stride || a[0].km.cs_keep != a[1].km.cs_keep) return UNIQL_E_KEEP;
+  if (a[0].bf16 != a[1].bf16) return UNIQL_E_SHAPE;
   int rc = check_arch();
   if (rc) return rc;
   bool fused = false;
@@ -380,9 +399,9 @@ extern "C" const char* uniql_strerror(int code) {
   switch (code) {
     case UNIQL_OK: return "ok";
     case UNIQL_E_NULL: return "a required pointer is NULL";
-    case UNIQL_E_SHAPE: return "impossible shape (group != 128, K_total % 128, M < 1, leading dimension too small, or K too long)";
+    case UNIQL_E_SHAPE: return "impossible shape (group != 128, K_total % 128, unknown dtype, M < 1, leading dimension too small, or K too long)";
     case UNIQL_E_KEEP: return "kept dimensions inconsistent with totals, segment rule or head counts";
-    case UNIQL_E_ALIGN: return "pointer alignment (qweight 16 B; fp16 tensors 2 B; int32 tables 4 B)";
+    case UNIQL_E_ALIGN: return "pointer alignment (qweight 16 B; 16-bit tensors 2 B; int32 tables 4 B)";
     case UNIQL_E_ARCH: return "current device is not gfx950";
     case UNIQL_E_HIP: return "HIP runtime error (see uniql_last_hip_error)";
     default: return "unknown uniql error code";

@@ -10,6 +10,9 @@ namespace uniql {
 typedef _Float16 half_t;
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
@@ -38,10 +41,11 @@ struct LinearArgs {
   const uint32_t* qweight;
   const uint16_t* scales;
   const uint8_t* zeros;
-  const half_t* x;
+  const half_t* x;    // 16-bit elements: fp16, or bfloat16 when bf16 is set
   half_t* y;
   long long ldx, ldy;
   int N_total, K_total, M;
+  int bf16;           // scales, x and y are bfloat16 (the weights are then rounded to bfloat16 as well)
   KeepMap km;
 };
 
@@ -163,6 +167,88 @@ __device__ __forceinline__ void dequant_word(uint32_t w, const GroupQ& g, const 
   d[3] = (h3 - g.zhi) * g.s2;
 }
 
+// ---- int4 -> bfloat16 ------------------------------------------------------
+// There is no packed bfloat16 arithmetic on this target, so the weight is formed in fp32 and rounded
+// once by the packed conversion instruction (nearest even): q as a float from its byte (the even and
+// the odd codes of a word are two masked words of four bytes each), then q * s - z * s in one fma.
+// Both products are exact (4 x 8 significant bits) and so is their difference, (q - z) * s.
+struct GroupQB {
+  float s;      // scale
+  float nzs;    // -(z * s)
+};
+
+__device__ __forceinline__ GroupQB make_groupqb(uint32_t scale_bits, uint32_t z) {
+  GroupQB g;
+  g.s = __builtin_bit_cast(float, scale_bits << 16);
+  g.nzs = -((float)z * g.s);
+  return g;
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  float2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));   // v_cvt_pk_bf16_f32
+}
+
+__device__ __forceinline__ float byte_f32(uint32_t v, int b) { return (float)((v >> (8 * b)) & 0xffu); }   // v_cvt_f32_ubyte<b>
+
+// The four dwords of a dequantised word, as pairs (w0,w4) (w1,w5) (w2,w6) (w3,w7) like dequant_word.
+// SIGNED_ZERO: a zero weight gets the sign of (q - z) * s (subtract first, then multiply: one more
+// instruction per weight); without it a zero weight is +0, which no sum can tell apart.
+template <bool SIGNED_ZERO>
+__device__ __forceinline__ uint4 dequant_word_bf16(uint32_t w, const GroupQB& g, float zf) {
+  uint32_t lo = w & 0x0F0F0F0Fu, hi = (w >> 4) & 0x0F0F0F0Fu;   // bytes q0 q2 q4 q6 / q1 q3 q5 q7
+  asm("" : "+v"(lo), "+v"(hi));   // keep the two masked words: the byte conversions below read them in place
+  float f[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const float qf = byte_f32(j & 1 ? hi : lo, j >> 1);
+    f[j] = SIGNED_ZERO ? (qf - zf) * g.s : __builtin_fmaf(qf, g.s, g.nzs);
+  }
+  return make_uint4(pack_bf16(f[0], f[4]), pack_bf16(f[1], f[5]), pack_bf16(f[2], f[6]), pack_bf16(f[3], f[7]));
+}
+
+// ---- the two formats behind one set of names (BF16 = false: fp16) -------------
+template <bool BF16> struct GroupOf { typedef GroupQ type; };
+template <> struct GroupOf<true> { typedef GroupQB type; };
+
+template <bool BF16>
+__device__ __forceinline__ typename GroupOf<BF16>::type make_group(uint32_t scale_bits, uint32_t z) {
+  if constexpr (BF16) return make_groupqb(scale_bits, z);
+  else return make_groupq(scale_bits, z);
+}
+
+// the MFMA weight operand of one word (8 weights in the pair order above)
+template <bool BF16>
+__device__ __forceinline__ uint4 dequant_word4(uint32_t w, const typename GroupOf<BF16>::type& g, const Magic& mg) {
+  if constexpr (BF16) {
+    return dequant_word_bf16<false>(w, g, 0.f);
+  } else {
+    half2_t d[4];
+    dequant_word(w, g, mg, d);
+    return make_uint4(as_u32(d[0]), as_u32(d[1]), as_u32(d[2]), as_u32(d[3]));
+  }
+}
+
+template <bool BF16>
+__device__ __forceinline__ float4_t mfma_16x16x32(const uint4& a, const uint4& b, float4_t c) {
+  if constexpr (BF16) return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+  else return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a), __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
+}
+
+// fp32 -> the 16-bit output element (nearest even), in the 16-bit container type of the pointers
+template <bool BF16>
+__device__ __forceinline__ half_t out16(float v) {
+  if constexpr (BF16) return __builtin_bit_cast(half_t, (__bf16)v);
+  else return (half_t)v;
+}
+
+// 16-bit element -> fp32
+template <bool BF16>
+__device__ __forceinline__ float in16(half_t v) {
+  if constexpr (BF16) return __builtin_bit_cast(float, (uint32_t)__builtin_bit_cast(uint16_t, v) << 16);
+  else return (float)v;
+}
+
 // host-side launchers (one per translation unit)
 hipError_t launch_w4_gemv(const LinearArgs& a, hipStream_t stream);
 hipError_t launch_w4_gemv_batch(const LinearArgs* probs, int n, hipStream_t stream);
@@ -171,19 +257,31 @@ hipError_t launch_w4_gemv_batch(const LinearArgs* probs, int n, hipStream_t stre
 hipError_t launch_w4_qkv_rope(const LinearArgs* probs, const RopeFuse& rf, hipStream_t stream, bool* fused);
 // gate and up of one token (probs[0], probs[1], same x) with h = SiLU(gate) * up written to probs[0].y
 hipError_t launch_w4_gate_up_silu(const LinearArgs* probs, hipStream_t stream, bool* fused);
-// the same four for matrices without zero points (a translation unit of their own)
+// the same four for matrices without zero points, and for bfloat16 with and without zero points (a
+// translation unit each)
 hipError_t launch_w4_gemv_sym(const LinearArgs& a, hipStream_t stream);
 hipError_t launch_w4_gemv_batch_sym(const LinearArgs* probs, int n, hipStream_t stream);
 hipError_t launch_w4_qkv_rope_sym(const LinearArgs* probs, const RopeFuse& rf, hipStream_t stream, bool* fused);
 hipError_t launch_w4_gate_up_silu_sym(const LinearArgs* probs, hipStream_t stream, bool* fused);
+hipError_t launch_w4_gemv_bf16(const LinearArgs& a, hipStream_t stream);
+hipError_t launch_w4_gemv_batch_bf16(const LinearArgs* probs, int n, hipStream_t stream);
+hipError_t launch_w4_qkv_rope_bf16(const LinearArgs* probs, const RopeFuse& rf, hipStream_t stream, bool* fused);
+hipError_t launch_w4_gate_up_silu_bf16(const LinearArgs* probs, hipStream_t stream, bool* fused);
+hipError_t launch_w4_gemv_bf16_sym(const LinearArgs& a, hipStream_t stream);
+hipError_t launch_w4_gemv_batch_bf16_sym(const LinearArgs* probs, int n, hipStream_t stream);
+hipError_t launch_w4_qkv_rope_bf16_sym(const LinearArgs* probs, const RopeFuse& rf, hipStream_t stream, bool* fused);
+hipError_t launch_w4_gate_up_silu_bf16_sym(const LinearArgs* probs, hipStream_t stream, bool* fused);
 // persistent streaming GEMV for tall row-prefix x column-prefix matrices; *done = false (nothing launched)
 // when the shape is not one it serves
 hipError_t launch_w4_gemv_stream(const LinearArgs& a, hipStream_t stream, bool* done);
 hipError_t launch_w4_gate_up_stream(const LinearArgs* probs, hipStream_t stream, bool* done);
+hipError_t launch_w4_gemv_stream_bf16(const LinearArgs& a, hipStream_t stream, bool* done);
+hipError_t launch_w4_gate_up_stream_bf16(const LinearArgs* probs, hipStream_t stream, bool* done);
 hipError_t launch_w4_gemm(const LinearArgs& a, hipStream_t stream);
+hipError_t launch_w4_gemm_bf16(const LinearArgs& a, hipStream_t stream);
 hipError_t launch_w4_dequant(const LinearArgs& a, hipStream_t stream);
 hipError_t launch_w4_embedding(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros, int K_total,
-                               const int32_t* ids, int n, half_t* out, long long ld, hipStream_t stream);
+                               const int32_t* ids, int n, half_t* out, long long ld, int bf16, hipStream_t stream);
 
 // Compact copy of the kept channels of a quantised matrix (host fills it from the repack plan).
 struct RepackArgs {
@@ -206,6 +304,7 @@ struct RopeArgs {
   const int32_t* kept_idx;
   int T, Hq, Hkv, H_tab, D_full, D_keep;
   double theta;
+  int bf16;   // q and k are bfloat16
 };
 hipError_t launch_pruned_rope(const RopeArgs& a, hipStream_t stream);
 hipError_t launch_stream_read(const void* src, long long bytes, uint32_t* out, hipStream_t stream);

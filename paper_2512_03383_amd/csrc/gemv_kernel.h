@@ -82,7 +82,8 @@ __device__ __forceinline__ ColMap make_colmap(const KeepMap& km) {
 // Waves 0..3 of a block compute R gate rows each, waves 4..7 the up rows of the same indices; the
 // sums meet in LDS and h = SiLU(gate) * up is written to the first problem's y.
 // ZP = false: the members have no zero points (every z = 8, Eq. 3's symmetric scheme) and none is loaded.
-template <int R, bool XVEC, int NCH, int EPI, bool ZP>
+// BF16: scales, x and y are bfloat16 and so are the dequantised weights (fp32 arithmetic, one rounding, bf16 MFMA).
+template <int R, bool XVEC, int NCH, int EPI, bool ZP, bool BF16>
 __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, int m, int nchunk_rt) {
   constexpr bool ROPE = EPI == 1, GLU = EPI == 2;
   static_assert(!ROPE || R == 1, "the rotary epilogue pairs single-row waves");
@@ -225,13 +226,19 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
     p.vz = (uint32_t)__builtin_amdgcn_ds_bpermute(pick_z + (tile % 16) * 16, (int)zreg[tile / 16 < NZ ? tile / 16 : 0]);
     return p;
   };
+  typedef typename GroupOf<BF16>::type Group;
   auto groupq_of = [&](const Picked& p) {
-    GroupQ g;
     const uint32_t zp = __builtin_amdgcn_perm(0u, p.vz, sel_z);
-    g.zlo = as_half2(zp | 0x64006400u);
-    g.zhi = as_half2((zp << 4) | 0x54005400u);
-    g.s2 = as_half2(__builtin_amdgcn_perm(0u, p.vs, sel_s));
-    return g;
+    const uint32_t ss = __builtin_amdgcn_perm(0u, p.vs, sel_s);
+    if constexpr (BF16) {
+      return make_groupqb(ss & 0xffffu, zp & 0xffu);
+    } else {
+      GroupQ g;
+      g.zlo = as_half2(zp | 0x64006400u);
+      g.zhi = as_half2((zp << 4) | 0x54005400u);
+      g.s2 = as_half2(ss);
+      return g;
+    }
   };
 
   // Row bases, once per wave (wave-uniform, so they live in scalar registers): a tile's addresses are
@@ -268,15 +275,10 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
   // its diagonal D[n][n] is the partial sum wanted, the rest is ignored.  Lane l holds D[4 (l / 16) + v][l % 16]
   // in register v, so the diagonal sits in lanes 5 m + 16 (m / 4) .. (one of every four), register l % 4.
   auto consume = [&](const Tile& t, const uint4 (&xr)[4], float4_t& acc, const Picked& pk) {
-    const GroupQ g = presz ? groupq_of(pk) : make_groupq(t.sbits, t.z);
+    const Group g = presz ? groupq_of(pk) : make_group<BF16>(t.sbits, t.z);
     const uint32_t wv[4] = {t.w.x, t.w.y, t.w.z, t.w.w};
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      half2_t d[4];
-      dequant_word(wv[q], g, mg, d);
-      const uint4 wq = make_uint4(as_u32(d[0]), as_u32(d[1]), as_u32(d[2]), as_u32(d[3]));
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, xr[q]), __builtin_bit_cast(half8_t, wq), acc, 0, 0, 0);
-    }
+    for (int q = 0; q < 4; ++q) acc = mfma_16x16x32<BF16>(xr[q], dequant_word4<BF16>(wv[q], g, mg), acc);
   };
 
   float4_t acc[R];
@@ -467,7 +469,7 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
     __syncthreads();
     const float x1 = pair_sum[wave & 3], x2 = pair_sum[(wave & 3) + 4];
     const float out = wave < 4 ? x1 * rope_cs - x2 * rope_sn : x2 * rope_cs + x1 * rope_sn;
-    if (lane == 0 && rope_ok) a.y[(size_t)m * a.ldy + rope_row] = (half_t)out;
+    if (lane == 0 && rope_ok) a.y[(size_t)m * a.ldy + rope_row] = out16<BF16>(out);
     return;
   }
   if (GLU) {
@@ -482,7 +484,7 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
       const float g = glu_sum[wave][lane], u = glu_sum[wave + 4][lane];
       const int rc = rg * R + lane;
       // SiLU(g) * u; exp and the reciprocal are the hardware approximations (about 1 ulp of fp32)
-      if (rc < km.n_keep) batch.p[0].y[(size_t)m * batch.p[0].ldy + rc] = (half_t)(g * u * __builtin_amdgcn_rcpf(1.0f + __expf(-g)));
+      if (rc < km.n_keep) batch.p[0].y[(size_t)m * batch.p[0].ldy + rc] = out16<BF16>(g * u * __builtin_amdgcn_rcpf(1.0f + __expf(-g)));
     }
     return;
   }
@@ -490,7 +492,7 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
   for (int r = 0; r < R; ++r) {
     const float v = row_sum(acc[r]);
     const int rc = rg * R + r;
-    if (lane == 0 && rc < km.n_keep) a.y[(size_t)m * a.ldy + rc] = (half_t)v;
+    if (lane == 0 && rc < km.n_keep) a.y[(size_t)m * a.ldy + rc] = out16<BF16>(v);
   }
 }
 
@@ -500,10 +502,10 @@ static int blocks_for(const LinearArgs& a) {
   return (row_groups + kGemvWaves - 1) / kGemvWaves;
 }
 
-template <bool ZP, int R, bool XVEC, int NCH, int EPI = 0>
+template <bool ZP, bool BF16, int R, bool XVEC, int NCH, int EPI = 0>
 static hipError_t launch_one(const LinearArgs* probs, int n, int m, int nchunk, hipStream_t stream, const RopeFuse* rf = nullptr) {
   const size_t smem = (size_t)nchunk * 4096;
-  auto kern = w4_gemv_kernel<R, XVEC, NCH, EPI, ZP>;
+  auto kern = w4_gemv_kernel<R, XVEC, NCH, EPI, ZP, BF16>;
   constexpr bool ROPE = EPI == 1, GLU = EPI == 2;
   if (smem > 160 * 1024) return hipErrorInvalidValue;
   if (smem > 64 * 1024) {
@@ -528,29 +530,29 @@ static hipError_t launch_one(const LinearArgs* probs, int n, int m, int nchunk, 
   return hipGetLastError();
 }
 
-template <bool ZP, int R, bool XVEC>
+template <bool ZP, bool BF16, int R, bool XVEC>
 static hipError_t launch_nch(const LinearArgs* probs, int n, int m, int nchunk, hipStream_t stream) {
   // the unrolled kernels fetch scales and zero points as dwords: rows of a multiple of four groups
   bool wide = true;
   for (int i = 0; i < n; ++i) wide = wide && (probs[i].K_total / kGroup) % 4 == 0;
   switch (wide ? nchunk : 0) {
-    case 1: return launch_one<ZP, R, XVEC, 1>(probs, n, m, nchunk, stream);
-    case 2: return launch_one<ZP, R, XVEC, 2>(probs, n, m, nchunk, stream);
-    case 3: return launch_one<ZP, R, XVEC, 3>(probs, n, m, nchunk, stream);
-    case 4: return launch_one<ZP, R, XVEC, 4>(probs, n, m, nchunk, stream);
-    case 5: return launch_one<ZP, R, XVEC, 5>(probs, n, m, nchunk, stream);
-    case 6: return launch_one<ZP, R, XVEC, 6>(probs, n, m, nchunk, stream);
-    case 7: return launch_one<ZP, R, XVEC, 7>(probs, n, m, nchunk, stream);
-    case 8: return launch_one<ZP, R, XVEC, 8>(probs, n, m, nchunk, stream);
-    default: return launch_one<ZP, R, XVEC, 0>(probs, n, m, nchunk, stream);
+    case 1: return launch_one<ZP, BF16, R, XVEC, 1>(probs, n, m, nchunk, stream);
+    case 2: return launch_one<ZP, BF16, R, XVEC, 2>(probs, n, m, nchunk, stream);
+    case 3: return launch_one<ZP, BF16, R, XVEC, 3>(probs, n, m, nchunk, stream);
+    case 4: return launch_one<ZP, BF16, R, XVEC, 4>(probs, n, m, nchunk, stream);
+    case 5: return launch_one<ZP, BF16, R, XVEC, 5>(probs, n, m, nchunk, stream);
+    case 6: return launch_one<ZP, BF16, R, XVEC, 6>(probs, n, m, nchunk, stream);
+    case 7: return launch_one<ZP, BF16, R, XVEC, 7>(probs, n, m, nchunk, stream);
+    case 8: return launch_one<ZP, BF16, R, XVEC, 8>(probs, n, m, nchunk, stream);
+    default: return launch_one<ZP, BF16, R, XVEC, 0>(probs, n, m, nchunk, stream);
   }
 }
 
-template <bool ZP, bool XVEC>
+template <bool ZP, bool BF16, bool XVEC>
 static hipError_t launch_rows(const LinearArgs* probs, int n, int r1, int m, int nchunk, hipStream_t stream) {
-  if (r1 == 4) return launch_nch<ZP, 4, XVEC>(probs, n, m, nchunk, stream);
-  if (r1 == 2) return launch_nch<ZP, 2, XVEC>(probs, n, m, nchunk, stream);
-  return launch_nch<ZP, 1, XVEC>(probs, n, m, nchunk, stream);
+  if (r1 == 4) return launch_nch<ZP, BF16, 4, XVEC>(probs, n, m, nchunk, stream);
+  if (r1 == 2) return launch_nch<ZP, BF16, 2, XVEC>(probs, n, m, nchunk, stream);
+  return launch_nch<ZP, BF16, 1, XVEC>(probs, n, m, nchunk, stream);
 }
 
 static inline int nchunk_of(const LinearArgs& a) {
@@ -567,14 +569,14 @@ static inline bool xvec_of(const LinearArgs& a, int) {
   return (a.km.cs_stride == 0 || (a.km.cs_stride % 8 == 0 && a.km.cs_keep >= 8)) && a.km.k_keep >= 8;
 }
 
-template <bool ZP>
+template <bool ZP, bool BF16>
 static hipError_t gemv_one(const LinearArgs& a, hipStream_t stream) {
   // rows per wave: fewer when the matrix is small, so that every CU still gets several waves
   // (long rows already at 4096: a block per CU with two rows per wave measured faster than two blocks with one)
   const int r1 = a.km.n_keep >= 16384 ? 4 : ((a.km.n_keep >= 6144 || (a.km.n_keep >= 4096 && nchunk_of(a) >= 4)) ? 2 : 1);
   for (int m = 0; m < a.M; ++m) {
-    hipError_t e = xvec_of(a, m) ? launch_rows<ZP, true>(&a, 1, r1, m, nchunk_of(a), stream)
-                                 : launch_rows<ZP, false>(&a, 1, r1, m, nchunk_of(a), stream);
+    hipError_t e = xvec_of(a, m) ? launch_rows<ZP, BF16, true>(&a, 1, r1, m, nchunk_of(a), stream)
+                                 : launch_rows<ZP, BF16, false>(&a, 1, r1, m, nchunk_of(a), stream);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
@@ -582,7 +584,7 @@ static hipError_t gemv_one(const LinearArgs& a, hipStream_t stream) {
 
 // n single-token linears in one launch when they can share a kernel instantiation (same chunk
 // count and x access mode); otherwise one launch each.
-template <bool ZP>
+template <bool ZP, bool BF16>
 static hipError_t gemv_batch(const LinearArgs* probs, int n, hipStream_t stream) {
   bool same = n <= kMaxBatch;
   long long rows = 0;
@@ -592,47 +594,47 @@ static hipError_t gemv_batch(const LinearArgs* probs, int n, hipStream_t stream)
   }
   if (!same) {
     for (int i = 0; i < n; ++i) {
-      hipError_t e = gemv_one<ZP>(probs[i], stream);
+      hipError_t e = gemv_one<ZP, BF16>(probs[i], stream);
       if (e != hipSuccess) return e;
     }
     return hipSuccess;
   }
   const int r1 = rows >= 16384 ? 4 : (rows >= 6144 ? 2 : 1);
-  return xvec_of(probs[0], 0) ? launch_rows<ZP, true>(probs, n, r1, 0, nchunk_of(probs[0]), stream)
-                              : launch_rows<ZP, false>(probs, n, r1, 0, nchunk_of(probs[0]), stream);
+  return xvec_of(probs[0], 0) ? launch_rows<ZP, BF16, true>(probs, n, r1, 0, nchunk_of(probs[0]), stream)
+                              : launch_rows<ZP, BF16, false>(probs, n, r1, 0, nchunk_of(probs[0]), stream);
 }
 
-template <bool ZP, bool XVEC>
+template <bool ZP, bool BF16, bool XVEC>
 static hipError_t launch_rope_nch(const LinearArgs* probs, int nchunk, hipStream_t stream, const RopeFuse& rf) {
   switch (nchunk) {
-    case 1: return launch_one<ZP, 1, XVEC, 1, 1>(probs, 3, 0, nchunk, stream, &rf);
-    case 2: return launch_one<ZP, 1, XVEC, 2, 1>(probs, 3, 0, nchunk, stream, &rf);
-    case 3: return launch_one<ZP, 1, XVEC, 3, 1>(probs, 3, 0, nchunk, stream, &rf);
-    case 4: return launch_one<ZP, 1, XVEC, 4, 1>(probs, 3, 0, nchunk, stream, &rf);
-    case 5: return launch_one<ZP, 1, XVEC, 5, 1>(probs, 3, 0, nchunk, stream, &rf);
-    case 6: return launch_one<ZP, 1, XVEC, 6, 1>(probs, 3, 0, nchunk, stream, &rf);
-    case 7: return launch_one<ZP, 1, XVEC, 7, 1>(probs, 3, 0, nchunk, stream, &rf);
-    default: return launch_one<ZP, 1, XVEC, 8, 1>(probs, 3, 0, nchunk, stream, &rf);
+    case 1: return launch_one<ZP, BF16, 1, XVEC, 1, 1>(probs, 3, 0, nchunk, stream, &rf);
+    case 2: return launch_one<ZP, BF16, 1, XVEC, 2, 1>(probs, 3, 0, nchunk, stream, &rf);
+    case 3: return launch_one<ZP, BF16, 1, XVEC, 3, 1>(probs, 3, 0, nchunk, stream, &rf);
+    case 4: return launch_one<ZP, BF16, 1, XVEC, 4, 1>(probs, 3, 0, nchunk, stream, &rf);
+    case 5: return launch_one<ZP, BF16, 1, XVEC, 5, 1>(probs, 3, 0, nchunk, stream, &rf);
+    case 6: return launch_one<ZP, BF16, 1, XVEC, 6, 1>(probs, 3, 0, nchunk, stream, &rf);
+    case 7: return launch_one<ZP, BF16, 1, XVEC, 7, 1>(probs, 3, 0, nchunk, stream, &rf);
+    default: return launch_one<ZP, BF16, 1, XVEC, 8, 1>(probs, 3, 0, nchunk, stream, &rf);
   }
 }
 
-template <bool ZP, int R, bool XVEC>
+template <bool ZP, bool BF16, int R, bool XVEC>
 static hipError_t launch_glu_nch(const LinearArgs* probs, int nchunk, hipStream_t stream) {
   switch (nchunk) {
-    case 1: return launch_one<ZP, R, XVEC, 1, 2>(probs, 2, 0, nchunk, stream);
-    case 2: return launch_one<ZP, R, XVEC, 2, 2>(probs, 2, 0, nchunk, stream);
-    case 3: return launch_one<ZP, R, XVEC, 3, 2>(probs, 2, 0, nchunk, stream);
-    case 4: return launch_one<ZP, R, XVEC, 4, 2>(probs, 2, 0, nchunk, stream);
-    case 5: return launch_one<ZP, R, XVEC, 5, 2>(probs, 2, 0, nchunk, stream);
-    case 6: return launch_one<ZP, R, XVEC, 6, 2>(probs, 2, 0, nchunk, stream);
-    case 7: return launch_one<ZP, R, XVEC, 7, 2>(probs, 2, 0, nchunk, stream);
-    default: return launch_one<ZP, R, XVEC, 8, 2>(probs, 2, 0, nchunk, stream);
+    case 1: return launch_one<ZP, BF16, R, XVEC, 1, 2>(probs, 2, 0, nchunk, stream);
+    case 2: return launch_one<ZP, BF16, R, XVEC, 2, 2>(probs, 2, 0, nchunk, stream);
+    case 3: return launch_one<ZP, BF16, R, XVEC, 3, 2>(probs, 2, 0, nchunk, stream);
+    case 4: return launch_one<ZP, BF16, R, XVEC, 4, 2>(probs, 2, 0, nchunk, stream);
+    case 5: return launch_one<ZP, BF16, R, XVEC, 5, 2>(probs, 2, 0, nchunk, stream);
+    case 6: return launch_one<ZP, BF16, R, XVEC, 6, 2>(probs, 2, 0, nchunk, stream);
+    case 7: return launch_one<ZP, BF16, R, XVEC, 7, 2>(probs, 2, 0, nchunk, stream);
+    default: return launch_one<ZP, BF16, R, XVEC, 8, 2>(probs, 2, 0, nchunk, stream);
   }
 }
 
 // gate and up of one token with h = SiLU(gate) * up as epilogue, written to probs[0].y; *fused = false
 // (nothing launched) when the shapes do not allow it
-template <bool ZP>
+template <bool ZP, bool BF16>
 static hipError_t gate_up_silu(const LinearArgs* probs, hipStream_t stream, bool* fused) {
   bool ok = probs[0].M == 1 && probs[1].M == 1 && nchunk_of(probs[0]) == nchunk_of(probs[1]) &&
             xvec_of(probs[0], 0) == xvec_of(probs[1], 0) && nchunk_of(probs[0]) >= 1 && nchunk_of(probs[0]) <= 8 &&
@@ -641,12 +643,12 @@ static hipError_t gate_up_silu(const LinearArgs* probs, hipStream_t stream, bool
   if (!ok) return hipSuccess;
   const int rows = 2 * probs[0].km.n_keep, nch = nchunk_of(probs[0]);
   const bool xv = xvec_of(probs[0], 0);
-  if (rows >= 16384) return xv ? launch_glu_nch<ZP, 4, true>(probs, nch, stream) : launch_glu_nch<ZP, 4, false>(probs, nch, stream);
-  if (rows >= 6144) return xv ? launch_glu_nch<ZP, 2, true>(probs, nch, stream) : launch_glu_nch<ZP, 2, false>(probs, nch, stream);
-  return xv ? launch_glu_nch<ZP, 1, true>(probs, nch, stream) : launch_glu_nch<ZP, 1, false>(probs, nch, stream);
+  if (rows >= 16384) return xv ? launch_glu_nch<ZP, BF16, 4, true>(probs, nch, stream) : launch_glu_nch<ZP, BF16, 4, false>(probs, nch, stream);
+  if (rows >= 6144) return xv ? launch_glu_nch<ZP, BF16, 2, true>(probs, nch, stream) : launch_glu_nch<ZP, BF16, 2, false>(probs, nch, stream);
+  return xv ? launch_glu_nch<ZP, BF16, 1, true>(probs, nch, stream) : launch_glu_nch<ZP, BF16, 1, false>(probs, nch, stream);
 }
 
-template <bool ZP>
+template <bool ZP, bool BF16>
 static hipError_t qkv_rope(const LinearArgs* probs, const RopeFuse& rf, hipStream_t stream, bool* fused) {
   // one launch needs the three problems to share a kernel instantiation: one token, the same
   // compile-time chunk count and x access mode, rows of a multiple of four groups
@@ -657,8 +659,8 @@ static hipError_t qkv_rope(const LinearArgs* probs, const RopeFuse& rf, hipStrea
   ok = ok && nchunk_of(probs[0]) >= 1 && nchunk_of(probs[0]) <= 8;
   *fused = ok;
   if (!ok) return hipSuccess;
-  return xvec_of(probs[0], 0) ? launch_rope_nch<ZP, true>(probs, nchunk_of(probs[0]), stream, rf)
-                              : launch_rope_nch<ZP, false>(probs, nchunk_of(probs[0]), stream, rf);
+  return xvec_of(probs[0], 0) ? launch_rope_nch<ZP, BF16, true>(probs, nchunk_of(probs[0]), stream, rf)
+                              : launch_rope_nch<ZP, BF16, false>(probs, nchunk_of(probs[0]), stream, rf);
 }
 
 }  // namespace gemv

@@ -34,7 +34,8 @@ __device__ __forceinline__ void angle_sincos(double pos, double inv_freq, float*
 // issued before the block builds its frequency table, whose latency they hide.
 constexpr int kHeadChunk = 4;
 
-template <bool V2, int kBatch>
+// BF16: q and k are bfloat16 (half_t / half2_t then only carry the bits).
+template <bool V2, int kBatch, bool BF16>
 __global__ __launch_bounds__(kRopeThreads) void pruned_rope_kernel(RopeArgs a, int tokens_per_block) {
   extern __shared__ __align__(8) unsigned char rope_smem[];
   double* invf = reinterpret_cast<double*>(rope_smem);   // [D_keep / 2]
@@ -117,13 +118,13 @@ __global__ __launch_bounds__(kRopeThreads) void pruned_rope_kernel(RopeArgs a, i
 #pragma unroll
         for (int b = 0; b < kBatch; ++b) {
           if constexpr (V2) {
-            const float a0 = (float)x1[b][u].x, a1 = (float)x1[b][u].y, b0 = (float)x2[b][u].x, b1 = (float)x2[b][u].y;
-            y1[b][u] = half2_t{(half_t)(a0 * cs[b][0] - b0 * sn[b][0]), (half_t)(a1 * cs[b][1] - b1 * sn[b][1])};
-            y2[b][u] = half2_t{(half_t)(b0 * cs[b][0] + a0 * sn[b][0]), (half_t)(b1 * cs[b][1] + a1 * sn[b][1])};
+            const float a0 = in16<BF16>(x1[b][u].x), a1 = in16<BF16>(x1[b][u].y), b0 = in16<BF16>(x2[b][u].x), b1 = in16<BF16>(x2[b][u].y);
+            y1[b][u] = half2_t{out16<BF16>(a0 * cs[b][0] - b0 * sn[b][0]), out16<BF16>(a1 * cs[b][1] - b1 * sn[b][1])};
+            y2[b][u] = half2_t{out16<BF16>(b0 * cs[b][0] + a0 * sn[b][0]), out16<BF16>(b1 * cs[b][1] + a1 * sn[b][1])};
           } else {
-            const float a0 = (float)x1[b][u], b0 = (float)x2[b][u];
-            y1[b][u] = (half_t)(a0 * cs[b][0] - b0 * sn[b][0]);
-            y2[b][u] = (half_t)(b0 * cs[b][0] + a0 * sn[b][0]);
+            const float a0 = in16<BF16>(x1[b][u]), b0 = in16<BF16>(x2[b][u]);
+            y1[b][u] = out16<BF16>(a0 * cs[b][0] - b0 * sn[b][0]);
+            y2[b][u] = out16<BF16>(b0 * cs[b][0] + a0 * sn[b][0]);
           }
         }
       if (h0 + kHeadChunk < nheads) load_chunk(h0 + kHeadChunk);
@@ -149,6 +150,18 @@ __global__ __launch_bounds__(kRopeThreads) void pruned_rope_kernel(RopeArgs a, i
   }
 }
 
+template <bool BF16>
+static hipError_t launch_rope_fmt(const RopeArgs& a, bool v2, bool tiny, dim3 grid, size_t smem, int tpb, hipStream_t stream) {
+  if (v2) {
+    if (tiny) hipLaunchKernelGGL((pruned_rope_kernel<true, 1, BF16>), grid, dim3(kRopeThreads), smem, stream, a, tpb);
+    else hipLaunchKernelGGL((pruned_rope_kernel<true, 4, BF16>), grid, dim3(kRopeThreads), smem, stream, a, tpb);
+  } else {
+    if (tiny) hipLaunchKernelGGL((pruned_rope_kernel<false, 1, BF16>), grid, dim3(kRopeThreads), smem, stream, a, tpb);
+    else hipLaunchKernelGGL((pruned_rope_kernel<false, 4, BF16>), grid, dim3(kRopeThreads), smem, stream, a, tpb);
+  }
+  return hipGetLastError();
+}
+
 hipError_t launch_pruned_rope(const RopeArgs& a, hipStream_t stream) {
   const int hk = a.D_keep >> 1;
   // half2 accesses need an even pair count (then every head row and both halves start on a
@@ -165,14 +178,7 @@ hipError_t launch_pruned_rope(const RopeArgs& a, hipStream_t stream) {
   if (tpb < 1) tpb = 1;
   dim3 grid((a.T + tpb - 1) / tpb, a.H_tab);
   const size_t smem = (size_t)hk * sizeof(double);
-  if (v2) {
-    if (tiny) hipLaunchKernelGGL((pruned_rope_kernel<true, 1>), grid, dim3(kRopeThreads), smem, stream, a, tpb);
-    else hipLaunchKernelGGL((pruned_rope_kernel<true, 4>), grid, dim3(kRopeThreads), smem, stream, a, tpb);
-  } else {
-    if (tiny) hipLaunchKernelGGL((pruned_rope_kernel<false, 1>), grid, dim3(kRopeThreads), smem, stream, a, tpb);
-    else hipLaunchKernelGGL((pruned_rope_kernel<false, 4>), grid, dim3(kRopeThreads), smem, stream, a, tpb);
-  }
-  return hipGetLastError();
+  return a.bf16 ? launch_rope_fmt<true>(a, v2, tiny, grid, smem, tpb, stream) : launch_rope_fmt<false>(a, v2, tiny, grid, smem, tpb, stream);
 }
 
 }  // namespace uniql

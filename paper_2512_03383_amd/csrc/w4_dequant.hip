@@ -1,12 +1,14 @@
-// Bit-exact dequantisation of the kept sub-matrix: w = RN_fp16((q - z) * s).
-// The product of the small integer (q - z) and the 11-bit significand of s is
-// exact in fp32, so the single fp32 -> fp16 conversion is the only rounding.
+// Bit-exact dequantisation of the kept sub-matrix: w = RN_fp16((q - z) * s), or RN_bf16 when scales and
+// output are bfloat16.
+// The product of the small integer (q - z) and the 11-bit (8-bit) significand of s is
+// exact in fp32, so the single fp32 -> 16-bit conversion is the only rounding.
 // (Written with scalar fp32 arithmetic on purpose: it is the independent check
 // of the packed-fp16 dequantisation used inside the GEMV / GEMM kernels.)
 #include "common.h"
 
 namespace uniql {
 
+template <bool BF16>
 __global__ __launch_bounds__(256) void w4_dequant_kernel(LinearArgs a) {
   const KeepMap& km = a.km;
   const int words_span = (km.k_span + 7) >> 3;
@@ -20,14 +22,14 @@ __global__ __launch_bounds__(256) void w4_dequant_kernel(LinearArgs a) {
     const size_t row = (size_t)stored_row(km, rc);
     const uint32_t word = a.qweight[row * words_per_row + w];
     const size_t g = row * groups_per_row + (w >> 4);
-    const float s = (float)__builtin_bit_cast(half_t, a.scales[g]);
+    const float s = in16<BF16>(__builtin_bit_cast(half_t, a.scales[g]));
     const int z = a.zeros ? a.zeros[g] : 8;   // no zero points: the symmetric scheme
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const int kc = compact_col(km, w * 8 + j);
       if (kc >= 0) {
         const int q = (int)((word >> (4 * j)) & 15u);
-        a.y[(size_t)rc * km.k_keep + kc] = (half_t)((float)(q - z) * s);
+        a.y[(size_t)rc * km.k_keep + kc] = out16<BF16>((float)(q - z) * s);
       }
     }
   }
@@ -38,7 +40,8 @@ hipError_t launch_w4_dequant(const LinearArgs& a, hipStream_t stream) {
   long long blocks = (total + 255) / 256;
   if (blocks > 65536) blocks = 65536;
   if (blocks < 1) blocks = 1;
-  hipLaunchKernelGGL(w4_dequant_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, a);
+  if (a.bf16) hipLaunchKernelGGL(w4_dequant_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, stream, a);
+  else hipLaunchKernelGGL(w4_dequant_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, stream, a);
   return hipGetLastError();
 }
 
@@ -46,7 +49,9 @@ hipError_t launch_w4_dequant(const LinearArgs& a, hipStream_t stream) {
 // A wave handles one (token, 2048-column chunk): a lane reads 16 bytes of codes and the scale and
 // zero point of its group, dequantises with the packed path of the GEMV, puts the 32 halves back
 // into column order and writes 64 contiguous bytes.  Rows are K_total wide (the hidden dimension
-// is never pruned).
+// is never pruned).  BF16: the table's scales and the output are bfloat16 (fp32 arithmetic, subtract then
+// multiply, so that a zero weight has the sign of (q - z) * s as in the fp16 path).
+template <bool BF16>
 __global__ __launch_bounds__(256) void w4_embedding_kernel(const uint32_t* qweight, const uint16_t* scales,
                                                            const uint8_t* zeros, int K_total, const int32_t* ids,
                                                            int n, half_t* out, long long ld) {
@@ -60,27 +65,33 @@ __global__ __launch_bounds__(256) void w4_embedding_kernel(const uint32_t* qweig
   const size_t row = (size_t)ids[tok];
   const uint4 w = *reinterpret_cast<const uint4*>(qweight + row * (size_t)(K_total >> 3) + (k0 >> 3));
   const size_t g = row * (size_t)(K_total / kGroup) + (k0 >> 7);
-  const GroupQ gq = make_groupq(scales[g], zeros ? zeros[g] : 8u);
+  const uint32_t z = zeros ? zeros[g] : 8u;
+  const typename GroupOf<BF16>::type gq = make_group<BF16>(scales[g], z);
   const Magic mg = make_magic();
   const uint32_t words[4] = {w.x, w.y, w.z, w.w};
   uint4* dst = reinterpret_cast<uint4*>(out + (size_t)tok * ld + k0);   // 16-byte aligned: checked by the host
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
-    half2_t d[4];
-    dequant_word(words[q], gq, mg, d);            // (w0,w4) (w1,w5) (w2,w6) (w3,w7)
-    const uint32_t a = as_u32(d[0]), b = as_u32(d[1]), cc = as_u32(d[2]), e = as_u32(d[3]);
+    uint4 d;                                      // (w0,w4) (w1,w5) (w2,w6) (w3,w7)
+    if constexpr (BF16) d = dequant_word_bf16<true>(words[q], gq, (float)z);
+    else d = dequant_word4<false>(words[q], gq, mg);
+    const uint32_t a = d.x, b = d.y, cc = d.z, e = d.w;
     dst[q] = make_uint4(__builtin_amdgcn_perm(b, a, 0x05040100u), __builtin_amdgcn_perm(e, cc, 0x05040100u),
                         __builtin_amdgcn_perm(b, a, 0x07060302u), __builtin_amdgcn_perm(e, cc, 0x07060302u));
   }
 }
 
 hipError_t launch_w4_embedding(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros, int K_total,
-                               const int32_t* ids, int n, half_t* out, long long ld, hipStream_t stream) {
+                               const int32_t* ids, int n, half_t* out, long long ld, int bf16, hipStream_t stream) {
   const long long items = (long long)n * ((K_total + 2047) / 2048);
   const long long blocks = (items + 3) / 4;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(w4_embedding_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, qweight, scales, zeros, K_total,
-                     ids, n, out, ld);
+  if (bf16)
+    hipLaunchKernelGGL(w4_embedding_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, stream, qweight, scales, zeros,
+                       K_total, ids, n, out, ld);
+  else
+    hipLaunchKernelGGL(w4_embedding_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, stream, qweight, scales, zeros,
+                       K_total, ids, n, out, ld);
   return hipGetLastError();
 }
 

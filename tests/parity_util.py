@@ -8,6 +8,9 @@ RoPE outputs: the floor is 1e-2 times the norm of the element's own pair.
 import numpy as np
 
 TOL = 2e-3
+# bfloat16 outputs: the one rounding of the fp32 sum to 8 significant bits is up to 2^-8 = 3.9e-3 of the
+# value by itself (fp16: 2^-11 = 4.9e-4, inside the 2e-3 bar); fp32 accumulation adds of the order of 1e-6 rms.
+TOL_BF16 = 2.0 ** -8 + 1e-4
 
 
 def linear_err(y_gpu_f16: np.ndarray, ref_f64: np.ndarray) -> float:

@@ -27,7 +27,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_layout_matches_header():
-    assert C.sizeof(W4) == 3 * 8 + 3 * 4 + 4      # three pointers, three int32, tail padding
+    assert C.sizeof(W4) == 3 * 8 + 4 * 4          # three pointers, four int32
+    assert W4.dtype.offset == 36
     assert C.sizeof(KeepDesc) == 10 * 4
     assert W4.N_total.offset == 24 and W4.group.offset == 32
     assert KeepDesc.col_seg_keep.offset == 24 and KeepDesc.row_seg2_limit.offset == 36
@@ -109,6 +110,36 @@ def test_dequant_rejects_bad_arguments():
 def _rope(q=P, k=P, pos=P, idx=P, T=1, Hq=8, Hkv=2, H_tab=2, D_full=128, D_keep=108, theta=1e4):
     return uq.lib().uniql_pruned_rope(C.c_void_p(q), C.c_void_p(k) if k else None, C.c_void_p(pos),
                                       C.c_void_p(idx), T, Hq, Hkv, H_tab, D_full, D_keep, theta, None)
+
+
+def test_dtype_field_is_validated():
+    """0 = fp16, 1 = bfloat16, anything else is refused before any launch; a bfloat16 matrix passes the same
+    host checks as an fp16 one; matrices that share a fused call must share the format."""
+    w = _w()
+    w.dtype = 2
+    assert _lin(w, None) == uq.UNIQL_E_SHAPE
+    w.dtype = -1
+    assert _lin(w, None) == uq.UNIQL_E_SHAPE
+    wb = _w()
+    wb.dtype = uq.UNIQL_BF16
+    assert _lin(wb, None, M=0) == uq.UNIQL_E_SHAPE
+    assert _lin(wb, KeepDesc(n_keep=999), M=1) == uq.UNIQL_E_KEEP
+    import torch
+    if not torch.cuda.is_available():
+        assert _lin(wb, None) in (uq.UNIQL_E_HIP, uq.UNIQL_E_ARCH)
+    # gate (fp16) and up (bfloat16) in one fused call
+    W = (W4 * 2)(_w(), wb)
+    assert uq.lib().uniql_w4_gate_up_silu(W, None, C.c_void_p(P), C.c_void_p(P), None) == uq.UNIQL_E_SHAPE
+
+
+def test_rope_bf16_entry_validates_like_the_fp16_one():
+    L = uq.lib()
+
+    def call(fn, q=P, D_keep=108, theta=5e5):
+        return fn(C.c_void_p(q), C.c_void_p(P), C.c_void_p(P), C.c_void_p(P), 1, 32, 8, 8, 128, D_keep, theta, None)
+    for kw, code in ((dict(q=0), uq.UNIQL_E_NULL), (dict(D_keep=107), uq.UNIQL_E_KEEP), (dict(theta=0.0), uq.UNIQL_E_KEEP),
+                     (dict(q=P + 1), uq.UNIQL_E_ALIGN)):
+        assert call(L.uniql_pruned_rope_bf16, **kw) == code == call(L.uniql_pruned_rope, **kw)
 
 
 def test_rope_rejects_bad_arguments():
