@@ -33,11 +33,25 @@ MFMA_F16_PEAK_TFLOPS = 2500.0
 # HBM bytes per gate+up+SiLU GEMV launch at pruning 15 %, from the two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE)
 # summarised in profiles/w4_gemv_llama3_8b_decode_p15.md: 25713.1 x 2.000 KiB read + 23.8 x 1.000 KiB written, each
 # scaled by what the counter reads for a 256 MiB elementwise copy (--pmc-calib).  Other rates were not measured.
-PMC_TRAFFIC_BYTES = {15: int(25619.4 * 1024 * (262144 / 131086)) + int(50.0 * 1024)}
+PMC_TRAFFIC_BYTES = {15: int(25617.9 * 1024 * (262144 / 131086)) + int(50.0 * 1024)}
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+FMT = "f16"          # 16-bit format of scales, activations and outputs: "f16", or "bf16" with --bf16
+
+
+def fdt(torch):
+    return torch.bfloat16 if FMT == "bf16" else torch.float16
+
+
+def dev16(torch, a):
+    """Generated 16-bit array (float16, or uint16 bit patterns of bfloat16) -> device tensor."""
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(a).cuda()
 
 
 class Layer:
@@ -51,7 +65,7 @@ class Layer:
         gen.manual_seed(wl.SEED_BASE + 1000 * rate + layer_index)
         for si, s in enumerate(specs):
             if layer_index == 0 and host_first:
-                w = wl.gen_linear(wl.rng_for(1, 100 * rate + si), s.N, s.K)
+                w = wl.gen_linear(wl.rng_for(1, 100 * rate + si), s.N, s.K, fmt=FMT)
                 if symmetric:
                     w["zeros"] = None
                 self.lin[s.name] = uq.QuantLinear.from_numpy(w)
@@ -61,7 +75,7 @@ class Layer:
             else:
                 qw = (torch.randint(0, 2 ** 32, (s.N, s.K // 8), dtype=torch.int64, device="cuda", generator=gen)
                       - 2 ** 31).to(torch.int32)
-                sc = (torch.rand((s.N, s.K // 128), device="cuda", generator=gen) * 0.015 + 0.005).to(torch.float16)
+                sc = (torch.rand((s.N, s.K // 128), device="cuda", generator=gen) * 0.015 + 0.005).to(fdt(torch))
                 zr = torch.randint(0, 16, (s.N, s.K // 128), dtype=torch.uint8, device="cuda", generator=gen)
                 self.lin[s.name] = uq.QuantLinear(qw, sc, None if symmetric else zr)
 
@@ -82,11 +96,11 @@ class DecodeStep:
                 self.host_x[s.name] = self.host_x[shared[s.name]]
                 self.xin[s.name] = self.xin[shared[s.name]]
             else:
-                x = wl.gen_activations(rng, M, s.k_keep)
+                x = wl.gen_activations(rng, M, s.k_keep, fmt=FMT)
                 self.host_x[s.name] = x
-                self.xin[s.name] = torch.from_numpy(x).cuda()
-            self.yout[s.name] = torch.empty((M, s.n_keep), dtype=torch.float16, device="cuda")
-        r = wl.gen_rope_inputs(rng, rope)
+                self.xin[s.name] = dev16(torch, x)
+            self.yout[s.name] = torch.empty((M, s.n_keep), dtype=fdt(torch), device="cuda")
+        r = wl.gen_rope_inputs(rng, rope, fmt=FMT)
         self.host_rope = r
         self.pos = torch.from_numpy(r["positions"]).cuda()
         self.idx = torch.from_numpy(r["kept_idx"]).cuda()
@@ -126,7 +140,7 @@ class DecodeStep:
         if key not in self._calls:
             sp = {s.name: s for s in self.specs}
             if not hasattr(self, "hbuf"):
-                self.hbuf = self.torch.empty((sp["gate_proj"].n_keep,), dtype=self.torch.float16, device="cuda")
+                self.hbuf = self.torch.empty((sp["gate_proj"].n_keep,), dtype=fdt(self.torch), device="cuda")
             self._calls[key] = self.uq.GateUpCall([layer.lin["gate_proj"], layer.lin["up_proj"]],
                                                   [sp["gate_proj"].keep, sp["up_proj"].keep],
                                                   self.xin["gate_proj"][0], self.hbuf)
@@ -191,8 +205,8 @@ def cpu_baseline(specs, rope, layer0, step, M):
     while reps < 3 or time.perf_counter() - t0 < 10.0:      # about 10 s of CPU work, at least 3 passes
         for s in specs:
             w = layer0.host[s.name]
-            oracle.w4_linear(w["qweight"], w["scales"], w["zeros"], step.host_x[s.name], s.keep)
-        oracle.pruned_rope(r["q"], r["k"], r["positions"], r["kept_idx"], rope.D_full, rope.theta)
+            oracle.w4_linear(w["qweight"], w["scales"], w["zeros"], step.host_x[s.name], s.keep, fmt=FMT)
+        oracle.pruned_rope(r["q"], r["k"], r["positions"], r["kept_idx"], rope.D_full, rope.theta, fmt=FMT)
         reps += 1
     dt = (time.perf_counter() - t0) / reps
     nbytes = sum(s.algorithmic_bytes(M) for s in specs) + rope.algorithmic_bytes()
@@ -201,7 +215,7 @@ def cpu_baseline(specs, rope, layer0, step, M):
     q = next(s for s in specs if s.name == "q_proj")
     w = layer0.host[q.name]
     t1 = time.perf_counter()
-    oracle.w4_linear(w["qweight"], w["scales"], w["zeros"], step.host_x[q.name], q.keep)
+    oracle.w4_linear(w["qweight"], w["scales"], w["zeros"], step.host_x[q.name], q.keep, fmt=FMT)
     dt1 = time.perf_counter() - t1
     oracle.set_threads(cores)
     return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
@@ -236,14 +250,14 @@ def detail_report(torch, uq, side):
         for _ in range(n):
             qw = (torch.randint(0, 2 ** 32, (spec.N, spec.K // 8), dtype=torch.int64, device="cuda", generator=gen)
                   - 2 ** 31).to(torch.int32)
-            sc = (torch.rand((spec.N, spec.K // 128), device="cuda", generator=gen) * 0.015 + 0.005).to(torch.float16)
+            sc = (torch.rand((spec.N, spec.K // 128), device="cuda", generator=gen) * 0.015 + 0.005).to(fdt(torch))
             zr = torch.randint(0, 16, (spec.N, spec.K // 128), dtype=torch.uint8, device="cuda", generator=gen)
             out.append(uq.QuantLinear(qw, sc, zr))
         return out
 
     def time_linear(spec, M, pool):
-        x = torch.randn((M, spec.k_keep), dtype=torch.float16, device="cuda")
-        y = torch.empty((M, spec.n_keep), dtype=torch.float16, device="cuda")
+        x = torch.randn((M, spec.k_keep), dtype=fdt(torch), device="cuda")
+        y = torch.empty((M, spec.n_keep), dtype=fdt(torch), device="cuda")
         us = graph_time_us(torch, side, lambda i: uq.uniql_w4_linear(pool[i % len(pool)], spec.keep, x, y), len(pool))
         nbytes = spec.algorithmic_bytes(M)
         return {"M": M, "MB": round(nbytes / 1e6, 3), "us": round(us, 2), "GBps": round(nbytes / us / 1e3, 1),
@@ -294,7 +308,7 @@ def detail_report(torch, uq, side):
     emb = pool_for(spec, min_bytes=1.0, max_copies=2)[0]
     for T in (1, 4096):
         ids = torch.randint(0, spec.N, (T,), dtype=torch.int32, device="cuda")
-        outs = [torch.empty((T, spec.K), dtype=torch.float16, device="cuda") for _ in range(4)]
+        outs = [torch.empty((T, spec.K), dtype=fdt(torch), device="cuda") for _ in range(4)]
         us = graph_time_us(torch, side, lambda i: uq.uniql_w4_embedding(emb, ids, out=outs[i % 4]), 8)
         nb = T * (spec.K // 2 + spec.K // 128 * 2.5 + 4 + 2 * spec.K)
         rep[f"embedding_llama3_T{T}"] = {"MB": round(nb / 1e6, 3), "us": round(us, 2), "GBps": round(nb / us / 1e3, 1),
@@ -316,8 +330,8 @@ def detail_report(torch, uq, side):
         torch.cuda.empty_cache()
     # RoPE: decode and prefill
     for name, rs in (("rope_decode_llama_p15", wl.llama3_8b_rope(15, T=1)), ("rope_prefill_llama_p15", wl.prefill_rope(15, 4096))):
-        r = wl.gen_rope_inputs(wl.rng_for(4, 7), rs)
-        bufs = [(torch.from_numpy(r["q"]).cuda(), torch.from_numpy(r["k"]).cuda()) for _ in range(8 if rs.T > 1 else 2)]
+        r = wl.gen_rope_inputs(wl.rng_for(4, 7), rs, fmt=FMT)
+        bufs = [(dev16(torch, r["q"]), dev16(torch, r["k"])) for _ in range(8 if rs.T > 1 else 2)]
         pos, idx = torch.from_numpy(r["positions"]).cuda(), torch.from_numpy(r["kept_idx"]).cuda()
         us = graph_time_us(torch, side, lambda i: uq.uniql_pruned_rope(bufs[i % len(bufs)][0], bufs[i % len(bufs)][1],
                                                                       pos, idx, rs.D_full, rs.theta), 16)
@@ -346,8 +360,13 @@ def main():
     ap.add_argument("--symmetric", action="store_true",
                     help="matrices without zero points (Eq. 3's symmetric scheme, every z = 8): no zero point is stored or "
                          "read; not the benchmark configuration, which is asymmetric")
+    ap.add_argument("--bf16", action="store_true",
+                    help="scales, activations and outputs in bfloat16 (the paper's compute type, Sec. 4.1) instead of the "
+                         "benchmark configuration's fp16")
     ap.add_argument("--detail", action="store_true", help="also time the other benchmark configurations (three rates, Qwen / Mamba shapes, prefill GEMM, RoPE)")
     args = ap.parse_args()
+    global FMT
+    FMT = "bf16" if args.bf16 else "f16"
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build measures the one-GPU hot path only; run with --gpus 1")
 
@@ -486,9 +505,9 @@ def main():
     out = {
         "metric": METRIC, "value": round(value, 2), "unit": "GB/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 6),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": FMT,
         "data": "synthetic",
-        "config": {"workload": f"Llama-3-8B shaped decode layer, batch 1, int4 group-128 weights{' without zero points (symmetric)' if args.symmetric else ''}, "
+        "config": {"workload": f"Llama-3-8B shaped decode layer, batch 1, int4 group-128 weights{' without zero points (symmetric)' if args.symmetric else ''}{', bfloat16 activations' if FMT == 'bf16' else ''}, "
                                f"pruning {rate}% (q+k+v{' with the pruned RoPE as epilogue' if fuse_rope else ', pruned RoPE'}, "
                                f"o, gate+up with SiLU(gate)*up as epilogue, down: W4A16 GEMV launches), "
                                f"{args.layers}-layer weight pool streamed from HBM",
@@ -497,9 +516,9 @@ def main():
         "us_per_step_gpu_events": round(ms_per_step_gpu * 1e3, 3),
         "per_linear": per_linear,
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None if args.symmetric else PMC_TRAFFIC_BYTES.get(rate),
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None if (args.symmetric or FMT == "bf16") else PMC_TRAFFIC_BYTES.get(rate),
                      "traffic_unit": "bytes per launch (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, copy-kernel scaled)",
-                     "kernel": "w4_gemv_stream_kernel<2,2,true> (gate_proj + up_proj + SiLU(gate)*up in one launch)",
+                     "kernel": f"w4_gemv_stream_kernel<2,2,{str(not args.symmetric).lower()},{str(FMT == 'bf16').lower()}> (gate_proj + up_proj + SiLU(gate)*up in one launch)",
                      "bytes_per_launch": int(dom_bytes), "us_per_launch": round(dom_us, 3),
                      "stream_ceiling_GBps": round(ceil_gbs, 1),
                      "frac_of_stream_ceiling": round(achieved / ceil_gbs, 4),
