@@ -351,7 +351,9 @@ static hipError_t launch_m(const LinearArgs& a, hipStream_t stream, PrefillLaunc
   // Decode batches (M <= 32) are bound by the weight stream: 16 rows per wave and the K range
   // split over the block's 8 waves, four ways when there are many row tiles, eight ways otherwise.
   const int row_tiles = (a.km.n_keep + 15) / 16;
-  if (a.M <= 16) return row_tiles >= 600 ? launch_cfg<BF16, 1, 1, 2, 4, 2, 2, XVEC>(a, stream) : launch_cfg<BF16, 1, 1, 1, 8, 1, 2, XVEC>(a, stream);
+  // (many row tiles: 32 rows per wave, so that an activation fragment read from LDS serves two weight fragments,
+  // 64 rows per block; few: 16 rows per block, two groups per wave and slab, which halves the number of barriers)
+  if (a.M <= 16) return row_tiles >= 600 ? launch_cfg<BF16, 1, 2, 2, 4, 1, 2, XVEC>(a, stream) : launch_cfg<BF16, 1, 1, 1, 8, 2, 1, XVEC>(a, stream);
   if (a.M <= 32) return row_tiles >= 600 ? launch_cfg<BF16, 2, 1, 2, 4, 1, 4, XVEC>(a, stream) : launch_cfg<BF16, 2, 1, 1, 8, 1, 2, XVEC>(a, stream);
   if (a.M <= 64) return launch_cfg<BF16, 4, 2, 4, 1, 1, 2, XVEC>(a, stream);
   // Prefill: the largest tile that still gives the chip about a block per CU.
