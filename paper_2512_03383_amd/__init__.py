@@ -370,7 +370,11 @@ def uniql_w4_gate_up_silu(Ws, keeps, x, h=None, stream=None):
 
 
 def uniql_stream_read_probe(src, nbytes: int, out, stream=None):
-    """Read nbytes of the tensor src once (measurement aid: the read-stream ceiling)."""
+    """Read nbytes of the tensor src once (measurement aid: the read-stream ceiling).  out (int32) receives
+    one word per 8 KB read."""
+    assert src.is_cuda and out.is_cuda and out.is_contiguous() and out.element_size() == 4
+    assert 0 <= int(nbytes) <= src.numel() * src.element_size(), "reads past the end of src"
+    assert out.numel() >= (int(nbytes) + 8191) // 8192, "out needs one 32-bit word per 8 KB read"
     rc = lib().uniql_stream_read_probe(C.c_void_p(src.data_ptr()), int(nbytes), C.c_void_p(out.data_ptr()),
                                        _stream_ptr(stream))
     _check(rc)
