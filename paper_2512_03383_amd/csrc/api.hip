@@ -3,6 +3,7 @@
 // error paths behave the same on a machine without a GPU.
 #include "../../include/uniql.h"
 #include "common.h"
+#include <atomic>
 #include <cmath>
 
 #include <string.h>
@@ -18,16 +19,17 @@ static int hip_fail(hipError_t e) {
 
 // gfx950 check, cached per device ordinal.
 static int check_arch() {
-  static int cached[64];   // 0 unknown, 1 ok, -1 wrong arch
+  static std::atomic<int> cached[64];   // 0 unknown, 1 ok, -1 wrong arch (host threads may race on the first call)
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return hip_fail(e);
-  if (dev >= 0 && dev < 64 && cached[dev] != 0) return cached[dev] > 0 ? UNIQL_OK : UNIQL_E_ARCH;
+  const int known = (dev >= 0 && dev < 64) ? cached[dev].load(std::memory_order_relaxed) : 0;
+  if (known != 0) return known > 0 ? UNIQL_OK : UNIQL_E_ARCH;
   hipDeviceProp_t prop;
   e = hipGetDeviceProperties(&prop, dev);
   if (e != hipSuccess) return hip_fail(e);
   int ok = strncmp(prop.gcnArchName, "gfx950", 6) == 0;
-  if (dev >= 0 && dev < 64) cached[dev] = ok ? 1 : -1;
+  if (dev >= 0 && dev < 64) cached[dev].store(ok ? 1 : -1, std::memory_order_relaxed);
   return ok ? UNIQL_OK : UNIQL_E_ARCH;
 }
 

@@ -16,6 +16,7 @@
 // h[r] = SiLU(gate) * up itself, so gate and up never meet through memory or LDS.
 #pragma once
 #include "gemv_kernel.h"
+#include <atomic>
 
 namespace uniql {
 namespace gemv {
@@ -210,19 +211,26 @@ template <int NCH, int NM, bool ZP, bool BF16>
 static hipError_t stream_launch(const StreamArgs& a, hipStream_t stream) {
   auto kern = w4_gemv_stream_kernel<NCH, NM, ZP, BF16>;
   const size_t smem = (size_t)NCH * 4096;
-  static int cu_count[64], occupancy[64];   // per device ordinal
+  // CU count and blocks per CU of this instantiation, per device ordinal: one word each (count | blocks << 16),
+  // written once, so that host threads that race on the first call all read a complete pair
+  static std::atomic<uint32_t> cached[64];
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
-  int cus = (dev >= 0 && dev < 64) ? cu_count[dev] : 0, per_cu = (dev >= 0 && dev < 64) ? occupancy[dev] : 0;
-  if (cus == 0) {
+  const bool slot = dev >= 0 && dev < 64;
+  uint32_t packed = slot ? cached[dev].load(std::memory_order_acquire) : 0u;
+  if (packed == 0) {
+    int cus = 0, per_cu = 0;
     e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(kern), kStreamThreads, smem);
     if (e != hipSuccess) return e;
     e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e != hipSuccess) return e;
     if (per_cu < 1) per_cu = 1;
-    if (dev >= 0 && dev < 64) { cu_count[dev] = cus; occupancy[dev] = per_cu; }
+    if (cus < 1 || cus > 0xffff || per_cu > 0xffff) return hipErrorInvalidValue;
+    packed = (uint32_t)cus | ((uint32_t)per_cu << 16);
+    if (slot) cached[dev].store(packed, std::memory_order_release);
   }
+  const int cus = (int)(packed & 0xffffu), per_cu = (int)(packed >> 16);
   // One block (8 waves, four tiles in flight each) per CU measured fastest up to the size of a gated MLP
   // (more waves only add start-up work); an output-head sized stream needs two to keep enough loads in flight.
   const long long bytes = (long long)NM * a.n_keep * (a.k_keep / 2);
