@@ -132,6 +132,16 @@ def test_dtype_field_is_validated():
     assert uq.lib().uniql_w4_gate_up_silu(W, None, C.c_void_p(P), C.c_void_p(P), None) == uq.UNIQL_E_SHAPE
 
 
+def test_read_probe_rejects_bad_arguments():
+    L = uq.lib()
+
+    def call(src=P, nbytes=4096, out=P):
+        return L.uniql_stream_read_probe(C.c_void_p(src), nbytes, C.c_void_p(out), None)
+    assert call(src=0) == uq.UNIQL_E_NULL and call(out=0) == uq.UNIQL_E_NULL
+    assert call(nbytes=-16) == uq.UNIQL_E_SHAPE
+    assert call(src=P + 8) == uq.UNIQL_E_ALIGN and call(out=P + 2) == uq.UNIQL_E_ALIGN
+
+
 def test_rope_bf16_entry_validates_like_the_fp16_one():
     L = uq.lib()
 

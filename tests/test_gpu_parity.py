@@ -895,3 +895,21 @@ def test_rope_prompt_sized_calls(env, uref, spec):
     n_in = r["q"][..., :hk].astype(np.float64) ** 2 + r["q"][..., hk:].astype(np.float64) ** 2
     n_out = gq[..., :hk].astype(np.float64) ** 2 + gq[..., hk:].astype(np.float64) ** 2
     assert np.max(np.abs(n_out - n_in) / np.maximum(n_in, 1e-3)) < 5e-3
+
+
+# ------------------------------------------------- the read probe (measurement aid)
+@pytest.mark.parametrize("nbytes", [16, 8192, 8192 * 3 + 4096 + 16, 5_000_000 // 16 * 16])
+def test_read_probe_xor_words(env, nbytes):
+    """One xor word per 8 KB read (the last piece may be short); words past the last piece stay untouched."""
+    uq, torch = env
+    rng = wl.rng_for(15, nbytes % 1000)
+    src = rng.integers(0, 2 ** 32, size=nbytes // 4 + 64, dtype=np.uint64).astype(np.uint32)
+    pieces = (nbytes + 8191) // 8192
+    out = torch.full((pieces + 5,), 0x5a5a5a5a, dtype=torch.int32, device="cuda")
+    uq.uniql_stream_read_probe(torch.from_numpy(src.view(np.int32)).cuda(), nbytes, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().view(np.uint32)
+    words = src[: nbytes // 4]
+    exp = [int(np.bitwise_xor.reduce(words[i * 2048:(i + 1) * 2048])) for i in range(pieces)]
+    assert list(got[:pieces]) == exp
+    assert np.all(got[pieces:] == 0x5a5a5a5a)
