@@ -206,6 +206,15 @@ int uniql_pruned_rope(void* q_f16, void* k_f16, const int32_t* positions, const 
                       int32_t T, int32_t Hq, int32_t Hkv, int32_t H_tab, int32_t D_full,
                       int32_t D_keep, double theta, void* hip_stream);
 
+/*
+ * Debug aid, host only (no GPU work, no launch): checks a kept-index table that lies in HOST memory for
+ * what the rotary kernels assume and never check on the device (Alg. 2 / Alg. A1: a row holds the
+ * original pair indices of the kept pairs of one (KV-)head, in importance order): every entry in
+ * [0, D_full / 2) and the entries of a row distinct.  kept_idx_host: int32 [H_tab][D_keep / 2].
+ * Errors: E_NULL, E_KEEP (the shape rules of uniql_pruned_rope, or a bad entry).
+ */
+int uniql_rope_table_check(const int32_t* kept_idx_host, int32_t H_tab, int32_t D_full, int32_t D_keep);
+
 /* The same rotation (Sec. 3.2, Alg. 2 / Alg. A1) of bfloat16 tensors (Sec. 4.1's compute type): every
  * argument, layout and error as in uniql_pruned_rope; q and k hold bfloat16 and are rounded to
  * bfloat16 (nearest even) once, after the fp32 rotation. */

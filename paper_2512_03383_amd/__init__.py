@@ -74,6 +74,8 @@ def lib():
         L.uniql_pruned_rope.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, C.c_double, vp]
         L.uniql_pruned_rope_bf16.restype = C.c_int
         L.uniql_pruned_rope_bf16.argtypes = L.uniql_pruned_rope.argtypes
+        L.uniql_rope_table_check.restype = C.c_int
+        L.uniql_rope_table_check.argtypes = [vp, i32, i32, i32]
         L.uniql_stream_read_probe.restype = C.c_int
         L.uniql_w4_qkv_rope.restype = C.c_int
         L.uniql_w4_qkv_rope.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, vp, vp, vp, vp, vp,
@@ -306,6 +308,15 @@ def uniql_pruned_rope(q, k, positions, kept_idx, D_full: int, theta: float, stre
             T, Hq, Hkv, kept_idx.shape[0], D_full, Dk, float(theta), _stream_ptr(stream))
     _check(rc)
     return q, k
+
+
+def uniql_rope_table_check(kept_idx, D_full: int) -> None:
+    """Raise UniqlError unless the kept-index table (numpy or CPU tensor, int32 [H_tab][D_keep / 2]) holds distinct
+    entries below D_full / 2 in every row -- what the rotary kernels assume without checking.  Host only."""
+    import numpy as np
+    a = np.ascontiguousarray(kept_idx.cpu().numpy() if hasattr(kept_idx, "cpu") else kept_idx)
+    assert a.dtype == np.int32 and a.ndim == 2
+    _check(lib().uniql_rope_table_check(a.ctypes.data_as(C.c_void_p), a.shape[0], int(D_full), 2 * a.shape[1]))
 
 
 class QkvRopeCall:

@@ -3,10 +3,12 @@
 // error paths behave the same on a machine without a GPU.
 #include "../../include/uniql.h"
 #include "common.h"
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 
 #include <string.h>
+#include <vector>
 
 using namespace uniql;
 
@@ -301,6 +303,22 @@ extern "C" int uniql_pruned_rope(void* q_f16, void* k_f16, const int32_t* positi
                                  int32_t T, int32_t Hq, int32_t Hkv, int32_t H_tab, int32_t D_full,
                                  int32_t D_keep, double theta, void* hip_stream) {
   return pruned_rope(q_f16, k_f16, positions, kept_idx, T, Hq, Hkv, H_tab, D_full, D_keep, theta, 0, hip_stream);
+}
+
+extern "C" int uniql_rope_table_check(const int32_t* kept_idx_host, int32_t H_tab, int32_t D_full, int32_t D_keep) {
+  if (!kept_idx_host) return UNIQL_E_NULL;
+  if (D_full < 2 || D_full % 2 || D_keep < 2 || D_keep % 2 || D_keep > D_full || H_tab < 1) return UNIQL_E_KEEP;
+  const int hk = D_keep / 2, half = D_full / 2;
+  std::vector<unsigned char> seen((size_t)half);
+  for (int h = 0; h < H_tab; ++h) {
+    std::fill(seen.begin(), seen.end(), 0);
+    for (int i = 0; i < hk; ++i) {
+      const int32_t j = kept_idx_host[(size_t)h * hk + i];
+      if (j < 0 || j >= half || seen[(size_t)j]) return UNIQL_E_KEEP;
+      seen[(size_t)j] = 1;
+    }
+  }
+  return UNIQL_OK;
 }
 
 extern "C" int uniql_pruned_rope_bf16(void* q_bf16, void* k_bf16, const int32_t* positions, const int32_t* kept_idx,

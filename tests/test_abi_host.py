@@ -132,6 +132,25 @@ def test_dtype_field_is_validated():
     assert uq.lib().uniql_w4_gate_up_silu(W, None, C.c_void_p(P), C.c_void_p(P), None) == uq.UNIQL_E_SHAPE
 
 
+def test_rope_table_check_on_the_host():
+    rng = np.random.default_rng(5)
+    good = np.stack([rng.permutation(64)[:54] for _ in range(8)]).astype(np.int32)
+    uq.uniql_rope_table_check(good, 128)
+    for bad_value, at in ((64, (3, 10)), (-1, (0, 0)), (int(good[7, 0]), (7, 53))):   # too large, negative, repeated
+        bad = good.copy()
+        bad[at] = bad_value
+        with pytest.raises(uq.UniqlError) as e:
+            uq.uniql_rope_table_check(bad, 128)
+        assert e.value.code == uq.UNIQL_E_KEEP
+    with pytest.raises(uq.UniqlError):
+        uq.uniql_rope_table_check(good, 100)          # 54 pairs do not fit a head of 100 channels
+    assert uq.lib().uniql_rope_table_check(None, 8, 128, 108) == uq.UNIQL_E_NULL
+    # the generated tables of the workloads pass
+    import workloads as wl
+    r = wl.gen_rope_inputs(wl.rng_for(1, 40), wl.llama3_8b_rope(15))
+    uq.uniql_rope_table_check(r["kept_idx"], 128)
+
+
 def test_read_probe_rejects_bad_arguments():
     L = uq.lib()
 
