@@ -35,3 +35,18 @@ def rope_err(y_gpu_f16: np.ndarray, ref_f64: np.ndarray) -> float:
     den = np.maximum(np.abs(ref_f64), 1e-2 * pn)
     den = np.where(den == 0.0, 1.0, den)
     return float(np.max(np.abs(y - ref_f64) / den))
+
+
+def normwise_err(y_gpu: np.ndarray, ref_f64: np.ndarray) -> float:
+    """max over token rows of ||y - ref||_2 / ||ref||_2 (no floor needed: a norm does not cancel)."""
+    y = y_gpu.astype(np.float64)
+    assert y.shape == ref_f64.shape
+    num = np.sqrt(np.sum((y - ref_f64) ** 2, axis=-1))
+    den = np.sqrt(np.sum(ref_f64 ** 2, axis=-1))
+    return float(np.max(num / np.where(den == 0.0, 1.0, den)))
+
+
+# Norm-wise bars: the output rounding is uniform within half an ulp, so its root mean square is about
+# 2^-11 / sqrt(3) = 2.8e-4 of the value in fp16 and 2^-8 / sqrt(3) = 2.3e-3 in bfloat16; accumulation adds ~1e-6.
+NORM_TOL = 4e-4
+NORM_TOL_BF16 = 3e-3

@@ -9,7 +9,7 @@ import pytest
 
 import workloads as wl
 from workloads import Keep
-from parity_util import TOL_BF16, linear_err, rope_err
+from parity_util import NORM_TOL_BF16, TOL_BF16, linear_err, normwise_err, rope_err
 
 pytestmark = pytest.mark.gpu
 FMT = "bf16"
@@ -152,6 +152,8 @@ def test_linear_parity_1024(env, uref, keep, M):
     ref = oracle_linear(uref, w, x, keep)
     y = run_linear(uq, torch, qw, keep, x, pad=3 if M in (1, 5, 33) else 0)
     assert linear_err(y, ref) <= TOL_BF16
+    if nk >= 64:
+        assert normwise_err(y, ref) <= NORM_TOL_BF16
 
 
 @pytest.mark.parametrize("N,K,keep,M", [
