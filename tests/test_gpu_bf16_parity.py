@@ -283,6 +283,10 @@ def test_fused_qkv_rope(env, uref, model, sym):
     (3584, 18944, Keep(k_keep=14208), 16),                 # its down_proj, sixteen tokens
     (4100, 6144, Keep(k_keep=6016), 4),
     (4096, 4096, Keep(k_keep=32 * 108, col_seg_stride=128, col_seg_keep=108), 8),   # o_proj, column segments
+    (14208 + 37, 3584, Keep(n_keep=14208), 32),            # the configurations of 17..32 and 33..64 tokens, tall and short
+    (14208 + 37, 3584, Keep(n_keep=14208), 64),
+    (3584, 18944, Keep(k_keep=14208), 32),
+    (3584, 18944, Keep(k_keep=14208), 64),
 ])
 def test_decode_batches(env, uref, N, K, keep, M):
     uq, torch = env

@@ -225,8 +225,10 @@ def test_llama3_8b_decode_layer_full_size(env, uref, rate):
         assert np.array_equal(y.view(np.uint16), y2.view(np.uint16))
 
 
-@pytest.mark.parametrize("M", [1, 8, 16])
+@pytest.mark.parametrize("M", [1, 8, 16, 17, 32, 33, 64, 65, 128])
 def test_qwen25_7b_shapes(env, uref, M):
+    """Every decode-batch configuration (up to 16, 32 and 64 tokens; tall and short matrices; column segments in
+    o_proj) and the small prefill tiles, at the model's sizes: sampled rows of every token."""
     uq, torch = env
     rng = wl.rng_for(2, M)
     for spec in wl.qwen25_7b_layer(25):
