@@ -14,7 +14,7 @@
 // VGPRs); a dequantised weight fragment is reused by AF MFMAs, an activation fragment by BF.
 // Small M (decode batches) is HBM-bound: AF = 1 and the K range is split over KS waves of the
 // block (reduced through LDS at the end) to get enough waves; large M (prefill) is MFMA-bound:
-// AF = 8, BF = 4, KS = 1.
+// AF = 8, BF = 2, eight waves side by side over 256 rows, KS = 1, two groups per slab.
 #pragma once
 #define UNIQL_ANDOR_PLAIN   // and-or as plain C here: the scheduler must be able to classify it as VALU
 #include "common.h"
@@ -343,11 +343,8 @@ static hipError_t launch_cfg(const LinearArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
-// prefill: the hand-scheduled 128 x 256 kernel of the format, or nullptr when it has none
-typedef hipError_t (*PrefillLauncher)(const LinearArgs&, hipStream_t);
-
 template <int XVEC, bool BF16>
-static hipError_t launch_m(const LinearArgs& a, hipStream_t stream, PrefillLauncher prefill) {
+static hipError_t launch_m(const LinearArgs& a, hipStream_t stream) {
   // Decode batches (M <= 32) are bound by the weight stream: 16 rows per wave and the K range
   // split over the block's 8 waves, four ways when there are many row tiles, eight ways otherwise.
   const int row_tiles = (a.km.n_keep + 15) / 16;
@@ -363,15 +360,15 @@ static hipError_t launch_m(const LinearArgs& a, hipStream_t stream, PrefillLaunc
   // Prefill: the largest tile that still gives the chip about a block per CU.
   auto blocks = [&](int bm, int bn) { return (long long)((a.km.n_keep + bn - 1) / bn) * ((a.M + bm - 1) / bm); };
   constexpr long long kEnough = 192;
+  // 128 x 256: eight waves side by side over rows, 8 x 2 fragments each, two groups per wave and slab (a block barrier per
+  // 256 columns) and two slabs of weight loads in flight
+  // (bfloat16: the longer unpack does not fit 256 registers beside 8 x 2 fragments and two slabs in flight; four waves
+  // with 8 x 4 fragments, one wave per SIMD, do not spill)
   if (blocks(128, 256) >= kEnough) {
-    // the prefill kernel addresses weights and one block's activations with 32-bit offsets
-    // and fetches scales eight groups at a time
-    const bool small_offsets = (unsigned long long)a.N_total * (unsigned long long)a.K_total / 2 < (1ull << 32) &&
-                               128ull * (unsigned long long)a.ldx * 2 < (1ull << 32);
-    if (prefill && XVEC == 1 && small_offsets && a.km.k_keep >= 128 && a.K_total >= 8 * kGroup) return prefill(a, stream);
-    return launch_cfg<BF16, 8, 4, 4, 1, 1, 1, XVEC>(a, stream);
+    if constexpr (BF16) return launch_cfg<BF16, 8, 4, 4, 1, 1, 1, XVEC>(a, stream);
+    else return launch_cfg<BF16, 8, 2, 8, 1, 2, 2, XVEC>(a, stream);
   }
-  if (blocks(64, 256) >= kEnough) return launch_cfg<BF16, 4, 2, 8, 1, 1, 2, XVEC>(a, stream);
+  if (blocks(64, 256) >= kEnough) return launch_cfg<BF16, 4, 2, 8, 1, 2, 2, XVEC>(a, stream);
   if (blocks(64, 128) >= kEnough) return launch_cfg<BF16, 4, 2, 4, 2, 2, 1, XVEC>(a, stream);   // K split over two waves
   // few tiles whatever the shape (e.g. 4096 rows at 128 or 256 tokens): 32 tokens x 128 rows, K over two waves
   // (down_proj at 256 tokens: 61 us against 77 us with 64 x 64 tiles)
@@ -380,13 +377,13 @@ static hipError_t launch_m(const LinearArgs& a, hipStream_t stream, PrefillLaunc
 
 // the staging mode of the activations, then the tile shape
 template <bool BF16>
-static hipError_t launch_gemm_fmt(const LinearArgs& a, hipStream_t stream, PrefillLauncher prefill) {
+static hipError_t launch_gemm_fmt(const LinearArgs& a, hipStream_t stream) {
   // 128-bit x loads: a column prefix (global loads of any size may start on any 2-byte boundary on
   // this target, so odd leading dimensions such as k_keep = 12185 qualify), or column segments
   // whose stride is a multiple of 8 and that keep at least 8 columns each
-  if (a.km.cs_stride == 0) return a.km.k_keep >= 8 ? launch_m<1, BF16>(a, stream, prefill) : launch_m<0, BF16>(a, stream, prefill);
-  if (a.km.cs_stride % 8 == 0 && a.km.cs_keep >= 8) return launch_m<2, BF16>(a, stream, prefill);
-  return launch_m<0, BF16>(a, stream, prefill);
+  if (a.km.cs_stride == 0) return a.km.k_keep >= 8 ? launch_m<1, BF16>(a, stream) : launch_m<0, BF16>(a, stream);
+  if (a.km.cs_stride % 8 == 0 && a.km.cs_keep >= 8) return launch_m<2, BF16>(a, stream);
+  return launch_m<0, BF16>(a, stream);
 }
 
 }  // namespace uniql
