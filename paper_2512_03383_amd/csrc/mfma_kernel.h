@@ -362,10 +362,9 @@ static hipError_t launch_m(const LinearArgs& a, hipStream_t stream) {
   constexpr long long kEnough = 192;
   // 128 x 256: eight waves side by side over rows, 8 x 2 fragments each, two groups per wave and slab (a block barrier per
   // 256 columns) and two slabs of weight loads in flight
-  // (bfloat16: the longer unpack does not fit 256 registers beside 8 x 2 fragments and two slabs in flight; four waves
-  // with 8 x 4 fragments, one wave per SIMD, do not spill)
+  // (bfloat16: with the longer unpack two slabs of weight loads in flight do not fit 256 registers; one does)
   if (blocks(128, 256) >= kEnough) {
-    if constexpr (BF16) return launch_cfg<BF16, 8, 4, 4, 1, 1, 1, XVEC>(a, stream);
+    if constexpr (BF16) return launch_cfg<BF16, 8, 2, 8, 1, 2, 1, XVEC>(a, stream);
     else return launch_cfg<BF16, 8, 2, 8, 1, 2, 2, XVEC>(a, stream);
   }
   if (blocks(64, 256) >= kEnough) return launch_cfg<BF16, 4, 2, 8, 1, 2, 2, XVEC>(a, stream);
