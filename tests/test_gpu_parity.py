@@ -917,3 +917,61 @@ def test_read_probe_xor_words(env, nbytes):
     exp = [int(np.bitwise_xor.reduce(words[i * 2048:(i + 1) * 2048])) for i in range(pieces)]
     assert list(got[:pieces]) == exp
     assert np.all(got[pieces:] == 0x5a5a5a5a)
+
+
+# ------------------------------------------------- HIP graph capture of the whole step
+def test_graph_replays_equal_eager_launches(env, uref):
+    """The four launches of a decode step (q/k/v + RoPE, o, gate + up + SiLU, down) captured once on a side stream and
+    replayed with new activations between the replays give the bits of eager launches every time: the entry points
+    allocate nothing, record no memset and never synchronise."""
+    uq, torch = env
+    rng = wl.rng_for(16, 0)
+    specs = {s.name: s for s in wl.llama3_8b_layer(15)}
+    rope = wl.llama3_8b_rope(15, T=1)
+    lin = {n: uq.QuantLinear.from_numpy(wl.gen_linear(rng, s.N, s.K)) for n, s in specs.items()}
+    r = wl.gen_rope_inputs(rng, rope)
+    pos, idx = to_dev(torch, r["positions"][:1].copy()), to_dev(torch, r["kept_idx"])
+    x_h = torch.empty(specs["q_proj"].k_keep, dtype=torch.float16, device="cuda")
+    x_o = torch.empty((1, specs["o_proj"].k_keep), dtype=torch.float16, device="cuda")
+    x_d = torch.empty((1, specs["down_proj"].k_keep), dtype=torch.float16, device="cuda")
+    q = torch.empty((rope.Hq, rope.D_keep), dtype=torch.float16, device="cuda")
+    k = torch.empty((rope.Hkv, rope.D_keep), dtype=torch.float16, device="cuda")
+    v = torch.empty(specs["v_proj"].n_keep, dtype=torch.float16, device="cuda")
+    yo = torch.empty((1, specs["o_proj"].n_keep), dtype=torch.float16, device="cuda")
+    h = torch.empty(specs["gate_proj"].n_keep, dtype=torch.float16, device="cuda")
+    yd = torch.empty((1, specs["down_proj"].n_keep), dtype=torch.float16, device="cuda")
+    qkv = uq.QkvRopeCall([lin[n] for n in ("q_proj", "k_proj", "v_proj")], [specs[n].keep for n in ("q_proj", "k_proj", "v_proj")],
+                         x_h, q, k, v, pos, idx, rope.D_full, rope.theta)
+    glu = uq.GateUpCall([lin["gate_proj"], lin["up_proj"]], [specs["gate_proj"].keep, specs["up_proj"].keep], x_h, h)
+
+    def step():
+        qkv.run()
+        uq.uniql_w4_linear(lin["o_proj"], specs["o_proj"].keep, x_o, yo)
+        glu.run()
+        uq.uniql_w4_linear(lin["down_proj"], specs["down_proj"].keep, x_d, yd)
+
+    def new_inputs(i):
+        x_h.copy_(to_dev(torch, wl.gen_activations(wl.rng_for(16, 10 + i), 1, x_h.numel())[0]))
+        x_o.copy_(to_dev(torch, wl.gen_activations(wl.rng_for(16, 20 + i), 1, x_o.shape[1])))
+        x_d.copy_(to_dev(torch, wl.gen_activations(wl.rng_for(16, 30 + i), 1, x_d.shape[1])))
+
+    outs = (q, k, v, yo, h, yd)
+    new_inputs(0)
+    step()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        step()
+    for i in range(1, 4):
+        new_inputs(i)
+        step()
+        torch.cuda.synchronize()
+        eager = [t.clone() for t in outs]
+        for t in outs:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for got, exp in zip(outs, eager):
+            assert torch.equal(got, exp), i
