@@ -572,9 +572,9 @@ static inline bool xvec_of(const LinearArgs& a, int) {
 template <bool ZP, bool BF16>
 static hipError_t gemv_one(const LinearArgs& a, hipStream_t stream) {
   // rows per wave: fewer when the matrix is small, so that every CU still gets several waves
-  // (a 4096-row matrix with long rows, down_proj, measured 8.75 us with one row per wave and two blocks per CU
-  // against 9.5 us with two rows per wave and one block per CU, at all three pruning rates)
-  const int r1 = a.km.n_keep >= 16384 ? 4 : (a.km.n_keep >= 6144 ? 2 : 1);
+  // (long rows already from 4096: one block per CU with two rows per wave gives steadier times than two blocks per CU
+  // with one, which measured anything from 0.7 us faster to 1 us slower from one run to the next)
+  const int r1 = a.km.n_keep >= 16384 ? 4 : ((a.km.n_keep >= 6144 || (a.km.n_keep >= 4096 && nchunk_of(a) >= 4)) ? 2 : 1);
   for (int m = 0; m < a.M; ++m) {
     hipError_t e = xvec_of(a, m) ? launch_rows<ZP, BF16, true>(&a, 1, r1, m, nchunk_of(a), stream)
                                  : launch_rows<ZP, BF16, false>(&a, 1, r1, m, nchunk_of(a), stream);

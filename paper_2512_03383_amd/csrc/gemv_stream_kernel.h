@@ -268,6 +268,7 @@ static hipError_t stream_nch(const StreamArgs& a, int nchunk, hipStream_t stream
 // registers or few LDS reads) already gain from one row per wave.
 constexpr int kStreamMinRows = 8192;
 constexpr int kStreamMinRowsShort = 2048;
+constexpr int kStreamMinRowsLong = 4096;    // row prefix with rows of more than four chunks (down_proj)
 
 static inline bool stream_shape(const LinearArgs& a, int max_chunks) {
   const KeepMap& km = a.km;
@@ -282,7 +283,8 @@ template <bool BF16>
 static hipError_t stream_one(const LinearArgs& a, hipStream_t stream, bool* done) {
   const int nchunks = ((a.km.k_keep + 31) / 32 * 32 + kChunk - 1) / kChunk;
   // (segmented row rules, one division per row, only from the higher threshold: q_proj sized launches measured slower)
-  *done = stream_shape(a, 8) && a.km.n_keep >= (nchunks <= 4 && a.km.rs_stride == 0 ? kStreamMinRowsShort : kStreamMinRows);
+  const int min_rows = a.km.rs_stride != 0 ? kStreamMinRows : (nchunks <= 4 ? kStreamMinRowsShort : kStreamMinRowsLong);
+  *done = stream_shape(a, 8) && a.km.n_keep >= min_rows;
   if (!*done) return hipSuccess;
   StreamArgs s;
   s.qweight[0] = s.qweight[1] = a.qweight;
