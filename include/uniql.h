@@ -275,6 +275,18 @@ int uniql_w4_gate_up_silu(const uniql_w4_t* W, const uniql_keep_t* keep, const v
  */
 int uniql_stream_read_probe(const void* src, int64_t bytes, void* out_words, void* hip_stream);
 
+/*
+ * Measurement aid, not part of the method: the launch of uniql_w4_gate_up_silu on its persistent streaming kernel
+ * (fp16 matrices with zero points, row prefix x column prefix, at least 4096 kept rows, rows of at most 8192 kept
+ * columns) with every load it issues -- codes, scales, zero points, activations -- and none of its arithmetic: the
+ * loads are folded into one meaningless 16-bit word per kept row, written to `h_f16`.  Same grid, same walk over the
+ * rows, same loads in flight, so its duration is the read-stream ceiling of exactly that launch.  Arguments as for
+ * uniql_w4_gate_up_silu.  Errors: E_NULL, E_SHAPE (also: a shape the streaming kernel does not serve), E_KEEP,
+ * E_ALIGN, E_ARCH, E_HIP.
+ */
+int uniql_w4_gate_up_stream_probe(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_f16, void* h_f16,
+                                  void* hip_stream);
+
 /* Static string for an error code (never NULL). */
 const char* uniql_strerror(int code);
 

@@ -82,6 +82,8 @@ def lib():
                                         i32, i32, i32, i32, i32, C.c_double, vp]
         L.uniql_w4_gate_up_silu.restype = C.c_int
         L.uniql_w4_gate_up_silu.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, vp, vp]
+        L.uniql_w4_gate_up_stream_probe.restype = C.c_int
+        L.uniql_w4_gate_up_stream_probe.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, vp, vp]
         L.uniql_w4_embedding.restype = C.c_int
         L.uniql_w4_embedding.argtypes = [C.POINTER(W4), vp, i32, vp, i64, vp]
         L.uniql_w4_repack_plan.restype = C.c_int
@@ -369,6 +371,10 @@ class GateUpCall:
 
     def run(self, stream=None):
         _check(lib().uniql_w4_gate_up_silu(self.W, self.keep, self.x, self.h, _stream_ptr(stream)))
+
+    def run_probe(self, stream=None):
+        """uniql_w4_gate_up_stream_probe on the same arguments (measurement aid: h receives meaningless words)."""
+        _check(lib().uniql_w4_gate_up_stream_probe(self.W, self.keep, self.x, self.h, _stream_ptr(stream)))
 
 
 def uniql_w4_gate_up_silu(Ws, keeps, x, h=None, stream=None):

@@ -13,8 +13,11 @@ OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["api.hip", "gemv.hip", "gemv_sym.hip", "gemv_bf16.hip", "gemv_bf16_sym.hip", "gemv_stream.hip", "gemv_stream_bf16.hip",
            "mfma_gemm.hip", "mfma_gemm_bf16.hip", "w4_dequant.hip", "rope.hip", "probe.hip"]
 # packed-fp32 VALU forms are switched off for every HIP translation unit
+# (and the compiler's rewrite of atomics as wave-wide reductions: the one LDS counter of the streaming GEMV is
+# incremented by one lane per wave, which the rewrite would wrap in a dozen extra instructions per loop body)
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall",
-               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               "-mllvm", "-amdgpu-atomic-optimizer-strategy=None"]
 
 
 def _hipcc() -> str:

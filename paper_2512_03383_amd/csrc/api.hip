@@ -405,6 +405,25 @@ extern "C" int uniql_w4_gate_up_silu(const uniql_w4_t* W, const uniql_keep_t* ke
   return fused ? UNIQL_OK : UNIQL_E_SHAPE;   // no scratch to fall back on: the caller runs the two linears itself
 }
 
+extern "C" int uniql_w4_gate_up_stream_probe(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_f16, void* h_f16,
+                                             void* hip_stream) {
+  if (!W) return UNIQL_E_NULL;
+  LinearArgs a[2];
+  for (int i = 0; i < 2; ++i) {
+    KeepMap km;
+    int rc = make_keepmap(&W[i], keep ? &keep[i] : nullptr, &km);
+    if (rc) return rc;
+    rc = fill_linear(&W[i], keep ? &keep[i] : nullptr, x_f16, km.k_keep, h_f16, km.n_keep, 1, &a[i]);
+    if (rc) return rc;
+  }
+  int rc = check_arch();
+  if (rc) return rc;
+  bool done = false;
+  hipError_t e = launch_w4_gate_up_stream_probe(a, (hipStream_t)hip_stream, &done);
+  if (e != hipSuccess) return hip_fail(e);
+  return done ? UNIQL_OK : UNIQL_E_SHAPE;
+}
+
 extern "C" int uniql_stream_read_probe(const void* src, int64_t bytes, void* out_words, void* hip_stream) {
   if (!src || !out_words) return UNIQL_E_NULL;
   if (bytes < 0) return UNIQL_E_SHAPE;

@@ -134,14 +134,8 @@ __device__ __forceinline__ GroupQ make_groupq(uint32_t scale_bits, uint32_t z) {
 // both constants are literals (a VOP3 encoding cannot carry two of them on this target), so the
 // mask is pinned to an SGPR and the exponent pattern to a VGPR.
 __device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t orv) {
-#ifdef UNIQL_ANDOR_PLAIN
   asm("" : "+s"(mask));
-  return (a & mask) | orv;
-#else
-  uint32_t r;
-  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask), "v"(orv));
-  return r;
-#endif
+  return (a & mask) | orv;   // selected as one v_and_or_b32 (written as inline asm it costs a wait state before every use)
 }
 
 // The two exponent patterns, materialised once per thread in VGPRs.
@@ -275,6 +269,7 @@ hipError_t launch_w4_gate_up_silu_bf16_sym(const LinearArgs* probs, hipStream_t 
 // when the shape is not one it serves
 hipError_t launch_w4_gemv_stream(const LinearArgs& a, hipStream_t stream, bool* done);
 hipError_t launch_w4_gate_up_stream(const LinearArgs* probs, hipStream_t stream, bool* done);
+hipError_t launch_w4_gate_up_stream_probe(const LinearArgs* probs, hipStream_t stream, bool* done);
 hipError_t launch_w4_gemv_stream_bf16(const LinearArgs& a, hipStream_t stream, bool* done);
 hipError_t launch_w4_gate_up_stream_bf16(const LinearArgs* probs, hipStream_t stream, bool* done);
 hipError_t launch_w4_gemm(const LinearArgs& a, hipStream_t stream);

@@ -1,20 +1,26 @@
 // Streaming W4A16 GEMV, one token per launch (decode).
 //
 // The op is bound by the HBM stream of packed nibbles, so the kernel is built
-// around that stream: a wave reads a kept row in contiguous 1 KB pieces (64
-// lanes x 128-bit), i.e. every lane owns 32 consecutive input columns that lie
-// in one quantisation group.  Pruned rows are never touched (row truncation
+// around that stream: a wave reads a kept row in wave-wide 128-bit loads ("tiles"), every lane 32 consecutive input
+// columns that lie in one quantisation group.  Pruned rows are never touched (row truncation
 // saves their bytes); pruned columns are handled by staging the activations
 // once per block into LDS at their *stored* column positions with zeros in the
 // pruned slots, so the weight stream needs no per-element masking.
+//
+// Column layout of a wave (shared with the persistent kernel of gemv_stream_kernel.h, so that a row's result has the
+// same bits whichever kernel serves it).  A row of NCH tiles: lanes 4g..4g+3 (a quad) own the NCH ADJACENT groups
+// g * NCH .. g * NCH + NCH - 1, and tile c is group g * NCH + c of every quad.  A quad reads 64 contiguous bytes per tile
+// (one request of the address unit, like a contiguous load), the NCH tiles of a row together read the row
+// contiguously, and the NCH scales of a lane are adjacent in memory, as are its zero points: a ROW needs one scale load
+// and one zero-point load, not one of each per tile.
 //
 // Per 32-bit word (8 weights): 1 shift + 4 and-or build exact fp16 codes, 4
 // packed subtracts and 4 packed multiplies give the canonical fp16 weights
 // RN16((q - z) s); the word's 8-element dot product with the lane's activations is
 // taken from the diagonal of one matrix instruction (see consume below), fp32.
 //
-// The kernel is fully unrolled over the row's 2048-column chunks (template NCH):
-// a wave's tiles (row, chunk) are loaded a few tiles ahead (DW in the kernel) and consumed in issue
+// The kernel is fully unrolled over the row's tiles (template NCH):
+// a wave's tiles (row, tile) are loaded a few tiles ahead (DW in the kernel) and consumed in issue
 // order, each as soon as it has arrived, so the arithmetic overlaps the stream
 // instead of starting after the last byte.
 #pragma once
@@ -27,28 +33,158 @@ constexpr int kGemvThreads = 512;
 constexpr int kGemvWaves = kGemvThreads / kWave;
 constexpr int kChunk = kWave * 32;   // stored columns one wave covers with one 128-bit load per lane
 
-__device__ __forceinline__ float dpp_xor_reduce(float v) {
-  // butterfly within each row of 16 lanes with DPP, then across rows through the LDS crossbar
-  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
-  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
-  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));  // row_half_mirror
-  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));  // row_mirror
-  v += __shfl_xor(v, 16);
-  v += __shfl_xor(v, 32);
-  return v;
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x3_t __attribute__((ext_vector_type(3)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+// tiles per row: the groups that hold kept columns (stored columns [0, k_span)), sixteen quads
+static inline int row_tiles(int k_span) { return ((k_span + kGroup - 1) / kGroup + 15) / 16; }
+// A quad's NCH groups must not straddle the end of a row (its scales are fetched as one run): the row's group count is
+// a multiple of NCH, or the sixteen quads end inside the row.
+static inline bool whole_quads(int K_total, int nch) {
+  const int gpr = K_total / kGroup;
+  return gpr % nch == 0 || 16 * nch <= gpr;
+}
+
+// Sum of the 16 diagonal elements of an MFMA accumulator (lane l holds D[4 (l / 16) + v][l % 16] in register v, so
+// the diagonal sits in quad r of row r, register = lane % 4), valid in lane 63.  Four DPP moves / adds gather a quad's
+// four diagonal registers into every lane of the quad, one select keeps the quads that are on the diagonal, two mirrors
+// add up a row of 16 lanes, the two row broadcasts add up the rows: 9 VALU instructions, no LDS crossbar.
+#define UNIQL_DPP_MOV(src, ctrl, rmask, bmask) \
+  __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, (src)), (ctrl), (rmask), (bmask), true))
+__device__ __forceinline__ float diag_sum_to_lane63(const float4_t& a, bool on_diag) {
+  // (the elements are copied to scalars first: a bit cast applied to a vector element directly reads element 0
+  // with this compiler)
+  const float a0 = a[0], a1 = a[1], a2 = a[2], a3 = a[3];
+  float t = UNIQL_DPP_MOV(a0, 0x00, 0xF, 0xF);    // quad_perm [0,0,0,0]
+  t += UNIQL_DPP_MOV(a1, 0x55, 0xF, 0xF);         // quad_perm [1,1,1,1]
+  t += UNIQL_DPP_MOV(a2, 0xAA, 0xF, 0xF);         // quad_perm [2,2,2,2]
+  t += UNIQL_DPP_MOV(a3, 0xFF, 0xF, 0xF);         // quad_perm [3,3,3,3]
+  t = on_diag ? t : 0.f;
+  t += UNIQL_DPP_MOV(t, 0x141, 0xF, 0xF);         // row_half_mirror
+  t += UNIQL_DPP_MOV(t, 0x140, 0xF, 0xF);         // row_mirror
+  // the row broadcasts add in place (rows outside the row mask keep their value), one instruction each; the
+  // s_nop is the wait a DPP instruction needs after the instruction that wrote its operand
+  asm volatile("s_nop 1\n\tv_add_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\ts_nop 1\n\t"
+               "v_add_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf" : "+v"(t));
+  return t;
+}
+// Two accumulators at once, the same arithmetic: the two chains alternate instruction by instruction, which fills the
+// two wait states a DPP instruction needs after the instruction that wrote one of its operands.
+__device__ __forceinline__ void diag_sums_to_lane63(const float4_t& a, const float4_t& b, bool on_diag, float& sa, float& sb) {
+  const float a0 = a[0], a1 = a[1], a2 = a[2], a3 = a[3], b0 = b[0], b1 = b[1], b2 = b[2], b3 = b[3];
+  float t = UNIQL_DPP_MOV(a0, 0x00, 0xF, 0xF), u = UNIQL_DPP_MOV(b0, 0x00, 0xF, 0xF);
+  t += UNIQL_DPP_MOV(a1, 0x55, 0xF, 0xF); u += UNIQL_DPP_MOV(b1, 0x55, 0xF, 0xF);
+  t += UNIQL_DPP_MOV(a2, 0xAA, 0xF, 0xF); u += UNIQL_DPP_MOV(b2, 0xAA, 0xF, 0xF);
+  t += UNIQL_DPP_MOV(a3, 0xFF, 0xF, 0xF); u += UNIQL_DPP_MOV(b3, 0xFF, 0xF, 0xF);
+  t = on_diag ? t : 0.f; u = on_diag ? u : 0.f;
+  t += UNIQL_DPP_MOV(t, 0x141, 0xF, 0xF); u += UNIQL_DPP_MOV(u, 0x141, 0xF, 0xF);
+  t += UNIQL_DPP_MOV(t, 0x140, 0xF, 0xF); u += UNIQL_DPP_MOV(u, 0x140, 0xF, 0xF);
+  asm volatile("s_nop 0\n\tv_add_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+               "v_add_f32_dpp %1, %1, %1 row_bcast:15 row_mask:0xa bank_mask:0xf\n\ts_nop 0\n\t"
+               "v_add_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+               "v_add_f32_dpp %1, %1, %1 row_bcast:31 row_mask:0xc bank_mask:0xf" : "+v"(t), "+v"(u));
+  sa = t;
+  sb = u;
 }
 
 struct Tile {
   uint4 w;          // 32 packed codes
-  uint32_t sbits;   // fp16 scale bits of the lane's group
-  uint32_t z;       // zero point of the lane's group
+  uint32_t sbits;   // fp16 scale bits of the lane's group (rows of a run-time tile count only)
+  uint32_t z;       // zero point of the lane's group     (rows of a run-time tile count only)
 };
 
-// LDS slot of the 8 stored columns k0..k0+7, k0 = c*2048 + l*32 + t*8: [c][t][l], 16 bytes,
+// A lane's scales (fp16 bits) and zero points (bytes) of one row: NCH adjacent groups.
+template <int NCH> struct RowQ {
+  uint32_t s[(2 * NCH + 3) / 4], z[(NCH + 3) / 4];
+};
+// Exactly NB bytes (NB <= 16) at p, in pieces of 16 / 12 / 8 / 4 / 2 / 1 bytes, packed little-endian into out[].
+// Nothing beyond the NB bytes is read, so the last row of an array is safe; p may have any alignment (the target
+// loads unaligned).
+template <int NB>
+__device__ __forceinline__ void load_bytes(const uint8_t* p, uint32_t (&out)[(NB + 3) / 4]) {
+  typedef uint32_t u32x4_u1 __attribute__((ext_vector_type(4), aligned(1)));
+  typedef uint32_t u32x3_u1 __attribute__((ext_vector_type(3), aligned(1)));
+  typedef uint32_t u32x2_u1 __attribute__((ext_vector_type(2), aligned(1)));
+  typedef uint16_t u16_u1 __attribute__((aligned(1)));
+  constexpr int W = NB / 4;   // whole dwords
+  if constexpr (W == 4) {
+    const u32x4_u1 v = *reinterpret_cast<const u32x4_u1*>(p);
+    out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+  } else if constexpr (W == 3) {
+    const u32x3_u1 v = *reinterpret_cast<const u32x3_u1*>(p);
+    out[0] = v.x; out[1] = v.y; out[2] = v.z;
+  } else if constexpr (W == 2) {
+    const u32x2_u1 v = *reinterpret_cast<const u32x2_u1*>(p);
+    out[0] = v.x; out[1] = v.y;
+  } else if constexpr (W == 1) {
+    out[0] = load_u32_unaligned(p);
+  }
+  constexpr int R = NB - 4 * W;   // 0..3 bytes left
+  if constexpr (R == 1) {
+    out[W] = p[4 * W];
+  } else if constexpr (R == 2) {
+    out[W] = *reinterpret_cast<const u16_u1*>(p + 4 * W);
+  } else if constexpr (R == 3) {
+    const uint32_t lo = *reinterpret_cast<const u16_u1*>(p + 4 * W);
+    const uint32_t hi = p[4 * W + 2];
+    out[W] = lo | (hi << 16);
+  }
+}
+// the same through a buffer resource (lane offset voff + scalar offset soff)
+template <int NB>
+__device__ __forceinline__ void load_bytes(__amdgpu_buffer_rsrc_t r, int voff, int soff, uint32_t (&out)[(NB + 3) / 4]) {
+  constexpr int W = NB / 4;
+  if constexpr (W == 4) {
+    const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
+    out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+  } else if constexpr (W == 3) {
+    const u32x3_t v = __builtin_amdgcn_raw_buffer_load_b96(r, voff, soff, 0);
+    out[0] = v.x; out[1] = v.y; out[2] = v.z;
+  } else if constexpr (W == 2) {
+    const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0);
+    out[0] = v.x; out[1] = v.y;
+  } else if constexpr (W == 1) {
+    out[0] = __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0);
+  }
+  constexpr int R = NB - 4 * W;
+  if constexpr (R == 1) {
+    out[W] = __builtin_amdgcn_raw_buffer_load_b8(r, voff + 4 * W, soff, 0);
+  } else if constexpr (R == 2) {
+    out[W] = __builtin_amdgcn_raw_buffer_load_b16(r, voff + 4 * W, soff, 0);
+  } else if constexpr (R == 3) {
+    const uint32_t lo = __builtin_amdgcn_raw_buffer_load_b16(r, voff + 4 * W, soff, 0);
+    const uint32_t hi = __builtin_amdgcn_raw_buffer_load_b8(r, voff + 4 * W + 2, soff, 0);
+    out[W] = lo | (hi << 16);
+  }
+}
+// group constants of tile c of a row (c is a compile-time constant after unrolling)
+template <bool ZP, bool BF16, int NCH>
+__device__ __forceinline__ typename GroupOf<BF16>::type group_of(const RowQ<NCH>& r, int c) {
+  const half_t sc = as_half2(r.s[c >> 1])[c & 1];
+  const half2_t sv = {sc, sc};   // (the compiler folds the splat into op_sel of the packed multiply)
+  const uint32_t ss = as_u32(sv);
+  const uint32_t zz = ZP ? __builtin_amdgcn_perm(0u, r.z[c >> 2], 0x0c000c00u | ((c & 3) * 0x00010001u)) : 0x00080008u;   // (z, z)
+  if constexpr (BF16) {
+    return make_groupqb(ss & 0xffffu, zz & 0xffu);
+  } else {
+    GroupQ g;
+    g.zlo = as_half2(zz | 0x64006400u);
+    g.zhi = as_half2((zz << 4) | 0x54005400u);
+    g.s2 = as_half2(ss);
+    return g;
+  }
+}
+
+// Unit u = the 8 stored columns [8u, 8u + 8).  Its LDS slot in the image [tile][word][lane] of a row of nch tiles,
 // halves ordered (k0,k0+4,k0+1,k0+5,k0+2,k0+6,k0+3,k0+7): dword p pairs with the dequantised
-// pair (w_p, w_{p+4}), and a wave reads one t-plane of a chunk with consecutive addresses.
-__device__ __forceinline__ int unit_k0(int u) { return (u >> 8) * kChunk + ((u >> 2) & 63) * 32 + (u & 3) * 8; }
-__device__ __forceinline__ int unit_slot(int u) { return ((u >> 8) * 4 + (u & 3)) * 64 + ((u >> 2) & 63); }
+// pair (w_p, w_{p+4}), and a wave reads one word-plane of a tile with consecutive addresses.
+__device__ __forceinline__ int unit_slot(int u, int nch) {
+  const int G = u >> 4, qd = G / nch, c = G - qd * nch;   // group of the unit, its quad and tile
+  return (c * 4 + (u & 3)) * 64 + qd * 4 + ((u >> 2) & 3);
+}
+// stored column where lane `lane` starts in tile c
+__device__ __forceinline__ int tile_k0(int lane, int c, int nch) { return ((lane >> 2) * nch + c) * kGroup + (lane & 3) * 32; }
 
 __device__ __forceinline__ uint4 pack_unit(const half_t v[8]) {
   half2_t p0 = {v[0], v[4]}, p1 = {v[1], v[5]}, p2 = {v[2], v[6]}, p3 = {v[3], v[7]};
@@ -180,67 +316,16 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
     }
   }
 
-  // Scales and zero points of ALL of the wave's tiles, fetched up front by two wide loads (one dword
-  // = two scales or four zero points per lane, rows contiguous) instead of two narrow loads per
-  // tile: the memory side sees a fifth fewer requests.  A tile's lanes later pick their group's
-  // value out of the holding lane with ds_bpermute.  Needs rows of a multiple of four groups and a
-  // compile-time tile count; otherwise (NCH = 0) every tile loads its own pair.
-  constexpr int TILES = NCH > 0 ? NCH * R : 1;
-  constexpr int NS = (TILES * 8 + 63) / 64, NZ = (TILES * 4 + 63) / 64;
-  constexpr bool presz = NCH > 0 && R < 4;   // (the host sends rows of any other group count to the NCH = 0 kernel)
-  uint32_t sreg[NS], zreg[NZ];
-  auto row_of_tile = [&](int tile) {   // stored row of tile id r * NCH + c, tile varies per lane
-    const int r = tile / (NCH > 0 ? NCH : 1);
-    int sr = srow[0];
-#pragma unroll
-    for (int rr = 1; rr < R; ++rr) sr = r == rr ? srow[rr] : sr;
-    return (size_t)sr * groups_per_row;
-  };
-  auto load_sz = [&]() {
-#pragma unroll
-    for (int i = 0; i < NS; ++i) {
-      const int flat = i * 64 + lane;
-      const int tile = flat / 8 < TILES ? flat / 8 : TILES - 1;
-      int d = (tile % (NCH > 0 ? NCH : 1)) * 8 + (flat & 7);          // dword of the row's scales
-      d = d < (groups_per_row >> 1) ? d : (groups_per_row >> 1) - 1;
-      sreg[i] = load_u32_unaligned(a.scales + row_of_tile(tile) + 2 * d);
-    }
-#pragma unroll
-    for (int i = 0; i < NZ; ++i) {
-      const int flat = i * 64 + lane;
-      const int tile = flat / 4 < TILES ? flat / 4 : TILES - 1;
-      int d = (tile % (NCH > 0 ? NCH : 1)) * 4 + (flat & 3);          // dword of the row's zero points
-      d = d < (groups_per_row >> 2) ? d : (groups_per_row >> 2) - 1;
-      zreg[i] = ZP ? load_u32_unaligned(a.zeros + row_of_tile(tile) + 4 * d) : 0x08080808u;
-    }
-  };
-  // lane constants of the pick: the lane's group inside a chunk is lane / 4
-  const int pick_s = (lane >> 3) * 4, pick_z = (lane >> 4) * 4;                      // byte index of the holding lane
-  const uint32_t sel_s = (lane >> 2) & 1 ? 0x03020302u : 0x01000100u;               // (s, s) from the low / high half
-  const uint32_t sel_z = 0x0c000c00u | (((lane >> 2) & 3) * 0x00010001u);           // (z, z) from byte lane/4 % 4
-  // the pick is issued one tile ahead (pick_tile) and turned into group constants when the tile is consumed
-  struct Picked { uint32_t vs, vz; };
-  auto pick_tile = [&](int tile) {   // tile = r * NCH + c, compile-time after unrolling
-    Picked p;
-    p.vs = (uint32_t)__builtin_amdgcn_ds_bpermute(pick_s + (tile % 8) * 32, (int)sreg[tile / 8 < NS ? tile / 8 : 0]);
-    p.vz = (uint32_t)__builtin_amdgcn_ds_bpermute(pick_z + (tile % 16) * 16, (int)zreg[tile / 16 < NZ ? tile / 16 : 0]);
-    return p;
-  };
+  // Scales and zero points: a lane's NCH groups of a row are adjacent (see the layout above), so every row costs one
+  // scale load and one zero-point load, issued with the row's first tile.  Rows of a run-time tile count (NCH = 0) load
+  // the pair of every tile instead.
+  constexpr int NCQ = NCH > 0 ? NCH : 1;
   typedef typename GroupOf<BF16>::type Group;
-  auto groupq_of = [&](const Picked& p) {
-    const uint32_t zp = __builtin_amdgcn_perm(0u, p.vz, sel_z);
-    const uint32_t ss = __builtin_amdgcn_perm(0u, p.vs, sel_s);
-    if constexpr (BF16) {
-      return make_groupqb(ss & 0xffffu, zp & 0xffu);
-    } else {
-      GroupQ g;
-      g.zlo = as_half2(zp | 0x64006400u);
-      g.zhi = as_half2((zp << 4) | 0x54005400u);
-      g.s2 = as_half2(ss);
-      return g;
-    }
-  };
-
+  const int quad = lane >> 2;
+  // first group of the lane; a quad past the row's groups reads the row start (its columns are pruned by definition).
+  // The host sends only rows whose quads do not straddle the row's end to the kernels with NCH > 0.
+  const int goff = (quad + 1) * NCQ <= groups_per_row ? quad * NCQ : 0;
+  RowQ<NCQ> rowq[R];
   // Row bases, once per wave (wave-uniform, so they live in scalar registers): a tile's addresses are
   // then base + a per-lane offset that depends on the chunk only.
   const uint32_t* qrow[R];
@@ -252,14 +337,14 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
     srow_s[r] = a.scales + (size_t)srow[r] * groups_per_row;
     srow_z[r] = ZP ? a.zeros + (size_t)srow[r] * groups_per_row : nullptr;
   }
-  // one tile = the lane's 32 columns of one row in chunk c (16 B of codes + scale + zero).
+  // one tile = the lane's 32 columns of one row in tile c (16 B of codes; + scale + zero for NCH = 0).
   // Lanes past the last kept column re-read the row start: their x slots hold zeros, so
   // whatever they fetch contributes nothing and no select has to wait on the loads.
   auto load_tile = [&](int c, int r, Tile& t) {
-    const int kb = c * kChunk + lane * 32;
+    const int kb = tile_k0(lane, c, nchunk);
     const int kbc = kb < k_span32 ? kb : 0;
     t.w = *reinterpret_cast<const uint4*>(qrow[r] + (kbc >> 3));
-    if (presz) {
+    if constexpr (NCH > 0) {
       t.sbits = 0;
       t.z = 0;
     } else {
@@ -268,14 +353,19 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
       else t.z = 8u;
     }
   };
+  auto load_rowq = [&](int r) {
+    if constexpr (NCH > 0) {
+      load_bytes<2 * NCQ>(reinterpret_cast<const uint8_t*>(srow_s[r] + goff), rowq[r].s);
+      if constexpr (ZP) load_bytes<NCQ>(srow_z[r] + goff, rowq[r].z);
+    }
+  };
   const Magic mg = make_magic();
   // The 8-element dot products of a word run on the matrix pipe, beside the VALU that dequantises:
   // with A = the lane's x values and B = its weights, v_mfma_f32_16x16x32_f16 forms D[i][n] =
   // sum over the four lanes {n, n+16, n+32, n+48} of dot(x of lane i + 16 ks, w of lane n + 16 ks);
   // its diagonal D[n][n] is the partial sum wanted, the rest is ignored.  Lane l holds D[4 (l / 16) + v][l % 16]
   // in register v, so the diagonal sits in lanes 5 m + 16 (m / 4) .. (one of every four), register l % 4.
-  auto consume = [&](const Tile& t, const uint4 (&xr)[4], float4_t& acc, const Picked& pk) {
-    const Group g = presz ? groupq_of(pk) : make_group<BF16>(t.sbits, t.z);
+  auto consume = [&](const Tile& t, const uint4 (&xr)[4], float4_t& acc, const Group& g) {
     const uint32_t wv[4] = {t.w.x, t.w.y, t.w.z, t.w.w};
 #pragma unroll
     for (int q = 0; q < 4; ++q) acc = mfma_16x16x32<BF16>(xr[q], dequant_word4<BF16>(wv[q], g, mg), acc);
@@ -284,13 +374,9 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
   float4_t acc[R];
 #pragma unroll
   for (int r = 0; r < R; ++r) acc[r] = float4_t{0.f, 0.f, 0.f, 0.f};
-  // the lane's diagonal element of an accumulator (zero in the lanes that hold none), summed over the wave
+  // the sum of an accumulator's diagonal over the wave, valid in lane 63
   const bool on_diag = (lane >> 4) == ((lane & 15) >> 2);
-  auto row_sum = [&](const float4_t& c) {
-    const int v = lane & 3;
-    float d = v == 0 ? c[0] : (v == 1 ? c[1] : (v == 2 ? c[2] : c[3]));
-    return dpp_xor_reduce(on_diag ? d : 0.f);
-  };
+  auto row_sum = [&](const float4_t& c) { return diag_sum_to_lane63(c, on_diag); };
   float rope_sn = 0.f, rope_cs = 1.f;
 
   const ColMap cm = make_colmap(km);
@@ -325,7 +411,7 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
 #pragma unroll
     for (int i = 0; i < XI; ++i) {
       const int uraw = tid + i * kGemvThreads;
-      const int k0 = unit_k0(uraw < NCH * 256 ? uraw : NCH * 256 - 1);   // past the end: a redundant, valid load
+      const int k0 = 8 * (uraw < NCH * 256 ? uraw : NCH * 256 - 1);   // past the end: a redundant, valid load
       okmask[i] = 0;
       if constexpr (XVEC) {
         int pos, nk;
@@ -361,7 +447,8 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
     constexpr int DW = R >= 2 ? 2 : 4;   // tiles in flight: few per wave when a wave owns several rows (many waves), more for one-row waves
     constexpr int D = T < DW ? T : DW;
     Tile ring[D];
-    if (presz) load_sz();   // after x (memory returns in issue order), before the tiles that need them
+#pragma unroll
+    for (int r = 0; r < R; ++r) load_rowq(r);   // after x (memory returns in issue order), before the tiles that need them
 #pragma unroll
     for (int t = 0; t < D; ++t) load_tile(t / R, t % R, ring[t]);
     __builtin_amdgcn_sched_barrier(0);
@@ -370,7 +457,7 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
 #pragma unroll
     for (int i = 0; i < XI; ++i) {
       const int u = tid + i * kGemvThreads;
-      const int k0 = unit_k0(u);
+      const int k0 = 8 * u;
       uint32_t e[8];
       if constexpr (XVEC) {
         // the unit's first nk columns are kept (8 or more: all of it; none: pruned); the partly kept unit
@@ -388,7 +475,7 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
         for (int j = 0; j < 8; ++j) e[j] = (okmask[i] >> j) & 1u ? rawe[i][j] : 0u;
       }
       if (u < NCH * 256)
-        xs[unit_slot(u)] = make_uint4(e[0] | (e[4] << 16), e[1] | (e[5] << 16), e[2] | (e[6] << 16), e[3] | (e[7] << 16));
+        xs[unit_slot(u, NCH)] = make_uint4(e[0] | (e[4] << 16), e[1] | (e[5] << 16), e[2] | (e[6] << 16), e[3] | (e[7] << 16));
     }
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
@@ -409,13 +496,9 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
 
     // ---- phase 4: consume tiles in issue order, re-issuing D tiles ahead
     uint4 xr[4];
-    Picked pk = {0, 0}, pk_next = {0, 0};
-    if (presz) pk_next = pick_tile(0);   // tile t = (chunk t / R, row t % R) has id r * NCH + c
 #pragma unroll
     for (int t = 0; t < T; ++t) {
       const int c = t / R, r = t % R;
-      pk = pk_next;
-      if (presz && t + 1 < T) pk_next = pick_tile(((t + 1) % R) * NCH + (t + 1) / R);
       if (r == 0) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) xr[q] = xs[(c * 4 + q) * 64 + lane];
@@ -426,13 +509,13 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
       Tile& tl = ring[t % D];
       asm volatile("" : "+v"(tl.w.x), "+v"(tl.w.y), "+v"(tl.w.z), "+v"(tl.w.w), "+v"(tl.sbits), "+v"(tl.z),
                         "+v"(acc[(t + R - 1) % R][0]));
-      consume(tl, xr, acc[r], pk);
+      consume(tl, xr, acc[r], group_of<ZP, BF16, NCQ>(rowq[r], c));
       if (t + D < T) load_tile((t + D) / R, (t + D) % R, tl);
     }
   } else {
     // ---- long rows: run-time chunk count, plain staging loop and a two-deep register pipeline
     for (int u = tid; u < units; u += kGemvThreads) {
-      const int k0 = unit_k0(u);
+      const int k0 = 8 * u;
       half_t v[8];
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
@@ -441,7 +524,7 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
         const half_t val = xrow[kc >= 0 ? kc : 0];
         v[j] = kc >= 0 ? val : (half_t)0;
       }
-      xs[unit_slot(u)] = pack_unit(v);
+      xs[unit_slot(u, nchunk)] = pack_unit(v);
     }
     Tile cur[R], nxt[R];
 #pragma unroll
@@ -456,7 +539,7 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
 #pragma unroll
       for (int q = 0; q < 4; ++q) xr[q] = xs[(c * 4 + q) * 64 + lane];
 #pragma unroll
-      for (int r = 0; r < R; ++r) consume(cur[r], xr, acc[r], Picked{0, 0});
+      for (int r = 0; r < R; ++r) consume(cur[r], xr, acc[r], make_group<BF16>(cur[r].sbits, cur[r].z));
 #pragma unroll
       for (int r = 0; r < R; ++r) cur[r] = nxt[r];
     }
@@ -465,11 +548,11 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
   if (ROPE && rope_heads > 0) {
     __shared__ float pair_sum[kGemvWaves];
     const float v = row_sum(acc[0]);
-    if (lane == 0) pair_sum[wave] = v;
+    if (lane == 63) pair_sum[wave] = v;
     __syncthreads();
     const float x1 = pair_sum[wave & 3], x2 = pair_sum[(wave & 3) + 4];
     const float out = wave < 4 ? x1 * rope_cs - x2 * rope_sn : x2 * rope_cs + x1 * rope_sn;
-    if (lane == 0 && rope_ok) a.y[(size_t)m * a.ldy + rope_row] = out16<BF16>(out);
+    if (lane == 63 && rope_ok) a.y[(size_t)m * a.ldy + rope_row] = out16<BF16>(out);
     return;
   }
   if (GLU) {
@@ -477,7 +560,7 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       const float v = row_sum(acc[r]);
-      if (lane == 0) glu_sum[wave][r] = v;
+      if (lane == 63) glu_sum[wave][r] = v;
     }
     __syncthreads();
     if (wave < 4 && lane < R) {
@@ -492,7 +575,7 @@ __global__ __launch_bounds__(kGemvThreads) void w4_gemv_kernel(GemvBatch batch, 
   for (int r = 0; r < R; ++r) {
     const float v = row_sum(acc[r]);
     const int rc = rg * R + r;
-    if (lane == 0 && rc < km.n_keep) a.y[(size_t)m * a.ldy + rc] = out16<BF16>(v);
+    if (lane == 63 && rc < km.n_keep) a.y[(size_t)m * a.ldy + rc] = out16<BF16>(v);
   }
 }
 
@@ -532,9 +615,9 @@ static hipError_t launch_one(const LinearArgs* probs, int n, int m, int nchunk, 
 
 template <bool ZP, bool BF16, int R, bool XVEC>
 static hipError_t launch_nch(const LinearArgs* probs, int n, int m, int nchunk, hipStream_t stream) {
-  // the unrolled kernels fetch scales and zero points as dwords: rows of a multiple of four groups
+  // the unrolled kernels fetch a quad's scales and zero points as one run: no quad may straddle the end of a row
   bool wide = true;
-  for (int i = 0; i < n; ++i) wide = wide && (probs[i].K_total / kGroup) % 4 == 0;
+  for (int i = 0; i < n; ++i) wide = wide && whole_quads(probs[i].K_total, nchunk);
   switch (wide ? nchunk : 0) {
     case 1: return launch_one<ZP, BF16, R, XVEC, 1>(probs, n, m, nchunk, stream);
     case 2: return launch_one<ZP, BF16, R, XVEC, 2>(probs, n, m, nchunk, stream);
@@ -555,10 +638,7 @@ static hipError_t launch_rows(const LinearArgs* probs, int n, int r1, int m, int
   return launch_nch<ZP, BF16, 1, XVEC>(probs, n, m, nchunk, stream);
 }
 
-static inline int nchunk_of(const LinearArgs& a) {
-  const int k_span32 = (a.km.k_span + 31) & ~31;
-  return (k_span32 + kChunk - 1) / kChunk;
-}
+static inline int nchunk_of(const LinearArgs& a) { return row_tiles(a.km.k_span); }
 static inline bool xvec_of(const LinearArgs& a, int) {
   // a column prefix is fetched with 128-bit loads whatever the alignment of x (global loads may
   // start on any 2-byte boundary on this target)
@@ -639,7 +719,7 @@ template <bool ZP, bool BF16>
 static hipError_t gate_up_silu(const LinearArgs* probs, hipStream_t stream, bool* fused) {
   bool ok = probs[0].M == 1 && probs[1].M == 1 && nchunk_of(probs[0]) == nchunk_of(probs[1]) &&
             xvec_of(probs[0], 0) == xvec_of(probs[1], 0) && nchunk_of(probs[0]) >= 1 && nchunk_of(probs[0]) <= 8 &&
-            (probs[0].K_total / kGroup) % 4 == 0 && (probs[1].K_total / kGroup) % 4 == 0;
+            whole_quads(probs[0].K_total, nchunk_of(probs[0])) && whole_quads(probs[1].K_total, nchunk_of(probs[0]));
   *fused = ok;
   if (!ok) return hipSuccess;
   const int rows = 2 * probs[0].km.n_keep, nch = nchunk_of(probs[0]);
@@ -656,7 +736,7 @@ static hipError_t qkv_rope(const LinearArgs* probs, const RopeFuse& rf, hipStrea
   bool ok = true;
   for (int i = 0; i < 3; ++i)
     ok = ok && probs[i].M == 1 && nchunk_of(probs[i]) == nchunk_of(probs[0]) && xvec_of(probs[i], 0) == xvec_of(probs[0], 0) &&
-         (probs[i].K_total / kGroup) % 4 == 0;
+         whole_quads(probs[i].K_total, nchunk_of(probs[0]));
   ok = ok && nchunk_of(probs[0]) >= 1 && nchunk_of(probs[0]) <= 8;
   *fused = ok;
   if (!ok) return hipSuccess;

@@ -16,4 +16,13 @@ hipError_t launch_w4_gate_up_stream(const LinearArgs* probs, hipStream_t stream,
   return probs[0].bf16 ? launch_w4_gate_up_stream_bf16(probs, stream, done) : gemv::stream_gate_up<false>(probs, stream, done);
 }
 
+// the loads of the gate + up launch without its arithmetic (fp16 matrices with zero points): the read-stream ceiling
+hipError_t launch_w4_gate_up_stream_probe(const LinearArgs* probs, hipStream_t stream, bool* done) {
+  if (probs[0].bf16 || probs[1].bf16) {
+    *done = false;
+    return hipSuccess;
+  }
+  return gemv::stream_gate_up<false, true>(probs, stream, done);
+}
+
 }  // namespace uniql

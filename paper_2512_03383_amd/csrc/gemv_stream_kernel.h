@@ -1,22 +1,35 @@
-// Persistent streaming GEMV for tall matrices (one token): any row rule x column prefix, at least a row
-// or two per wave of the whole chip -- gate / up / output-head / in_proj shaped linears.
+// Persistent streaming GEMV for tall matrices (one token): any row rule x column prefix -- gate / up / down /
+// output-head / in_proj shaped linears.
 //
-// The launch fills the chip once (one or two blocks per CU) and every wave walks its own rows,
-// row r of the wave being compact row wave_id + r * total_waves, so that at any moment the chip reads
-// one contiguous window of the matrix and every CU ends up with the same number of rows whatever
-// the pruning rate.  The activations are staged once per block (LDS, stored column positions, zeros
-// where pruned) and, for rows of at most two 2048-column chunks, held in registers for the whole walk:
-// after the one barrier behind the staging a wave runs alone -- no LDS traffic, no barrier.
-// A wave keeps D tiles (1 KB of codes + scale + zero point each) in flight: the loop body consumes D
-// tiles in issue order and re-issues each slot, as soon as it is free, with the same tile of the next
-// body.  Arithmetic per tile is that of gemv_kernel.h (13 VALU per word in fp16, 23 in bfloat16, dot products on the matrix
-// pipe's diagonal).
+// The launch fills the chip once (one block per CU) and every wave WALKS rows: a block's bodies (a body = the rows one
+// loop iteration serves, normally one row, or one row of W_gate and of W_up) are spread over the matrix with a stride of
+// the whole grid, so that at any moment the chip reads one contiguous window of the matrix and every CU ends up with the
+// same number of rows whatever the pruning rate.  Inside a block the bodies are handed out by a counter in LDS: the two
+// waves that share a SIMD do not advance at the same pace (the issue arbiter prefers the older one), and a fixed split
+// left the younger four waves of every block 2 us behind the older four.
+//
+// Column layout of a wave.  A row is covered by NCH wave-wide 128-bit loads ("tiles").  Lanes 4g..4g+3 (a quad) own NCH
+// ADJACENT quantisation groups, g * NCH .. g * NCH + NCH - 1, and tile c of the row is group g * NCH + c of every quad: a
+// quad reads 64 contiguous bytes per tile (one request of the address unit, like a contiguous load) and the NCH tiles of
+// a row together read the row contiguously.  What this buys: the NCH scales of a lane are adjacent in memory, and so are
+// its zero points, so a ROW needs one scale load and one zero-point load instead of one of each per TILE (with a
+// contiguous kilobyte per tile a lane's groups lie 16 apart; the small loads were the largest single cost of the body).
+//
+// The activations are staged once per block (LDS image [tile][word][lane], zeros where pruned) and, for short rows, held
+// in registers for the whole walk.  A wave keeps one body of tiles in flight as a ring: the loop consumes them in issue
+// order and re-issues each slot, as soon as it is free, with the same tile of the wave's next body; the scales and zero
+// points of that body are issued at the top.  A wave's last body re-issues nothing.  Arithmetic per 32-bit word: 13 VALU
+// in fp16 (23 in bfloat16) for the canonical weights RN16((q - z) s), the 8-element dot product on the diagonal of one
+// matrix instruction.  The kernel is bound by instruction issue as much as by the stream (every instruction of a body,
+// scalar ones included, costs a SIMD about 4.5 clocks), so the body is kept short: no LDS crossbar in the wave
+// reduction, scales applied through op_sel instead of a splat, the row rule a template parameter.
 //
 // NM = 2 is the gated MLP (Eq. 1): a wave streams row r of W_gate and of W_up side by side and writes
 // h[r] = SiLU(gate) * up itself, so gate and up never meet through memory or LDS.
 #pragma once
 #include "gemv_kernel.h"
 #include <atomic>
+#include <type_traits>
 
 namespace uniql {
 namespace gemv {
@@ -35,23 +48,24 @@ struct StreamArgs {
   KeepMap km;            // row map (rows only; the kept columns are a prefix)
 };
 
-template <int NCH, int NM, bool ZP, bool BF16>
+// PROBE: the kernel's loads alone, folded into one word per row -- the read-stream ceiling of exactly this launch
+// shape (what the arithmetic is measured against), not a linear.
+template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE = false>
 __global__ __launch_bounds__(kStreamThreads) void w4_gemv_stream_kernel(StreamArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   uint4* xs = reinterpret_cast<uint4*>(smem);   // [NCH][4][64] units of 8 halves
-  constexpr int TPR = NM * NCH;                           // tiles per row (pair)
-  constexpr int RB = TPR >= 4 ? 1 : 4 / TPR;              // rows per loop body
-  constexpr int D = RB * TPR;                             // tiles per body = tiles in flight
-  constexpr bool XREG = NCH <= 2;                         // activations live in registers
+  constexpr int TPR = NM * NCH;                                  // tiles per row (pair)
+  constexpr int RB = TPR >= 4 ? 1 : 4 / TPR;                     // rows per loop body
+  constexpr int D = RB * TPR;                                    // tiles per body = tiles in flight
+  constexpr bool XREG = NCH <= 2;                                // activations live in registers
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int gw = (int)blockIdx.x * kStreamWaves + wave;           // this wave among all waves
   const int total_waves = (int)gridDim.x * kStreamWaves;
   const int words_per_row = a.K_total >> 3, groups_per_row = a.K_total / kGroup;
   const int k_span32 = (a.k_keep + 31) & ~31;
 
-  // ---- x loads first (memory returns in issue order; x is an L2 hit)
+  // ---- x loads first (memory returns in issue order; x is an L2 hit).  Unit u = stored columns [8u, 8u + 8).
   constexpr int XI = (NCH * 256 + kStreamThreads - 1) / kStreamThreads;
   const int kv = a.k_keep & ~7;
   const uint16_t* xbits = reinterpret_cast<const uint16_t*>(a.x);
@@ -59,8 +73,7 @@ __global__ __launch_bounds__(kStreamThreads) void w4_gemv_stream_kernel(StreamAr
   uint32_t tailv[8];
 #pragma unroll
   for (int i = 0; i < XI; ++i) {
-    const int uraw = tid + i * kStreamThreads;
-    const int k0 = unit_k0(uraw < NCH * 256 ? uraw : NCH * 256 - 1);
+    const int k0 = 8 * (tid + i * kStreamThreads);
     const int k0c = k0 + 8 <= kv ? k0 : kv - 8;     // the host sends k_keep >= 8 only
     rawv[i] = load_u4_unaligned(a.x + k0c);
   }
@@ -71,19 +84,20 @@ __global__ __launch_bounds__(kStreamThreads) void w4_gemv_stream_kernel(StreamAr
     for (int j = 0; j < 8; ++j) tailv[j] = xbits[kv + j < a.k_keep ? kv + j : a.k_keep - 1];
   }
 
-  // ---- the wave's rows and the first body of tiles
-  // lane offsets of a tile inside its row, per chunk: lanes past the last kept column re-read the row
-  // start (their x is zero)
-  uint32_t woff[NCH], goff[NCH];   // byte offset of the lane's codes, index of its group
+  // ---- lane offsets inside a row.  Lanes whose columns lie past the last kept one re-read the row start: their
+  // activations are zero, so what they fetch does not matter.
+  const int quad = lane >> 2;
+  uint32_t woff[NCH];
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
-    const int kb = c * kChunk + lane * 32;
-    const int kbc = kb < k_span32 ? kb : 0;
-    woff[c] = (uint32_t)kbc >> 1;
-    goff[c] = (uint32_t)kbc >> 7;
+    const int kb = tile_k0(lane, c, NCH);
+    woff[c] = kb < k_span32 ? (uint32_t)kb >> 1 : 0u;
   }
-  // Buffer resources over the kept rows of each array (base, byte count): a tile's address is then
-  // resource + scalar row offset + 32-bit lane offset, and no per-lane 64-bit pointer exists.
+  // first group of the lane (a quad past the row's groups reads the row start).  A quad may own groups past the row's
+  // last one when 16 NCH exceeds the groups of a row: their columns are pruned by definition, what is read for them
+  // (the next row's values; nothing past the arrays, which the resources bound) is multiplied by zero.
+  const int goff = quad * NCH < groups_per_row ? quad * NCH : 0;
+  // Buffer resources over the arrays: an address is resource + scalar row offset + 32-bit lane offset.
   constexpr int kRsrcWord3 = 0x00020000;   // raw 32-bit data format of this target's buffer resource
   __amdgpu_buffer_rsrc_t rq[NM], rs[NM], rz[NM];
 #pragma unroll
@@ -93,37 +107,52 @@ __global__ __launch_bounds__(kStreamThreads) void w4_gemv_stream_kernel(StreamAr
     if constexpr (ZP)
       rz[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(a.zeros[m]), 0, a.N_total * groups_per_row, kRsrcWord3);
   }
-  typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-  auto load_tile = [&](int rc, int m, int c, Tile& t) {   // rc: compact row, clamped by the caller
-    const int sr = a.km.rs_stride ? stored_row(a.km, rc) : rc;              // uniform: scalar arithmetic
-    const int row_q = sr * words_per_row * 4, row_g = sr * groups_per_row;   // scalar byte offsets of the row
-    const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rq[m], (int)woff[c], row_q, 0);
-    t.w = make_uint4(v.x, v.y, v.z, v.w);
-    t.sbits = __builtin_amdgcn_raw_buffer_load_b16(rs[m], (int)(2u * goff[c]), 2 * row_g, 0);
-    if constexpr (ZP) t.z = __builtin_amdgcn_raw_buffer_load_b8(rz[m], (int)goff[c], row_g, 0);
-    else t.z = 8u;
+  struct RowOff { int q, g; };   // scalar byte / element offsets of a row inside the arrays (once per row)
+  auto row_off = [&](int rc) {   // rc: compact row, clamped by the caller
+    const int sr = SEG ? stored_row(a.km, rc) : rc;   // SEG = false: the kept rows are a prefix
+    return RowOff{sr * words_per_row * 4, sr * groups_per_row};
   };
-  // slot s of a body: row s / TPR of the body, then chunk-major with the matrices of a chunk adjacent
-  auto slot_row = [](int s) { return s / TPR; };
-  auto slot_chunk = [](int s) { return (s % TPR) / NM; };
+  typedef RowQ<NCH> RowQn;   // a lane's scales (fp16 bits) and zero points (bytes) of one row
+  auto load_rowq = [&](const RowOff& ro, int m, RowQn& r) {
+    load_bytes<2 * NCH>(rs[m], 2 * goff, 2 * ro.g, r.s);
+    if constexpr (ZP) load_bytes<NCH>(rz[m], goff, ro.g, r.z);
+  };
+  auto load_codes = [&](const RowOff& ro, int m, int c) {
+    return __builtin_amdgcn_raw_buffer_load_b128(rq[m], (int)woff[c], ro.q, 0);
+  };
+  // slot s of a body: row s / TPR of the body, then tile-major with the matrices of a tile adjacent
+  auto slot_tile = [](int s) { return (s % TPR) / NM; };
   auto slot_mat = [](int s) { return s % NM; };
   const int last = a.n_keep - 1;
-  auto row_of = [&](int body, int rr) { return gw + (body * RB + rr) * total_waves; };   // may exceed n_keep
+  // Bodies of a block: body j is RB adjacent rows, (block * 8 + j % 8) * RB + (j / 8) * RB * total_waves onwards (may
+  // exceed n_keep: bodies are valid up to some j and invalid from there on).  Wave w starts on body w; every further
+  // body is handed out by a counter in LDS to whichever wave of the block asks first.  The two waves that share a SIMD do
+  // not advance at the same pace (the issue arbiter prefers the older wave: with a fixed split the younger four waves of
+  // every block finished 2.3 us after the older four), so the faster ones simply take more bodies.
+  const int blk8 = (int)blockIdx.x * kStreamWaves;
+  auto row_of = [&](int j, int rr) { return (blk8 + (j & 7)) * RB + rr + (j >> 3) * RB * total_waves; };
+  __shared__ int next_body;
+  if (tid == 0) next_body = kStreamWaves;   // visible after the barrier behind the staging
 
-  Tile ring[D];
+  u32x4_t ring[D];
+  RowQn cur[RB][NM], nxt[RB][NM];
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-  for (int s = 0; s < D; ++s) {
-    const int rc = row_of(0, slot_row(s));
-    load_tile(rc < last ? rc : last, slot_mat(s), slot_chunk(s), ring[s]);
+  for (int rr = 0; rr < RB; ++rr) {
+    const int rc = row_of(wave, rr);
+    const RowOff ro = row_off(rc < last ? rc : last);
+#pragma unroll
+    for (int m = 0; m < NM; ++m) load_rowq(ro, m, cur[rr][m]);
+#pragma unroll
+    for (int t = 0; t < TPR; ++t) ring[rr * TPR + t] = load_codes(ro, slot_mat(t), slot_tile(t));
   }
   __builtin_amdgcn_sched_barrier(0);
 
-  // ---- x registers -> LDS in the pair order of the slot, zeros for pruned columns
+  // ---- x registers -> LDS image [tile][word][lane] in the pair order of the unpack, zeros for pruned columns
 #pragma unroll
   for (int i = 0; i < XI; ++i) {
     const int u = tid + i * kStreamThreads;
-    const int k0 = unit_k0(u);
+    const int k0 = 8 * u;
     const uint4 r = rawv[i];
     const uint32_t full[8] = {r.x & 0xffffu, r.x >> 16, r.y & 0xffffu, r.y >> 16,
                               r.z & 0xffffu, r.z >> 16, r.w & 0xffffu, r.w >> 16};
@@ -132,7 +161,8 @@ __global__ __launch_bounds__(kStreamThreads) void w4_gemv_stream_kernel(StreamAr
 #pragma unroll
     for (int j = 0; j < 8; ++j) e[j] = whole ? full[j] : ((tail && kv + j < a.k_keep) ? tailv[j] : 0u);
     if (u < NCH * 256)
-      xs[unit_slot(u)] = make_uint4(e[0] | (e[4] << 16), e[1] | (e[5] << 16), e[2] | (e[6] << 16), e[3] | (e[7] << 16));
+      xs[unit_slot(u, NCH)] =
+          make_uint4(e[0] | (e[4] << 16), e[1] | (e[5] << 16), e[2] | (e[6] << 16), e[3] | (e[7] << 16));
   }
   __builtin_amdgcn_sched_barrier(0);
   __syncthreads();
@@ -147,116 +177,144 @@ __global__ __launch_bounds__(kStreamThreads) void w4_gemv_stream_kernel(StreamAr
 
   const Magic mg = make_magic();
   const bool on_diag = (lane >> 4) == ((lane & 15) >> 2);
-  auto row_sum = [&](const float4_t& c) {
-    const int v = lane & 3;
-    float d = v == 0 ? c[0] : (v == 1 ? c[1] : (v == 2 ? c[2] : c[3]));
-    return dpp_xor_reduce(on_diag ? d : 0.f);
-  };
-  auto consume = [&](const Tile& t, const uint4 (&xf)[4], float4_t& acc) {
-    const typename GroupOf<BF16>::type g = make_group<BF16>(t.sbits, t.z);
-    const uint32_t wv[4] = {t.w.x, t.w.y, t.w.z, t.w.w};
+  typedef typename GroupOf<BF16>::type Group;
+  auto consume = [&](const u32x4_t& w, const Group& g, const uint4 (&xf)[4], float4_t& acc) {
+    const uint32_t wv[4] = {w.x, w.y, w.z, w.w};
+    if constexpr (PROBE) {
+      uint32_t fold = w.x ^ w.y ^ w.z ^ w.w;
+      if constexpr (BF16) fold ^= __builtin_bit_cast(uint32_t, g.s) ^ __builtin_bit_cast(uint32_t, g.nzs);
+      else fold ^= as_u32(g.s2) ^ as_u32(g.zlo);
+      acc[0] += __builtin_bit_cast(float, fold & 0x3fffffffu);
+      return;
+    }
 #pragma unroll
     for (int q = 0; q < 4; ++q) acc = mfma_16x16x32<BF16>(xf[q], dequant_word4<BF16>(wv[q], g, mg), acc);
   };
 
-  // rows of this wave: gw, gw + total_waves, ...; bodies of RB rows
-  const int my_rows = gw < a.n_keep ? (a.n_keep - gw + total_waves - 1) / total_waves : 0;
-  const int bodies = (my_rows + RB - 1) / RB;
   float4_t acc[RB][NM];
 #pragma unroll
   for (int rr = 0; rr < RB; ++rr)
 #pragma unroll
     for (int m = 0; m < NM; ++m) acc[rr][m] = float4_t{0.f, 0.f, 0.f, 0.f};
-  for (int body = 0; body < bodies; ++body) {
+
+  // One body: RB rows.  RELOAD: every slot is re-issued, as soon as it has been consumed, with the same tile of the
+  // next body (all bodies but the wave's last, which therefore issues no load that nobody consumes).
+  auto run_body = [&](int body, int body_next, auto reload_tag) {
+    constexpr bool RELOAD = decltype(reload_tag)::value;
+    RowOff nro[RB];
+    if constexpr (RELOAD) {
+#pragma unroll
+      for (int rr = 0; rr < RB; ++rr) {
+        const int rn = row_of(body_next, rr);   // the first row of the next body exists; its other rows may not
+        nro[rr] = row_off(rn < last ? rn : last);
+#pragma unroll
+        for (int m = 0; m < NM; ++m) load_rowq(nro[rr], m, nxt[rr][m]);
+      }
+    }
 #pragma unroll
     for (int rr = 0; rr < RB; ++rr) {
       // rows of a body past the wave's last one (only in its last body) are skipped as a whole
-      if (rr > 0 && body * RB + rr >= my_rows) break;
+      if (rr > 0 && row_of(body, rr) > last) break;
 #pragma unroll
       for (int t = 0; t < TPR; ++t) {
-        const int s = rr * TPR + t, c = slot_chunk(s), m = slot_mat(s);
+        const int s = rr * TPR + t, c = slot_tile(s), m = slot_mat(s);
         if (c == 0) acc[rr][m] = float4_t{0.f, 0.f, 0.f, 0.f};
-        Tile& tl = ring[s];
-        // order fence: this tile's unpacking may not be hoisted above the previous tile's arithmetic
+        // order fence: this tile's unpacking may not be hoisted above the previous tile's arithmetic.  The codes pass
+        // as ONE 128-bit operand, so that they keep their register tuple across the loop's back edge (copies of
+        // loaded registers there would wait for every load in flight).
         const int ps = (s + D - 1) % D;   // the tile consumed just before this one (compile-time after unrolling)
-        asm volatile("" : "+v"(tl.w.x), "+v"(tl.w.y), "+v"(tl.w.z), "+v"(tl.w.w), "+v"(tl.sbits), "+v"(tl.z),
-                          "+v"(acc[ps / TPR][ps % NM][0]));
+        asm volatile("" : "+v"(ring[s]), "+v"(acc[ps / TPR][ps % NM]));
+        const Group g = group_of<ZP, BF16, NCH>(cur[rr][m], c);
         if constexpr (XREG) {
-          consume(tl, xr[c], acc[rr][m]);
+          consume(ring[s], g, xr[c], acc[rr][m]);
         } else {
           uint4 xf[4];
 #pragma unroll
           for (int q = 0; q < 4; ++q) xf[q] = xs[(c * 4 + q) * 64 + lane];
-          consume(tl, xf, acc[rr][m]);
+          consume(ring[s], g, xf, acc[rr][m]);
         }
-        // the slot is free: the same tile of the next body (a valid row even when that body does not exist)
-        const int rn = row_of(body + 1, rr);
-        load_tile(rn < last ? rn : last, m, c, tl);
+        if constexpr (RELOAD) ring[s] = load_codes(nro[rr], m, c);
       }
       const int rc = row_of(body, rr);
       if constexpr (NM == 1) {
-        const float v = row_sum(acc[rr][0]);
-        if (lane == 0) a.y[rc] = out16<BF16>(v);
+        const float v = diag_sum_to_lane63(acc[rr][0], on_diag);
+        if (lane == 63) a.y[rc] = out16<BF16>(v);
       } else {
-        const float g = row_sum(acc[rr][0]), u = row_sum(acc[rr][1]);
+        float g, u;
+        diag_sums_to_lane63(acc[rr][0], acc[rr][1], on_diag, g, u);
         // SiLU(g) * u; exp and the reciprocal are the hardware approximations (about 1 ulp of fp32)
-        if (lane == 0) a.y[rc] = out16<BF16>(g * u * __builtin_amdgcn_rcpf(1.0f + __expf(-g)));
+        if (lane == 63) a.y[rc] = out16<BF16>(g * u * __builtin_amdgcn_rcpf(1.0f + __expf(-g)));
       }
     }
+    if constexpr (RELOAD) {
+#pragma unroll
+      for (int rr = 0; rr < RB; ++rr)
+#pragma unroll
+        for (int m = 0; m < NM; ++m) cur[rr][m] = nxt[rr][m];
+    }
+  };
+  auto grab = [&]() {   // one counter increment per wave
+    int v = 0;
+    if (lane == 0) v = __hip_atomic_fetch_add(&next_body, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    return __builtin_amdgcn_readfirstlane(v);
+  };
+  int cur_body = wave;
+  if (row_of(cur_body, 0) <= last) {
+    int nb = grab();
+    while (true) {
+      // the body after the next is asked for now and looked at in the next round (the counter's latency hides behind a body)
+      const int nnb = grab();
+      if (row_of(nb, 0) > last) break;
+      run_body(cur_body, nb, std::true_type{});
+      cur_body = nb;
+      nb = nnb;
+    }
+    run_body(cur_body, 0, std::false_type{});
   }
 }
 
-// blocks per CU that the kernel's register use allows, times the CU count: the persistent grid
-template <int NCH, int NM, bool ZP, bool BF16>
+
+template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE>
 static hipError_t stream_launch(const StreamArgs& a, hipStream_t stream) {
-  auto kern = w4_gemv_stream_kernel<NCH, NM, ZP, BF16>;
+  auto kern = w4_gemv_stream_kernel<NCH, NM, ZP, BF16, SEG, PROBE>;
   const size_t smem = (size_t)NCH * 4096;
-  // CU count and blocks per CU of this instantiation, per device ordinal: one word each (count | blocks << 16),
-  // written once, so that host threads that race on the first call all read a complete pair
-  static std::atomic<uint32_t> cached[64];
+  // CU count per device ordinal, read once (host threads that race on the first call all store the same value)
+  static std::atomic<int> cached[64];
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
   const bool slot = dev >= 0 && dev < 64;
-  uint32_t packed = slot ? cached[dev].load(std::memory_order_acquire) : 0u;
-  if (packed == 0) {
-    int cus = 0, per_cu = 0;
-    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(kern), kStreamThreads, smem);
-    if (e != hipSuccess) return e;
+  int cus = slot ? cached[dev].load(std::memory_order_acquire) : 0;
+  if (cus == 0) {
     e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e != hipSuccess) return e;
-    if (per_cu < 1) per_cu = 1;
-    if (cus < 1 || cus > 0xffff || per_cu > 0xffff) return hipErrorInvalidValue;
-    packed = (uint32_t)cus | ((uint32_t)per_cu << 16);
-    if (slot) cached[dev].store(packed, std::memory_order_release);
+    if (cus < 1) return hipErrorInvalidValue;
+    if (slot) cached[dev].store(cus, std::memory_order_release);
   }
-  const int cus = (int)(packed & 0xffffu), per_cu = (int)(packed >> 16);
-  // One block (8 waves, four tiles in flight each) per CU measured fastest up to the size of a gated MLP
-  // (more waves only add start-up work); an output-head sized stream needs two to keep enough loads in flight.
-  const long long bytes = (long long)NM * a.n_keep * (a.k_keep / 2);
-  const int want = bytes >= 100000000ll ? 2 : 1;
-  const int cap = cus * (want < per_cu ? want : per_cu);
-  int blocks = (a.n_keep + kStreamWaves - 1) / kStreamWaves;
-  if (blocks > cap) blocks = cap;
+  // One block (8 waves, one body of tiles in flight each) per CU: more waves or deeper rings measured slower at every
+  // size tried (the kernel is bound by instruction issue, and more loads in flight only queue).
+  constexpr int TPR = NM * NCH, RB = TPR >= 4 ? 1 : 4 / TPR;
+  int blocks = (a.n_keep + kStreamWaves * RB - 1) / (kStreamWaves * RB);
+  if (blocks > cus) blocks = cus;
   hipLaunchKernelGGL(kern, dim3(blocks), dim3(kStreamThreads), smem, stream, a);
   return hipGetLastError();
 }
 
-template <int NM, bool ZP, bool BF16>
-static hipError_t stream_nch(const StreamArgs& a, int nchunk, hipStream_t stream) {
-  switch (nchunk) {
-    case 1: return stream_launch<1, NM, ZP, BF16>(a, stream);
-    case 2: return stream_launch<2, NM, ZP, BF16>(a, stream);
-    case 3: return stream_launch<3, NM, ZP, BF16>(a, stream);
-    case 4: return stream_launch<4, NM, ZP, BF16>(a, stream);
+template <int NM, bool ZP, bool BF16, bool SEG, bool PROBE>
+static hipError_t stream_nch(const StreamArgs& a, int nch, hipStream_t stream) {
+  switch (nch) {
+    case 1: return stream_launch<1, NM, ZP, BF16, SEG, PROBE>(a, stream);
+    case 2: return stream_launch<2, NM, ZP, BF16, SEG, PROBE>(a, stream);
+    case 3: return stream_launch<3, NM, ZP, BF16, SEG, PROBE>(a, stream);
+    case 4: return stream_launch<4, NM, ZP, BF16, SEG, PROBE>(a, stream);
     default: break;
   }
   if constexpr (NM == 1) {
-    switch (nchunk) {
-      case 5: return stream_launch<5, 1, ZP, BF16>(a, stream);
-      case 6: return stream_launch<6, 1, ZP, BF16>(a, stream);
-      case 7: return stream_launch<7, 1, ZP, BF16>(a, stream);
-      case 8: return stream_launch<8, 1, ZP, BF16>(a, stream);
+    switch (nch) {
+      case 5: return stream_launch<5, 1, ZP, BF16, SEG, PROBE>(a, stream);
+      case 6: return stream_launch<6, 1, ZP, BF16, SEG, PROBE>(a, stream);
+      case 7: return stream_launch<7, 1, ZP, BF16, SEG, PROBE>(a, stream);
+      case 8: return stream_launch<8, 1, ZP, BF16, SEG, PROBE>(a, stream);
       default: break;
     }
   }
@@ -264,28 +322,21 @@ static hipError_t stream_nch(const StreamArgs& a, int nchunk, hipStream_t stream
 }
 
 // Rows below which the kernels of gemv_kernel.h are used: the walk pays off once every wave of the
-// persistent grid has more than a row or two.  Rows of up to four chunks (short tile rings, activations in
+// persistent grid has more than a row or two.  Rows of up to four tiles (short tile rings, activations in
 // registers or few LDS reads) already gain from one row per wave.
 constexpr int kStreamMinRows = 8192;
 constexpr int kStreamMinRowsShort = 2048;
-constexpr int kStreamMinRowsLong = 4096;    // row prefix with rows of more than four chunks (down_proj)
+constexpr int kStreamMinRowsLong = 4096;    // row prefix with rows of more than four tiles (down_proj)
 
-static inline bool stream_shape(const LinearArgs& a, int max_chunks) {
+static inline bool stream_shape(const LinearArgs& a, int max_tiles) {
   const KeepMap& km = a.km;
-  const int nch = ((km.k_keep + 31) / 32 * 32 + kChunk - 1) / kChunk;
+  const int nch = row_tiles(km.k_keep);
   // row offsets inside the buffer resources are signed 32-bit byte counts
   const bool fits = (long long)a.N_total * (a.K_total / 2) < (1ll << 31);
-  return a.M == 1 && km.cs_stride == 0 && km.k_keep >= 8 && nch <= max_chunks && fits;
+  return a.M == 1 && km.cs_stride == 0 && km.k_keep >= 8 && nch <= max_tiles && fits && whole_quads(a.K_total, nch);
 }
 
-// One linear: *done = false (nothing launched) when the shape is not one this kernel serves.
-template <bool BF16>
-static hipError_t stream_one(const LinearArgs& a, hipStream_t stream, bool* done) {
-  const int nchunks = ((a.km.k_keep + 31) / 32 * 32 + kChunk - 1) / kChunk;
-  // (segmented row rules, one division per row, only from the higher threshold: q_proj sized launches measured slower)
-  const int min_rows = a.km.rs_stride != 0 ? kStreamMinRows : (nchunks <= 4 ? kStreamMinRowsShort : kStreamMinRowsLong);
-  *done = stream_shape(a, 8) && a.km.n_keep >= min_rows;
-  if (!*done) return hipSuccess;
+static inline StreamArgs stream_args(const LinearArgs& a) {
   StreamArgs s;
   s.qweight[0] = s.qweight[1] = a.qweight;
   s.scales[0] = s.scales[1] = a.scales;
@@ -297,34 +348,48 @@ static hipError_t stream_one(const LinearArgs& a, hipStream_t stream, bool* done
   s.K_total = a.K_total;
   s.N_total = a.N_total;
   s.km = a.km;
-  const int nch = ((a.km.k_keep + 31) / 32 * 32 + kChunk - 1) / kChunk;
-  return a.zeros ? stream_nch<1, true, BF16>(s, nch, stream) : stream_nch<1, false, BF16>(s, nch, stream);
+  return s;
 }
 
-// gate and up of one token with h = SiLU(gate) * up written to probs[0].y
+// One linear: *done = false (nothing launched) when the shape is not one this kernel serves.
 template <bool BF16>
+static hipError_t stream_one(const LinearArgs& a, hipStream_t stream, bool* done) {
+  const int nch = row_tiles(a.km.k_keep);
+  // (segmented row rules, one division per row, only from the higher threshold: q_proj sized launches measured slower)
+  const int min_rows = a.km.rs_stride != 0 ? kStreamMinRows : (nch <= 4 ? kStreamMinRowsShort : kStreamMinRowsLong);
+  *done = stream_shape(a, 8) && a.km.n_keep >= min_rows;
+  if (!*done) return hipSuccess;
+  const StreamArgs s = stream_args(a);
+  if (a.km.rs_stride != 0)
+    return a.zeros ? stream_nch<1, true, BF16, true, false>(s, nch, stream) : stream_nch<1, false, BF16, true, false>(s, nch, stream);
+  return a.zeros ? stream_nch<1, true, BF16, false, false>(s, nch, stream) : stream_nch<1, false, BF16, false, false>(s, nch, stream);
+}
+
+// The loads of stream_one's launch without its arithmetic (y receives one folded word per row): the read-stream
+// ceiling of the same launch shape.  *done = false when the shape is not one the kernel serves.
+template <bool BF16>
+static hipError_t stream_probe(const LinearArgs& a, hipStream_t stream, bool* done) {
+  *done = stream_shape(a, 8) && a.km.rs_stride == 0 && a.zeros != nullptr;
+  if (!*done) return hipSuccess;
+  return stream_nch<1, true, BF16, false, true>(stream_args(a), row_tiles(a.km.k_keep), stream);
+}
+
+// gate and up of one token with h = SiLU(gate) * up written to probs[0].y (row prefix x column prefix)
+template <bool BF16, bool PROBE = false>
 static hipError_t stream_gate_up(const LinearArgs* p, hipStream_t stream, bool* done) {
   *done = stream_shape(p[0], 4) && stream_shape(p[1], 4) && p[0].km.n_keep >= kStreamMinRows / 2 &&
           p[0].km.n_keep == p[1].km.n_keep && p[0].km.k_keep == p[1].km.k_keep && p[0].K_total == p[1].K_total &&
           p[0].x == p[1].x && p[0].bf16 == p[1].bf16 && (p[0].zeros != nullptr) == (p[1].zeros != nullptr) && p[0].N_total == p[1].N_total &&
-          p[0].km.rs_stride == p[1].km.rs_stride && p[0].km.rs_keep == p[1].km.rs_keep && p[0].km.rs_limit == p[1].km.rs_limit &&
-          p[0].km.rs2_stride == p[1].km.rs2_stride && p[0].km.rs2_keep == p[1].km.rs2_keep && p[0].km.rs2_limit == p[1].km.rs2_limit;
+          p[0].km.rs_stride == 0 && p[1].km.rs_stride == 0;
+  if (PROBE) *done = *done && p[0].zeros != nullptr;
   if (!*done) return hipSuccess;
-  StreamArgs s;
-  for (int m = 0; m < 2; ++m) {
-    s.qweight[m] = p[m].qweight;
-    s.scales[m] = p[m].scales;
-    s.zeros[m] = p[m].zeros;
-  }
-  s.x = p[0].x;
-  s.y = p[0].y;
-  s.n_keep = p[0].km.n_keep;
-  s.k_keep = p[0].km.k_keep;
-  s.K_total = p[0].K_total;
-  s.N_total = p[0].N_total;
-  s.km = p[0].km;
-  const int nch = ((s.k_keep + 31) / 32 * 32 + kChunk - 1) / kChunk;
-  return p[0].zeros ? stream_nch<2, true, BF16>(s, nch, stream) : stream_nch<2, false, BF16>(s, nch, stream);
+  StreamArgs s = stream_args(p[0]);
+  s.qweight[1] = p[1].qweight;
+  s.scales[1] = p[1].scales;
+  s.zeros[1] = p[1].zeros;
+  const int nch = row_tiles(s.k_keep);
+  if constexpr (PROBE) return stream_nch<2, true, BF16, false, true>(s, nch, stream);
+  return p[0].zeros ? stream_nch<2, true, BF16, false, false>(s, nch, stream) : stream_nch<2, false, BF16, false, false>(s, nch, stream);
 }
 
 }  // namespace gemv

@@ -645,13 +645,20 @@ def test_gate_up_silu(env, uref, N, K, keep):
     assert linear_err(h.cpu().numpy().reshape(1, -1), ref) <= TOL
 
 
-def test_gate_up_silu_refuses_what_it_cannot_fuse(env):
+def test_gate_up_silu_refuses_what_it_cannot_fuse(env, uref):
     uq, torch = env
     rng = wl.rng_for(8, 1)
-    w = wl.gen_linear(rng, 64, 256)       # two groups per row: not a multiple of four
+    # 35 groups per row in three tiles: a quad's three groups would straddle the end of a row
+    w = wl.gen_linear(rng, 64, 35 * 128)
     q = uq.QuantLinear.from_numpy(w)
     with pytest.raises(Exception):
-        uq.uniql_w4_gate_up_silu([q, q], [None, None], torch.zeros(256, dtype=torch.float16, device="cuda"))
+        uq.uniql_w4_gate_up_silu([q, q], [None, None], torch.zeros(35 * 128, dtype=torch.float16, device="cuda"))
+    # two groups per row (most quads of a tile lie past the row's end) is served, and right
+    wg, wu = wl.gen_linear(rng, 64, 256), wl.gen_linear(rng, 64, 256)
+    x = wl.gen_activations(rng, 1, 256)
+    h = uq.uniql_w4_gate_up_silu([uq.QuantLinear.from_numpy(wg), uq.QuantLinear.from_numpy(wu)], [None, None], to_dev(torch, x[0]))
+    ref = uref.gate_up_silu(wg, Keep(), wu, Keep(), x)
+    assert linear_err(h.cpu().numpy().reshape(1, -1), ref) <= TOL
 
 
 # ------------------------------------------------- 4-bit embedding rows gathered by token id
