@@ -276,6 +276,48 @@ int uniql_w4_gate_up_silu(const uniql_w4_t* W, const uniql_keep_t* keep, const v
 int uniql_stream_read_probe(const void* src, int64_t bytes, void* out_words, void* hip_stream);
 
 /*
+ * The gated MLP of one token (Eq. 1): y = W_down' (SiLU(W_gate' x) * (W_up' x)), W[0] = gate, W[1] = up, W[2] = down,
+ * keep[0..2] their pruning rules (keep = NULL: unpruned).  The kept hidden dimension is the same for the three:
+ * n_keep(gate) = n_keep(up) = k_keep(down), which is how the method prunes the MLP (Sec. 3.1: the intermediate channels
+ * are sorted once, a rate keeps the leading ones of all three matrices).  x is [k_keep(gate)], y is [n_keep(down)],
+ * device pointers, 16-bit elements in the matrices' format.  The hidden vector is rounded to 16 bits once, like every
+ * activation of the path, and is bit-identical to what uniql_w4_gate_up_silu writes; y is bit-identical to
+ * uniql_w4_linear on that vector.
+ *
+ * `workspace` is device memory owned by the caller, 256-byte aligned, at least uniql_w4_mlp_workspace_bytes(n_keep(gate))
+ * bytes, zero-filled ONCE before its first use (not between calls) and used by one call at a time: calls that share a
+ * workspace must not overlap on the device (same stream, or ordered by events).  It holds the hidden vector and, for
+ * the single persistent launch that serves tall row-prefix x column-prefix matrices (hidden widths of 2049..4096
+ * columns, at least 4096 kept intermediate channels, at least 2048 outputs), a few control words and a word per block
+ * through which the launch's blocks tell each other that their part of the hidden vector has reached memory.  That launch occupies every compute unit
+ * and its blocks wait for each other, for at most 0.2 s: on a device that other work keeps busy beyond that, a block
+ * gives up, y is then incomplete, and uniql_w4_mlp_status reports it.  The launch keeps its serial number in the
+ * workspace, so a captured call may be replayed.  Other shapes run uniql_w4_gate_up_silu and uniql_w4_linear one after
+ * the other through the same workspace.
+ * Errors: as uniql_w4_gate_up_silu and uniql_w4_linear; E_KEEP also when k_keep(down) differs from n_keep(gate);
+ * E_SHAPE also when the workspace is too small; E_ALIGN for a workspace that is not 256-byte aligned.
+ */
+int uniql_w4_mlp(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_f16, void* y_f16,
+                 void* workspace, int64_t workspace_bytes, void* hip_stream);
+
+/* Bytes of workspace uniql_w4_mlp needs for n_hidden_keep kept intermediate channels (0 for a count below 1). */
+int64_t uniql_w4_mlp_workspace_bytes(int32_t n_hidden_keep);
+
+/*
+ * Where the last uniql_w4_mlp call with n_hidden_keep kept intermediate channels left its hidden vector inside
+ * `workspace`: *h_f16 receives a device pointer to n_hidden_keep 16-bit elements (valid once that call has finished).
+ * Host arithmetic only.  Errors: E_NULL, E_SHAPE.
+ */
+int uniql_w4_mlp_hidden(const void* workspace, int32_t n_hidden_keep, const void** h_f16);
+
+/*
+ * Waits for `hip_stream` and writes to *gave_up_serial (host) the give-up word of `workspace`: 0 when no call on that
+ * workspace ever gave up waiting, else the serial number (counted per workspace, from 1) of the last call that did.
+ * Errors: E_NULL, E_HIP.
+ */
+int uniql_w4_mlp_status(const void* workspace, uint32_t* gave_up_serial, void* hip_stream);
+
+/*
  * Measurement aid, not part of the method: the launch of uniql_w4_gate_up_silu on its persistent streaming kernel
  * (fp16 matrices with zero points, row prefix x column prefix, at least 4096 kept rows, rows of at most 8192 kept
  * columns) with every load it issues -- codes, scales, zero points, activations -- and none of its arithmetic: the

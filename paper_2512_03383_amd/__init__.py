@@ -82,6 +82,14 @@ def lib():
                                         i32, i32, i32, i32, i32, C.c_double, vp]
         L.uniql_w4_gate_up_silu.restype = C.c_int
         L.uniql_w4_gate_up_silu.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, vp, vp]
+        L.uniql_w4_mlp.restype = C.c_int
+        L.uniql_w4_mlp.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, vp, vp, i64, vp]
+        L.uniql_w4_mlp_workspace_bytes.restype = i64
+        L.uniql_w4_mlp_workspace_bytes.argtypes = [i32]
+        L.uniql_w4_mlp_hidden.restype = C.c_int
+        L.uniql_w4_mlp_hidden.argtypes = [vp, i32, C.POINTER(vp)]
+        L.uniql_w4_mlp_status.restype = C.c_int
+        L.uniql_w4_mlp_status.argtypes = [vp, C.POINTER(C.c_uint32), vp]
         L.uniql_w4_gate_up_stream_probe.restype = C.c_int
         L.uniql_w4_gate_up_stream_probe.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, vp, vp]
         L.uniql_w4_embedding.restype = C.c_int
@@ -384,6 +392,54 @@ def uniql_w4_gate_up_silu(Ws, keeps, x, h=None, stream=None):
         h = torch.empty((kept_dims(Ws[0], keeps[0])[0],), dtype=x.dtype, device=x.device)
     GateUpCall(Ws, keeps, x, h).run(stream)
     return h
+
+
+def mlp_workspace(n_hidden_keep: int, device="cuda"):
+    """Zero-filled workspace for uniql_w4_mlp (uint8 tensor; reusable by calls that do not overlap on the device)."""
+    import torch
+    return torch.zeros(int(lib().uniql_w4_mlp_workspace_bytes(int(n_hidden_keep))), dtype=torch.uint8, device=device)
+
+
+def mlp_hidden(workspace, n_hidden_keep: int, dtype):
+    """View of the hidden vector the last uniql_w4_mlp call left in its workspace (for tests)."""
+    p = C.c_void_p(0)
+    _check(lib().uniql_w4_mlp_hidden(C.c_void_p(workspace.data_ptr()), int(n_hidden_keep), C.byref(p)))
+    off = int(p.value) - workspace.data_ptr()
+    return workspace[off:off + 2 * int(n_hidden_keep)].view(dtype)
+
+
+class MlpCall:
+    """Marshalled arguments of one uniql_w4_mlp call, reusable (e.g. for graph capture)."""
+
+    def __init__(self, Ws, keeps, x, y, workspace):
+        assert len(Ws) == 3 and len(keeps) == 3
+        for t in (x, y):
+            assert t.dtype == Ws[0].ftype and t.is_cuda and t.is_contiguous() and t.dim() == 1
+        assert workspace.is_cuda and workspace.is_contiguous() and workspace.element_size() == 1
+        self.W = (W4 * 3)(*[w.desc() for w in Ws])
+        self.keep = (KeepDesc * 3)(*[(_keep_desc(kp) or KeepDesc()) for kp in keeps])
+        self.x, self.y = C.c_void_p(x.data_ptr()), C.c_void_p(y.data_ptr())
+        self.ws, self.ws_bytes = C.c_void_p(workspace.data_ptr()), int(workspace.numel())
+        self._refs = (Ws, x, y, workspace)
+
+    def run(self, stream=None):
+        _check(lib().uniql_w4_mlp(self.W, self.keep, self.x, self.y, self.ws, self.ws_bytes, _stream_ptr(stream)))
+
+
+def uniql_w4_mlp(Ws, keeps, x, workspace, y=None, stream=None):
+    """y = W_down' (SiLU(W_gate' x) * (W_up' x)) for one token x [k_keep]; Ws = (gate, up, down); returns y."""
+    import torch
+    if y is None:
+        y = torch.empty((kept_dims(Ws[2], keeps[2])[0],), dtype=x.dtype, device=x.device)
+    MlpCall(Ws, keeps, x, y, workspace).run(stream)
+    return y
+
+
+def uniql_w4_mlp_status(workspace, stream=None) -> int:
+    """0 when no call on this workspace gave up waiting for the other blocks, else the serial number of the last that did."""
+    out = C.c_uint32(0)
+    _check(lib().uniql_w4_mlp_status(C.c_void_p(workspace.data_ptr()), C.byref(out), _stream_ptr(stream)))
+    return int(out.value)
 
 
 def uniql_stream_read_probe(src, nbytes: int, out, stream=None):

@@ -405,6 +405,80 @@ extern "C" int uniql_w4_gate_up_silu(const uniql_w4_t* W, const uniql_keep_t* ke
   return fused ? UNIQL_OK : UNIQL_E_SHAPE;   // no scratch to fall back on: the caller runs the two linears itself
 }
 
+// ---- the gated MLP of one token (Eq. 1): gate + up + activation, then down, in one launch when the shapes allow
+// workspace: 256 bytes of control words and 4096 bytes of per-block arrival words (see mlp_stream_kernel.h), then the
+// hidden vector, padded to whole units of eight 16-bit elements
+static const int64_t kMlpHeader = 4352;
+static int64_t mlp_units(int32_t n) { return ((int64_t)n + 7) / 8 * 8; }
+
+extern "C" int64_t uniql_w4_mlp_workspace_bytes(int32_t n_hidden_keep) {
+  if (n_hidden_keep < 1) return 0;
+  return (kMlpHeader + mlp_units(n_hidden_keep) * 2 + 255) / 256 * 256;
+}
+
+static int mlp_run(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_f16, void* y_f16, void* scratch,
+                   int64_t scratch_bytes, hipStream_t stream) {
+  if (!W || !scratch) return UNIQL_E_NULL;
+  if (!aligned(scratch, 256)) return UNIQL_E_ALIGN;
+  LinearArgs a[3];
+  KeepMap km0;
+  int rc = make_keepmap(&W[0], keep ? &keep[0] : nullptr, &km0);
+  if (rc) return rc;
+  if (scratch_bytes < uniql_w4_mlp_workspace_bytes(km0.n_keep)) return UNIQL_E_SHAPE;
+  uint16_t* h = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(scratch) + kMlpHeader);
+  for (int i = 0; i < 2; ++i) {
+    KeepMap km;
+    rc = make_keepmap(&W[i], keep ? &keep[i] : nullptr, &km);
+    if (rc) return rc;
+    rc = fill_linear(&W[i], keep ? &keep[i] : nullptr, x_f16, km.k_keep, h, km.n_keep, 1, &a[i]);
+    if (rc) return rc;
+  }
+  if (a[0].km.n_keep != a[1].km.n_keep || a[0].K_total != a[1].K_total || a[0].km.k_keep != a[1].km.k_keep ||
+      a[0].km.cs_stride != a[1].km.cs_stride || a[0].km.cs_keep != a[1].km.cs_keep) return UNIQL_E_KEEP;
+  {
+    KeepMap km;
+    rc = make_keepmap(&W[2], keep ? &keep[2] : nullptr, &km);
+    if (rc) return rc;
+    if (km.k_keep != a[0].km.n_keep) return UNIQL_E_KEEP;   // down reads exactly the hidden vector gate / up write
+    rc = fill_linear(&W[2], keep ? &keep[2] : nullptr, h, km.k_keep, y_f16, km.n_keep, 1, &a[2]);
+    if (rc) return rc;
+  }
+  if (a[0].bf16 != a[1].bf16 || a[0].bf16 != a[2].bf16) return UNIQL_E_SHAPE;
+  rc = check_arch();
+  if (rc) return rc;
+  bool done = false;
+  hipError_t e = launch_w4_mlp_fused(a, scratch, stream, &done);
+  if (e != hipSuccess) return e == hipErrorInvalidValue ? UNIQL_E_SHAPE : hip_fail(e);
+  if (done) return UNIQL_OK;
+  // shapes the fused launch does not serve: the two launches one after the other, h through the same scratch memory
+  bool fused = false;
+  e = launch_w4_gate_up_silu(a, stream, &fused);
+  if (e != hipSuccess) return e == hipErrorInvalidValue ? UNIQL_E_SHAPE : hip_fail(e);
+  if (!fused) return UNIQL_E_SHAPE;
+  return run_linear(a[2], stream);
+}
+
+extern "C" int uniql_w4_mlp(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_f16, void* y_f16,
+                            void* workspace, int64_t workspace_bytes, void* hip_stream) {
+  return mlp_run(W, keep, x_f16, y_f16, workspace, workspace_bytes, (hipStream_t)hip_stream);
+}
+
+extern "C" int uniql_w4_mlp_hidden(const void* workspace, int32_t n_hidden_keep, const void** h_f16) {
+  if (!workspace || !h_f16) return UNIQL_E_NULL;
+  if (n_hidden_keep < 1) return UNIQL_E_SHAPE;
+  *h_f16 = reinterpret_cast<const char*>(workspace) + kMlpHeader;
+  return UNIQL_OK;
+}
+
+extern "C" int uniql_w4_mlp_status(const void* workspace, uint32_t* gave_up_serial, void* hip_stream) {
+  if (!workspace || !gave_up_serial) return UNIQL_E_NULL;
+  hipStream_t s = (hipStream_t)hip_stream;
+  hipError_t e = hipMemcpyAsync(gave_up_serial, reinterpret_cast<const char*>(workspace) + 8, 4, hipMemcpyDeviceToHost, s);
+  if (e != hipSuccess) return hip_fail(e);
+  e = hipStreamSynchronize(s);
+  return e == hipSuccess ? UNIQL_OK : hip_fail(e);
+}
+
 extern "C" int uniql_w4_gate_up_stream_probe(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_f16, void* h_f16,
                                              void* hip_stream) {
   if (!W) return UNIQL_E_NULL;

@@ -98,6 +98,16 @@ __device__ __forceinline__ uint4 load_u4_unaligned(const half_t* p) {
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// A load that sees what other compute units of the chip have written during the same launch (after the writer's
+// release and this reader's acquire at agent scope): relaxed atomic loads at agent scope, which bypass the caches that
+// are not coherent across the chip's dies.  8-byte aligned address.
+__device__ __forceinline__ uint4 load_u4_coherent(const half_t* p) {
+  const uint64_t* q = reinterpret_cast<const uint64_t*>(p);
+  const uint64_t lo = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const uint64_t hi = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_uint4((uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32));
+}
+
 __device__ __forceinline__ uint32_t load_u32_unaligned(const void* p) {
   typedef uint32_t u32_u1 __attribute__((aligned(1)));
   return *reinterpret_cast<const u32_u1*>(p);
@@ -272,6 +282,10 @@ hipError_t launch_w4_gate_up_stream(const LinearArgs* probs, hipStream_t stream,
 hipError_t launch_w4_gate_up_stream_probe(const LinearArgs* probs, hipStream_t stream, bool* done);
 hipError_t launch_w4_gemv_stream_bf16(const LinearArgs& a, hipStream_t stream, bool* done);
 hipError_t launch_w4_gate_up_stream_bf16(const LinearArgs* probs, hipStream_t stream, bool* done);
+// gate, up, down of one token in one persistent launch (probs[0..2]); the hidden vector (probs[0].y = probs[2].x) lies in
+// `scratch` behind the launch's control and arrival words (see mlp_stream_kernel.h)
+hipError_t launch_w4_mlp_fused(const LinearArgs* probs, void* scratch, hipStream_t stream, bool* done);
+hipError_t launch_w4_mlp_fused_bf16(const LinearArgs* probs, void* scratch, hipStream_t stream, bool* done);
 hipError_t launch_w4_gemm(const LinearArgs& a, hipStream_t stream);
 hipError_t launch_w4_gemm_bf16(const LinearArgs& a, hipStream_t stream);
 hipError_t launch_w4_dequant(const LinearArgs& a, hipStream_t stream);

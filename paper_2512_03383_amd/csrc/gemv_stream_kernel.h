@@ -46,14 +46,27 @@ struct StreamArgs {
   int n_keep, k_keep, K_total;
   int N_total;           // stored rows (extent of the buffer resources)
   KeepMap km;            // row map (rows only; the kept columns are a prefix)
+  // the fused gated MLP only (mlp_stream_kernel.h): a word per block of the grid, in which a block stores the launch's
+  // tag once its outputs have reached memory; the word a walk records a give-up in; the bound of its wait in 100 MHz
+  // ticks
+  uint32_t* arrived;
+  uint32_t* gave_up;
+  unsigned long long wait_ticks;
 };
 
 // PROBE: the kernel's loads alone, folded into one word per row -- the read-stream ceiling of exactly this launch
 // shape (what the arithmetic is measured against), not a linear.
-template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE = false>
-__global__ __launch_bounds__(kStreamThreads) void w4_gemv_stream_kernel(StreamArgs a) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  uint4* xs = reinterpret_cast<uint4*>(smem);   // [NCH][4][64] units of 8 halves
+//
+// The walk is a device function so that a launch may run several of them back to back (the fused gated MLP of
+// mlp_stream_kernel.h runs gate + up, then down).  YTHROUGH: the outputs are written through to memory (stores at
+// agent scope) for a later walk of the same launch.  XWAIT: the activations are such outputs: the walk issues its first
+// tiles, then waits until every block of the grid has stored this launch's tag in a.arrived (for at most a.wait_ticks)
+// and fetches the activations with loads that bypass the caches that are not coherent across the chip's dies; a.x
+// is then 16-byte aligned and padded to whole units of 8.  A block that gives up records the tag in a.gave_up and ends
+// its walk there (every wave still runs to its end).  The function returns false in that case.
+template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE, bool XWAIT = false, bool YTHROUGH = false>
+__device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* LDS, [NCH][4][64] units of 8 halves */,
+                                             int* next_body_p /* LDS */, uint32_t tag = 0) {
   constexpr int TPR = NM * NCH;                                  // tiles per row (pair)
   constexpr int RB = TPR >= 4 ? 1 : 4 / TPR;                     // rows per loop body
   constexpr int D = RB * TPR;                                    // tiles per body = tiles in flight
@@ -71,18 +84,51 @@ __global__ __launch_bounds__(kStreamThreads) void w4_gemv_stream_kernel(StreamAr
   const uint16_t* xbits = reinterpret_cast<const uint16_t*>(a.x);
   uint4 rawv[XI];
   uint32_t tailv[8];
+  auto load_x = [&]() {
 #pragma unroll
-  for (int i = 0; i < XI; ++i) {
-    const int k0 = 8 * (tid + i * kStreamThreads);
-    const int k0c = k0 + 8 <= kv ? k0 : kv - 8;     // the host sends k_keep >= 8 only
-    rawv[i] = load_u4_unaligned(a.x + k0c);
-  }
+    for (int i = 0; i < XI; ++i) {
+      const int k0 = 8 * (tid + i * kStreamThreads);
+      const int k0c = k0 + 8 <= kv ? k0 : kv - 8;     // the host sends k_keep >= 8 only
+      rawv[i] = load_u4_unaligned(a.x + k0c);
+    }
 #pragma unroll
-  for (int j = 0; j < 8; ++j) tailv[j] = 0;
-  if (kv < a.k_keep) {
+    for (int j = 0; j < 8; ++j) tailv[j] = 0;
+    if (kv < a.k_keep) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) tailv[j] = xbits[kv + j < a.k_keep ? kv + j : a.k_keep - 1];
-  }
+      for (int j = 0; j < 8; ++j) tailv[j] = xbits[kv + j < a.k_keep ? kv + j : a.k_keep - 1];
+    }
+  };
+  // XWAIT: wait for every block's arrival word (one wave polls, a load per lane and 64 blocks), then fetch the units
+  auto wait_x = [&](int* verdict /* LDS */) {
+    if (tid < kWave) {
+      const unsigned long long t0 = wall_clock64();
+      bool all = false;
+      for (int polls = 0;; ++polls) {
+        bool mine = true;
+        for (int b = tid; b < (int)gridDim.x; b += kWave)
+          mine = mine && __hip_atomic_load(a.arrived + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == tag;
+        all = __builtin_amdgcn_ballot_w64(mine) == ~0ull;
+        if (all) break;
+        if ((polls & 63) == 63 && wall_clock64() - t0 >= a.wait_ticks) break;   // the wait is bounded
+        __builtin_amdgcn_s_sleep(8);   // about a quarter of a microsecond between polls
+      }
+      if (tid == 0) {
+        *verdict = all ? 1 : 0;
+        if (!all) __hip_atomic_store(a.gave_up, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+    __syncthreads();
+    if (*verdict == 0) return false;
+#pragma unroll
+    for (int i = 0; i < XI; ++i) {
+      const int k0 = 8 * (tid + i * kStreamThreads);
+      rawv[i] = load_u4_coherent(a.x + (k0 < a.k_keep ? k0 : 0));   // the unit with the last kept columns is read whole
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) tailv[j] = 0;
+    return true;
+  };
+  if constexpr (!XWAIT) load_x();
 
   // ---- lane offsets inside a row.  Lanes whose columns lie past the last kept one re-read the row start: their
   // activations are zero, so what they fetch does not matter.
@@ -131,8 +177,7 @@ __global__ __launch_bounds__(kStreamThreads) void w4_gemv_stream_kernel(StreamAr
   // every block finished 2.3 us after the older four), so the faster ones simply take more bodies.
   const int blk8 = (int)blockIdx.x * kStreamWaves;
   auto row_of = [&](int j, int rr) { return (blk8 + (j & 7)) * RB + rr + (j >> 3) * RB * total_waves; };
-  __shared__ int next_body;
-  if (tid == 0) next_body = kStreamWaves;   // visible after the barrier behind the staging
+  int& next_body = *next_body_p;
 
   u32x4_t ring[D];
   RowQn cur[RB][NM], nxt[RB][NM];
@@ -147,6 +192,11 @@ __global__ __launch_bounds__(kStreamThreads) void w4_gemv_stream_kernel(StreamAr
     for (int t = 0; t < TPR; ++t) ring[rr * TPR + t] = load_codes(ro, slot_mat(t), slot_tile(t));
   }
   __builtin_amdgcn_sched_barrier(0);
+  if constexpr (XWAIT) {
+    if (!wait_x(next_body_p)) return false;   // (the body counter is free until it is set below, behind a barrier)
+    __syncthreads();
+  }
+  if (tid == 0) next_body = kStreamWaves;   // visible after the barrier behind the staging
 
   // ---- x registers -> LDS image [tile][word][lane] in the pair order of the unpack, zeros for pruned columns
 #pragma unroll
@@ -159,7 +209,7 @@ __global__ __launch_bounds__(kStreamThreads) void w4_gemv_stream_kernel(StreamAr
     const bool whole = k0 + 8 <= kv, tail = k0 == kv;
     uint32_t e[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) e[j] = whole ? full[j] : ((tail && kv + j < a.k_keep) ? tailv[j] : 0u);
+    for (int j = 0; j < 8; ++j) e[j] = whole ? full[j] : ((tail && kv + j < a.k_keep) ? (XWAIT ? full[j] : tailv[j]) : 0u);
     if (u < NCH * 256)
       xs[unit_slot(u, NCH)] =
           make_uint4(e[0] | (e[4] << 16), e[1] | (e[5] << 16), e[2] | (e[6] << 16), e[3] | (e[7] << 16));
@@ -176,6 +226,12 @@ __global__ __launch_bounds__(kStreamThreads) void w4_gemv_stream_kernel(StreamAr
   }
 
   const Magic mg = make_magic();
+  auto store_y = [&](int rc, half_t v) {
+    if constexpr (YTHROUGH)
+      __hip_atomic_store(reinterpret_cast<uint16_t*>(a.y + rc), __builtin_bit_cast(uint16_t, v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else
+      a.y[rc] = v;
+  };
   const bool on_diag = (lane >> 4) == ((lane & 15) >> 2);
   typedef typename GroupOf<BF16>::type Group;
   auto consume = [&](const u32x4_t& w, const Group& g, const uint4 (&xf)[4], float4_t& acc) {
@@ -238,12 +294,12 @@ __global__ __launch_bounds__(kStreamThreads) void w4_gemv_stream_kernel(StreamAr
       const int rc = row_of(body, rr);
       if constexpr (NM == 1) {
         const float v = diag_sum_to_lane63(acc[rr][0], on_diag);
-        if (lane == 63) a.y[rc] = out16<BF16>(v);
+        if (lane == 63) store_y(rc, out16<BF16>(v));
       } else {
         float g, u;
         diag_sums_to_lane63(acc[rr][0], acc[rr][1], on_diag, g, u);
         // SiLU(g) * u; exp and the reciprocal are the hardware approximations (about 1 ulp of fp32)
-        if (lane == 63) a.y[rc] = out16<BF16>(g * u * __builtin_amdgcn_rcpf(1.0f + __expf(-g)));
+        if (lane == 63) store_y(rc, out16<BF16>(g * u * __builtin_amdgcn_rcpf(1.0f + __expf(-g))));
       }
     }
     if constexpr (RELOAD) {
@@ -271,8 +327,16 @@ __global__ __launch_bounds__(kStreamThreads) void w4_gemv_stream_kernel(StreamAr
     }
     run_body(cur_body, 0, std::false_type{});
   }
+  return true;
 }
 
+
+template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE = false>
+__global__ __launch_bounds__(kStreamThreads) void w4_gemv_stream_kernel(StreamArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ int next_body;
+  stream_phase<NCH, NM, ZP, BF16, SEG, PROBE>(a, reinterpret_cast<uint4*>(smem), &next_body);
+}
 
 template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE>
 static hipError_t stream_launch(const StreamArgs& a, hipStream_t stream) {
@@ -348,6 +412,9 @@ static inline StreamArgs stream_args(const LinearArgs& a) {
   s.K_total = a.K_total;
   s.N_total = a.N_total;
   s.km = a.km;
+  s.arrived = nullptr;
+  s.gave_up = nullptr;
+  s.wait_ticks = 0;
   return s;
 }
 
