@@ -304,6 +304,22 @@ int uniql_w4_mlp(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_f1
 int64_t uniql_w4_mlp_workspace_bytes(int32_t n_hidden_keep);
 
 /*
+ * uniql_w4_mlp for callers that cannot allocate device memory or pass a workspace along: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  The workspace is a static array in device memory that the
+ * library's code object carries (68 KB; every device the library runs on holds its own copy until the process ends),
+ * large enough for uniql_w4_mlp_static_max_hidden() = 32768 kept intermediate channels: a larger n_keep(gate) returns
+ * E_SHAPE and launches nothing.  The call allocates nothing and frees nothing.  Everything else is uniql_w4_mlp: same
+ * arguments, same results bit for bit, same errors.  All calls on one device share that device's array, which keeps
+ * what the last call left in it (the serial number of the persistent launch among it, so nothing needs clearing):
+ * calls that overlap on one device -- two streams, two host threads -- race on it and must be ordered by the caller.
+ */
+int uniql_w4_mlp_static(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_f16, void* y_f16,
+                        void* hip_stream);
+
+/* Largest n_keep(gate) that uniql_w4_mlp_static accepts. */
+int32_t uniql_w4_mlp_static_max_hidden(void);
+
+/*
  * Where the last uniql_w4_mlp call with n_hidden_keep kept intermediate channels left its hidden vector inside
  * `workspace`: *h_f16 receives a device pointer to n_hidden_keep 16-bit elements (valid once that call has finished).
  * Host arithmetic only.  Errors: E_NULL, E_SHAPE.

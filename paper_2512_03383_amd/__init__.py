@@ -84,6 +84,9 @@ def lib():
         L.uniql_w4_gate_up_silu.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, vp, vp]
         L.uniql_w4_mlp.restype = C.c_int
         L.uniql_w4_mlp.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, vp, vp, i64, vp]
+        L.uniql_w4_mlp_static.restype = C.c_int
+        L.uniql_w4_mlp_static.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, vp, vp]
+        L.uniql_w4_mlp_static_max_hidden.restype = i32
         L.uniql_w4_mlp_workspace_bytes.restype = i64
         L.uniql_w4_mlp_workspace_bytes.argtypes = [i32]
         L.uniql_w4_mlp_hidden.restype = C.c_int
@@ -432,6 +435,20 @@ def uniql_w4_mlp(Ws, keeps, x, workspace, y=None, stream=None):
     if y is None:
         y = torch.empty((kept_dims(Ws[2], keeps[2])[0],), dtype=x.dtype, device=x.device)
     MlpCall(Ws, keeps, x, y, workspace).run(stream)
+    return y
+
+
+def uniql_w4_mlp_static(Ws, keeps, x, y=None, stream=None):
+    """uniql_w4_mlp on the library's own static workspace (allocates nothing when y is given)."""
+    import torch
+    assert len(Ws) == 3 and len(keeps) == 3
+    if y is None:
+        y = torch.empty((kept_dims(Ws[2], keeps[2])[0],), dtype=x.dtype, device=x.device)
+    for t in (x, y):
+        assert t.dtype == Ws[0].ftype and t.is_cuda and t.is_contiguous() and t.dim() == 1
+    Wd = (W4 * 3)(*[w.desc() for w in Ws])
+    kd = (KeepDesc * 3)(*[(_keep_desc(kp) or KeepDesc()) for kp in keeps])
+    _check(lib().uniql_w4_mlp_static(Wd, kd, C.c_void_p(x.data_ptr()), C.c_void_p(y.data_ptr()), _stream_ptr(stream)))
     return y
 
 

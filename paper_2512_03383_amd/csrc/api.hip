@@ -463,6 +463,48 @@ extern "C" int uniql_w4_mlp(const uniql_w4_t* W, const uniql_keep_t* keep, const
   return mlp_run(W, keep, x_f16, y_f16, workspace, workspace_bytes, (hipStream_t)hip_stream);
 }
 
+// ---- the same call for callers that cannot allocate: the workspace is a static array in device memory
+static const int32_t kMlpStaticMaxHidden = 32768;                       // kept intermediate channels the array holds
+static const int64_t kMlpStaticBytes = 4352 + 2 * (int64_t)32768;       // = uniql_w4_mlp_workspace_bytes(32768)
+static __device__ __align__(256) unsigned char scratch[kMlpStaticBytes];   // zero until the first launch on the device
+
+// Device address of `scratch` on the current device, looked up once per device ordinal (each device holds its own copy
+// of the array at its own address).  Host code must use this pointer, never the array's name.
+static int scratch_ptr(void** out) {
+  static std::atomic<void*> cached[64];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e);
+  if (dev < 0 || dev >= 64) return UNIQL_E_SHAPE;
+  void* p = cached[dev].load(std::memory_order_acquire);
+  if (!p) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e);
+    if (!p) return UNIQL_E_NULL;
+    cached[dev].store(p, std::memory_order_release);   // (host threads that race on the first call store the same address)
+  }
+  *out = p;
+  return UNIQL_OK;
+}
+
+extern "C" int uniql_w4_mlp_static(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_f16, void* y_f16,
+                                   void* hip_stream) {
+  if (!W) return UNIQL_E_NULL;
+  // the size check comes first and needs no device: a hidden dimension beyond the array is refused, not truncated
+  KeepMap km;
+  int rc = make_keepmap(&W[0], keep ? &keep[0] : nullptr, &km);
+  if (rc) return rc;
+  if (km.n_keep > kMlpStaticMaxHidden) return UNIQL_E_SHAPE;
+  rc = check_arch();
+  if (rc) return rc;
+  void* ws = nullptr;
+  rc = scratch_ptr(&ws);
+  if (rc) return rc;
+  return mlp_run(W, keep, x_f16, y_f16, ws, kMlpStaticBytes, (hipStream_t)hip_stream);
+}
+
+extern "C" int32_t uniql_w4_mlp_static_max_hidden(void) { return kMlpStaticMaxHidden; }
+
 extern "C" int uniql_w4_mlp_hidden(const void* workspace, int32_t n_hidden_keep, const void** h_f16) {
   if (!workspace || !h_f16) return UNIQL_E_NULL;
   if (n_hidden_keep < 1) return UNIQL_E_SHAPE;
