@@ -44,6 +44,9 @@ def lib():
         L.uref_double_to_bf16.argtypes = [dbl]
         L.uref_w4_dequant_fmt.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, i32]
         L.uref_w4_linear_fmt.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, i64, vp, i64, i32, vp, i32, i32]
+        L.uref_w4_linear_il.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, i64, vp, i64, i32, vp, i32, i32, i32]
+        L.uref_w4_dequant_il.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, i32, i32]
+        L.uref_w4_interleave.argtypes = [vp, i32, i32, i32, vp]
         L.uref_w4_embedding_fmt.argtypes = [vp, vp, vp, i32, i32, i32, vp, i32, vp, i32]
         L.uref_pruned_rope_fmt.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, dbl, vp, vp, i32]
         L.uref_set_threads.argtypes = [i32]
@@ -126,8 +129,9 @@ def count_kept(N_total: int, K_total: int, keep) -> tuple:
     return n.value, k.value
 
 
-def w4_dequant(qweight, scales, zeros, keep=None, group: int = 128, fmt: str = "f16") -> np.ndarray:
-    """[n_keep][k_keep] dequantised weights, RN16((q - z) * s), in the format of the scales."""
+def w4_dequant(qweight, scales, zeros, keep=None, group: int = 128, fmt: str = "f16", il_heads: int = 0) -> np.ndarray:
+    """[n_keep][k_keep] dequantised weights, RN16((q - z) * s), in the format of the scales.
+    il_heads > 0: qweight stores its words head-interleaved over that many heads (see uref.c)."""
     N, K8 = qweight.shape
     K = K8 * 8
     ft = _f16_dtype(fmt)
@@ -136,7 +140,7 @@ def w4_dequant(qweight, scales, zeros, keep=None, group: int = 128, fmt: str = "
     ka = _keep_arr(keep)
     nk, kk = count_kept(N, K, ka)
     out = np.empty((nk, kk), dtype=ft)
-    rc = lib().uref_w4_dequant_fmt(_p(qweight), _p(scales), _p(zeros), N, K, group, _p(ka), _p(out), FMTS[fmt])
+    rc = lib().uref_w4_dequant_il(_p(qweight), _p(scales), _p(zeros), N, K, group, _p(ka), _p(out), FMTS[fmt], int(il_heads))
     assert rc == 0
     return out
 
@@ -156,8 +160,9 @@ def w4_embedding(qweight, scales, zeros, ids, group: int = 128, fmt: str = "f16"
 
 
 def w4_linear(qweight, scales, zeros, x, keep=None, group: int = 128,
-              rows: Optional[Sequence[int]] = None, fmt: str = "f16") -> np.ndarray:
-    """fp64 y [M][n_keep] (or [M][len(rows)] for sampled compact rows); scales and x in format fmt."""
+              rows: Optional[Sequence[int]] = None, fmt: str = "f16", il_heads: int = 0) -> np.ndarray:
+    """fp64 y [M][n_keep] (or [M][len(rows)] for sampled compact rows); scales and x in format fmt.
+    il_heads > 0: qweight stores its words head-interleaved over that many heads (see uref.c)."""
     N, K8 = qweight.shape
     K = K8 * 8
     ft = _f16_dtype(fmt)
@@ -170,10 +175,20 @@ def w4_linear(qweight, scales, zeros, x, keep=None, group: int = 128,
     rl = None if rows is None else np.ascontiguousarray(rows, dtype=np.int32)
     n_out = nk if rl is None else rl.size
     y = np.empty((M, n_out), dtype=np.float64)
-    rc = lib().uref_w4_linear_fmt(_p(qweight), _p(scales), _p(zeros), N, K, group, _p(ka),
-                                  _p(x), kk, _p(y), n_out, M, _p(rl), 0 if rl is None else rl.size, FMTS[fmt])
+    rc = lib().uref_w4_linear_il(_p(qweight), _p(scales), _p(zeros), N, K, group, _p(ka),
+                                 _p(x), kk, _p(y), n_out, M, _p(rl), 0 if rl is None else rl.size, FMTS[fmt], int(il_heads))
     assert rc == 0, rc
     return y
+
+
+def w4_interleave(qweight, heads: int) -> np.ndarray:
+    """The words of every row in head-interleaved order over `heads` heads (Sec. 3.4's on-device repack for o_proj)."""
+    _chk(qweight, np.uint32, "qweight")
+    N, K8 = qweight.shape
+    out = np.empty_like(qweight)
+    rc = lib().uref_w4_interleave(_p(qweight), N, K8 * 8, int(heads), _p(out))
+    assert rc == 0, rc
+    return out
 
 
 def pruned_rope(q, k, positions, kept_idx, D_full: int, theta: float, fmt: str = "f16"):

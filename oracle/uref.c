@@ -58,6 +58,13 @@
  *                           : (k % col_seg_stride < col_seg_keep)
  *   n_keep == 0 / k_keep == 0 with stride 0 mean "all".  Kept rows and columns
  *   appear in compact y / x in increasing stored order.
+ *
+ * Head-interleaved words (the *_il functions, il_heads = H > 0): a second storage order of the same matrix, for the
+ *   linear that reads the attention heads (o_proj, Eq. 2; Sec. 3.4 prunes the head dimension of its inputs).  The K_total
+ *   input columns are H heads of D = K_total / H dims; column numbers, the keep rule, groups, scales and zero points all
+ *   refer to this head-major matrix (column c = h * D + d).  Only where a code is STORED differs: the 32-bit words of a
+ *   row are kept dim-block-major, word (d / 8) * H + h holding dims 8 (d / 8) .. + 7 of head h, so the code of column c is
+ *   nibble d % 8 of that word.  il_heads = 0 is the plain order above.  uref_w4_interleave converts.
  */
 #include <math.h>
 #include <stdint.h>
@@ -190,10 +197,17 @@ int uref_count_kept(int N_total, int K_total, const int32_t* keep, int32_t* n_ou
   return 0;
 }
 
+/* word of a row that stores column k */
+static int word_of_col(int K_total, int il_heads, int k) {
+  if (il_heads <= 0) return k / 8;
+  int D = K_total / il_heads, h = k / D, d = k % D;
+  return (d / 8) * il_heads + h;
+}
+
 /* one dequantised weight as 16-bit float bits of format fmt: RN16((q - z) * s) */
 static uint16_t dequant_one(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
-                            int K_total, int group, int r, int k, int fmt) {
-  uint32_t word = qweight[(size_t)r * (K_total / 8) + k / 8];
+                            int K_total, int group, int r, int k, int fmt, int il_heads) {
+  uint32_t word = qweight[(size_t)r * (K_total / 8) + word_of_col(K_total, il_heads, k)];
   int q = (int)((word >> (4 * (k % 8))) & 15u);
   size_t g = (size_t)r * (K_total / group) + k / group;
   int z = zeros ? zeros[g] : 8;   /* no zero points: the symmetric codes of Eq. 3, stored as signed code + 8 */
@@ -202,8 +216,9 @@ static uint16_t dequant_one(const uint32_t* qweight, const uint16_t* scales, con
 }
 
 /* w_f16: [n_keep][k_keep] compact, 16-bit float bits */
-int uref_w4_dequant_fmt(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
-                        int N_total, int K_total, int group, const int32_t* keep, uint16_t* w_f16, int fmt) {
+int uref_w4_dequant_il(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
+                       int N_total, int K_total, int group, const int32_t* keep, uint16_t* w_f16, int fmt, int il_heads) {
+  if (il_heads < 0 || (il_heads > 0 && (K_total % il_heads || (K_total / il_heads) % 8))) return -3;
   static const int32_t none[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   if (!keep) keep = none;
   int32_t* rows = (int32_t*)malloc(sizeof(int32_t) * (size_t)N_total);
@@ -213,9 +228,14 @@ int uref_w4_dequant_fmt(const uint32_t* qweight, const uint16_t* scales, const u
 #pragma omp parallel for num_threads(g_threads) schedule(static)
   for (int i = 0; i < nk; ++i)
     for (int j = 0; j < kk; ++j)
-      w_f16[(size_t)i * kk + j] = dequant_one(qweight, scales, zeros, K_total, group, rows[i], cols[j], fmt);
+      w_f16[(size_t)i * kk + j] = dequant_one(qweight, scales, zeros, K_total, group, rows[i], cols[j], fmt, il_heads);
   free(rows); free(cols);
   return 0;
+}
+
+int uref_w4_dequant_fmt(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
+                        int N_total, int K_total, int group, const int32_t* keep, uint16_t* w_f16, int fmt) {
+  return uref_w4_dequant_il(qweight, scales, zeros, N_total, K_total, group, keep, w_f16, fmt, 0);
 }
 
 int uref_w4_dequant(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
@@ -230,7 +250,7 @@ int uref_w4_embedding_fmt(const uint32_t* qweight, const uint16_t* scales, const
   for (int i = 0; i < n; ++i) {
     if (ids[i] < 0 || ids[i] >= N_total) return -3;
     for (int k = 0; k < K_total; ++k)
-      out[(size_t)i * K_total + k] = dequant_one(qweight, scales, zeros, K_total, group, ids[i], k, fmt);
+      out[(size_t)i * K_total + k] = dequant_one(qweight, scales, zeros, K_total, group, ids[i], k, fmt, 0);
   }
   return 0;
 }
@@ -244,10 +264,11 @@ int uref_w4_embedding(const uint32_t* qweight, const uint16_t* scales, const uin
  * x: fp16 bits [M][ldx] compact columns; y: fp64 [M][ldy] compact rows.
  * If row_list != NULL only the compact rows row_list[0..n_list) are computed,
  * and written to y[m][i] (i = position in the list) -- used to sample large cases. */
-int uref_w4_linear_fmt(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
-                       int N_total, int K_total, int group, const int32_t* keep,
-                       const uint16_t* x, int64_t ldx, double* y, int64_t ldy, int M,
-                       const int32_t* row_list, int n_list, int fmt) {
+int uref_w4_linear_il(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
+                      int N_total, int K_total, int group, const int32_t* keep,
+                      const uint16_t* x, int64_t ldx, double* y, int64_t ldy, int M,
+                      const int32_t* row_list, int n_list, int fmt, int il_heads) {
+  if (il_heads < 0 || (il_heads > 0 && (K_total % il_heads || (K_total / il_heads) % 8))) return -3;
   static const int32_t none[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   if (!keep) keep = none;
   int32_t* rows = (int32_t*)malloc(sizeof(int32_t) * (size_t)N_total);
@@ -256,7 +277,7 @@ int uref_w4_linear_fmt(const uint32_t* qweight, const uint16_t* scales, const ui
   int nk = kept_rows(keep, N_total, rows), kk = kept_cols(keep, K_total, cols);
   int n_out = row_list ? n_list : nk;
   int bad = 0;
-#pragma omp parallel for num_threads(g_threads) schedule(static)
+#pragma omp parallel for num_threads(g_threads) schedule(static) reduction(| : bad)
   for (int i = 0; i < n_out; ++i) {
     int rc = row_list ? row_list[i] : i;
     if (rc < 0 || rc >= nk) { bad = 1; continue; }
@@ -264,7 +285,7 @@ int uref_w4_linear_fmt(const uint32_t* qweight, const uint16_t* scales, const ui
     for (int m = 0; m < M; ++m) {
       double acc = 0.0;
       for (int j = 0; j < kk; ++j) {
-        double w = f16_to_double(dequant_one(qweight, scales, zeros, K_total, group, r, cols[j], fmt), fmt);
+        double w = f16_to_double(dequant_one(qweight, scales, zeros, K_total, group, r, cols[j], fmt, il_heads), fmt);
         acc += f16_to_double(x[(size_t)m * ldx + j], fmt) * w;
       }
       y[(size_t)m * ldy + i] = acc;
@@ -272,6 +293,26 @@ int uref_w4_linear_fmt(const uint32_t* qweight, const uint16_t* scales, const ui
   }
   free(rows); free(cols);
   return bad ? -2 : 0;
+}
+
+int uref_w4_linear_fmt(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
+                       int N_total, int K_total, int group, const int32_t* keep,
+                       const uint16_t* x, int64_t ldx, double* y, int64_t ldy, int M,
+                       const int32_t* row_list, int n_list, int fmt) {
+  return uref_w4_linear_il(qweight, scales, zeros, N_total, K_total, group, keep, x, ldx, y, ldy, M,
+                           row_list, n_list, fmt, 0);
+}
+
+/* The words of every row in head-interleaved order: out[r][(d / 8) * heads + h] = qweight[r][h * (D / 8) + d / 8],
+ * D = K_total / heads.  A permutation of words; scales and zero points are not touched. */
+int uref_w4_interleave(const uint32_t* qweight, int N_total, int K_total, int heads, uint32_t* out) {
+  if (heads < 1 || K_total % heads || (K_total / heads) % 8) return -3;
+  int wpr = K_total / 8, wph = wpr / heads;
+  for (int r = 0; r < N_total; ++r)
+    for (int h = 0; h < heads; ++h)
+      for (int b = 0; b < wph; ++b)
+        out[(size_t)r * wpr + (size_t)b * heads + h] = qweight[(size_t)r * wpr + (size_t)h * wph + b];
+  return 0;
 }
 
 int uref_w4_linear(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
