@@ -85,6 +85,12 @@ class Layer:
                 self.lin[s.name] = uq.QuantLinear(qw, sc, None if symmetric else zr)
 
 
+def interleave_o_proj(uq, layer, heads):
+    """One-time re-layout of a layer's o_proj (uniql_w4_interleave): the words of every row head-interleaved, so that
+    head-dimension pruning truncates the row.  The head-major copy stays for the comparison row."""
+    layer.lin["o_proj_il"] = uq.uniql_w4_interleave(layer.lin["o_proj"], heads)
+
+
 class DecodeStep:
     """Buffers shared by all layers plus the launch sequence of one step."""
 
@@ -163,6 +169,8 @@ class DecodeStep:
                                                self.xin["gate_proj"][0], self.yout["down_proj"][0], self.mlp_work)
         return self._calls[key]
 
+    o_name = "o_proj_il"      # which copy of o_proj the step uses ("o_proj": head-major, as the ABI stores it by default)
+
     def run(self, layer, only=None, fused=True, fuse_rope=True, fuse_mlp=True):
         """One step: q/k/v with the rotation of the fresh Q/K heads (one launch; fuse_rope=False: one
         launch for q/k/v, one for the rotation), o_proj, gate/up (one launch), down.
@@ -180,8 +188,8 @@ class DecodeStep:
             elif isinstance(only, tuple):
                 self.multi_call(layer, only).run()
             else:
-                s = next(s for s in self.specs if s.name == only)
-                uq.uniql_w4_linear(layer.lin[s.name], s.keep, self.xin[s.name], self.yout[s.name])
+                s = next(s for s in self.specs if s.name == only.replace("_il", ""))
+                uq.uniql_w4_linear(layer.lin[only], s.keep, self.xin[s.name], self.yout[s.name])
             return
         if not fused:
             for s in self.specs:
@@ -195,7 +203,7 @@ class DecodeStep:
         else:
             self.multi_call(layer, self.FUSED[0]).run()
             self.rope_qk()
-        uq.uniql_w4_linear(layer.lin["o_proj"], sp["o_proj"].keep, self.xin["o_proj"], self.yout["o_proj"])
+        uq.uniql_w4_linear(layer.lin[self.o_name], sp["o_proj"].keep, self.xin["o_proj"], self.yout["o_proj"])
         if self.M == 1 and fuse_mlp:
             self.mlp_call(layer).run()         # the whole gated MLP (Eq. 1) in one launch
             return
@@ -381,6 +389,9 @@ def main():
     ap.add_argument("--fused-mlp", action="store_true",
                     help="run the gated MLP (gate+up+SiLU, then down) as its one persistent launch (uniql_w4_mlp) instead of "
                          "two launches; the two take the same time on the device, the step is reported on the two launches")
+    ap.add_argument("--o-head-major", action="store_true",
+                    help="run o_proj on the head-major words the ABI stores by default (the pruned dims of every head are then "
+                         "fetched with the 32-byte sectors they share with kept ones) instead of the head-interleaved re-layout")
     ap.add_argument("--pmc-calib", action="store_true",
                     help="also launch a plain 256 MiB elementwise copy four times: the kernel of known size that "
                          "scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -412,7 +423,11 @@ def main():
     specs = wl.llama3_8b_layer(rate)
     rope = wl.llama3_8b_rope(rate, T=M)
     layers = [Layer(torch, uq, specs, rope, i, rate, symmetric=args.symmetric) for i in range(args.layers)]
+    for L in layers:
+        interleave_o_proj(uq, L, rope.Hq)
     step = DecodeStep(torch, uq, specs, rope, M)
+    if args.o_head_major:
+        step.o_name = "o_proj"
     nl = len(layers)
     # without zero points a touched group costs its 2-byte scale only
     lin_bytes = {s.name: s.algorithmic_bytes(M) - (s.n_keep * s.groups_touched() // 2 if args.symmetric else 0) for s in specs}
@@ -469,7 +484,7 @@ def main():
     # on the launch stream around a graph that issues that one launch back to back over the whole layer pool
     # (cold weights every launch, no host launch cost inside the bracket)
     first = "qkv_rope" if fuse_rope else DecodeStep.FUSED[0]
-    names = [first, "o_proj", "gate_up_silu", "down_proj", "mlp", "gate_up_probe"]
+    names = [first, "o_proj_il", "o_proj", "gate_up_silu", "down_proj", "mlp", "gate_up_probe"]
     lin_bytes = dict(lin_bytes)
     for grp in DecodeStep.FUSED:
         lin_bytes[grp] = sum(lin_bytes[n] for n in grp)
@@ -477,6 +492,7 @@ def main():
     # gate + up with the activation as epilogue writes one hidden vector instead of two
     lin_bytes["gate_up_silu"] = lin_bytes[DecodeStep.FUSED[1]] - 2 * next(s for s in specs if s.name == "gate_proj").n_keep
     lin_bytes["gate_up_probe"] = lin_bytes["gate_up_silu"]
+    lin_bytes["o_proj_il"] = lin_bytes["o_proj"]
     lin_bytes["mlp"] = lin_bytes["gate_up_silu"] + lin_bytes["down_proj"]
     if FMT == "bf16" or args.symmetric:
         names.remove("gate_up_probe")        # the probe exists for fp16 matrices with zero points
@@ -504,6 +520,7 @@ def main():
         warm_us[n] = time_events(torch, lambda i: gw.replay(), 8) * 1e3 / nl
     assert uq.uniql_w4_mlp_status(step.mlp_work) == 0, "a fused MLP launch gave up waiting for its blocks"
     label = {"qkv_rope": "q_proj+k_proj+v_proj+rope", "gate_up_silu": "gate_proj+up_proj+silu",
+             "o_proj_il": "o_proj (head-interleaved words)", "o_proj": "o_proj (head-major words)",
              "mlp": "gate_proj+up_proj+silu+down_proj (one launch)",
              "gate_up_probe": "loads of gate_proj+up_proj+silu without its arithmetic (persistent read probe)"}
     per_linear = {}
@@ -516,7 +533,7 @@ def main():
         per_linear["+".join(n) if isinstance(n, tuple) else label.get(n, n)] = v
     for n, v in per_linear.items():
         log(f"  {n:28s} {v}")
-    in_step = [first, "o_proj"] + (["mlp"] if fuse_mlp else ["gate_up_silu", "down_proj"])
+    in_step = [first, step.o_name] + (["mlp"] if fuse_mlp else ["gate_up_silu", "down_proj"])
     sum_us = sum(iso_us[n] for n in in_step)
 
     # the dominant kernel of the step: the launch that serves the gated MLP (or, with --separate-mlp, gate + up)
@@ -557,7 +574,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": FMT,
         "data": "synthetic",
         "config": {"workload": f"Llama-3-8B shaped decode layer, batch 1, int4 group-128 weights{' without zero points (symmetric)' if args.symmetric else ''}{', bfloat16 activations' if FMT == 'bf16' else ''}, "
-                               f"pruning {rate}% (q+k+v{' with the pruned RoPE as epilogue' if fuse_rope else ', pruned RoPE'}, o, "
+                               f"pruning {rate}% (q+k+v{' with the pruned RoPE as epilogue' if fuse_rope else ', pruned RoPE'}, "
+                               f"o{' on head-interleaved words (one-time re-layout, pruning still a run-time argument)' if step.o_name == 'o_proj_il' else ''}, "
                                f"{'the gated MLP gate+up+SiLU(gate)*up+down as one persistent launch' if fuse_mlp else 'gate+up with SiLU(gate)*up as epilogue, down'}: "
                                f"W4A16 GEMV launches), {args.layers}-layer weight pool streamed from HBM",
                    "prune_pct": rate, "M": M,

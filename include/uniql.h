@@ -64,6 +64,19 @@ enum {
  * the bfloat16 nearest (ties to even) to (q - z) * s, sums are still fp32 and rounded once.
  * Matrices that share a call (multi, qkv_rope, gate_up_silu) must share the format, except in
  * uniql_w4_linear_multi, which then runs them one by one.
+ *
+ * col_interleave = H > 0 is a second storage order of the SAME matrix, for the linear that reads the attention heads
+ * (o_proj, Eq. 2; Sec. 3.4 prunes the head dimension D_hd of its inputs and leaves D_h): the K_total inputs are H heads
+ * of D = K_total / H dims, and the 32-bit words of a row are stored dim-block-major, word (d / 8) * H + h holding the
+ * dims 8 (d / 8) .. 8 (d / 8) + 7 of head h (nibble j = dim 8 (d / 8) + j), instead of head-major (word h * D / 8 + d / 8).
+ * Nothing else changes: input column numbers, the keep rule, groups, scales and zero points all refer to the
+ * head-major matrix (column h * D + d, group (h * D + d) / 128), x and y are what they are for that matrix.  What it buys:
+ * keeping the leading D' dims of every head (column segments of stride D) keeps the leading ceil(D' / 8) * H words of
+ * every row, so the pruned codes are not fetched at all, where the head-major order fetches them with the 32-byte
+ * sectors they share with kept ones.  uniql_w4_interleave converts (a permutation of words, exact).  Served so far:
+ * uniql_w4_linear with M = 1 for H a multiple of 4 that divides 256, D = 128, unpruned rows, and either no column
+ * pruning or column segments of stride 128; uniql_w4_dequant for any H; every other call returns E_SHAPE for such a
+ * matrix.
  */
 enum { UNIQL_F16 = 0, UNIQL_BF16 = 1 };
 
@@ -73,6 +86,7 @@ typedef struct uniql_w4 {
   const uint8_t* zeros;    /* device, or NULL (symmetric) */
   int32_t N_total, K_total, group;
   int32_t dtype;           /* UNIQL_F16 or UNIQL_BF16; anything else: E_SHAPE */
+  int32_t col_interleave;  /* 0: words in column order; H > 0: head-interleaved over H heads (see above) */
 } uniql_w4_t;
 
 /*
@@ -274,6 +288,17 @@ int uniql_w4_gate_up_silu(const uniql_w4_t* W, const uniql_keep_t* keep, const v
  * benchmark reports beside the GEMV.  Errors: E_NULL, E_SHAPE, E_ALIGN, E_ARCH, E_HIP.
  */
 int uniql_stream_read_probe(const void* src, int64_t bytes, void* out_words, void* hip_stream);
+
+/*
+ * The words of a matrix in head-interleaved order (uniql_w4_t.col_interleave = heads): out_qweight[r][(d / 8) * heads + h]
+ * = W->qweight[r][h * (K_total / heads / 8) + d / 8] for every stored row r.  A permutation of 32-bit words, exact; the
+ * scales and zero points are shared with W as they are (they are indexed by the head-major column either way).  The
+ * on-device step of Sec. 3.4 (unpack, drop the pruned channels, pack again) for the one linear whose pruned channels
+ * cannot be dropped in place: after it, head-dimension pruning of o_proj is a truncation of every row.
+ * W must not be interleaved itself; K_total / heads must be a multiple of 8; out_qweight: device, 16-byte aligned,
+ * [N_total][K_total / 8], must not overlap W->qweight.  Errors: E_NULL, E_SHAPE, E_ALIGN, E_ARCH, E_HIP.
+ */
+int uniql_w4_interleave(const uniql_w4_t* W, int32_t heads, uint32_t* out_qweight, void* hip_stream);
 
 /*
  * The gated MLP of one token (Eq. 1): y = W_down' (SiLU(W_gate' x) * (W_up' x)), W[0] = gate, W[1] = up, W[2] = down,

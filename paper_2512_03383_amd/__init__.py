@@ -29,7 +29,8 @@ class UniqlError(RuntimeError):
 class W4(C.Structure):
     """uniql_w4_t"""
     _fields_ = [("qweight", C.c_void_p), ("scales", C.c_void_p), ("zeros", C.c_void_p),
-                ("N_total", C.c_int32), ("K_total", C.c_int32), ("group", C.c_int32), ("dtype", C.c_int32)]
+                ("N_total", C.c_int32), ("K_total", C.c_int32), ("group", C.c_int32), ("dtype", C.c_int32),
+                ("col_interleave", C.c_int32)]
 
 
 UNIQL_F16, UNIQL_BF16 = 0, 1
@@ -82,6 +83,8 @@ def lib():
                                         i32, i32, i32, i32, i32, C.c_double, vp]
         L.uniql_w4_gate_up_silu.restype = C.c_int
         L.uniql_w4_gate_up_silu.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, vp, vp]
+        L.uniql_w4_interleave.restype = C.c_int
+        L.uniql_w4_interleave.argtypes = [C.POINTER(W4), i32, vp, vp]
         L.uniql_w4_mlp.restype = C.c_int
         L.uniql_w4_mlp.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, vp, vp, i64, vp]
         L.uniql_w4_mlp_static.restype = C.c_int
@@ -144,6 +147,7 @@ class QuantLinear:
     qweight: "torch.Tensor"   # int32 [N][K/8] (bit pattern of the uint32 words)
     scales: "torch.Tensor"    # float16 or bfloat16 [N][K/128]: the format of activations and outputs too
     zeros: "Optional[torch.Tensor]"     # uint8 [N][K/128], or None: symmetric scheme, every zero point 8
+    col_interleave: int = 0   # > 0: the words of a row are stored head-interleaved over this many heads
 
     @property
     def N(self) -> int:
@@ -164,7 +168,7 @@ class QuantLinear:
         import torch
         return W4(self.qweight.data_ptr(), self.scales.data_ptr(),
                   self.zeros.data_ptr() if self.zeros is not None else None, self.N, self.K, 128,
-                  UNIQL_BF16 if self.ftype == torch.bfloat16 else UNIQL_F16)
+                  UNIQL_BF16 if self.ftype == torch.bfloat16 else UNIQL_F16, int(self.col_interleave))
 
     @staticmethod
     def from_numpy(w: dict, device="cuda") -> "QuantLinear":
@@ -395,6 +399,14 @@ def uniql_w4_gate_up_silu(Ws, keeps, x, h=None, stream=None):
         h = torch.empty((kept_dims(Ws[0], keeps[0])[0],), dtype=x.dtype, device=x.device)
     GateUpCall(Ws, keeps, x, h).run(stream)
     return h
+
+
+def uniql_w4_interleave(W: QuantLinear, heads: int, stream=None) -> QuantLinear:
+    """The same matrix with the words of every row in head-interleaved order (shares scales and zero points with W)."""
+    import torch
+    out = torch.empty_like(W.qweight)
+    _check(lib().uniql_w4_interleave(C.byref(W.desc()), int(heads), C.c_void_p(out.data_ptr()), _stream_ptr(stream)))
+    return QuantLinear(out, W.scales, W.zeros, int(heads))
 
 
 def mlp_workspace(n_hidden_keep: int, device="cuda"):

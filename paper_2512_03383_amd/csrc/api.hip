@@ -42,6 +42,8 @@ static int make_keepmap(const uniql_w4_t* W, const uniql_keep_t* keep, KeepMap* 
   if (!W || !W->qweight || !W->scales) return UNIQL_E_NULL;   // zeros may be NULL: every zero point is 8
   if (W->group != kGroup || W->N_total < 1 || W->K_total < kGroup || W->K_total % kGroup) return UNIQL_E_SHAPE;
   if (W->dtype != UNIQL_F16 && W->dtype != UNIQL_BF16) return UNIQL_E_SHAPE;
+  if (W->col_interleave < 0 || (W->col_interleave > 0 && (W->K_total % W->col_interleave || (W->K_total / W->col_interleave) % 8)))
+    return UNIQL_E_SHAPE;
   if (!aligned(W->qweight, 16) || !aligned(W->scales, 2)) return UNIQL_E_ALIGN;
   uniql_keep_t none;
   memset(&none, 0, sizeof(none));
@@ -112,10 +114,12 @@ static int fill_linear(const uniql_w4_t* W, const uniql_keep_t* keep, const void
   a->K_total = W->K_total;
   a->M = M;
   a->bf16 = W->dtype == UNIQL_BF16;
+  a->il_heads = W->col_interleave;
   return UNIQL_OK;
 }
 
 static int run_linear(const LinearArgs& a, hipStream_t s) {
+  if (a.il_heads > 0 && a.M != 1) return UNIQL_E_SHAPE;   // head-interleaved words: one token only
   hipError_t e = (a.M == 1) ? launch_w4_gemv(a, s) : launch_w4_gemm(a, s);
   if (e == hipErrorInvalidValue && a.M == 1) return UNIQL_E_SHAPE;   // K too long for the GEMV's staging
   return e == hipSuccess ? UNIQL_OK : hip_fail(e);
@@ -140,6 +144,7 @@ extern "C" int uniql_w4_linear_multi(int32_t n, const uniql_w4_t* W, const uniql
   for (int i = 0; i < n; ++i) {
     int rc = fill_linear(&W[i], keep ? &keep[i] : nullptr, x_f16[i], ldx[i], y_f16[i], ldy[i], M, &a[i]);
     if (rc) return rc;
+    if (a[i].il_heads > 0 && n > 1) return UNIQL_E_SHAPE;   // a head-interleaved matrix does not share a launch
   }
   int rc = check_arch();
   if (rc) return rc;
@@ -175,6 +180,7 @@ extern "C" int uniql_w4_dequant(const uniql_w4_t* W, const uniql_keep_t* keep, v
   a.K_total = W->K_total;
   a.M = 0;
   a.bf16 = W->dtype == UNIQL_BF16;
+  a.il_heads = W->col_interleave;
   hipError_t e = launch_w4_dequant(a, (hipStream_t)hip_stream);
   return e == hipSuccess ? UNIQL_OK : hip_fail(e);
 }
@@ -187,6 +193,7 @@ struct RepackPlan {
 static int make_repack_plan(const uniql_w4_t* W, const uniql_keep_t* keep, KeepMap* km, RepackPlan* p) {
   int rc = make_keepmap(W, keep, km);
   if (rc) return rc;
+  if (W->col_interleave > 0) return UNIQL_E_SHAPE;
   memset(p, 0, sizeof(*p));
   p->N_out = km->n_keep;
   const int K = W->K_total;
@@ -264,7 +271,7 @@ extern "C" int uniql_w4_embedding(const uniql_w4_t* W, const int32_t* ids, int32
   int rc = make_keepmap(W, nullptr, &km);
   if (rc) return rc;
   if (!ids || !out_f16) return UNIQL_E_NULL;
-  if (n < 1 || ld < W->K_total) return UNIQL_E_SHAPE;
+  if (n < 1 || ld < W->K_total || W->col_interleave > 0) return UNIQL_E_SHAPE;
   // every lane writes 64-byte pieces with 128-bit stores
   if (!aligned(ids, 4) || !aligned(out_f16, 16) || ld % 8) return UNIQL_E_ALIGN;
   rc = check_arch();
@@ -347,6 +354,7 @@ extern "C" int uniql_w4_qkv_rope(const uniql_w4_t* W, const uniql_keep_t* keep, 
     rc = fill_linear(&W[i], keep ? &keep[i] : nullptr, x_f16, km.k_keep, y[i], km.n_keep, 1, &a[i]);
     if (rc) return rc;
     if (km.k_keep != a[0].km.k_keep) return UNIQL_E_SHAPE;   // one x for all three
+    if (a[i].il_heads > 0) return UNIQL_E_SHAPE;
     if (a[i].bf16 != a[0].bf16) return UNIQL_E_SHAPE;        // ... in one format
   }
   // q and k come out as [heads][D_keep]
@@ -392,6 +400,7 @@ extern "C" int uniql_w4_gate_up_silu(const uniql_w4_t* W, const uniql_keep_t* ke
     // both members write their sums to LDS only; h takes the place of y in the descriptor of either
     rc = fill_linear(&W[i], keep ? &keep[i] : nullptr, x_f16, km.k_keep, h_f16, km.n_keep, 1, &a[i]);
     if (rc) return rc;
+    if (a[i].il_heads > 0) return UNIQL_E_SHAPE;
   }
   // one x and one h: the same kept rows in number, the same rule for the kept columns
   if (a[0].km.n_keep != a[1].km.n_keep || a[0].K_total != a[1].K_total || a[0].km.k_keep != a[1].km.k_keep ||
@@ -403,6 +412,19 @@ extern "C" int uniql_w4_gate_up_silu(const uniql_w4_t* W, const uniql_keep_t* ke
   hipError_t e = launch_w4_gate_up_silu(a, (hipStream_t)hip_stream, &fused);
   if (e != hipSuccess) return e == hipErrorInvalidValue ? UNIQL_E_SHAPE : hip_fail(e);
   return fused ? UNIQL_OK : UNIQL_E_SHAPE;   // no scratch to fall back on: the caller runs the two linears itself
+}
+
+extern "C" int uniql_w4_interleave(const uniql_w4_t* W, int32_t heads, uint32_t* out_qweight, void* hip_stream) {
+  KeepMap km;
+  int rc = make_keepmap(W, nullptr, &km);
+  if (rc) return rc;
+  if (!out_qweight) return UNIQL_E_NULL;
+  if (W->col_interleave != 0 || heads < 1 || W->K_total % heads || (W->K_total / heads) % 8) return UNIQL_E_SHAPE;
+  if (!aligned(out_qweight, 16)) return UNIQL_E_ALIGN;
+  rc = check_arch();
+  if (rc) return rc;
+  hipError_t e = launch_w4_interleave(W->qweight, out_qweight, W->N_total, W->K_total, heads, (hipStream_t)hip_stream);
+  return e == hipSuccess ? UNIQL_OK : hip_fail(e);
 }
 
 // ---- the gated MLP of one token (Eq. 1): gate + up + activation, then down, in one launch when the shapes allow
@@ -444,6 +466,7 @@ static int mlp_run(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_
     if (rc) return rc;
   }
   if (a[0].bf16 != a[1].bf16 || a[0].bf16 != a[2].bf16) return UNIQL_E_SHAPE;
+  if (a[0].il_heads > 0 || a[1].il_heads > 0 || a[2].il_heads > 0) return UNIQL_E_SHAPE;
   rc = check_arch();
   if (rc) return rc;
   bool done = false;
@@ -565,4 +588,4 @@ extern "C" const char* uniql_strerror(int code) {
 
 extern "C" int uniql_last_hip_error(void) { return g_last_hip_error; }
 
-extern "C" int uniql_version(void) { return 100; }
+extern "C" int uniql_version(void) { return 200; }

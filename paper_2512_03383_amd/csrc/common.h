@@ -46,6 +46,7 @@ struct LinearArgs {
   long long ldx, ldy;
   int N_total, K_total, M;
   int bf16;           // scales, x and y are bfloat16 (the weights are then rounded to bfloat16 as well)
+  int il_heads;       // > 0: the row's words are stored head-interleaved over this many heads (uniql_w4_t.col_interleave)
   KeepMap km;
 };
 
@@ -305,6 +306,8 @@ struct RepackArgs {
   KeepMap km;             // rows only
 };
 hipError_t launch_w4_repack(const RepackArgs& a, hipStream_t stream);
+// the words of every row from [heads][words per head] to [words per head][heads]
+hipError_t launch_w4_interleave(const uint32_t* qweight, uint32_t* out, int N_total, int K_total, int heads, hipStream_t stream);
 
 struct RopeArgs {
   half_t* q;

@@ -52,6 +52,9 @@ struct StreamArgs {
   uint32_t* arrived;
   uint32_t* gave_up;
   unsigned long long wait_ticks;
+  // head-interleaved words (HI): the row's words are stored as [dims / 8][heads], il_heads heads of 128 dims, of which
+  // the leading d_keep are kept; x is compact [heads][d_keep]
+  int il_heads, d_keep;
 };
 
 // PROBE: the kernel's loads alone, folded into one word per row -- the read-stream ceiling of exactly this launch
@@ -64,7 +67,14 @@ struct StreamArgs {
 // and fetches the activations with loads that bypass the caches that are not coherent across the chip's dies; a.x
 // is then 16-byte aligned and padded to whole units of 8.  A block that gives up records the tag in a.gave_up and ends
 // its walk there (every wave still runs to its end).  The function returns false in that case.
-template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE, bool XWAIT = false, bool YTHROUGH = false>
+//
+// HI: the matrix stores its words head-interleaved (uniql_w4_t.col_interleave: word (d / 8) * H + h holds dims
+// 8 (d / 8) .. + 7 of head h; a head is one quantisation group of 128 dims), so that pruning the trailing dims of
+// every head -- o_proj's per-head column segments -- leaves a PREFIX of the row's words: the pruned bytes are never
+// fetched.  Tiles are contiguous kilobytes here: lane l of every tile holds the four words of heads 4l % H .. + 3 at
+// dims 8 ((256 c + 4 l) / H) .., so the lane's four scales and zero points are adjacent, the same for all tiles of a
+// row (H divides 256), and every word has its own group constants, formed once per row.
+template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE, bool XWAIT = false, bool YTHROUGH = false, bool HI = false>
 __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* LDS, [NCH][4][64] units of 8 halves */,
                                              int* next_body_p /* LDS */, uint32_t tag = 0) {
   constexpr int TPR = NM * NCH;                                  // tiles per row (pair)
@@ -84,7 +94,25 @@ __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* L
   const uint16_t* xbits = reinterpret_cast<const uint16_t*>(a.x);
   uint4 rawv[XI];
   uint32_t tailv[8];
+  uint32_t elv[HI ? XI : 1][8];   // HI: the kept dims of a unit that is only partly kept, one per register
   auto load_x = [&]() {
+    if constexpr (HI) {
+#pragma unroll
+      for (int i = 0; i < XI; ++i) {
+        const int u = tid + i * kStreamThreads;           // word of the row: head u % H, dims 8 (u / H) ..
+        const int dblk = u / a.il_heads, head = u - dblk * a.il_heads;
+        const int nk = a.d_keep - 8 * dblk;               // kept dims of the unit, counted from its first
+        const int base = head * a.d_keep + 8 * dblk;
+        rawv[i] = load_u4_unaligned(a.x + (nk >= 8 ? base : 0));
+#pragma unroll
+        for (int j = 0; j < 8; ++j) elv[i][j] = 0;
+        if (nk > 0 && nk < 8) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) elv[i][j] = j < nk ? (uint32_t)xbits[base + j] : 0u;
+        }
+      }
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < XI; ++i) {
       const int k0 = 8 * (tid + i * kStreamThreads);
@@ -136,13 +164,18 @@ __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* L
   uint32_t woff[NCH];
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
-    const int kb = tile_k0(lane, c, NCH);
-    woff[c] = kb < k_span32 ? (uint32_t)kb >> 1 : 0u;
+    if constexpr (HI) {
+      const int w0 = c * 256 + 4 * lane;   // the lane's first word; its four words are of one block of 8 dims
+      woff[c] = w0 < ((a.d_keep + 7) >> 3) * a.il_heads ? (uint32_t)w0 * 4u : 0u;
+    } else {
+      const int kb = tile_k0(lane, c, NCH);
+      woff[c] = kb < k_span32 ? (uint32_t)kb >> 1 : 0u;
+    }
   }
   // first group of the lane (a quad past the row's groups reads the row start).  A quad may own groups past the row's
   // last one when 16 NCH exceeds the groups of a row: their columns are pruned by definition, what is read for them
   // (the next row's values; nothing past the arrays, which the resources bound) is multiplied by zero.
-  const int goff = quad * NCH < groups_per_row ? quad * NCH : 0;
+  const int goff = HI ? (4 * lane) % a.il_heads : (quad * NCH < groups_per_row ? quad * NCH : 0);
   // Buffer resources over the arrays: an address is resource + scalar row offset + 32-bit lane offset.
   constexpr int kRsrcWord3 = 0x00020000;   // raw 32-bit data format of this target's buffer resource
   __amdgpu_buffer_rsrc_t rq[NM], rs[NM], rz[NM];
@@ -158,10 +191,11 @@ __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* L
     const int sr = SEG ? stored_row(a.km, rc) : rc;   // SEG = false: the kept rows are a prefix
     return RowOff{sr * words_per_row * 4, sr * groups_per_row};
   };
-  typedef RowQ<NCH> RowQn;   // a lane's scales (fp16 bits) and zero points (bytes) of one row
+  constexpr int NGQ = HI ? 4 : NCH;   // groups of a lane per row
+  typedef RowQ<NGQ> RowQn;   // a lane's scales (fp16 bits) and zero points (bytes) of one row
   auto load_rowq = [&](const RowOff& ro, int m, RowQn& r) {
-    load_bytes<2 * NCH>(rs[m], 2 * goff, 2 * ro.g, r.s);
-    if constexpr (ZP) load_bytes<NCH>(rz[m], goff, ro.g, r.z);
+    load_bytes<2 * NGQ>(rs[m], 2 * goff, 2 * ro.g, r.s);
+    if constexpr (ZP) load_bytes<NGQ>(rz[m], goff, ro.g, r.z);
   };
   auto load_codes = [&](const RowOff& ro, int m, int c) {
     return __builtin_amdgcn_raw_buffer_load_b128(rq[m], (int)woff[c], ro.q, 0);
@@ -208,10 +242,16 @@ __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* L
                               r.z & 0xffffu, r.z >> 16, r.w & 0xffffu, r.w >> 16};
     const bool whole = k0 + 8 <= kv, tail = k0 == kv;
     uint32_t e[8];
+    if constexpr (HI) {
+      const int nk = a.d_keep - 8 * (u / a.il_heads);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) e[j] = whole ? full[j] : ((tail && kv + j < a.k_keep) ? (XWAIT ? full[j] : tailv[j]) : 0u);
+      for (int j = 0; j < 8; ++j) e[j] = nk >= 8 ? full[j] : elv[i][j];   // (elv is zero where nothing is kept)
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) e[j] = whole ? full[j] : ((tail && kv + j < a.k_keep) ? (XWAIT ? full[j] : tailv[j]) : 0u);
+    }
     if (u < NCH * 256)
-      xs[unit_slot(u, NCH)] =
+      xs[HI ? ((u >> 8) * 4 + (u & 3)) * 64 + ((u >> 2) & 63) : unit_slot(u, NCH)] =
           make_uint4(e[0] | (e[4] << 16), e[1] | (e[5] << 16), e[2] | (e[6] << 16), e[3] | (e[7] << 16));
   }
   __builtin_amdgcn_sched_barrier(0);
@@ -234,8 +274,9 @@ __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* L
   };
   const bool on_diag = (lane >> 4) == ((lane & 15) >> 2);
   typedef typename GroupOf<BF16>::type Group;
-  auto consume = [&](const u32x4_t& w, const Group& g, const uint4 (&xf)[4], float4_t& acc) {
+  auto consume = [&](const u32x4_t& w, const Group (&gq)[HI ? 4 : 1], const uint4 (&xf)[4], float4_t& acc) {
     const uint32_t wv[4] = {w.x, w.y, w.z, w.w};
+    const Group& g = gq[0];
     if constexpr (PROBE) {
       uint32_t fold = w.x ^ w.y ^ w.z ^ w.w;
       if constexpr (BF16) fold ^= __builtin_bit_cast(uint32_t, g.s) ^ __builtin_bit_cast(uint32_t, g.nzs);
@@ -244,7 +285,7 @@ __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* L
       return;
     }
 #pragma unroll
-    for (int q = 0; q < 4; ++q) acc = mfma_16x16x32<BF16>(xf[q], dequant_word4<BF16>(wv[q], g, mg), acc);
+    for (int q = 0; q < 4; ++q) acc = mfma_16x16x32<BF16>(xf[q], dequant_word4<BF16>(wv[q], gq[HI ? q : 0], mg), acc);
   };
 
   float4_t acc[RB][NM];
@@ -280,7 +321,13 @@ __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* L
         // loaded registers there would wait for every load in flight).
         const int ps = (s + D - 1) % D;   // the tile consumed just before this one (compile-time after unrolling)
         asm volatile("" : "+v"(ring[s]), "+v"(acc[ps / TPR][ps % NM]));
-        const Group g = group_of<ZP, BF16, NCH>(cur[rr][m], c);
+        Group g[HI ? 4 : 1];
+        if constexpr (HI) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) g[q] = group_of<ZP, BF16, 4>(cur[rr][m], q);   // (the same for every tile of the row)
+        } else {
+          g[0] = group_of<ZP, BF16, NCH>(cur[rr][m], c);
+        }
         if constexpr (XREG) {
           consume(ring[s], g, xr[c], acc[rr][m]);
         } else {
@@ -331,16 +378,16 @@ __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* L
 }
 
 
-template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE = false>
+template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE = false, bool HI = false>
 __global__ __launch_bounds__(kStreamThreads) void w4_gemv_stream_kernel(StreamArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int next_body;
-  stream_phase<NCH, NM, ZP, BF16, SEG, PROBE>(a, reinterpret_cast<uint4*>(smem), &next_body);
+  stream_phase<NCH, NM, ZP, BF16, SEG, PROBE, false, false, HI>(a, reinterpret_cast<uint4*>(smem), &next_body);
 }
 
-template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE>
+template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE, bool HI = false>
 static hipError_t stream_launch(const StreamArgs& a, hipStream_t stream) {
-  auto kern = w4_gemv_stream_kernel<NCH, NM, ZP, BF16, SEG, PROBE>;
+  auto kern = w4_gemv_stream_kernel<NCH, NM, ZP, BF16, SEG, PROBE, HI>;
   const size_t smem = (size_t)NCH * 4096;
   // CU count per device ordinal, read once (host threads that race on the first call all store the same value)
   static std::atomic<int> cached[64];
@@ -397,7 +444,7 @@ static inline bool stream_shape(const LinearArgs& a, int max_tiles) {
   const int nch = row_tiles(km.k_keep);
   // row offsets inside the buffer resources are signed 32-bit byte counts
   const bool fits = (long long)a.N_total * (a.K_total / 2) < (1ll << 31);
-  return a.M == 1 && km.cs_stride == 0 && km.k_keep >= 8 && nch <= max_tiles && fits && whole_quads(a.K_total, nch);
+  return a.M == 1 && a.il_heads == 0 && km.cs_stride == 0 && km.k_keep >= 8 && nch <= max_tiles && fits && whole_quads(a.K_total, nch);
 }
 
 static inline StreamArgs stream_args(const LinearArgs& a) {
@@ -415,12 +462,40 @@ static inline StreamArgs stream_args(const LinearArgs& a) {
   s.arrived = nullptr;
   s.gave_up = nullptr;
   s.wait_ticks = 0;
+  s.il_heads = a.il_heads;
+  s.d_keep = a.km.cs_stride ? a.km.cs_keep : kGroup;
   return s;
+}
+
+// A matrix with head-interleaved words (one token): every shape this layout is defined for runs here, there is no
+// other kernel for it.  hipErrorInvalidValue for the rest: more than four kilobytes of kept words per row, a head
+// count that does not divide 256 or is not a multiple of four, heads of another width than a group, pruned rows,
+// kept columns that are not the leading dims of every head.
+template <bool BF16>
+static hipError_t stream_interleaved(const LinearArgs& a, hipStream_t stream) {
+  const int H = a.il_heads;
+  const bool cols_ok = a.km.cs_stride == 0 ? a.km.k_keep == a.K_total : a.km.cs_stride == kGroup;
+  const bool fits = (long long)a.N_total * (a.K_total / 2) < (1ll << 31);
+  if (a.M != 1 || H < 4 || H % 4 || 256 % H || a.K_total != H * kGroup || a.km.rs_stride != 0 || !cols_ok || !fits)
+    return hipErrorInvalidValue;
+  const StreamArgs s = stream_args(a);
+  const int nch = (((s.d_keep + 7) >> 3) * H + 255) / 256;
+  switch (nch) {
+    case 1: return a.zeros ? stream_launch<1, 1, true, BF16, false, false, true>(s, stream) : stream_launch<1, 1, false, BF16, false, false, true>(s, stream);
+    case 2: return a.zeros ? stream_launch<2, 1, true, BF16, false, false, true>(s, stream) : stream_launch<2, 1, false, BF16, false, false, true>(s, stream);
+    case 3: return a.zeros ? stream_launch<3, 1, true, BF16, false, false, true>(s, stream) : stream_launch<3, 1, false, BF16, false, false, true>(s, stream);
+    case 4: return a.zeros ? stream_launch<4, 1, true, BF16, false, false, true>(s, stream) : stream_launch<4, 1, false, BF16, false, false, true>(s, stream);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 // One linear: *done = false (nothing launched) when the shape is not one this kernel serves.
 template <bool BF16>
 static hipError_t stream_one(const LinearArgs& a, hipStream_t stream, bool* done) {
+  if (a.il_heads > 0) {
+    *done = true;
+    return stream_interleaved<BF16>(a, stream);
+  }
   const int nch = row_tiles(a.km.k_keep);
   // (segmented row rules, one division per row, only from the higher threshold: q_proj sized launches measured slower)
   const int min_rows = a.km.rs_stride != 0 ? kStreamMinRows : (nch <= 4 ? kStreamMinRowsShort : kStreamMinRowsLong);

@@ -20,7 +20,13 @@ __global__ __launch_bounds__(256) void w4_dequant_kernel(LinearArgs a) {
     const int rc = (int)(i / words_span);
     const int w = (int)(i - (long long)rc * words_span);
     const size_t row = (size_t)stored_row(km, rc);
-    const uint32_t word = a.qweight[row * words_per_row + w];
+    // w counts words in column order; a head-interleaved row stores word (h, d / 8) at (d / 8) * H + h
+    int ws = w;
+    if (a.il_heads > 0) {
+      const int wph = words_per_row / a.il_heads, h = w / wph;
+      ws = (w - h * wph) * a.il_heads + h;
+    }
+    const uint32_t word = a.qweight[row * words_per_row + ws];
     const size_t g = row * groups_per_row + (w >> 4);
     const float s = in16<BF16>(__builtin_bit_cast(half_t, a.scales[g]));
     const int z = a.zeros ? a.zeros[g] : 8;   // no zero points: the symmetric scheme
@@ -118,6 +124,28 @@ __global__ __launch_bounds__(256) void w4_repack_kernel(RepackArgs a) {
       if (a.zeros) a.out_zeros[(size_t)rc * groups_out + go] = a.zeros[row * groups_src + g];
     }
   }
+}
+
+// Words of every row from head-major [heads][words per head] to [words per head][heads].  A thread moves one word;
+// consecutive threads write consecutive words (the reads stride by a head: the pass runs once per matrix).
+__global__ __launch_bounds__(256) void w4_interleave_kernel(const uint32_t* __restrict__ qweight, uint32_t* __restrict__ out,
+                                                            long long total, int words_per_row, int heads) {
+  const int wph = words_per_row / heads;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+    const long long row = i / words_per_row;
+    const int wo = (int)(i - row * words_per_row);    // output word: (d / 8) * heads + h
+    const int db = wo / heads, h = wo - db * heads;
+    out[i] = qweight[row * words_per_row + h * wph + db];
+  }
+}
+
+hipError_t launch_w4_interleave(const uint32_t* qweight, uint32_t* out, int N_total, int K_total, int heads, hipStream_t stream) {
+  const long long total = (long long)N_total * (K_total >> 3);
+  long long blocks = (total + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(w4_interleave_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, qweight, out, total, K_total >> 3, heads);
+  return hipGetLastError();
 }
 
 hipError_t launch_w4_repack(const RepackArgs& a, hipStream_t stream) {

@@ -27,8 +27,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_layout_matches_header():
-    assert C.sizeof(W4) == 3 * 8 + 4 * 4          # three pointers, four int32
-    assert W4.dtype.offset == 36
+    assert C.sizeof(W4) == 3 * 8 + 5 * 4 + 4      # three pointers, five int32, padding to the pointers' alignment
+    assert W4.dtype.offset == 36 and W4.col_interleave.offset == 40
     assert C.sizeof(KeepDesc) == 10 * 4
     assert W4.N_total.offset == 24 and W4.group.offset == 32
     assert KeepDesc.col_seg_keep.offset == 24 and KeepDesc.row_seg2_limit.offset == 36

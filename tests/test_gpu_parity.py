@@ -662,6 +662,64 @@ def test_gate_up_silu_refuses_what_it_cannot_fuse(env, uref):
     assert linear_err(h.cpu().numpy().reshape(1, -1), ref) <= TOL
 
 
+# ------------------------------------------------- head-interleaved words (o_proj: pruned head dims are never fetched)
+@pytest.mark.parametrize("N,heads,d_keep,sym", [
+    (4096, 32, 108, False),      # Llama-3-8B o_proj at 15 %
+    (4096, 32, 82, False),       # ... at 35 %: 11 blocks of 8 dims, the last one partly kept
+    (4096, 32, 128, True),       # unpruned, no zero points
+    (300, 4, 54, False),         # few rows, a quarter tile of words
+    (1000, 64, 96, False),       # K = 8192: three tiles
+    (77, 8, 1, False),           # one dim per head
+    (2050, 16, 127, True),
+])
+def test_head_interleaved_o_proj(env, uref, N, heads, d_keep, sym):
+    """uniql_w4_interleave bit for bit against the oracle's permutation; the dequantised kept sub-matrix of the
+    interleaved matrix bit for bit against the oracle (and equal to the plain matrix's); the one-token linear on it,
+    every row, against the oracle on the same interleaved words."""
+    uq, torch = env
+    rng = wl.rng_for(19, N + heads + d_keep)
+    K = heads * 128
+    w = wl.gen_linear(rng, N, K)
+    if sym:
+        w["zeros"] = None
+    keep = Keep() if d_keep == 128 else Keep(col_seg_stride=128, col_seg_keep=d_keep)
+    qw = uq.QuantLinear.from_numpy(w)
+    qi = uq.uniql_w4_interleave(qw, heads)
+    torch.cuda.synchronize()
+    words = qi.qweight.cpu().numpy().view(np.uint32)
+    assert np.array_equal(words, uref.w4_interleave(w["qweight"], heads))
+    d_gpu = uq.uniql_w4_dequant(qi, keep).cpu().numpy()
+    d_ref = uref.w4_dequant(words, w["scales"], w["zeros"], keep, il_heads=heads)
+    assert np.array_equal(d_gpu.view(np.uint16), d_ref.view(np.uint16))
+    assert np.array_equal(d_gpu.view(np.uint16), uq.uniql_w4_dequant(qw, keep).cpu().numpy().view(np.uint16))
+    x = wl.gen_activations(rng, 1, heads * d_keep)
+    y = uq.uniql_w4_linear(qi, keep, to_dev(torch, x)).cpu().numpy()
+    ref = uref.w4_linear(words, w["scales"], w["zeros"], x, keep, il_heads=heads)
+    assert y.shape == ref.shape and linear_err(y, ref) <= TOL
+    assert normwise_err(y, ref) <= NORM_TOL
+    y2 = uq.uniql_w4_linear(qi, keep, to_dev(torch, x)).cpu().numpy()
+    assert np.array_equal(y.view(np.uint16), y2.view(np.uint16))
+
+
+def test_head_interleaved_refusals(env):
+    uq, torch = env
+    rng = wl.rng_for(19, 1)
+    qw = uq.QuantLinear.from_numpy(wl.gen_linear(rng, 64, 1024))
+    qi = uq.uniql_w4_interleave(qw, 8)
+    x2 = torch.zeros((2, 1024), dtype=torch.float16, device="cuda")
+    with pytest.raises(uq.UniqlError):       # one token only
+        uq.uniql_w4_linear(qi, None, x2)
+    with pytest.raises(uq.UniqlError):       # kept columns must be the leading dims of every head
+        uq.uniql_w4_linear(qi, Keep(k_keep=512), x2[:1, :512].contiguous())
+    with pytest.raises(uq.UniqlError):       # an interleaved matrix is not interleaved again
+        uq.uniql_w4_interleave(qi, 8)
+    with pytest.raises(uq.UniqlError):       # 1024 columns are not 7 heads
+        uq.uniql_w4_interleave(qw, 7)
+    with pytest.raises(uq.UniqlError):       # 12 heads do not divide 256
+        uq.uniql_w4_linear(uq.uniql_w4_interleave(uq.QuantLinear.from_numpy(wl.gen_linear(rng, 8, 1536)), 12), None,
+                           torch.zeros((1, 1536), dtype=torch.float16, device="cuda"))
+
+
 # ------------------------------------------------- the whole gated MLP of one token (Eq. 1)
 def _mlp_specs(layer):
     sp = {s.name: s for s in layer}
