@@ -1012,6 +1012,10 @@ def test_decode_batches_on_tall_matrices(env, uref, N, K, keep, M, sym):
     wl.RopeSpec(T=128, Hq=2, Hkv=2, H_tab=1, D_full=32, D_keep=4, theta=1.0e4, pos_max=100),         # one word per half head
     wl.RopeSpec(T=96, Hq=3, Hkv=1, H_tab=1, D_full=64, D_keep=44, theta=1.0e4, pos_max=100),         # token rows not a multiple of 16 bytes
     wl.RopeSpec(T=70, Hq=4, Hkv=4, H_tab=4, D_full=64, D_keep=54, theta=1.0e4, pos_max=100),         # odd pair count: 2-byte accesses
+    wl.RopeSpec(T=41, Hq=18, Hkv=6, H_tab=2, D_full=256, D_keep=256, theta=1.0e4, pos_max=4096),     # a row fills a wave; 9 Q and 3 K heads per table row: several chunks of head steps
+    wl.RopeSpec(T=33, Hq=14, Hkv=6, H_tab=2, D_full=128, D_keep=40, theta=1.0e6, pos_max=70000),     # six rows per wave step, the last step of Q and of K partly filled
+    wl.RopeSpec(T=32, Hq=5, Hkv=5, H_tab=5, D_full=128, D_keep=124, theta=5.0e5, pos_max=8192),      # 31 units per row: odd half row, two rows per step, one head per table row
+    wl.RopeSpec(T=31, Hq=32, Hkv=8, H_tab=8, D_full=128, D_keep=108, theta=5.0e5, pos_max=8192),     # one token below the whole-row kernel's threshold
 ])
 def test_rope_prompt_sized_calls(env, uref, spec):
     uq, torch = env
