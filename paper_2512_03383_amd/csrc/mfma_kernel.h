@@ -18,6 +18,7 @@
 #pragma once
 #define UNIQL_ANDOR_PLAIN   // and-or as plain C here: the scheduler must be able to classify it as VALU
 #include "common.h"
+#include "smallm_kernel.h"
 #include <type_traits>
 
 namespace uniql {
@@ -345,9 +346,14 @@ static hipError_t launch_cfg(const LinearArgs& a, hipStream_t stream) {
 
 template <int XVEC, bool BF16>
 static hipError_t launch_m(const LinearArgs& a, hipStream_t stream) {
-  // Decode batches (M <= 32) are bound by the weight stream: 16 rows per wave and the K range
-  // split over the block's 8 waves, four ways when there are many row tiles, eight ways otherwise.
+  // Decode batches (M <= 32) are bound by the weight stream and have a kernel of their own (smallm_kernel.h), except
+  // tall matrices at more than 8 tokens: there this kernel's slab, staged once for 64 rows, costs less than every wave
+  // staging its own activations (14336-row gate at 16 / 32 tokens, weights from HBM: 12.3 / 15.3 us here, 14.1 / 19.5 us
+  // there; 3584-row down: 16.4 / 27.3 us here, 15.9 / 21.6 us there; up to 8 tokens the other kernel wins or ties
+  // everywhere).  What that kernel does not take falls through to this one: 16 rows per wave and the K range split over
+  // the block's 8 waves, four ways when there are many row tiles, eight ways otherwise.
   const int row_tiles = (a.km.n_keep + 15) / 16;
+  if (smallm_serves(a) && (a.M <= 8 || row_tiles < 600)) return smallm_dispatch<XVEC, BF16>(a, stream);
   // (many row tiles: 32 rows per wave, so that an activation fragment read from LDS serves two weight fragments,
   // 64 rows per block; few: 16 rows per block, two groups per wave and slab, which halves the number of barriers)
   if (a.M <= 16) return row_tiles >= 600 ? launch_cfg<BF16, 1, 2, 2, 4, 1, 2, XVEC>(a, stream) : launch_cfg<BF16, 1, 1, 1, 8, 2, 1, XVEC>(a, stream);

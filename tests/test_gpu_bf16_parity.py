@@ -140,7 +140,7 @@ def test_embedding_gather_bit_exact(env, uref, N, K, n, pad):
 
 
 # ------------------------------------------------------------------- linear
-@pytest.mark.parametrize("M", [1, 2, 5, 8, 16, 33, 64, 100])
+@pytest.mark.parametrize("M", [1, 2, 5, 8, 16, 17, 32, 33, 64, 100])
 @pytest.mark.parametrize("keep", KEEPS)
 def test_linear_parity_1024(env, uref, keep, M):
     uq, torch = env

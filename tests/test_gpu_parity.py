@@ -122,7 +122,7 @@ def test_small_case_config0(env, uref):
     assert linear_err(y, ref) <= TOL
 
 
-@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 8, 16, 33, 64, 100])
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 8, 16, 17, 32, 33, 64, 100])
 @pytest.mark.parametrize("keep", KEEPS)
 def test_linear_parity_1024(env, uref, keep, M):
     uq, torch = env
@@ -136,6 +136,33 @@ def test_linear_parity_1024(env, uref, keep, M):
     assert linear_err(y, ref) <= TOL
     if nk >= 64:      # the norm-wise figure needs enough outputs to average over
         assert normwise_err(y, ref) <= NORM_TOL
+
+
+@pytest.mark.parametrize("sym", [False, True])
+@pytest.mark.parametrize("M", [2, 7, 12, 20, 32])
+@pytest.mark.parametrize("N,K,keep", [
+    (999, 1152, Keep()),                               # 9 groups and an odd number of rows: the arrays end in the middle of a 32-bit word
+    (1000, 1408, Keep(n_keep=777, k_keep=1283)),       # 11 groups, the last kept group short, tail columns
+    (333, 2944, Keep(k_keep=2817)),                    # 23 groups over eight waves: three groups per wave, the last wave short
+    (4000, 1024, Keep()),                              # exactly 8 groups, K not split
+    (2500, 3200, Keep(k_keep=25 * 100, col_seg_stride=128, col_seg_keep=100)),    # column segments, 25 groups
+    (640, 1920, Keep(k_keep=15 * 77, col_seg_stride=128, col_seg_keep=77)),       # an odd number of kept columns per segment
+    (515, 896, Keep()),                                # 7 groups: fewer than the decode-batch kernel takes
+    (9700, 1024, Keep(n_keep=9650)),                   # more than 600 row tiles: above 8 tokens the slab kernel
+])
+def test_decode_batch_shapes(env, uref, N, K, keep, M, sym):
+    """2 .. 32 tokens on shapes that put the ends of the arrays, of the rows and of the K split in every position
+    (every row against the oracle: the last stored row reads the arrays' last bytes)."""
+    uq, torch = env
+    rng = wl.rng_for(21, N + K + M)
+    w = wl.gen_linear(rng, N, K, sym_zero=sym)
+    qw = uq.QuantLinear.from_numpy(w) if not sym else uq.QuantLinear.from_numpy({"qweight": w["qweight"], "scales": w["scales"], "zeros": None})
+    nk, kk = uq.kept_dims(qw, keep)
+    x = wl.gen_activations(rng, M, kk)
+    ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], x, keep)
+    y = run_linear(uq, torch, w, qw, keep, x, pad=5 if M in (7, 20) else 0)
+    assert linear_err(y, ref) <= TOL
+    assert normwise_err(y, ref) <= NORM_TOL
 
 
 @pytest.mark.parametrize("N,K,keep", [
