@@ -1,8 +1,10 @@
 """ctypes access to the CPU oracle (oracle/uref.c).
 
 TEST INFRASTRUCTURE ONLY: imported by tests/, the smoke check and the
-benchmark's cpu_baseline leg; never by the product package.  Argument
-marshalling only -- all arithmetic is in uref.c.
+benchmark's cpu_baseline leg; never by the product package.  The arithmetic of
+the single operations is in uref.c; two functions here compose them, in fp64:
+qkv_rope (three linears, then the rotation of Sec. 3.4 on their fp64 outputs)
+and gate_up_silu (two linears, then Eq. 1's SiLU(g) * u in numpy).
 """
 from __future__ import annotations
 

@@ -371,7 +371,11 @@ extern "C" int uniql_w4_qkv_rope(const uniql_w4_t* W, const uniql_keep_t* keep, 
   rf.heads[0] = Hq;
   rf.heads[1] = Hkv;
   bool fused = false;
-  hipError_t e = launch_w4_qkv_rope(a, rf, s, &fused);
+  // the persistent walk for the sizes it serves, else the block kernel with the rotation as epilogue
+  hipError_t e = launch_w4_qkv_rope_stream(a, rf, s, &fused);
+  if (e != hipSuccess) return e == hipErrorInvalidValue ? UNIQL_E_SHAPE : hip_fail(e);
+  if (fused) return UNIQL_OK;
+  e = launch_w4_qkv_rope(a, rf, s, &fused);
   if (e != hipSuccess) return e == hipErrorInvalidValue ? UNIQL_E_SHAPE : hip_fail(e);
   if (fused) return UNIQL_OK;
   // shapes that cannot share one launch: the three projections, then the stand-alone rotation

@@ -282,6 +282,10 @@ hipError_t launch_w4_gemv_stream(const LinearArgs& a, hipStream_t stream, bool* 
 hipError_t launch_w4_gate_up_stream(const LinearArgs* probs, hipStream_t stream, bool* done);
 hipError_t launch_w4_gate_up_stream_probe(const LinearArgs* probs, hipStream_t stream, bool* done);
 hipError_t launch_w4_gemv_stream_bf16(const LinearArgs& a, hipStream_t stream, bool* done);
+// q, k, v of one token with the rotation of q and k as one walk of the streaming kernel; *done = false (nothing
+// launched) when the shapes are not ones it serves
+hipError_t launch_w4_qkv_rope_stream(const LinearArgs* probs, const RopeFuse& rf, hipStream_t stream, bool* done);
+hipError_t launch_w4_qkv_rope_stream_bf16(const LinearArgs* probs, const RopeFuse& rf, hipStream_t stream, bool* done);
 hipError_t launch_w4_gate_up_stream_bf16(const LinearArgs* probs, hipStream_t stream, bool* done);
 // gate, up, down of one token in one persistent launch (probs[0..2]); the hidden vector (probs[0].y = probs[2].x) lies in
 // `scratch` behind the launch's control and arrival words (see mlp_stream_kernel.h)

@@ -213,7 +213,8 @@ __device__ __forceinline__ ColMap make_colmap(const KeepMap& km) {
 // an epilogue.  Their blocks own four kept pairs instead of eight consecutive rows: waves 0..3 compute
 // the first-half rows of the pairs, waves 4..7 the second-half rows, the two fp32 sums of a pair meet
 // in LDS and are rotated before the one rounding to fp16.  The pair's sin / cos are formed while the
-// weight stream is in flight, with the arithmetic of the stand-alone RoPE kernel.
+// weight stream is in flight: the angle in fp64 and in revolutions like the stand-alone RoPE kernel's, but
+// theta^(-2j/D) as base^j by binary powering (a dozen fp64 multiplies) where that kernel calls exp2.
 // EPI = 2: the launch holds exactly two problems, gate and up of a gated MLP (Eq. 1), over the same x.
 // Waves 0..3 of a block compute R gate rows each, waves 4..7 the up rows of the same indices; the
 // sums meet in LDS and h = SiLU(gate) * up is written to the first problem's y.

@@ -25,4 +25,9 @@ hipError_t launch_w4_gate_up_stream_probe(const LinearArgs* probs, hipStream_t s
   return gemv::stream_gate_up<false, true>(probs, stream, done);
 }
 
+// q, k, v of one token with the rotation of q and k on the walk; *done = false (nothing launched) for other shapes
+hipError_t launch_w4_qkv_rope_stream(const LinearArgs* probs, const RopeFuse& rf, hipStream_t stream, bool* done) {
+  return probs[0].bf16 ? launch_w4_qkv_rope_stream_bf16(probs, rf, stream, done) : gemv::stream_qkv_rope<false>(probs, rf, stream, done);
+}
+
 }  // namespace uniql

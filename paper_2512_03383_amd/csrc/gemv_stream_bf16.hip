@@ -11,4 +11,8 @@ hipError_t launch_w4_gate_up_stream_bf16(const LinearArgs* probs, hipStream_t st
   return gemv::stream_gate_up<true>(probs, stream, done);
 }
 
+hipError_t launch_w4_qkv_rope_stream_bf16(const LinearArgs* probs, const RopeFuse& rf, hipStream_t stream, bool* done) {
+  return gemv::stream_qkv_rope<true>(probs, rf, stream, done);
+}
+
 }  // namespace uniql

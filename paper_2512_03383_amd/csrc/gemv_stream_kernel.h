@@ -38,9 +38,9 @@ constexpr int kStreamThreads = 512;
 constexpr int kStreamWaves = kStreamThreads / kWave;
 
 struct StreamArgs {
-  const uint32_t* qweight[2];
-  const uint16_t* scales[2];
-  const uint8_t* zeros[2];
+  const uint32_t* qweight[3];
+  const uint16_t* scales[3];
+  const uint8_t* zeros[3];
   const half_t* x;
   half_t* y;
   int n_keep, k_keep, K_total;
@@ -55,6 +55,24 @@ struct StreamArgs {
   // head-interleaved words (HI): the row's words are stored as [dims / 8][heads], il_heads heads of 128 dims, of which
   // the leading d_keep are kept; x is compact [heads][d_keep]
   int il_heads, d_keep;
+  // q, k, v of one token with the rotation of q and k (QKV): three matrices over one x, outputs y3[].  A body is one
+  // pair of rows (p, p + hk) of a head, hk = D_keep / 2; bodies [0, pair_end[0]) are q's, [pair_end[0], pair_end[1])
+  // k's, the rest v's (pairs of a head's rows like the others, not rotated); n_keep = 2 * all pairs.  Head h of matrix
+  // i starts at stored row h * head_stride[i] and row p + hk of the head lies pair_off[i] stored rows behind row p;
+  // n_total3[i] = the matrix's stored rows.  hk_magic = ceil(2^32 / hk).
+  // The row of the kept-index table that head h of q or k uses: h / (heads per table row), by hpt_magic[].
+  half_t* y3[3];
+  int pair_end[2];
+  int hk;
+  unsigned long long hk_magic;
+  int head_stride[3];
+  int pair_off[3];   // stored rows between the two rows of a pair
+  int n_total3[3];
+  unsigned long long hpt_magic[2];   // ceil(2^32 / heads per table row) of q and k
+  const int32_t* positions;
+  const int32_t* kept_idx;
+  int H_tab;
+  double base;   // theta^(-2 / D_full): inv_freq_j = base^j
 };
 
 // PROBE: the kernel's loads alone, folded into one word per row -- the read-stream ceiling of exactly this launch
@@ -74,11 +92,19 @@ struct StreamArgs {
 // fetched.  Tiles are contiguous kilobytes here: lane l of every tile holds the four words of heads 4l % H .. + 3 at
 // dims 8 ((256 c + 4 l) / H) .., so the lane's four scales and zero points are adjacent, the same for all tiles of a
 // row (H divides 256), and every word has its own group constants, formed once per row.
-template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE, bool XWAIT = false, bool YTHROUGH = false, bool HI = false>
+//
+// QKV: three matrices of equal row length over one x (a.qweight[0..2]), q and k rotated (Sec. 3.4 fused rotary
+// embedding of the pruned head dimension).  A body is the pair of rows (p, p + D_keep / 2) of one head, so both halves
+// of a rotation pair end up in the same wave: lane 63 rotates them with the sin / cos of the pair, which the block
+// puts into LDS once ([table row][pair], then one identity entry for v), and writes both outputs.  The loads of a
+// body go through the resources of that body's matrix; they are switched when a wave's next body lies in another
+// matrix (bodies are handed out in rising order, so at most twice per wave).
+template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE, bool XWAIT = false, bool YTHROUGH = false, bool HI = false, bool QKV = false>
 __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* LDS, [NCH][4][64] units of 8 halves */,
                                              int* next_body_p /* LDS */, uint32_t tag = 0) {
   constexpr int TPR = NM * NCH;                                  // tiles per row (pair)
-  constexpr int RB = TPR >= 4 ? 1 : 4 / TPR;                     // rows per loop body
+  constexpr int RB = QKV ? 2 : (TPR >= 4 ? 1 : 4 / TPR);         // rows per loop body
+  static_assert(!QKV || (NM == 1 && !SEG && !PROBE && !XWAIT && !YTHROUGH && !HI), "the fused q / k / v walk is a mode of its own");
   constexpr int D = RB * TPR;                                    // tiles per body = tiles in flight
   constexpr bool XREG = NCH <= 2;                                // activations live in registers
 
@@ -157,6 +183,12 @@ __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* L
     return true;
   };
   if constexpr (!XWAIT) load_x();
+  // QKV: the position and this thread's entry of the kept-pair table (at most one per thread), requested with x
+  int rot_j = 0, rot_pos = 0;
+  if constexpr (QKV) {
+    rot_j = a.kept_idx[tid < a.H_tab * a.hk ? tid : 0];
+    rot_pos = a.positions[0];
+  }
 
   // ---- lane offsets inside a row.  Lanes whose columns lie past the last kept one re-read the row start: their
   // activations are zero, so what they fetch does not matter.
@@ -181,11 +213,44 @@ __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* L
   __amdgpu_buffer_rsrc_t rq[NM], rs[NM], rz[NM];
 #pragma unroll
   for (int m = 0; m < NM; ++m) {
-    rq[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(a.qweight[m]), 0, a.N_total * words_per_row * 4, kRsrcWord3);
-    rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.scales[m]), 0, a.N_total * groups_per_row * 2, kRsrcWord3);
+    const int rows = QKV ? a.n_total3[m] : a.N_total;
+    rq[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(a.qweight[m]), 0, rows * words_per_row * 4, kRsrcWord3);
+    rs[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.scales[m]), 0, rows * groups_per_row * 2, kRsrcWord3);
     if constexpr (ZP)
-      rz[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(a.zeros[m]), 0, a.N_total * groups_per_row, kRsrcWord3);
+      rz[m] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(a.zeros[m]), 0, rows * groups_per_row, kRsrcWord3);
   }
+  // QKV: loads are issued through the resources of the matrix of the body being fetched, rebuilt from that matrix's
+  // pointers when the matrix changes (a select between ready-made resources ends up in vector registers, and every
+  // load through such a resource becomes a loop over its distinct values)
+  int issue_mid = 0;
+  auto use_matrix = [&](int mid) {
+    if constexpr (QKV) {
+      if (mid != issue_mid) {
+        const int rows = mid == 1 ? a.n_total3[1] : a.n_total3[2];   // (bodies come in rising order: never back to q)
+        const uint32_t* qp = mid == 1 ? a.qweight[1] : a.qweight[2];
+        const uint16_t* sp = mid == 1 ? a.scales[1] : a.scales[2];
+        rq[0] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(qp), 0, rows * words_per_row * 4, kRsrcWord3);
+        rs[0] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(sp), 0, rows * groups_per_row * 2, kRsrcWord3);
+        if constexpr (ZP) {
+          const uint8_t* zp = mid == 1 ? a.zeros[1] : a.zeros[2];
+          rz[0] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(zp), 0, rows * groups_per_row, kRsrcWord3);
+        }
+        issue_mid = mid;
+      }
+    }
+  };
+  // QKV: pair -> matrix, head, pair of the head.  What the mapping needs of the arguments is pinned in scalar registers
+  // (left to itself the compiler indexes the argument block with the matrix number: a chain of dependent scalar
+  // loads per body).
+  struct PairLoc { int mid, head, p; };
+  auto locate = [&](int pair) {
+    PairLoc l;
+    l.mid = __builtin_amdgcn_readfirstlane((pair >= a.pair_end[0] ? 1 : 0) + (pair >= a.pair_end[1] ? 1 : 0));
+    const int lp = pair - (l.mid == 0 ? 0 : (l.mid == 1 ? a.pair_end[0] : a.pair_end[1]));
+    l.head = (int)(((unsigned long long)(uint32_t)lp * a.hk_magic) >> 32);
+    l.p = lp - l.head * a.hk;
+    return l;
+  };
   struct RowOff { int q, g; };   // scalar byte / element offsets of a row inside the arrays (once per row)
   auto row_off = [&](int rc) {   // rc: compact row, clamped by the caller
     const int sr = SEG ? stored_row(a.km, rc) : rc;   // SEG = false: the kept rows are a prefix
@@ -215,15 +280,36 @@ __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* L
 
   u32x4_t ring[D];
   RowQn cur[RB][NM], nxt[RB][NM];
+  PairLoc cur_loc = {0, 0, 0}, nxt_loc = {0, 0, 0};   // QKV: where the body in hand and the next one lie
+  // the RB rows of body j as offsets into the arrays (QKV: through the resources of the body's matrix, which become current)
+  auto body_offsets = [&](int j, RowOff (&ro)[RB], PairLoc& loc) {
+    if constexpr (QKV) {
+      const int pair = min(row_of(j, 0), last) >> 1;
+      loc = locate(pair);
+      use_matrix(loc.mid);
+      const int sr = loc.head * (loc.mid == 0 ? a.head_stride[0] : (loc.mid == 1 ? a.head_stride[1] : a.head_stride[2])) + loc.p;
+      const int sr2 = sr + (loc.mid == 0 ? a.pair_off[0] : (loc.mid == 1 ? a.pair_off[1] : a.pair_off[2]));
+      ro[0] = RowOff{sr * words_per_row * 4, sr * groups_per_row};
+      ro[1] = RowOff{sr2 * words_per_row * 4, sr2 * groups_per_row};
+    } else {
+#pragma unroll
+      for (int rr = 0; rr < RB; ++rr) {
+        const int rc = row_of(j, rr);   // the first row of a body that is fetched exists; its other rows may not
+        ro[rr] = row_off(rc < last ? rc : last);
+      }
+    }
+  };
   __builtin_amdgcn_sched_barrier(0);
+  {
+    RowOff ro0[RB];
+    body_offsets(wave, ro0, cur_loc);
 #pragma unroll
-  for (int rr = 0; rr < RB; ++rr) {
-    const int rc = row_of(wave, rr);
-    const RowOff ro = row_off(rc < last ? rc : last);
+    for (int rr = 0; rr < RB; ++rr) {
 #pragma unroll
-    for (int m = 0; m < NM; ++m) load_rowq(ro, m, cur[rr][m]);
+      for (int m = 0; m < NM; ++m) load_rowq(ro0[rr], m, cur[rr][m]);
 #pragma unroll
-    for (int t = 0; t < TPR; ++t) ring[rr * TPR + t] = load_codes(ro, slot_mat(t), slot_tile(t));
+      for (int t = 0; t < TPR; ++t) ring[rr * TPR + t] = load_codes(ro0[rr], slot_mat(t), slot_tile(t));
+    }
   }
   __builtin_amdgcn_sched_barrier(0);
   if constexpr (XWAIT) {
@@ -253,6 +339,28 @@ __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* L
     if (u < NCH * 256)
       xs[HI ? ((u >> 8) * 4 + (u & 3)) * 64 + ((u >> 2) & 63) : unit_slot(u, NCH)] =
           make_uint4(e[0] | (e[4] << 16), e[1] | (e[5] << 16), e[2] | (e[6] << 16), e[3] | (e[7] << 16));
+  }
+  // QKV: sin / cos of pos * theta^(-2j/D) for every (table row, kept pair), then the identity for v.  The angle is
+  // formed in fp64, in revolutions (theta^(-2j/D) = base^j by binary powering), and its fraction goes to the hardware
+  // sin / cos.
+  float2_t* rot = reinterpret_cast<float2_t*>(xs + NCH * 256);
+  if constexpr (QKV) {
+    const int n_tab = a.H_tab * a.hk;
+    if (tid <= n_tab) {
+      float sn = 0.f, cs = 1.f;
+      if (tid < n_tab) {
+        double inv_freq = 1.0, bpow = a.base;
+        for (int e = rot_j; e != 0; e >>= 1) {
+          inv_freq = e & 1 ? inv_freq * bpow : inv_freq;
+          bpow *= bpow;
+        }
+        const double rev = (double)rot_pos * inv_freq * 0.15915494309189534561;
+        const float rr = (float)(rev - rint(rev));
+        sn = __builtin_amdgcn_sinf(rr);
+        cs = __builtin_amdgcn_cosf(rr);
+      }
+      rot[tid] = float2_t{sn, cs};
+    }
   }
   __builtin_amdgcn_sched_barrier(0);
   __syncthreads();
@@ -300,10 +408,9 @@ __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* L
     constexpr bool RELOAD = decltype(reload_tag)::value;
     RowOff nro[RB];
     if constexpr (RELOAD) {
+      body_offsets(body_next, nro, nxt_loc);
 #pragma unroll
       for (int rr = 0; rr < RB; ++rr) {
-        const int rn = row_of(body_next, rr);   // the first row of the next body exists; its other rows may not
-        nro[rr] = row_off(rn < last ? rn : last);
 #pragma unroll
         for (int m = 0; m < NM; ++m) load_rowq(nro[rr], m, nxt[rr][m]);
       }
@@ -339,7 +446,9 @@ __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* L
         if constexpr (RELOAD) ring[s] = load_codes(nro[rr], m, c);
       }
       const int rc = row_of(body, rr);
-      if constexpr (NM == 1) {
+      if constexpr (QKV) {
+        // both rows of the pair are summed and rotated below
+      } else if constexpr (NM == 1) {
         const float v = diag_sum_to_lane63(acc[rr][0], on_diag);
         if (lane == 63) store_y(rc, out16<BF16>(v));
       } else {
@@ -348,6 +457,20 @@ __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* L
         // SiLU(g) * u; exp and the reciprocal are the hardware approximations (about 1 ulp of fp32)
         if (lane == 63) store_y(rc, out16<BF16>(g * u * __builtin_amdgcn_rcpf(1.0f + __expf(-g))));
       }
+    }
+    if constexpr (QKV) {
+      float x1, x2;
+      diag_sums_to_lane63(acc[0][0], acc[1][0], on_diag, x1, x2);
+      // q and k: the entry of (the head's table row, the pair); v: the identity behind the table
+      const int mid = cur_loc.mid;
+      const int tab_row = (int)(((unsigned long long)(uint32_t)cur_loc.head * (mid == 0 ? a.hpt_magic[0] : a.hpt_magic[1])) >> 32);
+      const float2_t sc = rot[mid == 2 ? a.H_tab * a.hk : tab_row * a.hk + cur_loc.p];
+      half_t* y = (mid == 0 ? a.y3[0] : (mid == 1 ? a.y3[1] : a.y3[2])) + cur_loc.head * (2 * a.hk) + cur_loc.p;
+      if (lane == 63) {
+        y[0] = out16<BF16>(x1 * sc.y - x2 * sc.x);
+        y[a.hk] = out16<BF16>(x2 * sc.y + x1 * sc.x);
+      }
+      if constexpr (RELOAD) cur_loc = nxt_loc;
     }
     if constexpr (RELOAD) {
 #pragma unroll
@@ -378,17 +501,18 @@ __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* L
 }
 
 
-template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE = false, bool HI = false>
+template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE = false, bool HI = false, bool QKV = false>
 __global__ __launch_bounds__(kStreamThreads) void w4_gemv_stream_kernel(StreamArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int next_body;
-  stream_phase<NCH, NM, ZP, BF16, SEG, PROBE, false, false, HI>(a, reinterpret_cast<uint4*>(smem), &next_body);
+  stream_phase<NCH, NM, ZP, BF16, SEG, PROBE, false, false, HI, QKV>(a, reinterpret_cast<uint4*>(smem), &next_body);
 }
 
-template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE, bool HI = false>
+template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE, bool HI = false, bool QKV = false>
 static hipError_t stream_launch(const StreamArgs& a, hipStream_t stream) {
-  auto kern = w4_gemv_stream_kernel<NCH, NM, ZP, BF16, SEG, PROBE, HI>;
-  const size_t smem = (size_t)NCH * 4096;
+  auto kern = w4_gemv_stream_kernel<NCH, NM, ZP, BF16, SEG, PROBE, HI, QKV>;
+  // the image of x, then (QKV) the sin / cos table and its identity entry
+  const size_t smem = (size_t)NCH * 4096 + (QKV ? ((size_t)a.H_tab * a.hk + 1) * sizeof(float2_t) : 0);
   // CU count per device ordinal, read once (host threads that race on the first call all store the same value)
   static std::atomic<int> cached[64];
   int dev = 0;
@@ -404,8 +528,9 @@ static hipError_t stream_launch(const StreamArgs& a, hipStream_t stream) {
   }
   // One block (8 waves, one body of tiles in flight each) per CU: more waves or deeper rings measured slower at every
   // size tried (the kernel is bound by instruction issue, and more loads in flight only queue).
-  constexpr int TPR = NM * NCH, RB = TPR >= 4 ? 1 : 4 / TPR;
+  constexpr int TPR = NM * NCH, RB = QKV ? 2 : (TPR >= 4 ? 1 : 4 / TPR);
   int blocks = (a.n_keep + kStreamWaves * RB - 1) / (kStreamWaves * RB);
+  // (QKV, a few thousand pairs in all: one, two or three blocks per compute unit measured the same, 6.7 us for 11.1 MB)
   if (blocks > cus) blocks = cus;
   hipLaunchKernelGGL(kern, dim3(blocks), dim3(kStreamThreads), smem, stream, a);
   return hipGetLastError();
@@ -438,6 +563,7 @@ static hipError_t stream_nch(const StreamArgs& a, int nch, hipStream_t stream) {
 constexpr int kStreamMinRows = 8192;
 constexpr int kStreamMinRowsShort = 2048;
 constexpr int kStreamMinRowsLong = 4096;    // row prefix with rows of more than four tiles (down_proj)
+constexpr int kStreamMinPairs = 1024;       // fused q / k / v: row pairs of the three matrices together
 
 static inline bool stream_shape(const LinearArgs& a, int max_tiles) {
   const KeepMap& km = a.km;
@@ -464,6 +590,13 @@ static inline StreamArgs stream_args(const LinearArgs& a) {
   s.wait_ticks = 0;
   s.il_heads = a.il_heads;
   s.d_keep = a.km.cs_stride ? a.km.cs_keep : kGroup;
+  s.qweight[2] = nullptr; s.scales[2] = nullptr; s.zeros[2] = nullptr;
+  s.y3[0] = s.y3[1] = s.y3[2] = nullptr;
+  s.pair_end[0] = s.pair_end[1] = 0;
+  s.hk = 0; s.hk_magic = 0;
+  for (int i = 0; i < 3; ++i) { s.head_stride[i] = 0; s.pair_off[i] = 0; s.n_total3[i] = 0; }
+  s.hpt_magic[0] = s.hpt_magic[1] = 0;
+  s.positions = nullptr; s.kept_idx = nullptr; s.H_tab = 0; s.base = 1.0;
   return s;
 }
 
@@ -532,6 +665,63 @@ static hipError_t stream_gate_up(const LinearArgs* p, hipStream_t stream, bool* 
   const int nch = row_tiles(s.k_keep);
   if constexpr (PROBE) return stream_nch<2, true, BF16, false, true>(s, nch, stream);
   return p[0].zeros ? stream_nch<2, true, BF16, false, false>(s, nch, stream) : stream_nch<2, false, BF16, false, false>(s, nch, stream);
+}
+
+// q, k, v of one token with q and k rotated, as one walk (*done = false, nothing launched, when the shapes are not
+// ones it serves): one x, kept columns a prefix, rows of at most four tiles, and in every matrix the kept rows are the
+// leading D_keep rows of each head (a row prefix, or one family of row segments that keeps D_keep rows each) or the
+// leading D_keep / 2 rows of either half of each head (segments of half a head).
+template <bool BF16>
+static hipError_t stream_qkv_rope(const LinearArgs* p, const RopeFuse& rf, hipStream_t stream, bool* done) {
+  const int D = rf.D_keep, hk = D / 2;
+  bool ok = hk >= 2 && (long long)rf.H_tab * hk < kStreamThreads;   // a table entry per thread, and the identity
+  int stride[3] = {0, 0, 0}, poff[3] = {0, 0, 0};
+  for (int i = 0; i < 3 && ok; ++i) {
+    const KeepMap& km = p[i].km;
+    ok = stream_shape(p[i], 4) && p[i].K_total == p[0].K_total && km.k_keep == p[0].km.k_keep && p[i].x == p[0].x &&
+         p[i].bf16 == p[0].bf16 && (p[i].zeros != nullptr) == (p[0].zeros != nullptr) && km.n_keep % D == 0;
+    const bool one_family = km.rs_segrows == km.n_keep && km.rs2_stride == 0;
+    if (km.rs_stride == 0) { stride[i] = D; poff[i] = hk; }   // a row prefix: heads of D_keep stored rows
+    else if (one_family && km.rs_keep == D) { stride[i] = km.rs_stride; poff[i] = hk; }   // the leading D_keep rows of every head
+    else if (one_family && km.rs_keep == hk) { stride[i] = 2 * km.rs_stride; poff[i] = km.rs_stride; }   // the leading pairs of either half of every head
+    else ok = false;
+  }
+  ok = ok && p[0].km.n_keep == rf.heads[0] * D && p[1].km.n_keep == rf.heads[1] * D;
+  const int pairs = ok ? (p[0].km.n_keep + p[1].km.n_keep + p[2].km.n_keep) / 2 : 0;
+  ok = ok && pairs >= kStreamMinPairs;
+  *done = ok;
+  if (!ok) return hipSuccess;
+  StreamArgs s = stream_args(p[0]);
+  for (int i = 0; i < 3; ++i) {
+    s.qweight[i] = p[i].qweight;
+    s.scales[i] = p[i].scales;
+    s.zeros[i] = p[i].zeros;
+    s.y3[i] = p[i].y;
+    s.head_stride[i] = stride[i];
+    s.pair_off[i] = poff[i];
+    s.n_total3[i] = p[i].N_total;
+  }
+  s.pair_end[0] = p[0].km.n_keep / 2;
+  s.pair_end[1] = s.pair_end[0] + p[1].km.n_keep / 2;
+  s.n_keep = 2 * pairs;
+  s.km = KeepMap{};
+  s.hk = hk;
+  s.hk_magic = ((1ull << 32) + hk - 1) / hk;
+  for (int i = 0; i < 2; ++i) {
+    const unsigned long long hpt = (unsigned long long)(rf.heads[i] / rf.H_tab);
+    s.hpt_magic[i] = ((1ull << 32) + hpt - 1) / hpt;
+  }
+  s.positions = rf.positions;
+  s.kept_idx = rf.kept_idx;
+  s.H_tab = rf.H_tab;
+  s.base = rf.base;
+  const bool zp = p[0].zeros != nullptr;
+  switch (row_tiles(s.k_keep)) {
+    case 1: return zp ? stream_launch<1, 1, true, BF16, false, false, false, true>(s, stream) : stream_launch<1, 1, false, BF16, false, false, false, true>(s, stream);
+    case 2: return zp ? stream_launch<2, 1, true, BF16, false, false, false, true>(s, stream) : stream_launch<2, 1, false, BF16, false, false, false, true>(s, stream);
+    case 3: return zp ? stream_launch<3, 1, true, BF16, false, false, false, true>(s, stream) : stream_launch<3, 1, false, BF16, false, false, false, true>(s, stream);
+    default: return zp ? stream_launch<4, 1, true, BF16, false, false, false, true>(s, stream) : stream_launch<4, 1, false, BF16, false, false, false, true>(s, stream);
+  }
 }
 
 }  // namespace gemv

@@ -647,6 +647,37 @@ def test_fused_qkv_rope_small_blocks(env, uref, hidden):
     assert max(errs) <= TOL and max(sep) <= 2e-3, (errs, sep)
 
 
+@pytest.mark.parametrize("case", ["whole_head_segments", "three_tiles_per_row", "one_tile_per_row", "shared_table_row"])
+def test_fused_qkv_rope_walk_shapes(env, uref, case):
+    """Attention blocks large enough for the persistent walk (a wave owns the two rows of a rotation pair), in the row
+    rules it takes: the leading rows of every head, the leading pairs of either half of every head, a row prefix; one
+    to three tiles per row; several heads and all heads per row of the kept-pair table."""
+    uq, torch = env
+    if case == "whole_head_segments":     # q and k keep the leading D_keep rows of every head (x1 block, then x2 block)
+        Hq, Hkv, H_tab, D, Dk, hidden = 24, 8, 8, 128, 100, 2048
+        seg = lambda H: Keep(n_keep=H * Dk, row_seg_stride=D, row_seg_keep=Dk, row_seg_limit=H * D)
+        keeps = (seg(Hq), seg(Hkv), seg(Hkv))
+    elif case == "three_tiles_per_row":   # 6144 columns, of which a prefix is kept
+        Hq, Hkv, H_tab, D, Dk, hidden = 16, 4, 4, 128, 128, 6144
+        keeps = (Keep(k_keep=5000), Keep(k_keep=5000), Keep(k_keep=5000))
+    elif case == "one_tile_per_row":
+        Hq, Hkv, H_tab, D, Dk, hidden = 40, 8, 8, 64, 52, 1024
+        half = lambda H: Keep(n_keep=H * Dk, row_seg_stride=D // 2, row_seg_keep=Dk // 2, row_seg_limit=H * D)
+        keeps = (half(Hq), half(Hkv), Keep(n_keep=Hkv * Dk, row_seg_stride=D, row_seg_keep=Dk, row_seg_limit=Hkv * D))
+    else:                                  # one table row for all heads, v a row prefix
+        Hq, Hkv, H_tab, D, Dk, hidden = 28, 4, 1, 128, 96, 3584
+        half = lambda H: Keep(n_keep=H * Dk, row_seg_stride=D // 2, row_seg_keep=Dk // 2, row_seg_limit=H * D)
+        keeps = (half(Hq), half(Hkv), Keep(n_keep=Hkv * Dk))
+    specs = {
+        "q_proj": wl.LinearSpec("q_proj", K=hidden, N=Hq * D, keep=keeps[0]),
+        "k_proj": wl.LinearSpec("k_proj", K=hidden, N=Hkv * D, keep=keeps[1]),
+        "v_proj": wl.LinearSpec("v_proj", K=hidden, N=Hkv * D, keep=keeps[2]),
+    }
+    rope = wl.RopeSpec(T=1, Hq=Hq, Hkv=Hkv, H_tab=H_tab, D_full=D, D_keep=Dk, theta=5.0e5, pos_max=100000)
+    errs, sep = _qkv_case(uq, torch, uref, specs, rope, wl.rng_for(0, 90 + len(case)))
+    assert max(errs) <= TOL and max(sep) <= 2e-3, (errs, sep)
+
+
 # ------------------------------------------------- gated MLP hidden vector: SiLU(x W_gate) * (x W_up)
 @pytest.mark.parametrize("N,K,keep", [
     (14336, 4096, Keep(n_keep=12185)),     # Llama-3-8B gate / up at 15 %: four rows per wave
