@@ -165,29 +165,36 @@ __global__ __launch_bounds__(WN * KS * 64) void w4_mfma_kernel(LinearArgs a) {
       }
     }
   };
+  // registers -> LDS: the unit's 8 halves in the pair order of the unpack, (0,4) (1,5) (2,6) (3,7): with 128-bit loads
+  // a mask per loaded word, then one byte permute per output word
   auto store_x = [&](int buf, const XRegs& xr) {
 #pragma unroll
     for (int i = 0; i < UPT; ++i) {
       const int u = tid + i * NT;
       const int tk = unit_token(u), cb = unit_chunk(u);
-      uint32_t e[8];
-      if constexpr (XVEC) {
-        const uint4 r = xr.v[i];
-        const uint32_t m = xr.ok[i];
-        e[0] = r.x & 0xffffu & m; e[1] = (r.x >> 16) & m; e[2] = r.y & 0xffffu & m; e[3] = (r.y >> 16) & m;
-        e[4] = r.z & 0xffffu & m; e[5] = (r.z >> 16) & m; e[6] = r.w & 0xffffu & m; e[7] = (r.w >> 16) & m;
-      } else if constexpr (XSEG) {
-        const uint4 r = xr.v[i];
-        const uint32_t full[8] = {r.x & 0xffffu, r.x >> 16, r.y & 0xffffu, r.y >> 16,
-                                  r.z & 0xffffu, r.z >> 16, r.w & 0xffffu, r.w >> 16};
-#pragma unroll
-        for (int j = 0; j < 8; ++j) e[j] = full[j] & (uint32_t)((int32_t)(xr.ok[i] << (31 - j)) >> 31);
+      uint4 o;
+      if constexpr (XVEC || XSEG) {
+        uint4 r = xr.v[i];
+        if constexpr (XVEC) {
+          const uint32_t m = xr.ok[i];
+          r.x &= m; r.y &= m; r.z &= m; r.w &= m;
+        } else {
+          // kept columns are the unit's first nk: a mask per 32-bit word (halves 2 w and 2 w + 1)
+          const uint32_t ok = xr.ok[i];
+          r.x &= (ok & 1u ? 0xffffu : 0u) | (ok & 2u ? 0xffff0000u : 0u);
+          r.y &= (ok & 4u ? 0xffffu : 0u) | (ok & 8u ? 0xffff0000u : 0u);
+          r.z &= (ok & 16u ? 0xffffu : 0u) | (ok & 32u ? 0xffff0000u : 0u);
+          r.w &= (ok & 64u ? 0xffffu : 0u) | (ok & 128u ? 0xffff0000u : 0u);
+        }
+        o = make_uint4(__builtin_amdgcn_perm(r.z, r.x, 0x05040100u), __builtin_amdgcn_perm(r.z, r.x, 0x07060302u),
+                       __builtin_amdgcn_perm(r.w, r.y, 0x05040100u), __builtin_amdgcn_perm(r.w, r.y, 0x07060302u));
       } else {
+        uint32_t e[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) e[j] = (xr.ok[i] >> j) & 1u ? xr.e[i][j] : 0u;
+        o = make_uint4(e[0] | (e[4] << 16), e[1] | (e[5] << 16), e[2] | (e[6] << 16), e[3] | (e[7] << 16));
       }
-      xs[(buf * NCH + cb) * BM + (tk ^ swz(cb))] =
-          make_uint4(e[0] | (e[4] << 16), e[1] | (e[5] << 16), e[2] | (e[6] << 16), e[3] | (e[7] << 16));
+      xs[(buf * NCH + cb) * BM + (tk ^ swz(cb))] = o;
     }
   };
 
