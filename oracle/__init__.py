@@ -63,6 +63,9 @@ def lib():
         L.uref_w4_repack.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp]
         L.uref_quantize_sym.argtypes = [vp, i32, i32, i32, vp, vp, vp]
         L.uref_quantize_asym.argtypes = [vp, i32, i32, i32, vp, vp, vp]
+        L.uref_wq_dequant.argtypes = [i32, vp, vp, vp, i32, i32, i32, vp, vp, i32]
+        L.uref_wq_linear.argtypes = [i32, vp, vp, vp, i32, i32, i32, vp, vp, i64, vp, i64, i32, vp, i32, i32]
+        L.uref_quantize_sym_bits.argtypes = [i32, vp, i32, i32, i32, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -181,6 +184,51 @@ def w4_linear(qweight, scales, zeros, x, keep=None, group: int = 128,
                                  _p(x), kk, _p(y), n_out, M, _p(rl), 0 if rl is None else rl.size, FMTS[fmt], int(il_heads))
     assert rc == 0, rc
     return y
+
+
+def wq_dequant(bits: int, qweight, scales, zeros, keep=None, group: int = 128, fmt: str = "f16") -> np.ndarray:
+    """Kept part of the dequantised matrix with codes of `bits` bits (4, or 8: qweight uint32 [N][K/4], zeros
+    0..255 or None = 128), as float16 (fmt "f16") or bfloat16 bit patterns (uint16, fmt "bf16")."""
+    _chk(qweight, np.uint32, "qweight"); _chk(scales, _f16_dtype(fmt), "scales"); _chkz(zeros)
+    N, Kw = qweight.shape
+    K = Kw * (32 // bits)
+    ka = _keep_arr(keep)
+    nk, kk = count_kept(N, K, ka)
+    out = np.empty((nk, kk), dtype=_f16_dtype(fmt))
+    rc = lib().uref_wq_dequant(bits, _p(qweight), _p(scales), _p(zeros), N, K, group, _p(ka), _p(out), FMTS[fmt])
+    assert rc == 0, rc
+    return out
+
+
+def wq_linear(bits: int, qweight, scales, zeros, x, keep=None, group: int = 128, rows=None, fmt: str = "f16") -> np.ndarray:
+    """fp64 y [M][n_keep] (or [M][len(rows)]) of the linear over codes of `bits` bits (see wq_dequant)."""
+    _chk(qweight, np.uint32, "qweight"); _chk(scales, _f16_dtype(fmt), "scales"); _chkz(zeros)
+    _chk(x, _f16_dtype(fmt), "x")
+    N, Kw = qweight.shape
+    K = Kw * (32 // bits)
+    ka = _keep_arr(keep)
+    nk, kk = count_kept(N, K, ka)
+    M = x.shape[0]
+    assert x.shape == (M, kk), (x.shape, kk)
+    rl = None if rows is None else np.ascontiguousarray(rows, dtype=np.int32)
+    n_out = nk if rl is None else rl.size
+    y = np.empty((M, n_out), dtype=np.float64)
+    rc = lib().uref_wq_linear(bits, _p(qweight), _p(scales), _p(zeros), N, K, group, _p(ka),
+                              _p(x), kk, _p(y), n_out, M, _p(rl), 0 if rl is None else rl.size, FMTS[fmt])
+    assert rc == 0, rc
+    return y
+
+
+def quantize_sym_bits(bits: int, w: np.ndarray, group: int = 128):
+    """Eq. 3 with N = bits: (qweight uint32 [N][K * bits / 32], scales float16, zeros uint8)."""
+    w = np.ascontiguousarray(w, dtype=np.float64)
+    N, K = w.shape
+    qweight = np.zeros((N, K * bits // 32), dtype=np.uint32)
+    scales = np.empty((N, K // group), dtype=np.float16)
+    zeros = np.empty((N, K // group), dtype=np.uint8)
+    rc = lib().uref_quantize_sym_bits(bits, _p(w), N, K, group, _p(qweight), _p(scales), _p(zeros))
+    assert rc == 0, rc
+    return qweight, scales, zeros
 
 
 def w4_interleave(qweight, heads: int) -> np.ndarray:

@@ -32,6 +32,9 @@
  *        index vector, one half stored; one table per KV head under GQA); Fig. 4a
  *   uref_pruned_rope_f64               the same rotation on fp64 inputs: the second half of the
  *        fused step y = RoPE(X W) (Eq. 2, then Sec. 3.2), no rounding in between
+ *   uref_wq_dequant / uref_wq_linear / uref_quantize_sym_bits   the same with codes of 8 bits (Eq. 3 with N = 8;
+ *        Sec. 3.4 and App. C say the method covers 8, 6, 4 and 3 bits; only 4 and 8 have a packed format here: 3-bit
+ *        the paper itself only simulates in FP16)
  *   uref_quantize_sym                  Eq. 3 (symmetric, N = 4)
  *   uref_quantize_asym                 the min/max asymmetric variant the
  *        benchmark configuration asks for (not in the paper; Eq. 3 is the case
@@ -204,15 +207,25 @@ static int word_of_col(int K_total, int il_heads, int k) {
   return (d / 8) * il_heads + h;
 }
 
-/* one dequantised weight as 16-bit float bits of format fmt: RN16((q - z) * s) */
-static uint16_t dequant_one(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
-                            int K_total, int group, int r, int k, int fmt, int il_heads) {
-  uint32_t word = qweight[(size_t)r * (K_total / 8) + word_of_col(K_total, il_heads, k)];
-  int q = (int)((word >> (4 * (k % 8))) & 15u);
+/* one dequantised weight as 16-bit float bits of format fmt: RN16((q - z) * s).  bits = 4 or 8 is the width of a
+ * code (Eq. 3's N): a word holds 32 / bits codes, code j in bits [bits * j, bits * j + bits), and without zero
+ * points z = 2^(bits - 1), the offset that stores Eq. 3's signed code as an unsigned one.  The product is exact in
+ * fp64 for either width (|q - z| <= 255 times an 11-bit significand). */
+static uint16_t dequant_bits(int bits, const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
+                             int K_total, int group, int r, int k, int fmt, int il_heads) {
+  int cpw = 32 / bits;   /* codes per word */
+  int word_idx = bits == 4 ? word_of_col(K_total, il_heads, k) : k / cpw;
+  uint32_t word = qweight[(size_t)r * (K_total / cpw) + word_idx];
+  int q = (int)((word >> (bits * (k % cpw))) & ((1u << bits) - 1u));
   size_t g = (size_t)r * (K_total / group) + k / group;
-  int z = zeros ? zeros[g] : 8;   /* no zero points: the symmetric codes of Eq. 3, stored as signed code + 8 */
+  int z = zeros ? zeros[g] : 1 << (bits - 1);   /* no zero points: the symmetric codes of Eq. 3, stored as signed code + 2^(N-1) */
   double s = f16_to_double(scales[g], fmt);
   return double_to_f16((double)(q - z) * s, fmt);
+}
+
+static uint16_t dequant_one(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
+                            int K_total, int group, int r, int k, int fmt, int il_heads) {
+  return dequant_bits(4, qweight, scales, zeros, K_total, group, r, k, fmt, il_heads);
 }
 
 /* w_f16: [n_keep][k_keep] compact, 16-bit float bits */
@@ -321,6 +334,86 @@ int uref_w4_linear(const uint32_t* qweight, const uint16_t* scales, const uint8_
                    const int32_t* row_list, int n_list) {
   return uref_w4_linear_fmt(qweight, scales, zeros, N_total, K_total, group, keep, x, ldx, y, ldy, M,
                             row_list, n_list, 0);
+}
+
+/* ---- other code widths (Sec. 3.4 / App. C: the method quantises to 8, 6, 4 and 3 bits; Eq. 3 with N = bits).
+ * bits = 8: qweight uint32 [N_total][K_total/4], byte j of word w of a row is input column 4w+j; zeros uint8 0..255
+ * or NULL (every zero point 128).  bits = 4 is the format above.  Everything else -- groups, the keep rule, RN16 of
+ * (q - z) * s, fp64 sums in index order -- is as in uref_w4_dequant_fmt / uref_w4_linear_fmt. */
+int uref_wq_dequant(int bits, const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
+                    int N_total, int K_total, int group, const int32_t* keep, uint16_t* w_f16, int fmt) {
+  if (bits != 4 && bits != 8) return -3;
+  static const int32_t none[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  if (!keep) keep = none;
+  int32_t* rows = (int32_t*)malloc(sizeof(int32_t) * (size_t)N_total);
+  int32_t* cols = (int32_t*)malloc(sizeof(int32_t) * (size_t)K_total);
+  if (!rows || !cols) { free(rows); free(cols); return -1; }
+  int nk = kept_rows(keep, N_total, rows), kk = kept_cols(keep, K_total, cols);
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+  for (int i = 0; i < nk; ++i)
+    for (int j = 0; j < kk; ++j)
+      w_f16[(size_t)i * kk + j] = dequant_bits(bits, qweight, scales, zeros, K_total, group, rows[i], cols[j], fmt, 0);
+  free(rows); free(cols);
+  return 0;
+}
+
+int uref_wq_linear(int bits, const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
+                   int N_total, int K_total, int group, const int32_t* keep,
+                   const uint16_t* x, int64_t ldx, double* y, int64_t ldy, int M,
+                   const int32_t* row_list, int n_list, int fmt) {
+  if (bits != 4 && bits != 8) return -3;
+  static const int32_t none[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  if (!keep) keep = none;
+  int32_t* rows = (int32_t*)malloc(sizeof(int32_t) * (size_t)N_total);
+  int32_t* cols = (int32_t*)malloc(sizeof(int32_t) * (size_t)K_total);
+  if (!rows || !cols) { free(rows); free(cols); return -1; }
+  int nk = kept_rows(keep, N_total, rows), kk = kept_cols(keep, K_total, cols);
+  int n_out = row_list ? n_list : nk;
+  int bad = 0;
+#pragma omp parallel for num_threads(g_threads) schedule(static) reduction(| : bad)
+  for (int i = 0; i < n_out; ++i) {
+    int rc = row_list ? row_list[i] : i;
+    if (rc < 0 || rc >= nk) { bad = 1; continue; }
+    int r = rows[rc];
+    for (int m = 0; m < M; ++m) {
+      double acc = 0.0;
+      for (int j = 0; j < kk; ++j) {
+        double w = f16_to_double(dequant_bits(bits, qweight, scales, zeros, K_total, group, r, cols[j], fmt, 0), fmt);
+        acc += f16_to_double(x[(size_t)m * ldx + j], fmt) * w;
+      }
+      y[(size_t)m * ldy + i] = acc;
+    }
+  }
+  free(rows); free(cols);
+  return bad ? -2 : 0;
+}
+
+/* Eq. 3 with N = bits: s = max|W| / (2^(N-1) - 1), code = clamp(rint(W / s), -2^(N-1), 2^(N-1) - 1), stored as
+ * code + 2^(N-1) with zero point 2^(N-1).  The scale is stored in fp16 and the codes are taken against the stored
+ * scale.  (Only used to build test inputs and for the round-trip pin.) */
+int uref_quantize_sym_bits(int bits, const double* w, int N, int K, int group, uint32_t* qweight,
+                           uint16_t* scales, uint8_t* zeros) {
+  if (bits != 4 && bits != 8) return -3;
+  int cpw = 32 / bits, half = 1 << (bits - 1);
+  memset(qweight, 0, sizeof(uint32_t) * (size_t)N * (size_t)(K / cpw));
+  for (int r = 0; r < N; ++r)
+    for (int g = 0; g < K / group; ++g) {
+      const double* wg = w + (size_t)r * K + (size_t)g * group;
+      double mx = 0.0;
+      for (int j = 0; j < group; ++j) mx = fmax(mx, fabs(wg[j]));
+      uint16_t s16 = uref_double_to_half(mx / (double)(half - 1));
+      double s = uref_half_to_double(s16);
+      scales[(size_t)r * (K / group) + g] = s16;
+      zeros[(size_t)r * (K / group) + g] = (uint8_t)half;
+      for (int j = 0; j < group; ++j) {
+        double qv = s > 0.0 ? rint(wg[j] / s) : 0.0;
+        if (qv < -(double)half) qv = -(double)half;
+        if (qv > (double)(half - 1)) qv = (double)(half - 1);
+        int k = g * group + j;
+        qweight[(size_t)r * (K / cpw) + k / cpw] |= (uint32_t)((int)qv + half) << (bits * (k % cpw));
+      }
+    }
+  return 0;
 }
 
 /* Pruned RoPE.  q: fp16 bits [T][Hq][D_keep]; k: [T][Hkv][D_keep] or NULL.
