@@ -77,6 +77,12 @@ enum {
  * uniql_w4_linear with M = 1 for H a multiple of 4 that divides 256, D = 128, unpruned rows, and either no column
  * pruning or column segments of stride 128; uniql_w4_dequant for any H; every other call returns E_SHAPE for such a
  * matrix.
+ *
+ * bits = 8 (Eq. 3 with N = 8; Sec. 3.4 and App. C name 8, 6, 4 and 3 bits as widths the method covers): qweight is
+ * [N_total][K_total/4], byte j of word w of a row is input column 4 w + j; zeros are 0..255, or NULL: every zero
+ * point is 128.  Groups, the keep rule and the weight RN16((q - z) * s) are as for 4-bit codes.  Served by
+ * uniql_w4_linear (any M; at most 32768 stored columns up to the last kept one, else E_SHAPE) and uniql_w4_dequant;
+ * every other call, and col_interleave > 0, return E_SHAPE for such a matrix.  Any other value of bits: E_SHAPE.
  */
 enum { UNIQL_F16 = 0, UNIQL_BF16 = 1 };
 
@@ -87,6 +93,7 @@ typedef struct uniql_w4 {
   int32_t N_total, K_total, group;
   int32_t dtype;           /* UNIQL_F16 or UNIQL_BF16; anything else: E_SHAPE */
   int32_t col_interleave;  /* 0: words in column order; H > 0: head-interleaved over H heads (see above) */
+  int32_t bits;            /* width of a code: 0 or 4 = the 4-bit format above; 8 = 8-bit codes (see below) */
 } uniql_w4_t;
 
 /*

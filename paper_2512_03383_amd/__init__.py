@@ -30,7 +30,7 @@ class W4(C.Structure):
     """uniql_w4_t"""
     _fields_ = [("qweight", C.c_void_p), ("scales", C.c_void_p), ("zeros", C.c_void_p),
                 ("N_total", C.c_int32), ("K_total", C.c_int32), ("group", C.c_int32), ("dtype", C.c_int32),
-                ("col_interleave", C.c_int32)]
+                ("col_interleave", C.c_int32), ("bits", C.c_int32)]
 
 
 UNIQL_F16, UNIQL_BF16 = 0, 1
@@ -148,6 +148,7 @@ class QuantLinear:
     scales: "torch.Tensor"    # float16 or bfloat16 [N][K/128]: the format of activations and outputs too
     zeros: "Optional[torch.Tensor]"     # uint8 [N][K/128], or None: symmetric scheme, every zero point 8
     col_interleave: int = 0   # > 0: the words of a row are stored head-interleaved over this many heads
+    bits: int = 4             # width of a code: 4, or 8 (then qweight is [N][K/4] and zeros are 0..255 or None = 128)
 
     @property
     def N(self) -> int:
@@ -155,7 +156,7 @@ class QuantLinear:
 
     @property
     def K(self) -> int:
-        return self.qweight.shape[1] * 8
+        return self.qweight.shape[1] * (32 // self.bits)
 
     @property
     def ftype(self):
@@ -168,10 +169,10 @@ class QuantLinear:
         import torch
         return W4(self.qweight.data_ptr(), self.scales.data_ptr(),
                   self.zeros.data_ptr() if self.zeros is not None else None, self.N, self.K, 128,
-                  UNIQL_BF16 if self.ftype == torch.bfloat16 else UNIQL_F16, int(self.col_interleave))
+                  UNIQL_BF16 if self.ftype == torch.bfloat16 else UNIQL_F16, int(self.col_interleave), int(self.bits))
 
     @staticmethod
-    def from_numpy(w: dict, device="cuda") -> "QuantLinear":
+    def from_numpy(w: dict, device="cuda", bits: int = 4) -> "QuantLinear":
         import numpy as np
         import torch
         scales = w["scales"]      # float16, or uint16 bit patterns of bfloat16
@@ -179,7 +180,7 @@ class QuantLinear:
                   else torch.from_numpy(scales))
         return QuantLinear(torch.from_numpy(w["qweight"].view(np.int32)).to(device),
                            scales.to(device),
-                           torch.from_numpy(w["zeros"]).to(device) if w.get("zeros") is not None else None)
+                           torch.from_numpy(w["zeros"]).to(device) if w.get("zeros") is not None else None, bits=bits)
 
 
 def kept_dims(W: QuantLinear, keep) -> tuple:

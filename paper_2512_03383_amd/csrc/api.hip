@@ -38,9 +38,12 @@ static int check_arch() {
 static bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
 // Validate W / keep and normalise the keep rule.  Pure host arithmetic.
-static int make_keepmap(const uniql_w4_t* W, const uniql_keep_t* keep, KeepMap* km) {
-  if (!W || !W->qweight || !W->scales) return UNIQL_E_NULL;   // zeros may be NULL: every zero point is 8
+// allow8: the caller serves codes of 8 bits as well (uniql_w4_linear and uniql_w4_dequant do)
+static int code_bits(const uniql_w4_t* W) { return W->bits == 0 ? 4 : W->bits; }
+static int make_keepmap(const uniql_w4_t* W, const uniql_keep_t* keep, KeepMap* km, bool allow8 = false) {
+  if (!W || !W->qweight || !W->scales) return UNIQL_E_NULL;   // zeros may be NULL: every zero point is 8 (128 for 8-bit codes)
   if (W->group != kGroup || W->N_total < 1 || W->K_total < kGroup || W->K_total % kGroup) return UNIQL_E_SHAPE;
+  if (code_bits(W) != 4 && !(code_bits(W) == 8 && allow8 && W->col_interleave == 0)) return UNIQL_E_SHAPE;
   if (W->dtype != UNIQL_F16 && W->dtype != UNIQL_BF16) return UNIQL_E_SHAPE;
   if (W->col_interleave < 0 || (W->col_interleave > 0 && (W->K_total % W->col_interleave || (W->K_total / W->col_interleave) % 8)))
     return UNIQL_E_SHAPE;
@@ -97,8 +100,8 @@ static int make_keepmap(const uniql_w4_t* W, const uniql_keep_t* keep, KeepMap* 
 
 // Validate one linear call and fill the kernel arguments.  Host arithmetic only.
 static int fill_linear(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_f16, int64_t ldx,
-                       void* y_f16, int64_t ldy, int32_t M, LinearArgs* a) {
-  int rc = make_keepmap(W, keep, &a->km);
+                       void* y_f16, int64_t ldy, int32_t M, LinearArgs* a, bool allow8 = false) {
+  int rc = make_keepmap(W, keep, &a->km, allow8);
   if (rc) return rc;
   if (!x_f16 || !y_f16) return UNIQL_E_NULL;
   if (M < 1 || ldx < a->km.k_keep || ldy < a->km.n_keep) return UNIQL_E_SHAPE;
@@ -115,10 +118,16 @@ static int fill_linear(const uniql_w4_t* W, const uniql_keep_t* keep, const void
   a->M = M;
   a->bf16 = W->dtype == UNIQL_BF16;
   a->il_heads = W->col_interleave;
+  a->bits = code_bits(W);
   return UNIQL_OK;
 }
 
 static int run_linear(const LinearArgs& a, hipStream_t s) {
+  if (a.bits == 8) {
+    hipError_t e8 = launch_w8_linear(a, s);
+    if (e8 == hipErrorInvalidValue) return UNIQL_E_SHAPE;   // more kept columns than the kernel's staging holds
+    return e8 == hipSuccess ? UNIQL_OK : hip_fail(e8);
+  }
   if (a.il_heads > 0 && a.M != 1) return UNIQL_E_SHAPE;   // head-interleaved words: one token only
   hipError_t e = (a.M == 1) ? launch_w4_gemv(a, s) : launch_w4_gemm(a, s);
   if (e == hipErrorInvalidValue && a.M == 1) return UNIQL_E_SHAPE;   // K too long for the GEMV's staging
@@ -128,7 +137,7 @@ static int run_linear(const LinearArgs& a, hipStream_t s) {
 extern "C" int uniql_w4_linear(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_f16, int64_t ldx,
                                void* y_f16, int64_t ldy, int32_t M, void* hip_stream) {
   LinearArgs a;
-  int rc = fill_linear(W, keep, x_f16, ldx, y_f16, ldy, M, &a);
+  int rc = fill_linear(W, keep, x_f16, ldx, y_f16, ldy, M, &a, true);
   if (rc) return rc;
   rc = check_arch();
   if (rc) return rc;
@@ -163,7 +172,7 @@ extern "C" int uniql_w4_linear_multi(int32_t n, const uniql_w4_t* W, const uniql
 
 extern "C" int uniql_w4_dequant(const uniql_w4_t* W, const uniql_keep_t* keep, void* w_f16, void* hip_stream) {
   LinearArgs a;
-  int rc = make_keepmap(W, keep, &a.km);
+  int rc = make_keepmap(W, keep, &a.km, true);
   if (rc) return rc;
   if (!w_f16) return UNIQL_E_NULL;
   if (!aligned(w_f16, 2)) return UNIQL_E_ALIGN;
@@ -181,7 +190,8 @@ extern "C" int uniql_w4_dequant(const uniql_w4_t* W, const uniql_keep_t* keep, v
   a.M = 0;
   a.bf16 = W->dtype == UNIQL_BF16;
   a.il_heads = W->col_interleave;
-  hipError_t e = launch_w4_dequant(a, (hipStream_t)hip_stream);
+  a.bits = code_bits(W);
+  hipError_t e = a.bits == 8 ? launch_w8_dequant(a, (hipStream_t)hip_stream) : launch_w4_dequant(a, (hipStream_t)hip_stream);
   return e == hipSuccess ? UNIQL_OK : hip_fail(e);
 }
 

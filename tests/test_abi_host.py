@@ -27,8 +27,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_layout_matches_header():
-    assert C.sizeof(W4) == 3 * 8 + 5 * 4 + 4      # three pointers, five int32, padding to the pointers' alignment
-    assert W4.dtype.offset == 36 and W4.col_interleave.offset == 40
+    assert C.sizeof(W4) == 3 * 8 + 6 * 4          # three pointers, six int32
+    assert W4.dtype.offset == 36 and W4.col_interleave.offset == 40 and W4.bits.offset == 44
     assert C.sizeof(KeepDesc) == 10 * 4
     assert W4.N_total.offset == 24 and W4.group.offset == 32
     assert KeepDesc.col_seg_keep.offset == 24 and KeepDesc.row_seg2_limit.offset == 36
@@ -130,6 +130,30 @@ def test_dtype_field_is_validated():
     # gate (fp16) and up (bfloat16) in one fused call
     W = (W4 * 2)(_w(), wb)
     assert uq.lib().uniql_w4_gate_up_silu(W, None, C.c_void_p(P), C.c_void_p(P), None) == uq.UNIQL_E_SHAPE
+
+
+def test_bits_field_is_validated():
+    """0 and 4 = 4-bit codes, 8 = 8-bit codes in the two calls that serve them, anything else refused; an 8-bit
+    matrix passes the same host checks as a 4-bit one there and is refused everywhere else before any launch."""
+    for bad in (1, 3, 6, 16, -4):
+        w = _w()
+        w.bits = bad
+        assert _lin(w, None) == uq.UNIQL_E_SHAPE
+    w4 = _w()
+    w4.bits = 4
+    assert _lin(w4, None, M=0) == uq.UNIQL_E_SHAPE and _lin(w4, KeepDesc(n_keep=999)) == uq.UNIQL_E_KEEP
+    w8 = _w()
+    w8.bits = 8
+    assert _lin(w8, None, M=0) == uq.UNIQL_E_SHAPE             # validated like any other matrix ...
+    assert _lin(w8, KeepDesc(n_keep=999)) == uq.UNIQL_E_KEEP
+    assert _lin(w8, None, x=P + 1) == uq.UNIQL_E_ALIGN
+    wi = _w()
+    wi.bits, wi.col_interleave = 8, 4
+    assert _lin(wi, None) == uq.UNIQL_E_SHAPE                  # ... but not head-interleaved
+    assert _multi(ws=[_w(), w8]) == uq.UNIQL_E_SHAPE           # and not in the calls that only know 4-bit codes
+    W = (W4 * 2)(w8, w8)
+    assert uq.lib().uniql_w4_gate_up_silu(W, None, C.c_void_p(P), C.c_void_p(P), None) == uq.UNIQL_E_SHAPE
+    assert uq.lib().uniql_w4_dequant(C.byref(w8), None, None, None) == uq.UNIQL_E_NULL   # dequant takes it (and then misses its output)
 
 
 def test_rope_table_check_on_the_host():

@@ -282,6 +282,20 @@ def gen_linear(rng: np.random.Generator, N: int, K: int,
     return {"qweight": qweight, "scales": scales, "zeros": zeros}
 
 
+def gen_linear8(rng: np.random.Generator, N: int, K: int,
+                sym_zero: bool = False, fmt: str = "f16") -> Dict[str, np.ndarray]:
+    """8-bit codes: random 32-bit words (four uniform bytes each), scales ~ U(0.0003, 0.0012) (the 4-bit range
+    divided by 16: the same weight range on a grid 16 times finer) and zeros ~ U{0..255} (or all 128 when sym_zero)."""
+    assert K % GROUP == 0
+    qweight = rng.integers(0, 2 ** 32, size=(N, K // 4), dtype=np.uint64).astype(np.uint32)
+    scales = _store16(rng.uniform(0.0003, 0.0012, size=(N, K // GROUP)), fmt)
+    if sym_zero:
+        zeros = np.full((N, K // GROUP), 128, dtype=np.uint8)
+    else:
+        zeros = rng.integers(0, 256, size=(N, K // GROUP), dtype=np.uint8)
+    return {"qweight": qweight, "scales": scales, "zeros": zeros}
+
+
 def gen_activations(rng: np.random.Generator, M: int, K: int, fmt: str = "f16") -> np.ndarray:
     return _store16(rng.standard_normal((M, K)), fmt)
 
