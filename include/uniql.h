@@ -136,10 +136,14 @@ typedef struct uniql_keep {
  * in fp32 and y is rounded once to fp16.
  *   x_f16 : device, fp16 [M][ldx], first k_keep entries of a row are the kept inputs
  *   y_f16 : device, fp16 [M][ldy], first n_keep entries of a row are written
- *   ldx >= k_keep, ldy >= n_keep (elements); x and y must not overlap.
- * M = 1 runs the streaming GEMV; M >= 2 the MFMA dequant-GEMM (K-split configuration for
- * decode batches up to 32 tokens, large tiles for prefill).
- * Errors: E_NULL, E_SHAPE, E_KEEP, E_ALIGN, E_ARCH, E_HIP.
+ *   ldx >= k_keep, ldy >= n_keep (elements); x and y must not overlap (this is not checked:
+ *   with overlapping buffers the result is undefined).
+ * M = 1 runs the streaming GEMV; M >= 2 the MFMA dequant-GEMM: 2..32 tokens the decode-batch
+ * kernels (a wave owns 16 rows and part of K; tall matrices above 8 tokens a slab kernel), up to
+ * 64 tokens tiles whose K range is split over the waves of a block, large tiles for prefill.
+ * Errors: E_NULL, E_SHAPE, E_KEEP, E_ALIGN, E_ARCH, E_HIP.  E_SHAPE also at M = 1 when the last
+ * kept column lies past stored column 81920 (the block's image of the activations in LDS holds
+ * 40 tiles of 2048 columns), and for 8-bit codes past column 32768 at any M.
  */
 int uniql_w4_linear(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_f16, int64_t ldx,
                     void* y_f16, int64_t ldy, int32_t M, void* hip_stream);

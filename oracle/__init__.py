@@ -17,14 +17,19 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "uref.c")
-_LIB = os.path.join(_HERE, "liburef.so")
+# UREF_SANITIZE=1 in the environment: a second library built with AddressSanitizer and UndefinedBehaviorSanitizer
+# (run the pins with it as  UREF_SANITIZE=1 LD_PRELOAD=$(gcc -print-file-name=libasan.so) ASAN_OPTIONS=detect_leaks=0
+# python -m pytest tests -m "not gpu"; the interpreter itself is not instrumented, so the runtime has to be preloaded)
+_SAN = os.environ.get("UREF_SANITIZE", "") not in ("", "0")
+_LIB = os.path.join(_HERE, "liburef_san.so" if _SAN else "liburef.so")
 _lib = None
 
 
 def build(force: bool = True) -> str:
     """Compile uref.c with gcc into oracle/liburef.so."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+        flags = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined"] if _SAN else ["-O2"]
+        subprocess.check_call(["gcc", *flags, "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
                                "-o", _LIB, _SRC, "-lm"])
     return _LIB
 
