@@ -54,6 +54,7 @@ def lib():
         L.uref_w4_linear_il.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, i64, vp, i64, i32, vp, i32, i32, i32]
         L.uref_w4_dequant_il.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, i32, i32]
         L.uref_w4_interleave.argtypes = [vp, i32, i32, i32, vp]
+        L.uref_w4_deinterleave.argtypes = [vp, i32, i32, i32, vp]
         L.uref_w4_embedding_fmt.argtypes = [vp, vp, vp, i32, i32, i32, vp, i32, vp, i32]
         L.uref_pruned_rope_fmt.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, dbl, vp, vp, i32]
         L.uref_set_threads.argtypes = [i32]
@@ -243,6 +244,17 @@ def w4_interleave(qweight, heads: int) -> np.ndarray:
     out = np.empty_like(qweight)
     rc = lib().uref_w4_interleave(_p(qweight), N, K8 * 8, int(heads), _p(out))
     assert rc == 0, rc
+    return out
+
+
+def w4_deinterleave(qweight_il, heads: int) -> np.ndarray:
+    """The words of a matrix that is head-interleaved over `heads` heads, back in column order."""
+    _chk(qweight_il, np.uint32, "qweight_il")
+    N, K8 = qweight_il.shape
+    out = np.empty_like(qweight_il)
+    rc = lib().uref_w4_deinterleave(_p(qweight_il), N, K8 * 8, int(heads), _p(out))
+    if rc != 0:
+        raise ValueError(f"uref_w4_deinterleave: {rc}")
     return out
 
 

@@ -67,7 +67,7 @@
  *   input columns are H heads of D = K_total / H dims; column numbers, the keep rule, groups, scales and zero points all
  *   refer to this head-major matrix (column c = h * D + d).  Only where a code is STORED differs: the 32-bit words of a
  *   row are kept dim-block-major, word (d / 8) * H + h holding dims 8 (d / 8) .. + 7 of head h, so the code of column c is
- *   nibble d % 8 of that word.  il_heads = 0 is the plain order above.  uref_w4_interleave converts.
+ *   nibble d % 8 of that word.  il_heads = 0 is the plain order above.  uref_w4_interleave converts, uref_w4_deinterleave converts back.
  */
 #include <math.h>
 #include <stdint.h>
@@ -325,6 +325,18 @@ int uref_w4_interleave(const uint32_t* qweight, int N_total, int K_total, int he
     for (int h = 0; h < heads; ++h)
       for (int b = 0; b < wph; ++b)
         out[(size_t)r * wpr + (size_t)b * heads + h] = qweight[(size_t)r * wpr + (size_t)h * wph + b];
+  return 0;
+}
+
+/* The inverse: the words of a head-interleaved matrix back in column order, out[r][h * (D / 8) + d / 8] =
+ * qweight_il[r][(d / 8) * heads + h]. */
+int uref_w4_deinterleave(const uint32_t* qweight_il, int N_total, int K_total, int heads, uint32_t* out) {
+  if (heads < 1 || K_total % heads || (K_total / heads) % 8) return -3;
+  int wpr = K_total / 8, wph = wpr / heads;
+  for (int r = 0; r < N_total; ++r)
+    for (int h = 0; h < heads; ++h)
+      for (int b = 0; b < wph; ++b)
+        out[(size_t)r * wpr + (size_t)h * wph + b] = qweight_il[(size_t)r * wpr + (size_t)b * heads + h];
   return 0;
 }
 

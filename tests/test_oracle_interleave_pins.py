@@ -86,3 +86,39 @@ def test_interleave_argument_checks():
         uref.w4_interleave(q, 3)                           # 256 is not a multiple of 3
     with pytest.raises(AssertionError):
         uref.w4_interleave(q, 64)                          # heads of 4 dims: not whole words
+
+
+@pytest.mark.parametrize("N,K,heads", [(3, 256, 2), (5, 512, 4), (2, 4096, 32), (4, 768, 3)])
+def test_deinterleave_is_the_inverse_word_transpose(N, K, heads):
+    """uref_w4_deinterleave against numpy's transpose of the [words per head][heads] view, against the round trip through
+    uref_w4_interleave in both orders, and spelled out for one entry."""
+    rng = wl.rng_for(18, 7 * N + K + heads)
+    q = rng.integers(0, 2 ** 32, (N, K // 8), dtype=np.uint64).astype(np.uint32)
+    D8 = K // 8 // heads
+    got = uref.w4_deinterleave(q, heads)
+    want = q.reshape(N, D8, heads).transpose(0, 2, 1).reshape(N, K // 8)
+    assert np.array_equal(got, want)
+    assert np.array_equal(uref.w4_deinterleave(uref.w4_interleave(q, heads), heads), q)
+    assert np.array_equal(uref.w4_interleave(uref.w4_deinterleave(q, heads), heads), q)
+    h, b = heads - 1, D8 - 2 if D8 > 1 else 0
+    assert got[N - 1, h * D8 + b] == q[N - 1, b * heads + h]
+
+
+def test_deinterleaved_matrix_is_the_plain_matrix():
+    """Reading the deinterleaved words in plain order gives the weights and the sums of the interleaved matrix read
+    with its head count, bit for bit (pruned heads included)."""
+    rng = wl.rng_for(18, 99)
+    N, K, heads = 6, 512, 4
+    keep = Keep(col_seg_stride=128, col_seg_keep=101)
+    w = wl.gen_linear(rng, N, K)
+    qi = rng.integers(0, 2 ** 32, (N, K // 8), dtype=np.uint64).astype(np.uint32)   # any words: an interleaved matrix
+    qp = uref.w4_deinterleave(qi, heads)
+    d_il = uref.w4_dequant(qi, w["scales"], w["zeros"], keep, il_heads=heads)
+    d_pl = uref.w4_dequant(qp, w["scales"], w["zeros"], keep)
+    assert np.array_equal(d_il.view(np.uint16), d_pl.view(np.uint16))
+    x = wl.gen_activations(rng, 2, heads * 101)
+    y_il = uref.w4_linear(qi, w["scales"], w["zeros"], x, keep, il_heads=heads)
+    y_pl = uref.w4_linear(qp, w["scales"], w["zeros"], x, keep)
+    assert np.array_equal(y_il.view(np.uint64), y_pl.view(np.uint64))
+    with pytest.raises(ValueError):
+        uref.w4_deinterleave(qi, 3)                          # 512 is not a multiple of 3
