@@ -73,10 +73,11 @@ enum {
  * head-major matrix (column h * D + d, group (h * D + d) / 128), x and y are what they are for that matrix.  What it buys:
  * keeping the leading D' dims of every head (column segments of stride D) keeps the leading ceil(D' / 8) * H words of
  * every row, so the pruned codes are not fetched at all, where the head-major order fetches them with the 32-byte
- * sectors they share with kept ones.  uniql_w4_interleave converts (a permutation of words, exact).  Served so far:
- * uniql_w4_linear with M = 1 for H a multiple of 4 that divides 256, D = 128, unpruned rows, and either no column
- * pruning or column segments of stride 128; uniql_w4_dequant for any H; every other call returns E_SHAPE for such a
- * matrix.
+ * sectors they share with kept ones.  uniql_w4_interleave converts (a permutation of words, exact) and
+ * uniql_w4_deinterleave converts back.  Served: uniql_w4_linear for H a multiple of 4 that divides 256, D = 128,
+ * unpruned rows, and either no column pruning or column segments of stride 128, with the one-token kernel (1..64 tokens
+ * run it token by token; more tokens: E_SHAPE, convert back for a prompt); uniql_w4_dequant for any H; every other call
+ * returns E_SHAPE for such a matrix.
  *
  * bits = 8 (Eq. 3 with N = 8; Sec. 3.4 and App. C name 8, 6, 4 and 3 bits as widths the method covers): qweight is
  * [N_total][K_total/4], byte j of word w of a row is input column 4 w + j; zeros are 0..255, or NULL: every zero
@@ -310,6 +311,16 @@ int uniql_stream_read_probe(const void* src, int64_t bytes, void* out_words, voi
  * [N_total][K_total / 8], must not overlap W->qweight.  Errors: E_NULL, E_SHAPE, E_ALIGN, E_ARCH, E_HIP.
  */
 int uniql_w4_interleave(const uniql_w4_t* W, int32_t heads, uint32_t* out_qweight, void* hip_stream);
+
+/*
+ * The inverse of uniql_w4_interleave: the words of a head-interleaved matrix (W->col_interleave = H > 0) back in column
+ * order, out_qweight[r][h * (K_total / H / 8) + d / 8] = W->qweight[r][(d / 8) * H + h].  For the calls that do not read
+ * interleaved words (more than 64 tokens, the fused launches, repack, embedding): a caller that keeps o_proj
+ * interleaved for decoding converts it into a scratch matrix for a prompt, the cost of one pass over the words.
+ * out_qweight: device, 16-byte aligned, [N_total][K_total / 8], must not overlap W->qweight; scales and zero points
+ * are shared as they are.  Errors: E_NULL, E_SHAPE (W is not interleaved), E_ALIGN, E_ARCH, E_HIP.
+ */
+int uniql_w4_deinterleave(const uniql_w4_t* W, uint32_t* out_qweight, void* hip_stream);
 
 /*
  * The gated MLP of one token (Eq. 1): y = W_down' (SiLU(W_gate' x) * (W_up' x)), W[0] = gate, W[1] = up, W[2] = down,

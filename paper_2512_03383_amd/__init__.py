@@ -85,6 +85,8 @@ def lib():
         L.uniql_w4_gate_up_silu.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, vp, vp]
         L.uniql_w4_interleave.restype = C.c_int
         L.uniql_w4_interleave.argtypes = [C.POINTER(W4), i32, vp, vp]
+        L.uniql_w4_deinterleave.restype = C.c_int
+        L.uniql_w4_deinterleave.argtypes = [C.POINTER(W4), vp, vp]
         L.uniql_w4_mlp.restype = C.c_int
         L.uniql_w4_mlp.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, vp, vp, i64, vp]
         L.uniql_w4_mlp_static.restype = C.c_int
@@ -408,6 +410,14 @@ def uniql_w4_interleave(W: QuantLinear, heads: int, stream=None) -> QuantLinear:
     out = torch.empty_like(W.qweight)
     _check(lib().uniql_w4_interleave(C.byref(W.desc()), int(heads), C.c_void_p(out.data_ptr()), _stream_ptr(stream)))
     return QuantLinear(out, W.scales, W.zeros, int(heads))
+
+
+def uniql_w4_deinterleave(W: QuantLinear, stream=None) -> QuantLinear:
+    """The same matrix with the words of every row back in column order (shares scales and zero points with W)."""
+    import torch
+    out = torch.empty_like(W.qweight)
+    _check(lib().uniql_w4_deinterleave(C.byref(W.desc()), C.c_void_p(out.data_ptr()), _stream_ptr(stream)))
+    return QuantLinear(out, W.scales, W.zeros, 0)
 
 
 def mlp_workspace(n_hidden_keep: int, device="cuda"):

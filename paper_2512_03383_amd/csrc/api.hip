@@ -122,13 +122,29 @@ static int fill_linear(const uniql_w4_t* W, const uniql_keep_t* keep, const void
   return UNIQL_OK;
 }
 
+constexpr int kInterleavedMaxTokens = 64;   // a matrix with head-interleaved words: tokens per call
+
 static int run_linear(const LinearArgs& a, hipStream_t s) {
   if (a.bits == 8) {
     hipError_t e8 = launch_w8_linear(a, s);
     if (e8 == hipErrorInvalidValue) return UNIQL_E_SHAPE;   // more kept columns than the kernel's staging holds
     return e8 == hipSuccess ? UNIQL_OK : hip_fail(e8);
   }
-  if (a.il_heads > 0 && a.M != 1) return UNIQL_E_SHAPE;   // head-interleaved words: one token only
+  if (a.il_heads > 0 && a.M != 1) {
+    // head-interleaved words are read by the one-token kernel only: a decode batch runs it token by token (the
+    // matrix stays in the memory-side cache between the launches); prompts want the words in column order
+    if (a.M > kInterleavedMaxTokens) return UNIQL_E_SHAPE;
+    for (int m = 0; m < a.M; ++m) {
+      LinearArgs t = a;
+      t.M = 1;
+      t.x = a.x + (size_t)m * a.ldx;
+      t.y = a.y + (size_t)m * a.ldy;
+      hipError_t et = launch_w4_gemv(t, s);
+      if (et == hipErrorInvalidValue) return UNIQL_E_SHAPE;
+      if (et != hipSuccess) return hip_fail(et);
+    }
+    return UNIQL_OK;
+  }
   hipError_t e = (a.M == 1) ? launch_w4_gemv(a, s) : launch_w4_gemm(a, s);
   if (e == hipErrorInvalidValue && a.M == 1) return UNIQL_E_SHAPE;   // K too long for the GEMV's staging
   return e == hipSuccess ? UNIQL_OK : hip_fail(e);
@@ -437,7 +453,20 @@ extern "C" int uniql_w4_interleave(const uniql_w4_t* W, int32_t heads, uint32_t*
   if (!aligned(out_qweight, 16)) return UNIQL_E_ALIGN;
   rc = check_arch();
   if (rc) return rc;
-  hipError_t e = launch_w4_interleave(W->qweight, out_qweight, W->N_total, W->K_total, heads, (hipStream_t)hip_stream);
+  hipError_t e = launch_w4_interleave(W->qweight, out_qweight, W->N_total, W->K_total, heads, false, (hipStream_t)hip_stream);
+  return e == hipSuccess ? UNIQL_OK : hip_fail(e);
+}
+
+extern "C" int uniql_w4_deinterleave(const uniql_w4_t* W, uint32_t* out_qweight, void* hip_stream) {
+  KeepMap km;
+  int rc = make_keepmap(W, nullptr, &km);
+  if (rc) return rc;
+  if (!out_qweight) return UNIQL_E_NULL;
+  if (W->col_interleave < 1) return UNIQL_E_SHAPE;
+  if (!aligned(out_qweight, 16)) return UNIQL_E_ALIGN;
+  rc = check_arch();
+  if (rc) return rc;
+  hipError_t e = launch_w4_interleave(W->qweight, out_qweight, W->N_total, W->K_total, W->col_interleave, true, (hipStream_t)hip_stream);
   return e == hipSuccess ? UNIQL_OK : hip_fail(e);
 }
 

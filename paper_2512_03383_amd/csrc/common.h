@@ -315,7 +315,8 @@ struct RepackArgs {
 };
 hipError_t launch_w4_repack(const RepackArgs& a, hipStream_t stream);
 // the words of every row from [heads][words per head] to [words per head][heads]
-hipError_t launch_w4_interleave(const uint32_t* qweight, uint32_t* out, int N_total, int K_total, int heads, hipStream_t stream);
+hipError_t launch_w4_interleave(const uint32_t* qweight, uint32_t* out, int N_total, int K_total, int heads, bool inverse,
+                                hipStream_t stream);
 
 struct RopeArgs {
   half_t* q;

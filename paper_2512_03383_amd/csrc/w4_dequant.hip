@@ -126,25 +126,37 @@ __global__ __launch_bounds__(256) void w4_repack_kernel(RepackArgs a) {
   }
 }
 
-// Words of every row from head-major [heads][words per head] to [words per head][heads].  A thread moves one word;
-// consecutive threads write consecutive words (the reads stride by a head: the pass runs once per matrix).
+// Words of every row from head-major [heads][words per head] to [words per head][heads], or back (INV).  A thread
+// moves one word; consecutive threads write consecutive words (the reads stride: the pass runs once per matrix).
+template <bool INV>
 __global__ __launch_bounds__(256) void w4_interleave_kernel(const uint32_t* __restrict__ qweight, uint32_t* __restrict__ out,
                                                             long long total, int words_per_row, int heads) {
   const int wph = words_per_row / heads;
   for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
     const long long row = i / words_per_row;
-    const int wo = (int)(i - row * words_per_row);    // output word: (d / 8) * heads + h
-    const int db = wo / heads, h = wo - db * heads;
-    out[i] = qweight[row * words_per_row + h * wph + db];
+    const int wo = (int)(i - row * words_per_row);    // output word
+    int src;
+    if constexpr (INV) {                              // wo = h * wph + d / 8
+      const int h = wo / wph, db = wo - h * wph;
+      src = db * heads + h;
+    } else {                                          // wo = (d / 8) * heads + h
+      const int db = wo / heads, h = wo - db * heads;
+      src = h * wph + db;
+    }
+    out[i] = qweight[row * words_per_row + src];
   }
 }
 
-hipError_t launch_w4_interleave(const uint32_t* qweight, uint32_t* out, int N_total, int K_total, int heads, hipStream_t stream) {
+hipError_t launch_w4_interleave(const uint32_t* qweight, uint32_t* out, int N_total, int K_total, int heads, bool inverse,
+                                hipStream_t stream) {
   const long long total = (long long)N_total * (K_total >> 3);
   long long blocks = (total + 255) / 256;
   if (blocks > 65536) blocks = 65536;
   if (blocks < 1) blocks = 1;
-  hipLaunchKernelGGL(w4_interleave_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, qweight, out, total, K_total >> 3, heads);
+  if (inverse)
+    hipLaunchKernelGGL(w4_interleave_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, stream, qweight, out, total, K_total >> 3, heads);
+  else
+    hipLaunchKernelGGL(w4_interleave_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, stream, qweight, out, total, K_total >> 3, heads);
   return hipGetLastError();
 }
 

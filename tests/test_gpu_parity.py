@@ -759,14 +759,69 @@ def test_head_interleaved_o_proj(env, uref, N, heads, d_keep, sym):
     assert np.array_equal(y.view(np.uint16), y2.view(np.uint16))
 
 
+@pytest.mark.parametrize("N,heads,d_keep,M", [(4096, 32, 108, 2), (4096, 32, 108, 8), (300, 4, 54, 64), (1000, 64, 128, 5)])
+def test_head_interleaved_decode_batches(env, uref, N, heads, d_keep, M):
+    """2..64 tokens on head-interleaved words (the one-token kernel, token by token), strided x and y: every output
+    against the oracle on the same words, and each token's row bit-identical to the one-token call."""
+    uq, torch = env
+    rng = wl.rng_for(19, N + heads + d_keep + M)
+    K = heads * 128
+    w = wl.gen_linear(rng, N, K)
+    keep = Keep() if d_keep == 128 else Keep(col_seg_stride=128, col_seg_keep=d_keep)
+    qi = uq.uniql_w4_interleave(uq.QuantLinear.from_numpy(w), heads)
+    words = qi.qweight.cpu().numpy().view(np.uint32)
+    kk = heads * d_keep
+    x = wl.gen_activations(rng, M, kk)
+    xd = torch.zeros((M, kk + 24), dtype=torch.float16, device="cuda")
+    xd[:, :kk] = to_dev(torch, x)
+    yd = torch.full((M, N + 8), 7.0, dtype=torch.float16, device="cuda")
+    uq.uniql_w4_linear(qi, keep, xd[:, :kk], yd[:, :N])
+    y = yd.cpu().numpy()
+    assert np.all(y[:, N:] == 7.0)                                    # nothing written past a row's outputs
+    ref = uref.w4_linear(words, w["scales"], w["zeros"], x, keep, il_heads=heads)
+    assert linear_err(y[:, :N], ref) <= TOL and normwise_err(y[:, :N], ref) <= NORM_TOL
+    for m in (0, M - 1):
+        y1 = uq.uniql_w4_linear(qi, keep, to_dev(torch, x[m:m + 1])).cpu().numpy()
+        assert np.array_equal(y1.view(np.uint16), np.ascontiguousarray(y[m:m + 1, :N]).view(np.uint16))
+
+
+@pytest.mark.parametrize("N,heads", [(4096, 32), (77, 8), (5, 3), (1000, 64)])
+def test_deinterleave_bit_exact(env, uref, N, heads):
+    """uniql_w4_deinterleave against the oracle's permutation, and the round trip through uniql_w4_interleave; the
+    result is the plain matrix: a prompt-sized linear on it equals the oracle on the interleaved words."""
+    uq, torch = env
+    rng = wl.rng_for(19, 3 * N + heads)
+    K = heads * 128
+    w = wl.gen_linear(rng, N, K)
+    qw = uq.QuantLinear.from_numpy(w)
+    qi = uq.uniql_w4_interleave(qw, heads)
+    back = uq.uniql_w4_deinterleave(qi)
+    torch.cuda.synchronize()
+    words_il = qi.qweight.cpu().numpy().view(np.uint32)
+    words = back.qweight.cpu().numpy().view(np.uint32)
+    assert back.col_interleave == 0
+    assert np.array_equal(words, uref.w4_deinterleave(words_il, heads))
+    assert np.array_equal(words, w["qweight"])
+    if N >= 64:
+        keep = Keep(col_seg_stride=128, col_seg_keep=108)
+        M = 70
+        x = wl.gen_activations(rng, M, heads * 108)
+        y = uq.uniql_w4_linear(back, keep, to_dev(torch, x)).cpu().numpy()
+        rows = np.unique(rng.integers(0, N, 48)).astype(np.int32)
+        ref = uref.w4_linear(words_il, w["scales"], w["zeros"], x, keep, rows=rows, il_heads=heads)
+        assert linear_err(y[:, rows], ref) <= TOL
+
+
 def test_head_interleaved_refusals(env):
     uq, torch = env
     rng = wl.rng_for(19, 1)
     qw = uq.QuantLinear.from_numpy(wl.gen_linear(rng, 64, 1024))
     qi = uq.uniql_w4_interleave(qw, 8)
     x2 = torch.zeros((2, 1024), dtype=torch.float16, device="cuda")
-    with pytest.raises(uq.UniqlError):       # one token only
-        uq.uniql_w4_linear(qi, None, x2)
+    with pytest.raises(uq.UniqlError):       # at most 64 tokens on interleaved words
+        uq.uniql_w4_linear(qi, None, torch.zeros((65, 1024), dtype=torch.float16, device="cuda"))
+    with pytest.raises(uq.UniqlError):       # a matrix in column order has nothing to undo
+        uq.uniql_w4_deinterleave(qw)
     with pytest.raises(uq.UniqlError):       # kept columns must be the leading dims of every head
         uq.uniql_w4_linear(qi, Keep(k_keep=512), x2[:1, :512].contiguous())
     with pytest.raises(uq.UniqlError):       # an interleaved matrix is not interleaved again
