@@ -561,9 +561,13 @@ static hipError_t stream_nch(const StreamArgs& a, int nch, hipStream_t stream) {
 // Rows below which the kernels of gemv_kernel.h are used: the walk pays off once every wave of the
 // persistent grid has more than a row or two.  Rows of up to four tiles (short tile rings, activations in
 // registers or few LDS reads) already gain from one row per wave.
-constexpr int kStreamMinRows = 8192;
+// (one-token launches, weights from HBM, this walk against the block kernel: 3584 rows of seven tiles 9.1 against
+// 10.1 us; segmented row rules, one division per row, 3072 rows x 3584 columns 4.2 against 4.5 us and 3482 x 4096 4.7
+// against 5.0 us)
+constexpr int kStreamMinRows = 8192;        // fused launches are measured from half of this
 constexpr int kStreamMinRowsShort = 2048;
-constexpr int kStreamMinRowsLong = 4096;    // row prefix with rows of more than four tiles (down_proj)
+constexpr int kStreamMinRowsLong = 2048;    // row prefix with rows of more than four tiles (down_proj)
+constexpr int kStreamMinRowsSeg = 2048;     // segmented row rules (q_proj's heads)
 constexpr int kStreamMinPairs = 1024;       // fused q / k / v: row pairs of the three matrices together
 
 static inline bool stream_shape(const LinearArgs& a, int max_tiles) {
@@ -631,8 +635,7 @@ static hipError_t stream_one(const LinearArgs& a, hipStream_t stream, bool* done
     return stream_interleaved<BF16>(a, stream);
   }
   const int nch = row_tiles(a.km.k_keep);
-  // (segmented row rules, one division per row, only from the higher threshold: q_proj sized launches measured slower)
-  const int min_rows = a.km.rs_stride != 0 ? kStreamMinRows : (nch <= 4 ? kStreamMinRowsShort : kStreamMinRowsLong);
+  const int min_rows = a.km.rs_stride != 0 ? kStreamMinRowsSeg : (nch <= 4 ? kStreamMinRowsShort : kStreamMinRowsLong);
   *done = stream_shape(a, 8) && a.km.n_keep >= min_rows;
   if (!*done) return hipSuccess;
   const StreamArgs s = stream_args(a);
