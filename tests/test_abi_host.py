@@ -322,6 +322,29 @@ def test_repack_rejects_bad_arguments():
     assert uq.lib().uniql_w4_repack_plan(C.byref(w), C.byref(bad), C.byref(n), C.byref(k), C.byref(ko)) == uq.UNIQL_E_KEEP
 
 
+def test_interleave_and_deinterleave_reject_bad_arguments():
+    """The two word permutations validate before any launch: NULL, a matrix in the wrong storage order, head counts that do not
+    cut the row into whole words, alignment; valid arguments get as far as the architecture check."""
+    lib = uq.lib()
+    il = lambda w, heads, out=P: lib.uniql_w4_interleave(C.byref(w) if w is not None else None, heads, C.c_void_p(out), None)
+    de = lambda w, out=P: lib.uniql_w4_deinterleave(C.byref(w) if w is not None else None, C.c_void_p(out), None)
+    plain, inter = _w(K=1024), _w(K=1024)
+    inter.col_interleave = 8
+    assert il(None, 8) == uq.UNIQL_E_NULL and de(None) == uq.UNIQL_E_NULL
+    assert il(plain, 8, out=0) == uq.UNIQL_E_NULL and de(inter, out=0) == uq.UNIQL_E_NULL
+    assert il(inter, 8) == uq.UNIQL_E_SHAPE                 # already interleaved
+    assert de(plain) == uq.UNIQL_E_SHAPE                    # nothing to undo
+    assert il(plain, 0) == uq.UNIQL_E_SHAPE and il(plain, 7) == uq.UNIQL_E_SHAPE and il(plain, 256) == uq.UNIQL_E_SHAPE
+    bad = _w(K=1024)
+    bad.col_interleave = 7                                  # a descriptor that claims an impossible head count
+    assert de(bad) == uq.UNIQL_E_SHAPE
+    assert il(plain, 8, out=P + 8) == uq.UNIQL_E_ALIGN and de(inter, out=P + 8) == uq.UNIQL_E_ALIGN
+    assert il(_w(K=1024, group=64), 8) == uq.UNIQL_E_SHAPE
+    import torch
+    if not torch.cuda.is_available():
+        assert il(plain, 8) in (uq.UNIQL_E_HIP, uq.UNIQL_E_ARCH) and de(inter) in (uq.UNIQL_E_HIP, uq.UNIQL_E_ARCH)
+
+
 def test_repack_plan_matches_the_oracle(uref):
     """The plan is host arithmetic (closed forms); the oracle derives it by scanning rows, columns and
     groups one by one."""
