@@ -55,6 +55,9 @@ struct StreamArgs {
   // head-interleaved words (HI): the row's words are stored as [dims / 8][heads], il_heads heads of 128 dims, of which
   // the leading d_keep are kept; x is compact [heads][d_keep]
   int il_heads, d_keep;
+  // column segments (CS): every cs_units * 8 stored columns keep their leading d_keep; the stored columns up to the last
+  // kept one are [0, k_span); x is compact [segments][d_keep]
+  int cs_units, k_span;
   // q, k, v of one token with the rotation of q and k (QKV): three matrices over one x, outputs y3[].  A body is one
   // pair of rows (p, p + hk) of a head, hk = D_keep / 2; bodies [0, pair_end[0]) are q's, [pair_end[0], pair_end[1])
   // k's, the rest v's (pairs of a head's rows like the others, not rotated); n_keep = 2 * all pairs.  Head h of matrix
@@ -99,12 +102,14 @@ struct StreamArgs {
 // puts into LDS once ([table row][pair], then one identity entry for v), and writes both outputs.  The loads of a
 // body go through the resources of that body's matrix; they are switched when a wave's next body lies in another
 // matrix (bodies are handed out in rising order, so at most twice per wave).
-template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE, bool XWAIT = false, bool YTHROUGH = false, bool HI = false, bool QKV = false>
+template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE, bool XWAIT = false, bool YTHROUGH = false, bool HI = false, bool QKV = false,
+          bool CS = false>
 __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* LDS, [NCH][4][64] units of 8 halves */,
                                              int* next_body_p /* LDS */, uint32_t tag = 0) {
   constexpr int TPR = NM * NCH;                                  // tiles per row (pair)
   constexpr int RB = QKV ? 2 : (TPR >= 4 ? 1 : 4 / TPR);         // rows per loop body
-  static_assert(!QKV || (NM == 1 && !SEG && !PROBE && !XWAIT && !YTHROUGH && !HI), "the fused q / k / v walk is a mode of its own");
+  static_assert(!QKV || (NM == 1 && !SEG && !PROBE && !XWAIT && !YTHROUGH && !HI && !CS), "the fused q / k / v walk is a mode of its own");
+  static_assert(!CS || (NM == 1 && !PROBE && !XWAIT && !HI), "column segments: one matrix, plain words");
   constexpr int D = RB * TPR;                                    // tiles per body = tiles in flight
   constexpr bool XREG = NCH <= 2;                                // activations live in registers
 
@@ -112,7 +117,7 @@ __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* L
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int total_waves = (int)gridDim.x * kStreamWaves;
   const int words_per_row = a.K_total >> 3, groups_per_row = a.K_total / kGroup;
-  const int k_span32 = (a.k_keep + 31) & ~31;
+  const int k_span32 = ((CS ? a.k_span : a.k_keep) + 31) & ~31;
 
   // ---- x loads first (memory returns in issue order; x is an L2 hit).  Unit u = stored columns [8u, 8u + 8).
   constexpr int XI = (NCH * 256 + kStreamThreads - 1) / kStreamThreads;
@@ -120,14 +125,19 @@ __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* L
   const uint16_t* xbits = reinterpret_cast<const uint16_t*>(a.x);
   uint4 rawv[XI];
   uint32_t tailv[8];
-  uint32_t elv[HI ? XI : 1][8];   // HI: the kept dims of a unit that is only partly kept, one per register
+  uint32_t elv[(HI || CS) ? XI : 1][8];   // HI, CS: the kept dims of a unit that is only partly kept, one per register
   auto load_x = [&]() {
-    if constexpr (HI) {
+    if constexpr (HI || CS) {
 #pragma unroll
       for (int i = 0; i < XI; ++i) {
-        const int u = tid + i * kStreamThreads;           // word of the row: head u % H, dims 8 (u / H) ..
-        const int dblk = u / a.il_heads, head = u - dblk * a.il_heads;
-        const int nk = a.d_keep - 8 * dblk;               // kept dims of the unit, counted from its first
+        // HI: word u of the row is head u % H, dims 8 (u / H) ..; CS: unit u is segment u / cs_units, columns
+        // 8 (u % cs_units) .. of it (nothing past the row's last kept column)
+        const int u = tid + i * kStreamThreads;
+        int dblk, head;
+        if constexpr (HI) { dblk = u / a.il_heads; head = u - dblk * a.il_heads; }
+        else { head = u / a.cs_units; dblk = u - head * a.cs_units; }
+        int nk = a.d_keep - 8 * dblk;                     // kept dims of the unit, counted from its first
+        if constexpr (CS) nk = 8 * u < a.k_span ? nk : 0;
         const int base = head * a.d_keep + 8 * dblk;
         rawv[i] = load_u4_unaligned(a.x + (nk >= 8 ? base : 0));
 #pragma unroll
@@ -328,8 +338,9 @@ __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* L
                               r.z & 0xffffu, r.z >> 16, r.w & 0xffffu, r.w >> 16};
     const bool whole = k0 + 8 <= kv, tail = k0 == kv;
     uint32_t e[8];
-    if constexpr (HI) {
-      const int nk = a.d_keep - 8 * (u / a.il_heads);
+    if constexpr (HI || CS) {
+      int nk = a.d_keep - 8 * (HI ? u / a.il_heads : u % a.cs_units);
+      if constexpr (CS) nk = 8 * u < a.k_span ? nk : 0;
 #pragma unroll
       for (int j = 0; j < 8; ++j) e[j] = nk >= 8 ? full[j] : elv[i][j];   // (elv is zero where nothing is kept)
     } else {
@@ -501,16 +512,16 @@ __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* L
 }
 
 
-template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE = false, bool HI = false, bool QKV = false>
+template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE = false, bool HI = false, bool QKV = false, bool CS = false>
 __global__ __launch_bounds__(kStreamThreads) void w4_gemv_stream_kernel(StreamArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int next_body;
-  stream_phase<NCH, NM, ZP, BF16, SEG, PROBE, false, false, HI, QKV>(a, reinterpret_cast<uint4*>(smem), &next_body);
+  stream_phase<NCH, NM, ZP, BF16, SEG, PROBE, false, false, HI, QKV, CS>(a, reinterpret_cast<uint4*>(smem), &next_body);
 }
 
-template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE, bool HI = false, bool QKV = false>
+template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE, bool HI = false, bool QKV = false, bool CS = false>
 static hipError_t stream_launch(const StreamArgs& a, hipStream_t stream) {
-  auto kern = w4_gemv_stream_kernel<NCH, NM, ZP, BF16, SEG, PROBE, HI, QKV>;
+  auto kern = w4_gemv_stream_kernel<NCH, NM, ZP, BF16, SEG, PROBE, HI, QKV, CS>;
   // the image of x, then (QKV) the sin / cos table and its identity entry
   const size_t smem = (size_t)NCH * 4096 + (QKV ? ((size_t)a.H_tab * a.hk + 1) * sizeof(float2_t) : 0);
   // CU count per device ordinal, read once (host threads that race on the first call all store the same value)
@@ -537,21 +548,21 @@ static hipError_t stream_launch(const StreamArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
-template <int NM, bool ZP, bool BF16, bool SEG, bool PROBE>
+template <int NM, bool ZP, bool BF16, bool SEG, bool PROBE, bool CS = false>
 static hipError_t stream_nch(const StreamArgs& a, int nch, hipStream_t stream) {
   switch (nch) {
-    case 1: return stream_launch<1, NM, ZP, BF16, SEG, PROBE>(a, stream);
-    case 2: return stream_launch<2, NM, ZP, BF16, SEG, PROBE>(a, stream);
-    case 3: return stream_launch<3, NM, ZP, BF16, SEG, PROBE>(a, stream);
-    case 4: return stream_launch<4, NM, ZP, BF16, SEG, PROBE>(a, stream);
+    case 1: return stream_launch<1, NM, ZP, BF16, SEG, PROBE, false, false, CS>(a, stream);
+    case 2: return stream_launch<2, NM, ZP, BF16, SEG, PROBE, false, false, CS>(a, stream);
+    case 3: return stream_launch<3, NM, ZP, BF16, SEG, PROBE, false, false, CS>(a, stream);
+    case 4: return stream_launch<4, NM, ZP, BF16, SEG, PROBE, false, false, CS>(a, stream);
     default: break;
   }
   if constexpr (NM == 1) {
     switch (nch) {
-      case 5: return stream_launch<5, 1, ZP, BF16, SEG, PROBE>(a, stream);
-      case 6: return stream_launch<6, 1, ZP, BF16, SEG, PROBE>(a, stream);
-      case 7: return stream_launch<7, 1, ZP, BF16, SEG, PROBE>(a, stream);
-      case 8: return stream_launch<8, 1, ZP, BF16, SEG, PROBE>(a, stream);
+      case 5: return stream_launch<5, 1, ZP, BF16, SEG, PROBE, false, false, CS>(a, stream);
+      case 6: return stream_launch<6, 1, ZP, BF16, SEG, PROBE, false, false, CS>(a, stream);
+      case 7: return stream_launch<7, 1, ZP, BF16, SEG, PROBE, false, false, CS>(a, stream);
+      case 8: return stream_launch<8, 1, ZP, BF16, SEG, PROBE, false, false, CS>(a, stream);
       default: break;
     }
   }
@@ -578,6 +589,16 @@ static inline bool stream_shape(const LinearArgs& a, int max_tiles) {
   return a.M == 1 && a.il_heads == 0 && km.cs_stride == 0 && km.k_keep >= 8 && nch <= max_tiles && fits && whole_quads(a.K_total, nch);
 }
 
+// The same for column segments whose stride is a whole number of 8-column units (o_proj on head-major words, the SSM
+// output projection): the activations are staged segment by segment, everything else is the walk over a row prefix.
+static inline bool stream_shape_cs(const LinearArgs& a, int max_tiles) {
+  const KeepMap& km = a.km;
+  const int nch = row_tiles(km.k_span);
+  const bool fits = (long long)a.N_total * (a.K_total / 2) < (1ll << 31);
+  return a.M == 1 && a.il_heads == 0 && km.cs_stride >= 8 && km.cs_stride % 8 == 0 && km.cs_keep >= 1 && km.k_keep >= 8 &&
+         km.rs_stride == 0 && nch <= max_tiles && fits && whole_quads(a.K_total, nch);
+}
+
 static inline StreamArgs stream_args(const LinearArgs& a) {
   StreamArgs s;
   s.qweight[0] = s.qweight[1] = a.qweight;
@@ -595,6 +616,8 @@ static inline StreamArgs stream_args(const LinearArgs& a) {
   s.wait_ticks = 0;
   s.il_heads = a.il_heads;
   s.d_keep = a.km.cs_stride ? a.km.cs_keep : kGroup;
+  s.cs_units = a.km.cs_stride ? a.km.cs_stride / 8 : 1;
+  s.k_span = a.km.k_span;
   s.qweight[2] = nullptr; s.scales[2] = nullptr; s.zeros[2] = nullptr;
   s.y3[0] = s.y3[1] = s.y3[2] = nullptr;
   s.pair_end[0] = s.pair_end[1] = 0;
@@ -633,6 +656,13 @@ static hipError_t stream_one(const LinearArgs& a, hipStream_t stream, bool* done
   if (a.il_heads > 0) {
     *done = true;
     return stream_interleaved<BF16>(a, stream);
+  }
+  if (a.km.cs_stride != 0) {
+    *done = stream_shape_cs(a, 8) && a.km.n_keep >= kStreamMinRowsShort;
+    if (!*done) return hipSuccess;
+    const StreamArgs s = stream_args(a);
+    const int nch_cs = row_tiles(a.km.k_span);
+    return a.zeros ? stream_nch<1, true, BF16, false, false, true>(s, nch_cs, stream) : stream_nch<1, false, BF16, false, false, true>(s, nch_cs, stream);
   }
   const int nch = row_tiles(a.km.k_keep);
   const int min_rows = a.km.rs_stride != 0 ? kStreamMinRowsSeg : (nch <= 4 ? kStreamMinRowsShort : kStreamMinRowsLong);
