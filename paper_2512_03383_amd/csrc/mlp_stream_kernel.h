@@ -46,7 +46,11 @@ __global__ __launch_bounds__(kStreamThreads) void w4_mlp_stream_kernel(MlpArgs m
   // this launch's tag: one more than the last finished launch's (nobody changes the word while this launch runs)
   const uint32_t tag = __hip_atomic_load(m.ctrl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
   stream_phase<NCH1, 2, ZP, BF16, false, false, false, true>(m.gu, xs, &next_body, tag);
-  // every wave waits for the acknowledgements of its stores to h; then the block says that it has arrived
+  // every wave waits for the acknowledgements of its own stores to h (written through: acknowledged from memory), and
+  // only then meets the others; then the block says that it has arrived.  The wait is spelled out: a release fence
+  // at workgroup scope orders the stores for the waves of this block only and does not wait for them, and the waiting
+  // that the compiler puts before thread 0's store below covers the stores of that one wave.
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __syncthreads();
   if (threadIdx.x == 0) __hip_atomic_store(m.dn.arrived + blockIdx.x, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
