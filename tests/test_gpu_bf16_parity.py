@@ -207,6 +207,11 @@ def test_llama3_8b_decode_layer_full_size(env, uref, rate):
     (8300, 6144, Keep(k_keep=6100)),                       # three chunks: activations read from LDS per tile
     (8200, 14336, Keep(k_keep=12185)),                     # six
     (8200, 16384, Keep(k_keep=16383)),                     # eight chunks
+    (2304, 1024, Keep(col_seg_stride=128, col_seg_keep=108)),              # column segments: a partly kept unit per segment
+    (2100, 2048, Keep(col_seg_stride=64, col_seg_keep=37)),                # odd keep
+    (2200, 6144, Keep(col_seg_stride=128, col_seg_keep=82)),               # three chunks
+    (4096, 1024, Keep(n_keep=3456, row_seg_stride=128, row_seg_keep=108, row_seg_limit=4096)),   # row segments
+    (2048, 10240, Keep()),                                 # the row threshold of long rows
 ])
 @pytest.mark.parametrize("sym", [False, True])
 def test_streaming_gemv_shapes(env, uref, N, K, keep, sym):

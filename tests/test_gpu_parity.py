@@ -1038,10 +1038,14 @@ def test_fused_launches_dequant_embedding_repack_without_zero_points(env, uref):
 
 # ------------------------------------------------- persistent streaming GEMV (tall row-prefix x column-prefix matrices)
 @pytest.mark.parametrize("N,K,keep", [
-    (2048, 128, Keep()),                                   # one chunk, a single group per row, exactly the row threshold of short rows
+    (2048, 128, Keep()),                                   # one chunk, a single group per row, exactly the row threshold
     (2047, 1024, Keep()),                                  # one row below it: the block-per-rows kernel
     (2560, 5120, Keep(k_keep=4352)),                       # Mamba2 out_proj: three chunks
-    (8192, 10240, Keep()),                                 # exactly the row threshold of long rows
+    (8192, 10240, Keep()),                                 # five chunks, tall
+    (2048, 10240, Keep()),                                 # exactly the row threshold of long rows
+    (2047, 10240, Keep()),                                 # one row below it: the block-per-rows kernel
+    (4096, 1024, Keep(n_keep=3456, row_seg_stride=128, row_seg_keep=108, row_seg_limit=4096)),   # row segments (q_proj's rule) on the walk
+    (2432, 2048, Keep(n_keep=2052, row_seg_stride=64, row_seg_keep=54, row_seg_limit=2432, k_keep=2001)),   # ... just above its threshold, with a column tail
     (9001, 1024, Keep(k_keep=1001)),                       # ragged rows, column prefix with a tail of one
     (12000, 2304, Keep(n_keep=8193, k_keep=2055)),         # two chunks, 18 groups per row, tail of seven
     (8200, 4096, Keep(n_keep=8197, k_keep=8)),             # the narrowest prefix the vector staging takes
@@ -1065,6 +1069,38 @@ def test_streaming_gemv_shapes(env, uref, N, K, keep, sym):
     # every row against the oracle: the walk must reach each one exactly once
     ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], x, keep)
     assert y.shape == ref.shape and linear_err(y, ref) <= TOL
+
+
+@pytest.mark.parametrize("N,K,keep", [
+    (2304, 1024, Keep(col_seg_stride=128, col_seg_keep=108)),              # o_proj's rule: a partly kept unit per segment
+    (2304, 1024, Keep(col_seg_stride=128, col_seg_keep=1)),                # one column per segment
+    (2100, 2048, Keep(col_seg_stride=64, col_seg_keep=37)),                # odd keep, two segments per group
+    (2048, 4096, Keep(col_seg_stride=8, col_seg_keep=5)),                  # a segment is one unit; the row threshold
+    (2047, 4096, Keep(col_seg_stride=8, col_seg_keep=5)),                  # one row below it: the block-per-rows kernel
+    (2500, 4096, Keep(n_keep=2049, col_seg_stride=256, col_seg_keep=255)), # row prefix x column segments
+    (2200, 6144, Keep(col_seg_stride=128, col_seg_keep=82)),               # three chunks
+    (3584, 3584, Keep(col_seg_stride=128, col_seg_keep=96)),               # Qwen2.5-7B o_proj at 25 %
+    (2100, 16384, Keep(col_seg_stride=1024, col_seg_keep=1000)),           # eight chunks
+    (2100, 1024, Keep(col_seg_stride=128, col_seg_keep=128)),              # segments kept whole
+])
+@pytest.mark.parametrize("sym", [False, True])
+def test_streaming_gemv_column_segments(env, uref, N, K, keep, sym):
+    """One token on matrices whose kept columns are the leading ones of every segment (stride a multiple of 8), from
+    the row count the persistent walk takes: every row against the oracle, and the same bits on a second call."""
+    uq, torch = env
+    rng = wl.rng_for(13, 7 * N + K + keep.col_seg_keep)
+    w = wl.gen_linear(rng, N, K)
+    if sym:
+        w["zeros"] = None
+    qw = uq.QuantLinear.from_numpy(w)
+    nk, kk = uref.count_kept(N, K, keep)
+    x = wl.gen_activations(rng, 1, kk)
+    y = run_linear(uq, torch, w, qw, keep, x, pad=5)
+    ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], x, keep)
+    assert y.shape == ref.shape and linear_err(y, ref) <= TOL
+    assert normwise_err(y, ref) <= NORM_TOL
+    y2 = run_linear(uq, torch, w, qw, keep, x, pad=5)
+    assert np.array_equal(y.view(np.uint16), y2.view(np.uint16))
 
 
 @pytest.mark.parametrize("N,K,keep", [
