@@ -318,13 +318,32 @@ def test_prefill_gemm_sampled(env, uref, M):
         x = wl.gen_activations(rng, M, spec.k_keep, fmt=FMT)
         y = uq.uniql_w4_linear(qw, spec.keep, dev_bf16(torch, x))
         torch.cuda.synchronize()
-        toks = np.unique(np.concatenate([[0, M - 1], rng.integers(0, M, 6)]))
+        toks = np.unique(np.concatenate([[0, 255, M - 256, M - 1], rng.integers(0, M, 6)]))
         rows = _sample_rows(spec.n_keep, rng, 64)
         ref = oracle_linear(uref, w, np.ascontiguousarray(x[toks]), spec.keep, rows=rows)
         rms = np.sqrt(np.mean(ref ** 2, axis=-1, keepdims=True))
         got = host_vals(y[torch.from_numpy(toks).cuda()][:, torch.from_numpy(rows.astype(np.int64)).cuda()])
         err = np.max(np.abs(got - ref) / np.maximum(np.abs(ref), 1e-2 * rms))
         assert err <= TOL_BF16, (spec.name, err)
+
+
+def test_prefill_persistent_tiles_ragged(env, uref):
+    """256 x 256 tiles on the persistent grid with ragged rows, tokens and a column tail: sampled (token, row) pairs
+    that include the edges of the first and last tiles."""
+    uq, torch = env
+    rng = wl.rng_for(28, 1)
+    N, K, keep, M = 12300, 1152, Keep(n_keep=12200, k_keep=1100), 1000
+    w = gen(rng, N, K)
+    qw = uq.QuantLinear.from_numpy(w)
+    x = wl.gen_activations(rng, M, 1100, fmt=FMT)
+    y = uq.uniql_w4_linear(qw, keep, dev_bf16(torch, x))
+    torch.cuda.synchronize()
+    toks = np.unique(np.concatenate([[0, 255, 256, 767, 768, M - 1], rng.integers(0, M, 6)]))
+    rows = np.unique(np.concatenate([_sample_rows(12200, rng, 64), [255, 256, 12031, 12032, 12199]])).astype(np.int32)
+    ref = oracle_linear(uref, w, np.ascontiguousarray(x[toks]), keep, rows=rows)
+    rms = np.sqrt(np.mean(ref ** 2, axis=-1, keepdims=True))
+    got = host_vals(y[torch.from_numpy(toks).cuda()][:, torch.from_numpy(rows.astype(np.int64)).cuda()])
+    assert np.max(np.abs(got - ref) / np.maximum(np.abs(ref), 1e-2 * rms)) <= TOL_BF16
 
 
 def test_prefill_tiles_ragged(env, uref):

@@ -347,7 +347,7 @@ def test_prefill_gemm_sampled(env, uref, M):
         qw = uq.QuantLinear.from_numpy(w)
         x = wl.gen_activations(rng, M, spec.k_keep)
         y = run_linear(uq, torch, w, qw, spec.keep, x)
-        toks = np.unique(np.concatenate([[0, 127, 128, M - 129, M - 128, M - 1], rng.integers(0, M, 6)]))
+        toks = np.unique(np.concatenate([[0, 127, 128, 255, M - 257, M - 256, M - 129, M - 128, M - 1], rng.integers(0, M, 6)]))
         rows = np.unique(np.concatenate([_sample_rows(spec.n_keep, rng, 64),
                                          [255, 256, spec.n_keep - spec.n_keep % 256 - 1, spec.n_keep - spec.n_keep % 256]]))
         rows = rows[(rows >= 0) & (rows < spec.n_keep)].astype(np.int32)
@@ -381,6 +381,9 @@ def test_lm_head_sized_gemv_sampled(env, uref):
     (3072, 1280, Keep(k_keep=1279), 500),                  # 64 x 128 tiles with K split over two waves
     (6144, 1024, Keep(k_keep=1000), 500),                  # 64 x 256 tiles
     (512, 2048, Keep(), 130),
+    (12300, 1152, Keep(n_keep=12200, k_keep=1100), 1000),  # 256 x 256 tiles on the persistent grid: ragged rows, tokens, K tail
+    (12288, 1024, Keep(k_keep=1017), 4096),                # ... three tiles per block, a column tail of one
+    (4096, 2176, Keep(k_keep=2049), 4000),                 # ... one tile per block, the last token tile ragged
 ])
 def test_prefill_tiles_ragged(env, uref, N, K, keep, M):
     """The prefill tile configurations (128 x 256 hand-scheduled kernel when the grid fills the chip, smaller
@@ -392,9 +395,9 @@ def test_prefill_tiles_ragged(env, uref, N, K, keep, M):
     nk, kk = uq.kept_dims(qw, keep)
     x = wl.gen_activations(rng, M, kk)
     y = run_linear(uq, torch, w, qw, keep, x)
-    toks = np.unique(np.concatenate([[0, 63, 64, 127, 128, M - 1], rng.integers(0, M, 6)]))
+    toks = np.unique(np.concatenate([[0, 63, 64, 127, 128, min(255, M - 1), min(256, M - 1), M - M % 256 - 1, M - 1], rng.integers(0, M, 6)]))
     rows = _sample_rows(nk, rng, 96)
-    rows = np.unique(np.concatenate([rows, [255, 256, min(nk - 1, 4095)]])).astype(np.int32)
+    rows = np.unique(np.concatenate([rows, [255, 256, min(nk - 1, 4095), nk - nk % 256 - 1, nk - 1]])).astype(np.int32)
     ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], np.ascontiguousarray(x[toks]), keep, rows=rows)
     rms = np.sqrt(np.mean(ref ** 2, axis=-1, keepdims=True))
     got = y[np.ix_(toks, rows)].astype(np.float64)
