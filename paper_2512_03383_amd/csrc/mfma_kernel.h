@@ -404,12 +404,12 @@ static hipError_t launch_m(const LinearArgs& a, hipStream_t stream) {
   // (bfloat16: with the longer unpack two slabs of weight loads in flight do not fit 256 registers; one does)
   // 256 x 256 on a persistent grid (prefill_kernel.h), where its tiles fill the chip in fewer, longer rounds than
   // twice as many 128 x 256 tiles would: a round of it takes about 1.8 rounds of those
-  // (gate / up at 4096 tokens 428 against 487 us in the same process, down 433 against 472, gate / up at 1000 tokens 139 against 160)
+  // (gate / up at 4096 tokens 412 against 472 us in the same process, down 389 against 477, gate / up at 1000 tokens 131 against 164)
   if constexpr (XVEC == 1) {
     if (prefill_serves(a) && blocks(256, 256) >= kEnough) {
       const long long cus = prefill_grid_limit();
       const long long rounds_big = (blocks(256, 256) + cus - 1) / cus, rounds_std = (blocks(128, 256) + cus - 1) / cus;
-      if (rounds_big * 18 < rounds_std * 10) return launch_prefill_cfg<BF16, 16, 2, 8, 1, 1, 8, 4, 0>(a, stream);
+      if (rounds_big * 18 < rounds_std * 10) return launch_prefill_cfg<BF16, 16, 2, 8, 1, 1, 8, 2, 1>(a, stream);
     }
   }
   if (blocks(128, 256) >= kEnough) {

@@ -12,9 +12,11 @@
 //  - activations and weights are fetched through buffer resources: one VGPR offset per thread that never changes,
 //    the per-unit and per-iteration parts are scalar, rows past the last token return zeros by the range check; the
 //    LDS address of a thread's units differs by a constant, so the writes carry immediate offsets;
-//  - the 128 accumulator registers leave room for one set of eight activation fragments, so a step runs in two
-//    phases (read eight fragments, sixteen matrix instructions) and it is the SIMD's other wave that covers the LDS
-//    latency; the staging registers hold half a slab's units at a time;
+//  - beside the 128 accumulator registers there is room for two sets of eight activation fragments (a step runs in
+//    two phases; the fragments of the next phase are read from LDS while the current phase multiplies) because the
+//    staging registers hold only a quarter of a slab's units at a time and one slab of weight loads is in flight;
+//    the only branch-free way found to drop the column mask of the staging from the common path (two loops under a
+//    uniform branch) cost 8 to 19 % and is not used;
 //  - the matrix instruction takes the weights as its first operand, so a lane ends up with four consecutive output
 //    rows of one token and stores them with one 8-byte store;
 //  - the grid is persistent (see the kernel).
