@@ -384,6 +384,7 @@ def test_lm_head_sized_gemv_sampled(env, uref):
     (12300, 1152, Keep(n_keep=12200, k_keep=1100), 1000),  # 256 x 256 tiles on the persistent grid: ragged rows, tokens, K tail
     (12288, 1024, Keep(k_keep=1017), 4096),                # ... three tiles per block, a column tail of one
     (4096, 2176, Keep(k_keep=2049), 4000),                 # ... one tile per block, the last token tile ragged
+    (12800, 1024, Keep(n_keep=12400, row_seg_stride=128, row_seg_keep=124, row_seg_limit=12800), 1024),   # ... row segments
 ])
 def test_prefill_tiles_ragged(env, uref, N, K, keep, M):
     """The prefill tile configurations (128 x 256 hand-scheduled kernel when the grid fills the chip, smaller
