@@ -359,6 +359,31 @@ def test_prefill_gemm_sampled(env, uref, M):
         assert normwise_err(y[np.ix_(toks, rows)], ref) <= NORM_TOL, spec.name
 
 
+def test_prefill_persistent_kernel_without_zero_points_and_strided(env, uref):
+    """The 256 x 256 persistent prefill kernel on a matrix without zero points, x and y with row strides larger than
+    their widths (odd ones), sampled against the oracle; nothing is written between the rows of y."""
+    uq, torch = env
+    rng = wl.rng_for(4, 777)
+    N, K, M = 12288, 1024, 1030
+    keep = Keep(n_keep=12285, k_keep=1003)
+    w = wl.gen_linear(rng, N, K)
+    w["zeros"] = None
+    qw = uq.QuantLinear.from_numpy(w)
+    x = wl.gen_activations(rng, M, 1003)
+    xd = torch.zeros((M, 1003 + 19), dtype=torch.float16, device="cuda")
+    xd[:, :1003] = to_dev(torch, x)
+    yd = torch.full((M, 12285 + 7), 3.0, dtype=torch.float16, device="cuda")
+    uq.uniql_w4_linear(qw, keep, xd[:, :1003], yd[:, :12285])
+    y = yd.cpu().numpy()
+    assert np.all(y[:, 12285:] == 3.0)
+    toks = np.unique(np.concatenate([[0, 255, 256, 1023, 1024, M - 1], rng.integers(0, M, 6)]))
+    rows = np.unique(np.concatenate([_sample_rows(12285, rng, 96), [255, 256, 12031, 12032, 12283, 12284]])).astype(np.int32)
+    ref = uref.w4_linear(w["qweight"], w["scales"], None, np.ascontiguousarray(x[toks]), keep, rows=rows)
+    rms = np.sqrt(np.mean(ref ** 2, axis=-1, keepdims=True))
+    got = y[np.ix_(toks, rows)].astype(np.float64)
+    assert np.max(np.abs(got - ref) / np.maximum(np.abs(ref), 1e-2 * rms)) <= TOL
+
+
 def test_lm_head_sized_gemv_sampled(env, uref):
     """The output-head shape (128256 x 4096, unpruned), M = 1: sampled rows against the oracle."""
     uq, torch = env
