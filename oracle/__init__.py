@@ -193,11 +193,11 @@ def w4_linear(qweight, scales, zeros, x, keep=None, group: int = 128,
 
 
 def wq_dequant(bits: int, qweight, scales, zeros, keep=None, group: int = 128, fmt: str = "f16") -> np.ndarray:
-    """Kept part of the dequantised matrix with codes of `bits` bits (4, or 8: qweight uint32 [N][K/4], zeros
-    0..255 or None = 128), as float16 (fmt "f16") or bfloat16 bit patterns (uint16, fmt "bf16")."""
+    """Kept part of the dequantised matrix with codes of `bits` bits (3, 4, 6 or 8: qweight uint32 [N][K * bits / 32],
+    a row's codes as one little-endian bit stream; zeros 0..2^bits - 1 or None = 2^(bits-1)), as float16 (fmt "f16") or bfloat16 bit patterns (uint16, fmt "bf16")."""
     _chk(qweight, np.uint32, "qweight"); _chk(scales, _f16_dtype(fmt), "scales"); _chkz(zeros)
     N, Kw = qweight.shape
-    K = Kw * (32 // bits)
+    K = Kw * 32 // bits
     ka = _keep_arr(keep)
     nk, kk = count_kept(N, K, ka)
     out = np.empty((nk, kk), dtype=_f16_dtype(fmt))
@@ -211,7 +211,7 @@ def wq_linear(bits: int, qweight, scales, zeros, x, keep=None, group: int = 128,
     _chk(qweight, np.uint32, "qweight"); _chk(scales, _f16_dtype(fmt), "scales"); _chkz(zeros)
     _chk(x, _f16_dtype(fmt), "x")
     N, Kw = qweight.shape
-    K = Kw * (32 // bits)
+    K = Kw * 32 // bits
     ka = _keep_arr(keep)
     nk, kk = count_kept(N, K, ka)
     M = x.shape[0]

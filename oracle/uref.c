@@ -32,9 +32,9 @@
  *        index vector, one half stored; one table per KV head under GQA); Fig. 4a
  *   uref_pruned_rope_f64               the same rotation on fp64 inputs: the second half of the
  *        fused step y = RoPE(X W) (Eq. 2, then Sec. 3.2), no rounding in between
- *   uref_wq_dequant / uref_wq_linear / uref_quantize_sym_bits   the same with codes of 8 bits (Eq. 3 with N = 8;
- *        Sec. 3.4 and App. C say the method covers 8, 6, 4 and 3 bits; only 4 and 8 have a packed format here: 3-bit
- *        the paper itself only simulates in FP16)
+ *   uref_wq_dequant / uref_wq_linear / uref_quantize_sym_bits   the same with codes of 8, 6 or 3 bits (Eq. 3 with
+ *        N = bits; Sec. 3.4 and App. C name 8, 6, 4 and 3 bits as the widths the method covers; the paper states a
+ *        packing for none but INT4-in-INT32, the bit-stream order below is this build's reading)
  *   uref_quantize_sym                  Eq. 3 (symmetric, N = 4)
  *   uref_quantize_asym                 the min/max asymmetric variant the
  *        benchmark configuration asks for (not in the paper; Eq. 3 is the case
@@ -207,16 +207,28 @@ static int word_of_col(int K_total, int il_heads, int k) {
   return (d / 8) * il_heads + h;
 }
 
-/* one dequantised weight as 16-bit float bits of format fmt: RN16((q - z) * s).  bits = 4 or 8 is the width of a
- * code (Eq. 3's N): a word holds 32 / bits codes, code j in bits [bits * j, bits * j + bits), and without zero
- * points z = 2^(bits - 1), the offset that stores Eq. 3's signed code as an unsigned one.  The product is exact in
- * fp64 for either width (|q - z| <= 255 times an 11-bit significand). */
+/* one dequantised weight as 16-bit float bits of format fmt: RN16((q - z) * s).  bits = 3, 4, 6 or 8 is the width
+ * of a code (Eq. 3's N).  A row's codes form one little-endian bit stream over its 32-bit words: code k occupies bits
+ * [bits * k, bits * k + bits) of the stream, bit b of the stream being bit b % 32 of word b / 32 (for 4 and 8 bits
+ * that is the nibble / byte order above; codes of 3 and 6 bits may run over a word boundary, low part in the earlier
+ * word).  Without zero points z = 2^(bits - 1), the offset that stores Eq. 3's signed code as an unsigned one.  The
+ * product is exact in fp64 for every width (|q - z| <= 255 times an 11-bit significand). */
+static int code_width_ok(int bits) { return bits == 3 || bits == 4 || bits == 6 || bits == 8; }
+
 static uint16_t dequant_bits(int bits, const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
                              int K_total, int group, int r, int k, int fmt, int il_heads) {
-  int cpw = 32 / bits;   /* codes per word */
-  int word_idx = bits == 4 ? word_of_col(K_total, il_heads, k) : k / cpw;
-  uint32_t word = qweight[(size_t)r * (K_total / cpw) + word_idx];
-  int q = (int)((word >> (bits * (k % cpw))) & ((1u << bits) - 1u));
+  size_t words_per_row = (size_t)K_total * (size_t)bits / 32;
+  const uint32_t* row = qweight + (size_t)r * words_per_row;
+  int q;
+  if (bits == 4) {
+    q = (int)((row[word_of_col(K_total, il_heads, k)] >> (4 * (k % 8))) & 15u);
+  } else {
+    q = 0;
+    for (int b = 0; b < bits; ++b) {          /* bit by bit from the stream */
+      size_t pos = (size_t)bits * (size_t)k + (size_t)b;
+      q |= (int)((row[pos / 32] >> (pos % 32)) & 1u) << b;
+    }
+  }
   size_t g = (size_t)r * (K_total / group) + k / group;
   int z = zeros ? zeros[g] : 1 << (bits - 1);   /* no zero points: the symmetric codes of Eq. 3, stored as signed code + 2^(N-1) */
   double s = f16_to_double(scales[g], fmt);
@@ -349,12 +361,14 @@ int uref_w4_linear(const uint32_t* qweight, const uint16_t* scales, const uint8_
 }
 
 /* ---- other code widths (Sec. 3.4 / App. C: the method quantises to 8, 6, 4 and 3 bits; Eq. 3 with N = bits).
- * bits = 8: qweight uint32 [N_total][K_total/4], byte j of word w of a row is input column 4w+j; zeros uint8 0..255
- * or NULL (every zero point 128).  bits = 4 is the format above.  Everything else -- groups, the keep rule, RN16 of
+ * qweight uint32 [N_total][K_total * bits / 32], a row's codes as one bit stream (see dequant_bits; bits = 8: byte j of
+ * word w is input column 4w+j); zeros uint8 0..2^bits - 1 or NULL (every zero point 2^(bits-1)).  bits = 4 is the
+ * format above.  K_total must be a multiple of 32 so that rows are whole words (it is a multiple of the group).
+ * Everything else -- groups, the keep rule, RN16 of
  * (q - z) * s, fp64 sums in index order -- is as in uref_w4_dequant_fmt / uref_w4_linear_fmt. */
 int uref_wq_dequant(int bits, const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros,
                     int N_total, int K_total, int group, const int32_t* keep, uint16_t* w_f16, int fmt) {
-  if (bits != 4 && bits != 8) return -3;
+  if (!code_width_ok(bits)) return -3;
   static const int32_t none[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   if (!keep) keep = none;
   int32_t* rows = (int32_t*)malloc(sizeof(int32_t) * (size_t)N_total);
@@ -373,7 +387,7 @@ int uref_wq_linear(int bits, const uint32_t* qweight, const uint16_t* scales, co
                    int N_total, int K_total, int group, const int32_t* keep,
                    const uint16_t* x, int64_t ldx, double* y, int64_t ldy, int M,
                    const int32_t* row_list, int n_list, int fmt) {
-  if (bits != 4 && bits != 8) return -3;
+  if (!code_width_ok(bits)) return -3;
   static const int32_t none[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   if (!keep) keep = none;
   int32_t* rows = (int32_t*)malloc(sizeof(int32_t) * (size_t)N_total);
@@ -405,9 +419,10 @@ int uref_wq_linear(int bits, const uint32_t* qweight, const uint16_t* scales, co
  * scale.  (Only used to build test inputs and for the round-trip pin.) */
 int uref_quantize_sym_bits(int bits, const double* w, int N, int K, int group, uint32_t* qweight,
                            uint16_t* scales, uint8_t* zeros) {
-  if (bits != 4 && bits != 8) return -3;
-  int cpw = 32 / bits, half = 1 << (bits - 1);
-  memset(qweight, 0, sizeof(uint32_t) * (size_t)N * (size_t)(K / cpw));
+  if (!code_width_ok(bits)) return -3;
+  int half = 1 << (bits - 1);
+  size_t words_per_row = (size_t)K * (size_t)bits / 32;
+  memset(qweight, 0, sizeof(uint32_t) * (size_t)N * words_per_row);
   for (int r = 0; r < N; ++r)
     for (int g = 0; g < K / group; ++g) {
       const double* wg = w + (size_t)r * K + (size_t)g * group;
@@ -422,7 +437,11 @@ int uref_quantize_sym_bits(int bits, const double* w, int N, int K, int group, u
         if (qv < -(double)half) qv = -(double)half;
         if (qv > (double)(half - 1)) qv = (double)(half - 1);
         int k = g * group + j;
-        qweight[(size_t)r * (K / cpw) + k / cpw] |= (uint32_t)((int)qv + half) << (bits * (k % cpw));
+        uint32_t code = (uint32_t)((int)qv + half);
+        for (int b = 0; b < bits; ++b) {        /* bit by bit into the row's stream */
+          size_t pos = (size_t)bits * (size_t)k + (size_t)b;
+          qweight[(size_t)r * words_per_row + pos / 32] |= ((code >> b) & 1u) << (pos % 32);
+        }
       }
     }
   return 0;

@@ -296,6 +296,22 @@ def gen_linear8(rng: np.random.Generator, N: int, K: int,
     return {"qweight": qweight, "scales": scales, "zeros": zeros}
 
 
+def gen_linear_bits(rng: np.random.Generator, N: int, K: int, bits: int,
+                    sym_zero: bool = False, fmt: str = "f16") -> Dict[str, np.ndarray]:
+    """Codes of 3 or 6 bits (any width that divides into whole words per group): random 32-bit words, i.e. a uniform
+    bit stream of K * bits / 32 words per row, scales ~ U(0.005, 0.02) * 16 / 2^bits (the 4-bit weight range on a
+    grid of 2^bits levels) and zeros ~ U{0..2^bits - 1} (or all 2^(bits-1) when sym_zero)."""
+    assert K % GROUP == 0 and (K * bits) % 32 == 0
+    qweight = rng.integers(0, 2 ** 32, size=(N, K * bits // 32), dtype=np.uint64).astype(np.uint32)
+    f = 16.0 / (1 << bits)
+    scales = _store16(rng.uniform(0.005 * f, 0.02 * f, size=(N, K // GROUP)), fmt)
+    if sym_zero:
+        zeros = np.full((N, K // GROUP), 1 << (bits - 1), dtype=np.uint8)
+    else:
+        zeros = rng.integers(0, 1 << bits, size=(N, K // GROUP), dtype=np.uint8)
+    return {"qweight": qweight, "scales": scales, "zeros": zeros}
+
+
 def gen_activations(rng: np.random.Generator, M: int, K: int, fmt: str = "f16") -> np.ndarray:
     return _store16(rng.standard_normal((M, K)), fmt)
 
