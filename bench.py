@@ -332,25 +332,29 @@ def detail_report(torch, uq, side):
     for spec in wl.mamba2_2p7b_layer_heads_and_state(15):
         rep[f"mamba2_2p7b_heads_state_p15_{spec.name}"] = time_linear(spec, 1, pool_for(spec))
     torch.cuda.empty_cache()
-    # 8-bit codes (Eq. 3 with N = 8) on the gate / up and down shapes, 15 %, M = 1: a byte per weight
-    for spec in wl.llama3_8b_layer(15):
-        if spec.name not in ("gate_proj", "down_proj"):
-            continue
-        gen = torch.Generator(device="cuda")
-        gen.manual_seed(wl.SEED_BASE + 8 + spec.N)
-        pool8 = []
-        for _ in range(12):
-            qw = (torch.randint(0, 2 ** 32, (spec.N, spec.K // 4), dtype=torch.int64, device="cuda", generator=gen)
-                  - 2 ** 31).to(torch.int32)
-            sc = (torch.rand((spec.N, spec.K // 128), device="cuda", generator=gen) * 0.0009 + 0.0003).to(fdt(torch))
-            zr = torch.randint(0, 256, (spec.N, spec.K // 128), dtype=torch.uint8, device="cuda", generator=gen)
-            pool8.append(uq.QuantLinear(qw, sc, zr, bits=8))
-        r = time_linear(spec, 1, pool8)
-        nb8 = spec.algorithmic_bytes(1) + spec.n_keep * spec.k_keep // 2 + spec.n_keep * spec.groups_touched() // 2   # a byte per code and per zero point
-        r.update({"MB": round(nb8 / 1e6, 3), "GBps": round(nb8 / r["us"] / 1e3, 1), "frac_hbm": round(nb8 / r["us"] / 1e3 / HBM_PEAK_GBS, 4)})
-        rep[f"llama3_8b_p15_w8_{spec.name}_M1"] = r
-        del pool8
-    torch.cuda.empty_cache()
+    # codes of 8, 6 and 3 bits (Eq. 3 with N = 8, 6, 3) on the gate / up and down shapes, 15 %, M = 1
+    for bits in (8, 6, 3):
+        for spec in wl.llama3_8b_layer(15):
+            if spec.name not in ("gate_proj", "down_proj"):
+                continue
+            gen = torch.Generator(device="cuda")
+            gen.manual_seed(wl.SEED_BASE + bits + spec.N)
+            poolb = []
+            f = 16.0 / (1 << bits)
+            for _ in range(12 if bits == 8 else 16):
+                qw = (torch.randint(0, 2 ** 32, (spec.N, spec.K * bits // 32), dtype=torch.int64, device="cuda", generator=gen)
+                      - 2 ** 31).to(torch.int32)
+                sc = (torch.rand((spec.N, spec.K // 128), device="cuda", generator=gen) * (0.015 * f) + 0.005 * f).to(fdt(torch))
+                zr = torch.randint(0, 1 << bits, (spec.N, spec.K // 128), dtype=torch.uint8, device="cuda", generator=gen)
+                poolb.append(uq.QuantLinear(qw, sc, zr, bits=bits))
+            r = time_linear(spec, 1, poolb)
+            # bits / 8 bytes per code and a byte per zero point instead of the 4-bit format's halves
+            nbb = (spec.algorithmic_bytes(1) - spec.n_keep * spec.k_keep // 2 + spec.n_keep * spec.k_keep * bits // 8
+                   + spec.n_keep * spec.groups_touched() // 2)
+            r.update({"MB": round(nbb / 1e6, 3), "GBps": round(nbb / r["us"] / 1e3, 1), "frac_hbm": round(nbb / r["us"] / 1e3 / HBM_PEAK_GBS, 4)})
+            rep[f"llama3_8b_p15_w{bits}_{spec.name}_M1"] = r
+            del poolb
+        torch.cuda.empty_cache()
     # the 4-bit output head (128256 x 4096), M = 1: the same GEMV at a size where launch latency is small
     spec = wl.lm_head_llama3()
     rep["lm_head_llama3_M1"] = time_linear(spec, 1, pool_for(spec, min_bytes=1.3e9, max_copies=5))

@@ -83,7 +83,15 @@ enum {
  * [N_total][K_total/4], byte j of word w of a row is input column 4 w + j; zeros are 0..255, or NULL: every zero
  * point is 128.  Groups, the keep rule and the weight RN16((q - z) * s) are as for 4-bit codes.  Served by
  * uniql_w4_linear (any M; at most 32768 stored columns up to the last kept one, else E_SHAPE) and uniql_w4_dequant;
- * every other call, and col_interleave > 0, return E_SHAPE for such a matrix.  Any other value of bits: E_SHAPE.
+ * every other call, and col_interleave > 0, return E_SHAPE for such a matrix.
+ *
+ * bits = 3 or 6 (Eq. 3 with N = 3, 6; the same passages): the paper fixes no packing for these widths; here a row's
+ * codes are one little-endian bit stream over its words, qweight [N_total][K_total * bits / 32]: code k occupies bits
+ * [bits * k, bits * k + bits) of the stream, bit b of the stream = bit b % 32 of word b / 32 (a code may run over a
+ * word boundary; a group of 128 columns is 12 or 24 whole words).  Zeros are 0..2^bits - 1, or NULL: every zero point
+ * is 2^(bits - 1).  Served like 8-bit codes: uniql_w4_linear (any M; at most 32768 stored columns up to the last kept
+ * one) and uniql_w4_dequant; every other call, and col_interleave > 0, return E_SHAPE.
+ * Any other value of bits: E_SHAPE.
  */
 enum { UNIQL_F16 = 0, UNIQL_BF16 = 1 };
 
@@ -94,7 +102,7 @@ typedef struct uniql_w4 {
   int32_t N_total, K_total, group;
   int32_t dtype;           /* UNIQL_F16 or UNIQL_BF16; anything else: E_SHAPE */
   int32_t col_interleave;  /* 0: words in column order; H > 0: head-interleaved over H heads (see above) */
-  int32_t bits;            /* width of a code: 0 or 4 = the 4-bit format above; 8 = 8-bit codes (see below) */
+  int32_t bits;            /* width of a code: 0 or 4 = the 4-bit format above; 8, 6 or 3: see above */
 } uniql_w4_t;
 
 /*

@@ -150,7 +150,7 @@ class QuantLinear:
     scales: "torch.Tensor"    # float16 or bfloat16 [N][K/128]: the format of activations and outputs too
     zeros: "Optional[torch.Tensor]"     # uint8 [N][K/128], or None: symmetric scheme, every zero point 8
     col_interleave: int = 0   # > 0: the words of a row are stored head-interleaved over this many heads
-    bits: int = 4             # width of a code: 4, or 8 (then qweight is [N][K/4] and zeros are 0..255 or None = 128)
+    bits: int = 4             # width of a code: 4, or 8 / 6 / 3 (then qweight is [N][K * bits / 32], zeros 0..2^bits - 1 or None = 2^(bits-1))
 
     @property
     def N(self) -> int:
@@ -158,7 +158,7 @@ class QuantLinear:
 
     @property
     def K(self) -> int:
-        return self.qweight.shape[1] * (32 // self.bits)
+        return self.qweight.shape[1] * 32 // self.bits
 
     @property
     def ftype(self):

@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libuniql.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["api.hip", "gemv.hip", "gemv_sym.hip", "gemv_bf16.hip", "gemv_bf16_sym.hip", "gemv_stream.hip", "gemv_stream_bf16.hip", "mlp_stream.hip", "mlp_stream_bf16.hip",
-           "mfma_gemm.hip", "mfma_gemm_bf16.hip", "w4_dequant.hip", "w8.hip", "rope.hip", "probe.hip"]
+           "mfma_gemm.hip", "mfma_gemm_bf16.hip", "w4_dequant.hip", "w8.hip", "wbits.hip", "rope.hip", "probe.hip"]
 # packed-fp32 VALU forms are switched off for every HIP translation unit
 # (and the compiler's rewrite of atomics as wave-wide reductions: the one LDS counter of the streaming GEMV is
 # incremented by one lane per wave, which the rewrite would wrap in a dozen extra instructions per loop body)

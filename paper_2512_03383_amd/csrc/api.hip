@@ -38,12 +38,12 @@ static int check_arch() {
 static bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
 // Validate W / keep and normalise the keep rule.  Pure host arithmetic.
-// allow8: the caller serves codes of 8 bits as well (uniql_w4_linear and uniql_w4_dequant do)
+// allow8: the caller serves codes of 8, 6 and 3 bits as well (uniql_w4_linear and uniql_w4_dequant do)
 static int code_bits(const uniql_w4_t* W) { return W->bits == 0 ? 4 : W->bits; }
 static int make_keepmap(const uniql_w4_t* W, const uniql_keep_t* keep, KeepMap* km, bool allow8 = false) {
   if (!W || !W->qweight || !W->scales) return UNIQL_E_NULL;   // zeros may be NULL: every zero point is 8 (128 for 8-bit codes)
   if (W->group != kGroup || W->N_total < 1 || W->K_total < kGroup || W->K_total % kGroup) return UNIQL_E_SHAPE;
-  if (code_bits(W) != 4 && !(code_bits(W) == 8 && allow8 && W->col_interleave == 0)) return UNIQL_E_SHAPE;
+  if (code_bits(W) != 4 && !((code_bits(W) == 8 || code_bits(W) == 6 || code_bits(W) == 3) && allow8 && W->col_interleave == 0)) return UNIQL_E_SHAPE;
   if (W->dtype != UNIQL_F16 && W->dtype != UNIQL_BF16) return UNIQL_E_SHAPE;
   if (W->col_interleave < 0 || (W->col_interleave > 0 && (W->K_total % W->col_interleave || (W->K_total / W->col_interleave) % 8)))
     return UNIQL_E_SHAPE;
@@ -125,8 +125,8 @@ static int fill_linear(const uniql_w4_t* W, const uniql_keep_t* keep, const void
 constexpr int kInterleavedMaxTokens = 64;   // a matrix with head-interleaved words: tokens per call
 
 static int run_linear(const LinearArgs& a, hipStream_t s) {
-  if (a.bits == 8) {
-    hipError_t e8 = launch_w8_linear(a, s);
+  if (a.bits != 4) {
+    hipError_t e8 = a.bits == 8 ? launch_w8_linear(a, s) : launch_wb_linear(a, s);
     if (e8 == hipErrorInvalidValue) return UNIQL_E_SHAPE;   // more kept columns than the kernel's staging holds
     return e8 == hipSuccess ? UNIQL_OK : hip_fail(e8);
   }
@@ -207,7 +207,8 @@ extern "C" int uniql_w4_dequant(const uniql_w4_t* W, const uniql_keep_t* keep, v
   a.bf16 = W->dtype == UNIQL_BF16;
   a.il_heads = W->col_interleave;
   a.bits = code_bits(W);
-  hipError_t e = a.bits == 8 ? launch_w8_dequant(a, (hipStream_t)hip_stream) : launch_w4_dequant(a, (hipStream_t)hip_stream);
+  hipError_t e = a.bits == 8 ? launch_w8_dequant(a, (hipStream_t)hip_stream)
+                 : a.bits == 4 ? launch_w4_dequant(a, (hipStream_t)hip_stream) : launch_wb_dequant(a, (hipStream_t)hip_stream);
   return e == hipSuccess ? UNIQL_OK : hip_fail(e);
 }
 

@@ -47,7 +47,7 @@ struct LinearArgs {
   int N_total, K_total, M;
   int bf16;           // scales, x and y are bfloat16 (the weights are then rounded to bfloat16 as well)
   int il_heads;       // > 0: the row's words are stored head-interleaved over this many heads (uniql_w4_t.col_interleave)
-  int bits;           // width of a code: 4, or 8 (w8.hip serves those)
+  int bits;           // width of a code: 4, or 8 (w8.hip serves those), or 3 / 6 (wbits.hip)
   KeepMap km;
 };
 
@@ -298,6 +298,9 @@ hipError_t launch_w4_dequant(const LinearArgs& a, hipStream_t stream);
 // codes of 8 bits: the dequantised matrix, and the linear for any number of tokens
 hipError_t launch_w8_dequant(const LinearArgs& a, hipStream_t stream);
 hipError_t launch_w8_linear(const LinearArgs& a, hipStream_t stream);
+// codes of 3 and 6 bits (a.bits), packed as a bit stream: the same two operations
+hipError_t launch_wb_dequant(const LinearArgs& a, hipStream_t stream);
+hipError_t launch_wb_linear(const LinearArgs& a, hipStream_t stream);
 hipError_t launch_w4_embedding(const uint32_t* qweight, const uint16_t* scales, const uint8_t* zeros, int K_total,
                                const int32_t* ids, int n, half_t* out, long long ld, int bf16, hipStream_t stream);
 

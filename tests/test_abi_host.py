@@ -133,27 +133,28 @@ def test_dtype_field_is_validated():
 
 
 def test_bits_field_is_validated():
-    """0 and 4 = 4-bit codes, 8 = 8-bit codes in the two calls that serve them, anything else refused; an 8-bit
-    matrix passes the same host checks as a 4-bit one there and is refused everywhere else before any launch."""
-    for bad in (1, 3, 6, 16, -4):
+    """0 and 4 = 4-bit codes, 8 / 6 / 3 = codes of those widths in the two calls that serve them, anything else refused;
+    such a matrix passes the same host checks as a 4-bit one there and is refused everywhere else before any launch."""
+    for bad in (1, 2, 5, 7, 16, -4):
         w = _w()
         w.bits = bad
         assert _lin(w, None) == uq.UNIQL_E_SHAPE
     w4 = _w()
     w4.bits = 4
     assert _lin(w4, None, M=0) == uq.UNIQL_E_SHAPE and _lin(w4, KeepDesc(n_keep=999)) == uq.UNIQL_E_KEEP
-    w8 = _w()
-    w8.bits = 8
-    assert _lin(w8, None, M=0) == uq.UNIQL_E_SHAPE             # validated like any other matrix ...
-    assert _lin(w8, KeepDesc(n_keep=999)) == uq.UNIQL_E_KEEP
-    assert _lin(w8, None, x=P + 1) == uq.UNIQL_E_ALIGN
-    wi = _w()
-    wi.bits, wi.col_interleave = 8, 4
-    assert _lin(wi, None) == uq.UNIQL_E_SHAPE                  # ... but not head-interleaved
-    assert _multi(ws=[_w(), w8]) == uq.UNIQL_E_SHAPE           # and not in the calls that only know 4-bit codes
-    W = (W4 * 2)(w8, w8)
-    assert uq.lib().uniql_w4_gate_up_silu(W, None, C.c_void_p(P), C.c_void_p(P), None) == uq.UNIQL_E_SHAPE
-    assert uq.lib().uniql_w4_dequant(C.byref(w8), None, None, None) == uq.UNIQL_E_NULL   # dequant takes it (and then misses its output)
+    for bits in (8, 6, 3):
+        w8 = _w()
+        w8.bits = bits
+        assert _lin(w8, None, M=0) == uq.UNIQL_E_SHAPE             # validated like any other matrix ...
+        assert _lin(w8, KeepDesc(n_keep=999)) == uq.UNIQL_E_KEEP
+        assert _lin(w8, None, x=P + 1) == uq.UNIQL_E_ALIGN
+        wi = _w()
+        wi.bits, wi.col_interleave = bits, 4
+        assert _lin(wi, None) == uq.UNIQL_E_SHAPE                  # ... but not head-interleaved
+        assert _multi(ws=[_w(), w8]) == uq.UNIQL_E_SHAPE           # and not in the calls that only know 4-bit codes
+        W = (W4 * 2)(w8, w8)
+        assert uq.lib().uniql_w4_gate_up_silu(W, None, C.c_void_p(P), C.c_void_p(P), None) == uq.UNIQL_E_SHAPE
+        assert uq.lib().uniql_w4_dequant(C.byref(w8), None, None, None) == uq.UNIQL_E_NULL   # dequant takes it (and then misses its output)
 
 
 def test_rope_table_check_on_the_host():
