@@ -323,6 +323,24 @@ def detail_report(torch, uq, side):
             qpools[key] = pool_for(spec)
         for M in (1, 8, 16):
             rep[f"qwen25_7b_p25_{spec.name}_M{M}"] = time_linear(spec, M, qpools[key])
+    # the same decode batches with q + k + v and gate + up as one uniql_w4_linear_multi call each (one launch per call)
+    qspecs = {s.name: s for s in wl.qwen25_7b_layer(25)}
+    for label, names in (("qkv", ("q_proj", "k_proj", "v_proj")), ("gate_up", ("gate_proj", "up_proj"))):
+        members = [qspecs[n] for n in names]
+        mpools = []
+        for j, sp in enumerate(members):
+            pl = qpools[(sp.N, sp.K)]
+            mpools.append([pl[(i + j * (len(pl) // 2)) % len(pl)] for i in range(len(pl))])   # members never share a matrix
+        npool = min(len(pl) for pl in mpools)
+        for M in (8, 16):
+            x = torch.randn((M, members[0].k_keep), dtype=fdt(torch), device="cuda")
+            ys = [torch.empty((M, sp.n_keep), dtype=fdt(torch), device="cuda") for sp in members]
+            keeps = [sp.keep for sp in members]
+            us = graph_time_us(torch, side, lambda i: uq.uniql_w4_linear_multi([pl[i % npool] for pl in mpools], keeps, [x] * len(members), ys), npool)
+            nbytes = sum(sp.algorithmic_bytes(M) for sp in members) - (len(members) - 1) * M * members[0].k_keep * 2
+            rep[f"qwen25_7b_p25_{label}_one_call_M{M}"] = {"M": M, "MB": round(nbytes / 1e6, 3), "us": round(us, 2),
+                                                            "GBps": round(nbytes / us / 1e3, 1),
+                                                            "frac_hbm": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4)}
     qpools.clear()
     torch.cuda.empty_cache()
     # Mamba2-2.7B shapes, 15 %

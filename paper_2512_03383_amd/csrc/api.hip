@@ -179,6 +179,17 @@ extern "C" int uniql_w4_linear_multi(int32_t n, const uniql_w4_t* W, const uniql
     if (e == hipErrorInvalidValue) return UNIQL_E_SHAPE;
     return e == hipSuccess ? UNIQL_OK : hip_fail(e);
   }
+  if (n > 1 && M <= 32) {
+    // a decode batch: one launch when the decode-batch kernel takes every member (the same format: fill_linear's
+    // entries of one call may differ in it, then they go one by one)
+    bool same = true, done = false;
+    for (int i = 1; i < n; ++i) same = same && a[i].bf16 == a[0].bf16;
+    if (same) {
+      hipError_t e = launch_w4_gemm_batch(a, n, s, &done);
+      if (e != hipSuccess) return hip_fail(e);
+      if (done) return UNIQL_OK;
+    }
+  }
   for (int i = 0; i < n; ++i) {
     rc = run_linear(a[i], s);
     if (rc) return rc;

@@ -294,6 +294,9 @@ hipError_t launch_w4_mlp_fused(const LinearArgs* probs, void* scratch, hipStream
 hipError_t launch_w4_mlp_fused_bf16(const LinearArgs* probs, void* scratch, hipStream_t stream, bool* done);
 hipError_t launch_w4_gemm(const LinearArgs& a, hipStream_t stream);
 hipError_t launch_w4_gemm_bf16(const LinearArgs& a, hipStream_t stream);
+// n (2..4) linears of one decode batch in one launch where the decode-batch kernel takes them all (*done says whether)
+hipError_t launch_w4_gemm_batch(const LinearArgs* a, int n, hipStream_t stream, bool* done);
+hipError_t launch_w4_gemm_batch_bf16(const LinearArgs* a, int n, hipStream_t stream, bool* done);
 hipError_t launch_w4_dequant(const LinearArgs& a, hipStream_t stream);
 // codes of 8 bits: the dequantised matrix, and the linear for any number of tokens
 hipError_t launch_w8_dequant(const LinearArgs& a, hipStream_t stream);

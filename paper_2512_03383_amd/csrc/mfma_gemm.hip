@@ -9,4 +9,11 @@ hipError_t launch_w4_gemm(const LinearArgs& a, hipStream_t stream) {
   return launch_gemm_fmt<false>(a, stream);
 }
 
+// n linears of one decode batch (2..32 tokens, the same format) in one launch when the decode-batch kernel takes them
+// all; *done = false: nothing was launched, run them one by one
+hipError_t launch_w4_gemm_batch(const LinearArgs* a, int n, hipStream_t stream, bool* done) {
+  if (a[0].bf16) return launch_w4_gemm_batch_bf16(a, n, stream, done);
+  return smallm_batch<false>(a, n, stream, done);
+}
+
 }  // namespace uniql

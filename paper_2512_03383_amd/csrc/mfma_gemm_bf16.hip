@@ -4,5 +4,8 @@
 namespace uniql {
 
 hipError_t launch_w4_gemm_bf16(const LinearArgs& a, hipStream_t stream) { return launch_gemm_fmt<true>(a, stream); }
+hipError_t launch_w4_gemm_batch_bf16(const LinearArgs* a, int n, hipStream_t stream, bool* done) {
+  return smallm_batch<true>(a, n, stream, done);
+}
 
 }  // namespace uniql

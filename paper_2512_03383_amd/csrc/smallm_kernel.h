@@ -35,8 +35,9 @@ struct SmallMShape {
 // AF: 16-token fragments (1 or 2); XT: tokens staged per group (>= M; 4, 8, 16 or 32); XM: how the activations are
 // fetched (0 = element by element through the column map, 1 = column prefix, 2 = column segments whose stride is a
 // multiple of 8), as in mfma_kernel.h
-template <int AF, int XT, int XM, bool BF16, int OCC>
-__global__ __launch_bounds__(kSmThreads, OCC) void w4_smallm_kernel(LinearArgs a, SmallMShape sh) {
+// (block: the block's index within its linear -- blockIdx.x when the launch serves one linear)
+template <int AF, int XT, int XM, bool BF16>
+__device__ __forceinline__ void smallm_body(const LinearArgs& a, const SmallMShape sh, const int block) {
   constexpr bool XVEC = XM == 1, XSEG = XM == 2;
   constexpr int D = kSmRing;
   constexpr int BM = 16 * AF;                 // token slots of a staged tile
@@ -72,7 +73,7 @@ __global__ __launch_bounds__(kSmThreads, OCC) void w4_smallm_kernel(LinearArgs a
   const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<half_t*>(a.x), 0, (int)(((long long)(a.M - 1) * a.ldx + km.k_keep) * 2), kRsrcWord3);
 
   // stored row of this lane's weight fragment (clamped: a lane past the last row re-reads it and stores nothing)
-  const int rc = (blockIdx.x * WN + wn) * 16 + n;
+  const int rc = (block * WN + wn) * 16 + n;
   const int wrow = stored_row(km, rc < km.n_keep ? rc : km.n_keep - 1);
   typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
   typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
@@ -283,6 +284,31 @@ __global__ __launch_bounds__(kSmThreads, OCC) void w4_smallm_kernel(LinearArgs a
     }
 }
 
+template <int AF, int XT, int XM, bool BF16, int OCC>
+__global__ __launch_bounds__(kSmThreads, OCC) void w4_smallm_kernel(LinearArgs a, SmallMShape sh) {
+  smallm_body<AF, XT, XM, BF16>(a, sh, (int)blockIdx.x);
+}
+
+// Up to four linears with the same token count in one launch (q, k, v or gate, up of a decode batch: a launch of this
+// size is bound by its latency, not by its bytes).  Every block does exactly what it does in a launch of its own
+// linear, so the results are the same bits.
+struct SmallMBatch {
+  LinearArgs p[kMaxBatch];
+  SmallMShape sh[kMaxBatch];
+  int first_block[kMaxBatch];
+  int n;
+};
+template <int AF, int XT, int XM, bool BF16, int OCC>
+__global__ __launch_bounds__(kSmThreads, OCC) void w4_smallm_batch_kernel(SmallMBatch b) {
+  int pi = 0;
+#pragma unroll
+  for (int i = 1; i < kMaxBatch; ++i) pi += (i < b.n && (int)blockIdx.x >= b.first_block[i]) ? 1 : 0;
+  // by value: the member's fields come from the argument buffer in a few wide scalar loads up front
+  const LinearArgs a = b.p[pi];
+  const SmallMShape sh = b.sh[pi];
+  smallm_body<AF, XT, XM, BF16>(a, sh, (int)blockIdx.x - b.first_block[pi]);
+}
+
 // K split and groups per wave: the fewest waves along K that give the launch at least 1280 waves (five per compute
 // unit; measured on 888 row tiles x 28 groups at 8 tokens: 16.0 / 11.1 / 11.5 / 13.4 us with K over 1 / 2 / 4 / 8
 // waves), with at least four groups per wave
@@ -330,6 +356,49 @@ static hipError_t smallm_dispatch(const LinearArgs& a, hipStream_t stream) {
   if (a.M <= 8) return smallm_launch<1, 8, XM, BF16>(a, stream);
   if (a.M <= 16) return smallm_launch<1, 16, XM, BF16>(a, stream);
   return smallm_launch<2, 32, XM, BF16>(a, stream);
+}
+
+template <int AF, int XT, bool BF16, int OCC = (XT <= 8 ? 4 : 2)>
+static hipError_t smallm_launch_batch(const LinearArgs* a, int n, hipStream_t stream) {
+  const size_t smem = (size_t)kSmWaves * 2 * 16 * 16 * AF * sizeof(uint4) + (size_t)kSmWaves * AF * 4 * 64 * sizeof(float);
+  auto kern = w4_smallm_batch_kernel<AF, XT, 1, BF16, OCC>;
+  if (smem > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+  }
+  SmallMBatch b;
+  b.n = n;
+  int blocks = 0;
+  for (int i = 0; i < kMaxBatch; ++i) {
+    b.p[i] = a[i < n ? i : 0];
+    b.sh[i] = smallm_shape(b.p[i]);
+    b.first_block[i] = blocks;
+    if (i >= n) continue;
+    const int wn = kSmWaves / b.sh[i].ks;
+    blocks += ((a[i].km.n_keep + 15) / 16 + wn - 1) / wn;
+  }
+  hipLaunchKernelGGL(kern, dim3(blocks), dim3(kSmThreads), smem, stream, b);
+  return hipGetLastError();
+}
+
+// n (2..4) linears of one decode batch in one launch: column prefixes of at least 8 columns, the same token count and
+// format (the caller checks), each one a linear that smallm_dispatch<1> would take.  *done = false: not such a set,
+// nothing was launched.
+template <bool BF16>
+static hipError_t smallm_batch(const LinearArgs* a, int n, hipStream_t stream, bool* done) {
+  *done = false;
+  for (int i = 0; i < n; ++i) {
+    const int row_tiles = (a[i].km.n_keep + 15) / 16;
+    if (a[i].km.cs_stride != 0 || a[i].km.k_keep < 8 || a[i].M != a[0].M || !smallm_serves(a[i]) ||
+        !(a[i].M <= 8 || row_tiles < 600))
+      return hipSuccess;
+  }
+  *done = true;
+  const int M = a[0].M;
+  if (M <= 4) return smallm_launch_batch<1, 4, BF16>(a, n, stream);
+  if (M <= 8) return smallm_launch_batch<1, 8, BF16>(a, n, stream);
+  if (M <= 16) return smallm_launch_batch<1, 16, BF16>(a, n, stream);
+  return smallm_launch_batch<2, 32, BF16>(a, n, stream);
 }
 
 }  // namespace uniql

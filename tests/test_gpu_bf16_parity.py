@@ -387,6 +387,36 @@ def test_multi_call_and_mixed_formats(env, uref):
     assert torch.equal(yb, ys[1]) and torch.equal(y16, uq.uniql_w4_linear(q16, None, x16))
 
 
+@pytest.mark.parametrize("M", [3, 8, 16, 32])
+def test_multi_call_decode_batches_share_a_launch(env, uref, M):
+    """q / k / v of a decode batch in bfloat16 through one launch of the decode-batch kernel: the bits of single calls
+    and the oracle within the bfloat16 bar; the same tokens with an fp16 member mixed in go one by one."""
+    uq, torch = env
+    rng = wl.rng_for(29, 40 + M)
+    specs = {s.name: s for s in wl.llama3_8b_layer(15)}
+    names = ["q_proj", "k_proj", "v_proj"]
+    ws = [gen(rng, specs[n].N, specs[n].K) for n in names]
+    qws = [uq.QuantLinear.from_numpy(w) for w in ws]
+    keeps = [specs[n].keep for n in names]
+    xh = wl.gen_activations(rng, M, 4096, fmt=FMT)
+    x = dev_bf16(torch, xh)
+    ys = [torch.empty((M, specs[n].n_keep), dtype=torch.bfloat16, device="cuda") for n in names]
+    uq.uniql_w4_linear_multi(qws, keeps, [x] * 3, ys)
+    torch.cuda.synchronize()
+    for w, qw, kp, y in zip(ws, qws, keeps, ys):
+        assert torch.equal(uq.uniql_w4_linear(qw, kp, x), y)
+        ref = oracle_linear(uref, w, xh, kp)
+        assert linear_err(y.float().cpu().numpy().astype(np.float64), ref) <= TOL_BF16
+    w16 = wl.gen_linear(rng, 512, 4096)
+    q16 = uq.QuantLinear.from_numpy(w16)
+    x16 = torch.from_numpy(wl.gen_activations(rng, M, 4096)).cuda()
+    y16 = torch.empty((M, 512), dtype=torch.float16, device="cuda")
+    yb = torch.empty((M, specs["k_proj"].n_keep), dtype=torch.bfloat16, device="cuda")
+    uq.uniql_w4_linear_multi([q16, qws[1]], [None, keeps[1]], [x16, x], [y16, yb])
+    torch.cuda.synchronize()
+    assert torch.equal(yb, ys[1]) and torch.equal(y16, uq.uniql_w4_linear(q16, None, x16))
+
+
 def test_repack_carries_bf16_scales(env, uref):
     """The compact copy moves scales as they are stored: the repacked matrix gives the same bits."""
     uq, torch = env

@@ -589,6 +589,43 @@ def test_multi_call_mixed_shapes_and_tokens(env, uref):
             assert torch.equal(single, y)
 
 
+@pytest.mark.parametrize("M", [2, 4, 7, 8, 16, 31])
+def test_multi_call_decode_batches_share_a_launch(env, uref, M):
+    """q / k / v (row segments, GQA sizes) and gate / up (row prefix) of a decode batch through uniql_w4_linear_multi:
+    2..32 tokens with column prefixes go out as ONE launch of the decode-batch kernel; the bits of separate calls, the
+    oracle on sampled rows, padding of strided outputs untouched.  A member the kernel does not take (fewer than 8
+    groups per row) sends the whole call down the one-by-one path with the same results."""
+    uq, torch = env
+    rng = wl.rng_for(0, 70 + M)
+    hidden = 2048
+    sets = [
+        [(2048, hidden, Keep(n_keep=16 * 108, k_keep=1741, row_seg_stride=64, row_seg_keep=54, row_seg_limit=2048)),
+         (512, hidden, Keep(n_keep=4 * 108, k_keep=1741, row_seg_stride=64, row_seg_keep=54, row_seg_limit=512)),
+         (512, hidden, Keep(n_keep=4 * 108, k_keep=1741, row_seg_stride=128, row_seg_keep=108, row_seg_limit=512))],
+        [(5632, hidden, Keep(n_keep=4787)), (5632, hidden, Keep(n_keep=4787))],
+        [(300, 1024, Keep(n_keep=257)), (64, 4096, Keep(k_keep=3001)), (128, 256, Keep()), (48, 1024, Keep(k_keep=9))],
+    ]
+    for shapes in sets:
+        ws = [wl.gen_linear(rng, N, K) for N, K, _ in shapes]
+        qws = [uq.QuantLinear.from_numpy(w) for w in ws]
+        dims = [uq.kept_dims(qw, kp) for qw, (_, _, kp) in zip(qws, shapes)]
+        xs_h = [wl.gen_activations(rng, M, kk) for _, kk in dims]
+        xs = [to_dev(torch, x) for x in xs_h]
+        ybufs = [torch.full((M, nk + 5), -7.0, dtype=torch.float16, device="cuda") for nk, _ in dims]
+        ys = [yb[:, :nk] for yb, (nk, _) in zip(ybufs, dims)]
+        uq.uniql_w4_linear_multi(qws, [kp for _, _, kp in shapes], xs, ys)
+        torch.cuda.synchronize()
+        for w, qw, (_, _, kp), x, xh, yb, (nk, kk) in zip(ws, qws, shapes, xs, xs_h, ybufs, dims):
+            assert torch.all(yb[:, nk:] == -7.0)
+            single = uq.uniql_w4_linear(qw, kp, x)
+            assert torch.equal(single, yb[:, :nk])
+            rows = _sample_rows(nk, rng, 48)
+            ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], xh, kp, rows=rows)
+            got = yb[:, :nk].cpu().numpy().astype(np.float64)[:, rows]
+            rms = np.sqrt(np.mean(ref ** 2))
+            assert np.max(np.abs(got - ref) / np.maximum(np.abs(ref), 1e-2 * rms)) <= TOL
+
+
 # ------------------------------------------------- fused q / k / v projections + rotary embedding
 def _qkv_case(uq, torch, uref, specs, rope, rng):
     """One token through uniql_w4_qkv_rope against the oracle's y = RoPE(x W).  The rotation preserves
