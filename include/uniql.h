@@ -162,8 +162,10 @@ int uniql_w4_linear(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x
  * projections of a layer (Eq. 2) or gate and up (Eq. 1), which read the same x.  W, keep (or NULL
  * = all unpruned), x_f16, ldx, y_f16, ldy are host arrays of n entries; each entry follows the
  * rules of uniql_w4_linear.  At M = 1 linears that stream rows of the same length are served by
- * ONE kernel launch (a decode step is launch-latency bound); otherwise they are launched one
- * after the other on the stream.  Results are identical to n separate uniql_w4_linear calls.
+ * ONE kernel launch (a decode step is launch-latency bound), and so are the linears of a decode
+ * batch (M = 2..32) when each keeps a column prefix of at least 8 columns and is one the
+ * decode-batch kernel takes; otherwise they are launched one after the other on the stream.
+ * Results are identical to n separate uniql_w4_linear calls.
  * Errors: E_SHAPE also for n outside 1..4; otherwise as uniql_w4_linear (nothing is launched if
  * any entry is invalid).
  */
