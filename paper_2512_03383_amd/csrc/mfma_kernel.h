@@ -383,10 +383,11 @@ static hipError_t launch_m(const LinearArgs& a, hipStream_t stream) {
   // tall matrices at more than 8 tokens: there this kernel's slab, staged once for 64 rows, costs less than every wave
   // staging its own activations (14336-row gate at 16 / 32 tokens, weights from HBM: 12.3 / 15.3 us here, 14.1 / 19.5 us
   // there; 3584-row down: 16.4 / 27.3 us here, 15.9 / 21.6 us there; up to 8 tokens the other kernel wins or ties
-  // everywhere).  What that kernel does not take falls through to this one: 16 rows per wave and the K range split over
+  // everywhere; with the activations staged once per block -- column prefixes of at most 32 groups, up to 16 tokens --
+  // the other kernel takes the tall matrices at 9..16 tokens too: 18944-row gate at 16 tokens 11.6 against 12.7 us).  What that kernel does not take falls through to this one: 16 rows per wave and the K range split over
   // the block's 8 waves, four ways when there are many row tiles, eight ways otherwise.
   const int row_tiles = (a.km.n_keep + 15) / 16;
-  if (smallm_serves(a) && (a.M <= 8 || row_tiles < 600)) return smallm_dispatch<XVEC, BF16>(a, stream);
+  if (smallm_takes(a, XVEC == 1)) return smallm_dispatch<XVEC, BF16>(a, stream);
   // (many row tiles: 32 rows per wave, so that an activation fragment read from LDS serves two weight fragments,
   // 64 rows per block; few: 16 rows per block, two groups per wave and slab, which halves the number of barriers)
   if (a.M <= 16) return row_tiles >= 600 ? launch_cfg<BF16, 1, 2, 2, 4, 1, 2, XVEC>(a, stream) : launch_cfg<BF16, 1, 1, 1, 8, 2, 1, XVEC>(a, stream);

@@ -26,6 +26,7 @@ namespace uniql {
 constexpr int kSmWaves = 8;
 constexpr int kSmThreads = kSmWaves * kWave;
 constexpr int kSmRing = 8;   // weight tiles in flight per wave = groups per batch of scales
+constexpr int kSmPreGroups = 32;   // groups of a row the pre-staged activation image holds
 
 struct SmallMShape {
   int ks;    // waves along K
@@ -36,9 +37,15 @@ struct SmallMShape {
 // fetched (0 = element by element through the column map, 1 = column prefix, 2 = column segments whose stride is a
 // multiple of 8), as in mfma_kernel.h
 // (block: the block's index within its linear -- blockIdx.x when the launch serves one linear)
-template <int AF, int XT, int XM, bool BF16>
+//
+// PRE (column prefixes of at most 32 groups, up to 16 tokens): the block stages the activations of ALL its groups once,
+// before the loop -- every thread fetches its share with 128-bit loads issued ahead of the first weight loads, one
+// block barrier -- and the loop only reads them.  The per-wave staging above costs as much as the unpack and the
+// matrix instructions together, and with two to four waves per SIMD nothing hides it.
+template <int AF, int XT, int XM, bool BF16, bool PRE>
 __device__ __forceinline__ void smallm_body(const LinearArgs& a, const SmallMShape sh, const int block) {
   constexpr bool XVEC = XM == 1, XSEG = XM == 2;
+  static_assert(!PRE || (XM == 1 && AF == 1 && XT <= 16), "the pre-staged image: a column prefix, one token fragment");
   constexpr int D = kSmRing;
   constexpr int BM = 16 * AF;                 // token slots of a staged tile
   constexpr int UPL = XT * 16 / kWave;        // 16-byte units (8 columns of one token) per lane and group
@@ -52,8 +59,9 @@ __device__ __forceinline__ void smallm_body(const LinearArgs& a, const SmallMSha
   const int KS = sh.ks, WN = kSmWaves / KS;
   const int wn = wave % WN, wk = wave / WN;
   const int n = lane & 15, ks = lane >> 4;
-  uint4* xs = reinterpret_cast<uint4*>(smem) + (size_t)wave * 2 * TILE_UNITS;                      // this wave's two tiles
-  float* red = reinterpret_cast<float*>(smem + (size_t)kSmWaves * 2 * TILE_UNITS * sizeof(uint4));   // [8][AF * 4][64]
+  // PRE: one image for the block, [group][16 chunks][XT token slots]; else this wave's two tiles
+  uint4* xs = reinterpret_cast<uint4*>(smem) + (PRE ? 0 : (size_t)wave * 2 * TILE_UNITS);
+  float* red = reinterpret_cast<float*>(smem + (PRE ? (size_t)kSmPreGroups * 16 * XT : (size_t)kSmWaves * 2 * TILE_UNITS) * sizeof(uint4));   // [8][AF * 4][64]
 
   const int words_per_row = a.K_total >> 3, groups_per_row = a.K_total / kGroup;
   const int ngroups = (km.k_span + kGroup - 1) / kGroup;
@@ -187,17 +195,50 @@ __device__ __forceinline__ void smallm_body(const LinearArgs& a, const SmallMSha
   // groups i and i + 1, the registers the one of group i + 2 on its way.
   XRegs xr;
   u32x4_t ring[D];
-  fetch_x(0, xr);
-  __builtin_amdgcn_sched_barrier(0);
-  XRegs x1;
-  fetch_x(1, x1);
-  SZ sz_cur = load_sz(0), sz_nxt = sz_cur;
+  SZ sz_cur, sz_nxt;
+  if constexpr (PRE) {
+    // unit u of the image: token u / (16 G), chunk-of-row u % (16 G) (G = groups of the row's kept span): consecutive
+    // lanes fetch consecutive 16 bytes of one token.  XT units per thread cover 32 groups; all are requested before
+    // the weights, so they arrive first.
+    const int chunks = ngroups * 16;
+    u32x4_t pre[XT];
 #pragma unroll
-  for (int p = 0; p < D; ++p) ring[p] = load_w(p);
-  __builtin_amdgcn_sched_barrier(0);
-  store_x(0, xr);
-  xr = x1;
-  __builtin_amdgcn_sched_barrier(0);
+    for (int j = 0; j < XT; ++j) {
+      const int u = tid + kSmThreads * j;
+      const int tok = u / chunks, gc = u - tok * chunks;
+      const bool there = tok < a.M && tok < XT && gc * 8 + 8 <= kv;
+      pre[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, there ? 2 * (tok * (int)a.ldx + gc * 8) : kNone, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    sz_cur = load_sz(0);
+    sz_nxt = sz_cur;
+#pragma unroll
+    for (int p = 0; p < D; ++p) ring[p] = load_w(p);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < XT; ++j) {
+      const int u = tid + kSmThreads * j;
+      const int tok = u / chunks, gc = u - tok * chunks;
+      const u32x4_t r = pre[j];
+      if (tok < XT)
+        xs[gc * XT + tok] = make_uint4(__builtin_amdgcn_perm(r.z, r.x, 0x05040100u), __builtin_amdgcn_perm(r.z, r.x, 0x07060302u),
+                                       __builtin_amdgcn_perm(r.w, r.y, 0x05040100u), __builtin_amdgcn_perm(r.w, r.y, 0x07060302u));
+    }
+    __syncthreads();
+  } else {
+    fetch_x(0, xr);
+    __builtin_amdgcn_sched_barrier(0);
+    XRegs x1;
+    fetch_x(1, x1);
+    sz_cur = load_sz(0);
+    sz_nxt = sz_cur;
+#pragma unroll
+    for (int p = 0; p < D; ++p) ring[p] = load_w(p);
+    __builtin_amdgcn_sched_barrier(0);
+    store_x(0, xr);
+    xr = x1;
+    __builtin_amdgcn_sched_barrier(0);
+  }
 
   // the walk over the wave's groups; it leaves through the first group past the last one.  The scheduling barriers
   // keep every load where it is written (the scheduler would otherwise sink a load to its first use to save registers).
@@ -210,8 +251,10 @@ __device__ __forceinline__ void smallm_body(const LinearArgs& a, const SmallMSha
         const int i = i0 + p;
         if (i >= ng) return;
         const int buf = p & 1;
-        store_x(buf ^ 1, xr);      // group i + 1
-        fetch_x(i + 2, xr);
+        if constexpr (!PRE) {
+          store_x(buf ^ 1, xr);      // group i + 1
+          fetch_x(i + 2, xr);
+        }
         __builtin_amdgcn_sched_barrier(0);
         const uint32_t sv[4] = {sz_cur.s.x, sz_cur.s.y, sz_cur.s.z, sz_cur.s.w};
         const uint32_t zv[2] = {sz_cur.z.x, sz_cur.z.y};
@@ -219,13 +262,19 @@ __device__ __forceinline__ void smallm_body(const LinearArgs& a, const SmallMSha
         const uint32_t z = has_z ? (zv[p >> 2] >> (8 * (p & 3))) & 0xffu : 8u;   // no zero points: the symmetric scheme, z = 8
         const typename GroupOf<BF16>::type gq = make_group<BF16>(sbits, z);
         const uint32_t wv[4] = {ring[p].x, ring[p].y, ring[p].z, ring[p].w};
-        const uint4* xb = xs + (buf * 16 + ks * 4) * BM;
+        // PRE: chunk ks * 4 + t of group g0 + i, token slot n (lanes past the staged tokens re-read a staged one: their
+        // rows of the product are never stored)
+        const uint4* xb = PRE ? xs + ((g0 + i) * 16 + ks * 4) * XT + (n & (XT - 1)) : xs + (buf * 16 + ks * 4) * BM;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
           const uint4 b = dequant_word4<BF16>(wv[t], gq, mg);
+          if constexpr (PRE) {
+            acc[0] = mfma_16x16x32<BF16>(xb[t * XT], b, acc[0]);
+          } else {
 #pragma unroll
-          for (int af = 0; af < AF; ++af)
-            acc[af] = mfma_16x16x32<BF16>(xb[t * BM + af * 16 + (n ^ (ks | (t << 2)))], b, acc[af]);
+            for (int af = 0; af < AF; ++af)
+              acc[af] = mfma_16x16x32<BF16>(xb[t * BM + af * 16 + (n ^ (ks | (t << 2)))], b, acc[af]);
+          }
         }
         __builtin_amdgcn_sched_barrier(0);
         ring[p] = load_w(i + D);
@@ -284,9 +333,9 @@ __device__ __forceinline__ void smallm_body(const LinearArgs& a, const SmallMSha
     }
 }
 
-template <int AF, int XT, int XM, bool BF16, int OCC>
+template <int AF, int XT, int XM, bool BF16, int OCC, bool PRE>
 __global__ __launch_bounds__(kSmThreads, OCC) void w4_smallm_kernel(LinearArgs a, SmallMShape sh) {
-  smallm_body<AF, XT, XM, BF16>(a, sh, (int)blockIdx.x);
+  smallm_body<AF, XT, XM, BF16, PRE>(a, sh, (int)blockIdx.x);
 }
 
 // Up to four linears with the same token count in one launch (q, k, v or gate, up of a decode batch: a launch of this
@@ -298,7 +347,7 @@ struct SmallMBatch {
   int first_block[kMaxBatch];
   int n;
 };
-template <int AF, int XT, int XM, bool BF16, int OCC>
+template <int AF, int XT, int XM, bool BF16, int OCC, bool PRE>
 __global__ __launch_bounds__(kSmThreads, OCC) void w4_smallm_batch_kernel(SmallMBatch b) {
   int pi = 0;
 #pragma unroll
@@ -306,7 +355,7 @@ __global__ __launch_bounds__(kSmThreads, OCC) void w4_smallm_batch_kernel(SmallM
   // by value: the member's fields come from the argument buffer in a few wide scalar loads up front
   const LinearArgs a = b.p[pi];
   const SmallMShape sh = b.sh[pi];
-  smallm_body<AF, XT, XM, BF16>(a, sh, (int)blockIdx.x - b.first_block[pi]);
+  smallm_body<AF, XT, XM, BF16, PRE>(a, sh, (int)blockIdx.x - b.first_block[pi]);
 }
 
 // K split and groups per wave: the fewest waves along K that give the launch at least 1280 waves (five per compute
@@ -322,13 +371,20 @@ static inline SmallMShape smallm_shape(const LinearArgs& a) {
 
 // (waves per SIMD the compiler may count on: four with up to 8 staged tokens, which leaves 128 registers and lets two
 // blocks share a compute unit; with 16 tokens that budget spills and measured 15.5 against 12.4 us)
-template <int AF, int XT, int XM, bool BF16, int OCC = ((XT <= 8 && XM != 0) ? 4 : 2)>
+// LDS of a block: the waves' private tiles, or the block's image of the activations, and the K-split partial sums
+template <int AF, int XT, bool PRE>
+static constexpr size_t smallm_lds() {
+  return (PRE ? (size_t)kSmPreGroups * 16 * XT : (size_t)kSmWaves * 2 * 16 * 16 * AF) * sizeof(uint4) +
+         (size_t)kSmWaves * AF * 4 * 64 * sizeof(float);
+}
+
+template <int AF, int XT, int XM, bool BF16, bool PRE = false, int OCC = ((XT <= 8 && XM != 0) ? 4 : 2)>
 static hipError_t smallm_launch(const LinearArgs& a, hipStream_t stream) {
   const SmallMShape sh = smallm_shape(a);
   const int wn = kSmWaves / sh.ks;
   const int row_tiles = (a.km.n_keep + 15) / 16;
-  const size_t smem = (size_t)kSmWaves * 2 * 16 * 16 * AF * sizeof(uint4) + (size_t)kSmWaves * AF * 4 * 64 * sizeof(float);
-  auto kern = w4_smallm_kernel<AF, XT, XM, BF16, OCC>;
+  constexpr size_t smem = smallm_lds<AF, XT, PRE>();
+  auto kern = w4_smallm_kernel<AF, XT, XM, BF16, OCC, PRE>;
   if (smem > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
@@ -344,6 +400,18 @@ static inline bool smallm_serves(const LinearArgs& a) {
          ((long long)(a.M - 1) * a.ldx + a.km.k_keep) * 2 < lim;
 }
 
+// the pre-staged image serves: a column prefix (the caller's XM = 1) of at most 32 groups, up to 16 tokens
+static inline bool smallm_pre(const LinearArgs& a) {
+  return a.M <= 16 && (a.km.k_span + kGroup - 1) / kGroup <= kSmPreGroups && smallm_shape(a).ks <= 2;
+}
+
+// which linears this kernel takes (prefix: the activations are a column prefix of at least 8 columns): up to 8 tokens
+// all it serves; beyond that the short matrices, and the tall ones when their activations can be staged once per block
+static inline bool smallm_takes(const LinearArgs& a, bool prefix) {
+  const int row_tiles = (a.km.n_keep + 15) / 16;
+  return smallm_serves(a) && (a.M <= 8 || row_tiles < 600 || (prefix && smallm_pre(a)));
+}
+
 template <int XM, bool BF16>
 static hipError_t smallm_dispatch(const LinearArgs& a, hipStream_t stream) {
   // column segments: a unit that holds a segment's last kept columns is read as 16 bytes that may run past the end of
@@ -352,16 +420,23 @@ static hipError_t smallm_dispatch(const LinearArgs& a, hipStream_t stream) {
   if constexpr (XM == 2) {
     if (a.km.cs_keep % 2 != 0) return smallm_dispatch<0, BF16>(a, stream);
   }
+  if constexpr (XM == 1) {
+    if (smallm_pre(a)) {
+      if (a.M <= 4) return smallm_launch<1, 4, 1, BF16, true>(a, stream);
+      if (a.M <= 8) return smallm_launch<1, 8, 1, BF16, true>(a, stream);
+      return smallm_launch<1, 16, 1, BF16, true>(a, stream);
+    }
+  }
   if (a.M <= 4) return smallm_launch<1, 4, XM, BF16>(a, stream);
   if (a.M <= 8) return smallm_launch<1, 8, XM, BF16>(a, stream);
   if (a.M <= 16) return smallm_launch<1, 16, XM, BF16>(a, stream);
   return smallm_launch<2, 32, XM, BF16>(a, stream);
 }
 
-template <int AF, int XT, bool BF16, int OCC = (XT <= 8 ? 4 : 2)>
+template <int AF, int XT, bool BF16, bool PRE = false, int OCC = (XT <= 8 ? 4 : 2)>
 static hipError_t smallm_launch_batch(const LinearArgs* a, int n, hipStream_t stream) {
-  const size_t smem = (size_t)kSmWaves * 2 * 16 * 16 * AF * sizeof(uint4) + (size_t)kSmWaves * AF * 4 * 64 * sizeof(float);
-  auto kern = w4_smallm_batch_kernel<AF, XT, 1, BF16, OCC>;
+  constexpr size_t smem = smallm_lds<AF, XT, PRE>();
+  auto kern = w4_smallm_batch_kernel<AF, XT, 1, BF16, OCC, PRE>;
   if (smem > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
@@ -388,13 +463,17 @@ template <bool BF16>
 static hipError_t smallm_batch(const LinearArgs* a, int n, hipStream_t stream, bool* done) {
   *done = false;
   for (int i = 0; i < n; ++i) {
-    const int row_tiles = (a[i].km.n_keep + 15) / 16;
-    if (a[i].km.cs_stride != 0 || a[i].km.k_keep < 8 || a[i].M != a[0].M || !smallm_serves(a[i]) ||
-        !(a[i].M <= 8 || row_tiles < 600))
-      return hipSuccess;
+    if (a[i].km.cs_stride != 0 || a[i].km.k_keep < 8 || a[i].M != a[0].M || !smallm_takes(a[i], true)) return hipSuccess;
   }
   *done = true;
   const int M = a[0].M;
+  bool pre = true;
+  for (int i = 0; i < n; ++i) pre = pre && smallm_pre(a[i]);
+  if (pre) {
+    if (M <= 4) return smallm_launch_batch<1, 4, BF16, true>(a, n, stream);
+    if (M <= 8) return smallm_launch_batch<1, 8, BF16, true>(a, n, stream);
+    return smallm_launch_batch<1, 16, BF16, true>(a, n, stream);
+  }
   if (M <= 4) return smallm_launch_batch<1, 4, BF16>(a, n, stream);
   if (M <= 8) return smallm_launch_batch<1, 8, BF16>(a, n, stream);
   if (M <= 16) return smallm_launch_batch<1, 16, BF16>(a, n, stream);
