@@ -292,6 +292,9 @@ def test_fused_qkv_rope(env, uref, model, sym):
     (14208 + 37, 3584, Keep(n_keep=14208), 64),
     (3584, 18944, Keep(k_keep=14208), 32),
     (3584, 18944, Keep(k_keep=14208), 64),
+    (14208 + 37, 3584, Keep(n_keep=14208), 16),            # activations staged once per block: sixteen, three and
+    (10300, 4096, Keep(n_keep=10241, k_keep=4089), 3),     # thirteen tokens, ragged rows and columns
+    (20600, 1024, Keep(n_keep=20481, k_keep=1017), 13),
 ])
 def test_decode_batches(env, uref, N, K, keep, M):
     uq, torch = env

@@ -268,6 +268,32 @@ def test_qwen25_7b_shapes(env, uref, M):
         assert err <= TOL, (spec.name, err)
 
 
+@pytest.mark.parametrize("M", [2, 8, 12, 16])
+def test_qwen25_7b_decode_batch_in_one_call(env, uref, M):
+    """q + k + v and gate + up of a Qwen2.5-7B decode batch through uniql_w4_linear_multi at the model's sizes (one
+    launch of the decode-batch kernel per call; gate / up with the activations staged once per block): sampled rows of
+    every token against the oracle, and the bits of single calls."""
+    uq, torch = env
+    rng = wl.rng_for(2, 300 + M)
+    specs = {s.name: s for s in wl.qwen25_7b_layer(25)}
+    for names in (("q_proj", "k_proj", "v_proj"), ("gate_proj", "up_proj")):
+        ws = [wl.gen_linear(rng, specs[n].N, specs[n].K) for n in names]
+        qws = [uq.QuantLinear.from_numpy(w) for w in ws]
+        keeps = [specs[n].keep for n in names]
+        x = wl.gen_activations(rng, M, specs[names[0]].k_keep)
+        xd = to_dev(torch, x)
+        ys = [torch.full((M, specs[n].n_keep), 9.0, dtype=torch.float16, device="cuda") for n in names]
+        uq.uniql_w4_linear_multi(qws, keeps, [xd] * len(names), ys)
+        torch.cuda.synchronize()
+        for n, w, qw, kp, y in zip(names, ws, qws, keeps, ys):
+            assert torch.equal(uq.uniql_w4_linear(qw, kp, xd), y), n
+            rows = _sample_rows(specs[n].n_keep, rng, 64)
+            ref = uref.w4_linear(w["qweight"], w["scales"], w["zeros"], x, kp, rows=rows)
+            rms = np.sqrt(np.mean(ref ** 2, axis=-1, keepdims=True))
+            got = y.cpu().numpy().astype(np.float64)[:, rows]
+            assert np.max(np.abs(got - ref) / np.maximum(np.abs(ref), 1e-2 * rms)) <= TOL, n
+
+
 def test_mamba2_shapes(env, uref):
     uq, torch = env
     rng = wl.rng_for(3)
@@ -1199,10 +1225,17 @@ def test_streaming_gate_up_silu_shapes(env, uref, N, K, keep, sym):
     (4100, 6144, Keep(k_keep=6016), 4),                    # three chunks
     (2500, 8192, Keep(n_keep=2049, k_keep=8184), 8),       # four chunks, 128 KB of activations
     (2100, 8192, Keep(), 7),
+    # activations staged once per block (640 row tiles and more, at most 32 groups, up to 16 tokens):
+    (10300, 4096, Keep(n_keep=10241, k_keep=4089), 3),     # 32 groups, one kept column past the last whole block of 8, four token slots
+    (20600, 1024, Keep(n_keep=20481, k_keep=1017), 13),    # K not split (1281 row tiles), 16 token slots, ragged rows and columns
+    (10400, 2048, Keep(), 16),                             # every token slot used
+    (10400, 4224, Keep(k_keep=4096), 9),                   # exactly 32 kept groups of a longer row
+    (10400, 4224, Keep(k_keep=4100), 8),                   # 33 groups: the per-wave staging again
+    (12800, 1024, Keep(n_keep=100 * 108, row_seg_stride=128, row_seg_keep=108, row_seg_limit=12800), 6),   # row segments
 ])
 @pytest.mark.parametrize("sym", [False, True])
 def test_decode_batches_on_tall_matrices(env, uref, N, K, keep, M, sym):
-    """2..8 tokens on tall row-prefix x column-prefix matrices (small decode batches on gate / up shaped
+    """2..16 tokens on tall row-prefix x column-prefix matrices (small decode batches on gate / up shaped
     linears), every output against the oracle."""
     uq, torch = env
     rng = wl.rng_for(15, N + K + M)
