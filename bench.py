@@ -341,6 +341,18 @@ def detail_report(torch, uq, side):
             rep[f"qwen25_7b_p25_{label}_one_call_M{M}"] = {"M": M, "MB": round(nbytes / 1e6, 3), "us": round(us, 2),
                                                             "GBps": round(nbytes / us / 1e3, 1),
                                                             "frac_hbm": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4)}
+    # gate + up + SiLU(gate) * up of the same decode batches in one launch
+    gsp = qspecs["gate_proj"]
+    gpl = qpools[(gsp.N, gsp.K)]
+    for M in (8, 16):
+        x = torch.randn((M, gsp.k_keep), dtype=fdt(torch), device="cuda")
+        h = torch.empty((M, gsp.n_keep), dtype=fdt(torch), device="cuda")
+        half = len(gpl) // 2
+        us = graph_time_us(torch, side, lambda i: uq.uniql_w4_gate_up_silu_batch([gpl[i % half], gpl[half + i % half]], [gsp.keep, gsp.keep], x, h), half)
+        nbytes = 2 * gsp.algorithmic_bytes(M) - M * gsp.k_keep * 2 - M * gsp.n_keep * 2
+        rep[f"qwen25_7b_p25_gate_up_silu_M{M}"] = {"M": M, "MB": round(nbytes / 1e6, 3), "us": round(us, 2),
+                                                    "GBps": round(nbytes / us / 1e3, 1),
+                                                    "frac_hbm": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4)}
     qpools.clear()
     torch.cuda.empty_cache()
     # Mamba2-2.7B shapes, 15 %

@@ -303,6 +303,22 @@ int uniql_w4_gate_up_silu(const uniql_w4_t* W, const uniql_keep_t* keep, const v
                           void* hip_stream);
 
 /*
+ * The same hidden vectors for a decode batch of M tokens in ONE launch (Eq. 1, row by row):
+ *   h[m] = sigma(x[m] W_gate') * (x[m] W_up'),  sigma = SiLU
+ * gate and up sums stay in fp32 until h is rounded once.
+ *   x_f16 : device [M][ldx], the first k_keep entries of a row are the kept inputs;  h_f16 : device [M][ldh], the first
+ *   n_keep entries of a row are written;  W, keep as in uniql_w4_gate_up_silu.
+ * M = 1 is uniql_w4_gate_up_silu (ldx, ldh unused).  M = 2..16 is served where a block of the decode-batch kernel
+ * can hold the activations of all its rows' groups: the kept columns are a prefix of at least 8 and at most 4096
+ * stored columns, rows have at least 8 groups, and the K range of a row goes over at most two waves of a block (at
+ * least 10225 kept rows, or rows of at most 12 groups up to their last kept column).  Everything else returns E_SHAPE: the library has no scratch memory for separate gate and up
+ * results (run uniql_w4_linear_multi and the activation yourself).
+ * Errors: as uniql_w4_gate_up_silu.
+ */
+int uniql_w4_gate_up_silu_batch(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_f16, int64_t ldx,
+                                void* h_f16, int64_t ldh, int32_t M, void* hip_stream);
+
+/*
  * Measurement aid, not part of the method: reads `bytes` of device memory at `src`
  * (16-byte aligned) once with wave-wide 128-bit loads, the access shape of the GEMV's
  * weight stream, and writes one xor word per 8 KB to `out_words` (device, at least

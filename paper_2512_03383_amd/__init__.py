@@ -83,6 +83,8 @@ def lib():
                                         i32, i32, i32, i32, i32, C.c_double, vp]
         L.uniql_w4_gate_up_silu.restype = C.c_int
         L.uniql_w4_gate_up_silu.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, vp, vp]
+        L.uniql_w4_gate_up_silu_batch.restype = C.c_int
+        L.uniql_w4_gate_up_silu_batch.argtypes = [C.POINTER(W4), C.POINTER(KeepDesc), vp, i64, vp, i64, i32, vp]
         L.uniql_w4_interleave.restype = C.c_int
         L.uniql_w4_interleave.argtypes = [C.POINTER(W4), i32, vp, vp]
         L.uniql_w4_deinterleave.restype = C.c_int
@@ -401,6 +403,20 @@ def uniql_w4_gate_up_silu(Ws, keeps, x, h=None, stream=None):
     if h is None:
         h = torch.empty((kept_dims(Ws[0], keeps[0])[0],), dtype=x.dtype, device=x.device)
     GateUpCall(Ws, keeps, x, h).run(stream)
+    return h
+
+
+def uniql_w4_gate_up_silu_batch(Ws, keeps, x, h=None, stream=None):
+    """h[m] = SiLU(x[m] W_gate') * (x[m] W_up') for the tokens of a decode batch, x [M][k_keep]; returns h [M][n_keep]."""
+    import torch
+    assert len(Ws) == 2 and len(keeps) == 2 and x.dim() == 2 and x.stride(1) == 1 and x.dtype == Ws[0].ftype
+    if h is None:
+        h = torch.empty((x.shape[0], kept_dims(Ws[0], keeps[0])[0]), dtype=x.dtype, device=x.device)
+    assert h.dim() == 2 and h.stride(1) == 1 and h.dtype == x.dtype and h.shape[0] == x.shape[0]
+    W = (W4 * 2)(*[w.desc() for w in Ws])
+    kd = (KeepDesc * 2)(*[(_keep_desc(kp) or KeepDesc()) for kp in keeps])
+    _check(lib().uniql_w4_gate_up_silu_batch(W, kd, C.c_void_p(x.data_ptr()), x.stride(0), C.c_void_p(h.data_ptr()),
+                                             h.stride(0), x.shape[0], _stream_ptr(stream)))
     return h
 
 

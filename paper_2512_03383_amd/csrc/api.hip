@@ -456,6 +456,27 @@ extern "C" int uniql_w4_gate_up_silu(const uniql_w4_t* W, const uniql_keep_t* ke
   return fused ? UNIQL_OK : UNIQL_E_SHAPE;   // no scratch to fall back on: the caller runs the two linears itself
 }
 
+extern "C" int uniql_w4_gate_up_silu_batch(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_f16, int64_t ldx,
+                                           void* h_f16, int64_t ldh, int32_t M, void* hip_stream) {
+  if (!W) return UNIQL_E_NULL;
+  LinearArgs a[2];
+  for (int i = 0; i < 2; ++i) {
+    int rc = fill_linear(&W[i], keep ? &keep[i] : nullptr, x_f16, ldx, h_f16, ldh, M, &a[i]);
+    if (rc) return rc;
+    if (a[i].il_heads > 0) return UNIQL_E_SHAPE;
+  }
+  if (a[0].km.n_keep != a[1].km.n_keep || a[0].K_total != a[1].K_total || a[0].km.k_keep != a[1].km.k_keep ||
+      a[0].km.cs_stride != a[1].km.cs_stride || a[0].km.cs_keep != a[1].km.cs_keep) return UNIQL_E_KEEP;
+  if (a[0].bf16 != a[1].bf16) return UNIQL_E_SHAPE;
+  if (M == 1) return uniql_w4_gate_up_silu(W, keep, x_f16, h_f16, hip_stream);
+  int rc = check_arch();
+  if (rc) return rc;
+  bool done = false;
+  hipError_t e = launch_w4_gate_up_silu_batch(a, (hipStream_t)hip_stream, &done);
+  if (e != hipSuccess) return hip_fail(e);
+  return done ? UNIQL_OK : UNIQL_E_SHAPE;   // no scratch to fall back on: the caller runs the two linears itself
+}
+
 extern "C" int uniql_w4_interleave(const uniql_w4_t* W, int32_t heads, uint32_t* out_qweight, void* hip_stream) {
   KeepMap km;
   int rc = make_keepmap(W, nullptr, &km);

@@ -297,6 +297,9 @@ hipError_t launch_w4_gemm_bf16(const LinearArgs& a, hipStream_t stream);
 // n (2..4) linears of one decode batch in one launch where the decode-batch kernel takes them all (*done says whether)
 hipError_t launch_w4_gemm_batch(const LinearArgs* a, int n, hipStream_t stream, bool* done);
 hipError_t launch_w4_gemm_batch_bf16(const LinearArgs* a, int n, hipStream_t stream, bool* done);
+// gate (p[0]) and up (p[1]) of a decode batch (2..16 tokens) with h = SiLU(g) * u in one launch (*done says whether)
+hipError_t launch_w4_gate_up_silu_batch(const LinearArgs* p, hipStream_t stream, bool* done);
+hipError_t launch_w4_gate_up_silu_batch_bf16(const LinearArgs* p, hipStream_t stream, bool* done);
 hipError_t launch_w4_dequant(const LinearArgs& a, hipStream_t stream);
 // codes of 8 bits: the dequantised matrix, and the linear for any number of tokens
 hipError_t launch_w8_dequant(const LinearArgs& a, hipStream_t stream);

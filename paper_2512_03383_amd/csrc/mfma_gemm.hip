@@ -16,4 +16,10 @@ hipError_t launch_w4_gemm_batch(const LinearArgs* a, int n, hipStream_t stream, 
   return smallm_batch<false>(a, n, stream, done);
 }
 
+// gate and up of a decode batch with h = SiLU(g) * u (Eq. 1) in one launch; *done = false: nothing was launched
+hipError_t launch_w4_gate_up_silu_batch(const LinearArgs* p, hipStream_t stream, bool* done) {
+  if (p[0].bf16) return launch_w4_gate_up_silu_batch_bf16(p, stream, done);
+  return smallm_glu<false>(p, stream, done);
+}
+
 }  // namespace uniql

@@ -8,4 +8,8 @@ hipError_t launch_w4_gemm_batch_bf16(const LinearArgs* a, int n, hipStream_t str
   return smallm_batch<true>(a, n, stream, done);
 }
 
+hipError_t launch_w4_gate_up_silu_batch_bf16(const LinearArgs* p, hipStream_t stream, bool* done) {
+  return smallm_glu<true>(p, stream, done);
+}
+
 }  // namespace uniql

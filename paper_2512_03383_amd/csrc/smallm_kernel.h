@@ -42,10 +42,17 @@ struct SmallMShape {
 // before the loop -- every thread fetches its share with 128-bit loads issued ahead of the first weight loads, one
 // block barrier -- and the loop only reads them.  The per-wave staging above costs as much as the unpack and the
 // matrix instructions together, and with two to four waves per SIMD nothing hides it.
-template <int AF, int XT, int XM, bool BF16, bool PRE>
-__device__ __forceinline__ void smallm_body(const LinearArgs& a, const SmallMShape sh, const int block) {
+//
+// GLU (with PRE): the block serves the gate and the up matrix of a gated MLP (Eq. 1) on the same activations -- waves
+// with an even index along the rows take the gate rows of a row tile, their odd neighbours the up rows of the same tile
+// -- and after the K-split sums the up wave hands its fp32 sums to the gate wave through LDS, which stores
+// h = SiLU(g) * u rounded once.
+template <int AF, int XT, int XM, bool BF16, bool PRE, bool GLU = false>
+__device__ __forceinline__ void smallm_body(const LinearArgs& a_first, const SmallMShape sh, const int block,
+                                            const LinearArgs* a_up = nullptr) {
   constexpr bool XVEC = XM == 1, XSEG = XM == 2;
   static_assert(!PRE || (XM == 1 && AF == 1 && XT <= 16), "the pre-staged image: a column prefix, one token fragment");
+  static_assert(!GLU || PRE, "gate and up share the block's image of the activations");
   constexpr int D = kSmRing;
   constexpr int BM = 16 * AF;                 // token slots of a staged tile
   constexpr int UPL = XT * 16 / kWave;        // 16-byte units (8 columns of one token) per lane and group
@@ -53,12 +60,14 @@ __device__ __forceinline__ void smallm_body(const LinearArgs& a, const SmallMSha
   constexpr int TILE_UNITS = 16 * BM;         // [16 chunks][BM token slots]
 
   extern __shared__ __align__(16) unsigned char smem[];
-  const KeepMap& km = a.km;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int KS = sh.ks, WN = kSmWaves / KS;
   const int wn = wave % WN, wk = wave / WN;
   const int n = lane & 15, ks = lane >> 4;
+  const bool is_up = GLU && (wn & 1) != 0;            // wave-uniform
+  const LinearArgs& a = is_up ? *a_up : a_first;
+  const KeepMap& km = a.km;
   // PRE: one image for the block, [group][16 chunks][XT token slots]; else this wave's two tiles
   uint4* xs = reinterpret_cast<uint4*>(smem) + (PRE ? 0 : (size_t)wave * 2 * TILE_UNITS);
   float* red = reinterpret_cast<float*>(smem + (PRE ? (size_t)kSmPreGroups * 16 * XT : (size_t)kSmWaves * 2 * TILE_UNITS) * sizeof(uint4));   // [8][AF * 4][64]
@@ -81,7 +90,7 @@ __device__ __forceinline__ void smallm_body(const LinearArgs& a, const SmallMSha
   const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<half_t*>(a.x), 0, (int)(((long long)(a.M - 1) * a.ldx + km.k_keep) * 2), kRsrcWord3);
 
   // stored row of this lane's weight fragment (clamped: a lane past the last row re-reads it and stores nothing)
-  const int rc = (block * WN + wn) * 16 + n;
+  const int rc = (GLU ? (block * WN + wn) >> 1 : block * WN + wn) * 16 + n;
   const int wrow = stored_row(km, rc < km.n_keep ? rc : km.n_keep - 1);
   typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
   typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
@@ -294,8 +303,10 @@ __device__ __forceinline__ void smallm_body(const LinearArgs& a, const SmallMSha
 #pragma unroll
       for (int v = 0; v < 4; ++v) mine[(af * 4 + v) * 64 + lane] = acc[af][v];
     __syncthreads();
-    if (wk != 0) return;
-    for (int k2 = 1; k2 < KS; ++k2) {
+    if constexpr (!GLU) {
+      if (wk != 0) return;
+    }
+    for (int k2 = 1; k2 < KS && wk == 0; ++k2) {
       const float* other = red + (size_t)(k2 * WN + wn) * AF * 4 * 64;
 #pragma unroll
       for (int af = 0; af < AF; ++af)
@@ -303,9 +314,10 @@ __device__ __forceinline__ void smallm_body(const LinearArgs& a, const SmallMSha
         for (int v = 0; v < 4; ++v) acc[af][v] += other[(af * 4 + v) * 64 + lane];
     }
   }
+  const bool owner = wk == 0;   // (GLU keeps every wave to the last barrier)
   if constexpr (XVEC) {
     // the kept columns kv .. k_keep-1 (fewer than 8: one word of one group per row), in fp32
-    if (kv < km.k_keep) {
+    if (kv < km.k_keep && owner) {
       const uint32_t word = a.qweight[(size_t)wrow * words_per_row + (kv >> 3)];
       const size_t gi = (size_t)wrow * groups_per_row + (kv >> 7);
       const float sf = in16<BF16>(__builtin_bit_cast(half_t, a.scales[gi]));
@@ -324,6 +336,27 @@ __device__ __forceinline__ void smallm_body(const LinearArgs& a, const SmallMSha
       }
     }
   }
+  if constexpr (GLU) {
+    // the up wave's region of the partial-sum buffer is its own (the K-split sums above read the regions of the waves
+    // further along K only): u through it to the gate wave next door
+    float* mine = red + (size_t)wave * 4 * 64;
+    if (owner && is_up) {
+#pragma unroll
+      for (int v = 0; v < 4; ++v) mine[v * 64 + lane] = acc[0][v];
+    }
+    __syncthreads();
+    if (owner && !is_up) {
+      const float* theirs = red + (size_t)(wave + 1) * 4 * 64;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int tok = 4 * ks + v;
+        const float g = acc[0][v], u = theirs[v * 64 + lane];
+        if (tok < a.M && rc < km.n_keep)
+          a.y[(size_t)tok * a.ldy + rc] = out16<BF16>(g * u * __builtin_amdgcn_rcpf(1.0f + __expf(-g)));
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int af = 0; af < AF; ++af)
 #pragma unroll
@@ -331,6 +364,12 @@ __device__ __forceinline__ void smallm_body(const LinearArgs& a, const SmallMSha
       const int tok = af * 16 + 4 * ks + v;
       if (tok < a.M && rc < km.n_keep) a.y[(size_t)tok * a.ldy + rc] = out16<BF16>(acc[af][v]);
     }
+}
+
+// the gated MLP's hidden vectors of a decode batch: gate and up in one launch, h = SiLU(g) * u
+template <int XT, bool BF16, int OCC>
+__global__ __launch_bounds__(kSmThreads, OCC) void w4_smallm_glu_kernel(LinearArgs gate, LinearArgs up, SmallMShape sh) {
+  smallm_body<1, XT, 1, BF16, true, true>(gate, sh, (int)blockIdx.x, &up);
 }
 
 template <int AF, int XT, int XM, bool BF16, int OCC, bool PRE>
@@ -478,6 +517,35 @@ static hipError_t smallm_batch(const LinearArgs* a, int n, hipStream_t stream, b
   if (M <= 8) return smallm_launch_batch<1, 8, BF16>(a, n, stream);
   if (M <= 16) return smallm_launch_batch<1, 16, BF16>(a, n, stream);
   return smallm_launch_batch<2, 32, BF16>(a, n, stream);
+}
+
+template <int XT, bool BF16, int OCC = (XT <= 8 ? 4 : 2)>
+static hipError_t smallm_launch_glu(const LinearArgs* p, hipStream_t stream) {
+  const SmallMShape sh = smallm_shape(p[0]);
+  const int wn = kSmWaves / sh.ks;                 // (at least 4: the K range goes over at most two waves)
+  const int row_tiles = (p[0].km.n_keep + 15) / 16;
+  constexpr size_t smem = smallm_lds<1, XT, true>();
+  auto kern = w4_smallm_glu_kernel<XT, BF16, OCC>;
+  if (smem > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(kern, dim3((2 * row_tiles + wn - 1) / wn), dim3(kSmThreads), smem, stream, p[0], p[1], sh);
+  return hipGetLastError();
+}
+
+// gate (p[0]) and up (p[1]) of a decode batch with h = SiLU(g) * u in one launch: 2..16 tokens, the same kept rows in
+// number and the same column prefix (the caller checks), tall matrices whose activations fit the block's image.
+// *done = false: not such a pair, nothing was launched.
+template <bool BF16>
+static hipError_t smallm_glu(const LinearArgs* p, hipStream_t stream, bool* done) {
+  *done = false;
+  for (int i = 0; i < 2; ++i)
+    if (p[i].km.cs_stride != 0 || p[i].km.k_keep < 8 || !smallm_serves(p[i]) || !smallm_pre(p[i])) return hipSuccess;
+  *done = true;
+  if (p[0].M <= 4) return smallm_launch_glu<4, BF16>(p, stream);
+  if (p[0].M <= 8) return smallm_launch_glu<8, BF16>(p, stream);
+  return smallm_launch_glu<16, BF16>(p, stream);
 }
 
 }  // namespace uniql

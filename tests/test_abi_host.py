@@ -281,6 +281,26 @@ def test_gate_up_silu_rejects_bad_arguments():
     assert _glu(keeps=[KeepDesc(col_seg_stride=128, col_seg_keep=64), KeepDesc(k_keep=256)]) == uq.UNIQL_E_KEEP
 
 
+def _glub(ws=None, keeps=None, x=P, h=P, ldx=512, ldh=512, M=4):
+    ws = ws if ws is not None else [_w(), _w()]
+    W = (W4 * 2)(*ws)
+    K = (KeepDesc * 2)(*keeps) if keeps is not None else None
+    return uq.lib().uniql_w4_gate_up_silu_batch(W, K, C.c_void_p(x), ldx, C.c_void_p(h), ldh, M, None)
+
+
+def test_gate_up_silu_batch_rejects_bad_arguments():
+    assert uq.lib().uniql_w4_gate_up_silu_batch(None, None, C.c_void_p(P), 512, C.c_void_p(P), 512, 4, None) == uq.UNIQL_E_NULL
+    assert _glub(x=0) == uq.UNIQL_E_NULL
+    assert _glub(h=0) == uq.UNIQL_E_NULL
+    assert _glub(M=0) == uq.UNIQL_E_SHAPE
+    assert _glub(ldx=100) == uq.UNIQL_E_SHAPE                      # shorter than the kept columns
+    assert _glub(ws=[_w(), _w(group=64)]) == uq.UNIQL_E_SHAPE
+    assert _glub(h=P + 1) == uq.UNIQL_E_ALIGN
+    assert _glub(keeps=[KeepDesc(n_keep=100), KeepDesc(n_keep=101)]) == uq.UNIQL_E_KEEP
+    assert _glub(keeps=[KeepDesc(k_keep=100), KeepDesc(k_keep=104)]) == uq.UNIQL_E_KEEP
+    assert _glub(ws=[_w(), _w(K=1024)], ldx=1024) == uq.UNIQL_E_KEEP
+
+
 def _emb(w=None, ids=P, n=4, out=P, ld=512):
     w = w if w is not None else _w()
     return uq.lib().uniql_w4_embedding(C.byref(w), C.c_void_p(ids), n, C.c_void_p(out), ld, None)

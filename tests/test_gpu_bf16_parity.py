@@ -254,6 +254,30 @@ def test_gate_up_silu(env, uref, N, K, keep, sym):
     assert np.max(np.abs(got - ref) / np.maximum(np.abs(ref), 1e-2 * rms)) <= TOL_BF16
 
 
+@pytest.mark.parametrize("N,K,keep,M", [
+    (14208 + 37, 3584, Keep(n_keep=14208), 8),             # Qwen2.5-7B gate / up at 25 %
+    (10300, 4096, Keep(n_keep=10241, k_keep=4089), 13),    # ragged rows and columns, sixteen token slots
+])
+def test_gate_up_silu_decode_batches(env, uref, N, K, keep, M):
+    """The gated MLP's hidden vectors of a decode batch in bfloat16, one launch: sampled rows of every token."""
+    uq, torch = env
+    rng = wl.rng_for(24, 500 + N + M)
+    wg, wu = gen(rng, N, K), gen(rng, N, K)
+    nk, kk = uref.count_kept(N, K, keep)
+    x = wl.gen_activations(rng, M, kk, fmt=FMT)
+    h = uq.uniql_w4_gate_up_silu_batch([uq.QuantLinear.from_numpy(wg), uq.QuantLinear.from_numpy(wu)], [keep, keep],
+                                       dev_bf16(torch, x))
+    torch.cuda.synchronize()
+    assert h.shape == (M, nk) and h.dtype == torch.bfloat16
+    rows = _sample_rows(nk, rng, 256)
+    g = oracle_linear(uref, wg, x, keep, rows=rows)
+    u = oracle_linear(uref, wu, x, keep, rows=rows)
+    ref = g / (1.0 + np.exp(-g)) * u
+    got = host_vals(h)[:, rows]
+    rms = np.sqrt(np.mean(ref ** 2, axis=-1, keepdims=True))
+    assert np.max(np.abs(got - ref) / np.maximum(np.abs(ref), 1e-2 * rms)) <= TOL_BF16
+
+
 @pytest.mark.parametrize("model", ["llama3_8b_p15", "qwen25_7b_p25"])
 @pytest.mark.parametrize("sym", [False, True])
 def test_fused_qkv_rope(env, uref, model, sym):

@@ -1218,6 +1218,63 @@ def test_streaming_gate_up_silu_shapes(env, uref, N, K, keep, sym):
 
 
 @pytest.mark.parametrize("N,K,keep,M", [
+    (14208 + 37, 3584, Keep(n_keep=14208), 8),             # Qwen2.5-7B gate / up at 25 %
+    (14336, 4096, Keep(n_keep=12185), 16),                 # Llama-3-8B gate / up at 15 %, every token slot
+    (10300, 4096, Keep(n_keep=10241, k_keep=4089), 3),     # ragged rows (the last tile holds one row) and columns, four token slots
+    (20600, 1024, Keep(n_keep=20481, k_keep=1017), 13),    # K not split: every wave owns its tile
+    (12800, 1024, Keep(n_keep=100 * 108, row_seg_stride=128, row_seg_keep=108, row_seg_limit=12800), 2),   # row segments
+])
+@pytest.mark.parametrize("sym", [False, True])
+def test_gate_up_silu_decode_batches(env, uref, N, K, keep, M, sym):
+    """h = SiLU(x Wg) * (x Wu) for 2..16 tokens in one launch: every output against the oracle, strided x and h with
+    the padding untouched, the same bits on a second call; one token through the same entry is the one-token call."""
+    uq, torch = env
+    rng = wl.rng_for(16, N + K + M)
+    wg, wu = wl.gen_linear(rng, N, K), wl.gen_linear(rng, N, K)
+    if sym:
+        wg["zeros"] = None          # one member without zero points: each wave reads its own matrix's
+    qg, qu = uq.QuantLinear.from_numpy(wg), uq.QuantLinear.from_numpy(wu)
+    nk, kk = uref.count_kept(N, K, keep)
+    x = wl.gen_activations(rng, M, kk)
+    xb = torch.full((M, kk + 3), 55.0, dtype=torch.float16, device="cuda")
+    xb[:, :kk] = to_dev(torch, x)
+    hb = torch.full((M, nk + 5), -3.0, dtype=torch.float16, device="cuda")
+    uq.uniql_w4_gate_up_silu_batch([qg, qu], [keep, keep], xb[:, :kk], hb[:, :nk])
+    torch.cuda.synchronize()
+    assert torch.all(hb[:, nk:] == -3.0)
+    ref = uref.gate_up_silu(wg, keep, wu, keep, x)
+    h = hb[:, :nk].cpu().numpy()
+    assert linear_err(h, ref) <= TOL
+    h2 = uq.uniql_w4_gate_up_silu_batch([qg, qu], [keep, keep], xb[:, :kk])
+    torch.cuda.synchronize()
+    assert torch.equal(h2, hb[:, :nk])
+    if not sym and N == 14336:
+        h1 = uq.uniql_w4_gate_up_silu_batch([qg, qu], [keep, keep], xb[:1, :kk])
+        assert torch.equal(h1[0], uq.uniql_w4_gate_up_silu([qg, qu], [keep, keep], xb[0, :kk].contiguous()))
+
+
+def test_gate_up_silu_decode_batches_refusals(env):
+    """Shapes whose activations a block cannot hold (or too few rows for a K range over at most two waves) and token
+    counts beyond 16 are refused: there is no scratch memory to fall back on."""
+    uq, torch = env
+    rng = wl.rng_for(16, 1)
+    def call(N, K, keep, M):
+        w = uq.QuantLinear.from_numpy(wl.gen_linear(rng, N, K))
+        nk, kk = uq.kept_dims(w, keep)
+        x = to_dev(torch, wl.gen_activations(rng, M, kk))
+        return uq.uniql_w4_gate_up_silu_batch([w, w], [keep, keep], x)
+    for N, K, keep, M in ((4096, 2048, Keep(), 4),                 # 256 row tiles of 16 groups: K over four waves
+                          (10400, 4224, Keep(), 4),                # 33 groups
+                          (10400, 1024, Keep(), 17),               # more tokens than the image holds
+                          (10400, 1024, Keep(k_keep=8 * 108, col_seg_stride=128, col_seg_keep=108), 4)):   # column segments
+        with pytest.raises(uq.UniqlError) as e:
+            call(N, K, keep, M)
+        assert e.value.code == uq.UNIQL_E_SHAPE
+    assert call(10400, 1024, Keep(), 16).shape == (16, 10400)
+    assert call(4096, 1024, Keep(), 4).shape == (4, 4096)          # few rows of 8 groups: K over two waves, served
+
+
+@pytest.mark.parametrize("N,K,keep,M", [
     (2048, 128, Keep(), 2),                                # one chunk, the row threshold, two tokens
     (3000, 1024, Keep(n_keep=2500, k_keep=1000), 3),       # padded to four tokens; kept width a multiple of 8
     (14208 + 37, 3584, Keep(n_keep=14208), 8),             # Qwen2.5-7B gate / up at 25 %, eight tokens
