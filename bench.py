@@ -38,7 +38,7 @@ MFMA_F16_PEAK_TFLOPS = 2500.0
 # copy (--pmc-calib).  A separate run of this script under the profiler, NOT a measurement of the present run; other
 # rates, formats and launch groupings were not measured (traffic = null).
 PMC_TRAFFIC_SOURCE = "profiles/w4_gemv_llama3_8b_decode_p15.md"
-PMC_TRAFFIC_BYTES = {("gate_up_silu", 15): 52476000, ("mlp", 15): 79741000}     # {(launch, rate): bytes}
+PMC_TRAFFIC_BYTES = {("gate_up_silu", 15): 52480000, ("mlp", 15): 79742000}     # {(launch, rate): bytes}
 
 
 def log(*a):
