@@ -664,4 +664,4 @@ extern "C" const char* uniql_strerror(int code) {
 
 extern "C" int uniql_last_hip_error(void) { return g_last_hip_error; }
 
-extern "C" int uniql_version(void) { return 210; }
+extern "C" int uniql_version(void) { return 220; }
