@@ -76,7 +76,7 @@ enum {
  * sectors they share with kept ones.  uniql_w4_interleave converts (a permutation of words, exact) and
  * uniql_w4_deinterleave converts back.  Served: uniql_w4_linear for H a multiple of 4 that divides 256, D = 128,
  * unpruned rows, and either no column pruning or column segments of stride 128, with the one-token kernel (1..64 tokens
- * run it token by token; more tokens: E_SHAPE, convert back for a prompt); uniql_w4_dequant for any H; every other call
+ * run it with one token per grid row of one launch; more tokens: E_SHAPE, convert back for a prompt); uniql_w4_dequant for any H; every other call
  * returns E_SHAPE for such a matrix.
  *
  * bits = 8 (Eq. 3 with N = 8; Sec. 3.4 and App. C name 8, 6, 4 and 3 bits as widths the method covers): qweight is

@@ -131,19 +131,12 @@ static int run_linear(const LinearArgs& a, hipStream_t s) {
     return e8 == hipSuccess ? UNIQL_OK : hip_fail(e8);
   }
   if (a.il_heads > 0 && a.M != 1) {
-    // head-interleaved words are read by the one-token kernel only: a decode batch runs it token by token (the
-    // matrix stays in the memory-side cache between the launches); prompts want the words in column order
+    // head-interleaved words are read by the one-token kernel only: a decode batch runs it with one token per grid
+    // row (the later tokens' words come from the caches); prompts want the words in column order
     if (a.M > kInterleavedMaxTokens) return UNIQL_E_SHAPE;
-    for (int m = 0; m < a.M; ++m) {
-      LinearArgs t = a;
-      t.M = 1;
-      t.x = a.x + (size_t)m * a.ldx;
-      t.y = a.y + (size_t)m * a.ldy;
-      hipError_t et = launch_w4_gemv(t, s);
-      if (et == hipErrorInvalidValue) return UNIQL_E_SHAPE;
-      if (et != hipSuccess) return hip_fail(et);
-    }
-    return UNIQL_OK;
+    hipError_t et = launch_w4_gemv(a, s);
+    if (et == hipErrorInvalidValue) return UNIQL_E_SHAPE;
+    return et == hipSuccess ? UNIQL_OK : hip_fail(et);
   }
   hipError_t e = (a.M == 1) ? launch_w4_gemv(a, s) : launch_w4_gemm(a, s);
   if (e == hipErrorInvalidValue && a.M == 1) return UNIQL_E_SHAPE;   // K too long for the GEMV's staging

@@ -43,6 +43,10 @@ struct StreamArgs {
   const uint8_t* zeros[3];
   const half_t* x;
   half_t* y;
+  // a launch may serve several tokens, one per grid row (blockIdx.y): token t reads x + t * tok_x and writes
+  // y + t * tok_y (elements); the weights of the later tokens come from the caches
+  long long tok_x, tok_y;
+  int tokens;
   int n_keep, k_keep, K_total;
   int N_total;           // stored rows (extent of the buffer resources)
   KeepMap km;            // row map (rows only; the kept columns are a prefix)
@@ -516,6 +520,10 @@ template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE = false, boo
 __global__ __launch_bounds__(kStreamThreads) void w4_gemv_stream_kernel(StreamArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int next_body;
+  if (a.tokens > 1) {
+    a.x += (long long)blockIdx.y * a.tok_x;
+    a.y += (long long)blockIdx.y * a.tok_y;
+  }
   stream_phase<NCH, NM, ZP, BF16, SEG, PROBE, false, false, HI, QKV, CS>(a, reinterpret_cast<uint4*>(smem), &next_body);
 }
 
@@ -544,7 +552,7 @@ static hipError_t stream_launch(const StreamArgs& a, hipStream_t stream) {
   // (QKV, a few thousand pairs in all: one, two or three blocks per compute unit measured the same, 6.7 us for 11.1 MB)
   // (down_proj, two rows per wave: two blocks per compute unit 8.6 against 8.2 us)
   if (blocks > cus) blocks = cus;
-  hipLaunchKernelGGL(kern, dim3(blocks), dim3(kStreamThreads), smem, stream, a);
+  hipLaunchKernelGGL(kern, dim3(blocks, a.tokens), dim3(kStreamThreads), smem, stream, a);
   return hipGetLastError();
 }
 
@@ -606,6 +614,8 @@ static inline StreamArgs stream_args(const LinearArgs& a) {
   s.zeros[0] = s.zeros[1] = a.zeros;
   s.x = a.x;
   s.y = a.y;
+  s.tok_x = s.tok_y = 0;
+  s.tokens = 1;
   s.n_keep = a.km.n_keep;
   s.k_keep = a.km.k_keep;
   s.K_total = a.K_total;
@@ -628,8 +638,8 @@ static inline StreamArgs stream_args(const LinearArgs& a) {
   return s;
 }
 
-// A matrix with head-interleaved words (one token): every shape this layout is defined for runs here, there is no
-// other kernel for it.  hipErrorInvalidValue for the rest: more than four kilobytes of kept words per row, a head
+// A matrix with head-interleaved words (1..64 tokens, one per grid row: a decode batch re-reads the words through the
+// caches): every shape this layout is defined for runs here, there is no other kernel for it.  hipErrorInvalidValue for the rest: more than four kilobytes of kept words per row, a head
 // count that does not divide 256 or is not a multiple of four, heads of another width than a group, pruned rows,
 // kept columns that are not the leading dims of every head.
 template <bool BF16>
@@ -637,9 +647,12 @@ static hipError_t stream_interleaved(const LinearArgs& a, hipStream_t stream) {
   const int H = a.il_heads;
   const bool cols_ok = a.km.cs_stride == 0 ? a.km.k_keep == a.K_total : a.km.cs_stride == kGroup;
   const bool fits = (long long)a.N_total * (a.K_total / 2) < (1ll << 31);
-  if (a.M != 1 || H < 4 || H % 4 || 256 % H || a.K_total != H * kGroup || a.km.rs_stride != 0 || !cols_ok || !fits)
+  if (a.M < 1 || a.M > 64 || H < 4 || H % 4 || 256 % H || a.K_total != H * kGroup || a.km.rs_stride != 0 || !cols_ok || !fits)
     return hipErrorInvalidValue;
-  const StreamArgs s = stream_args(a);
+  StreamArgs s = stream_args(a);
+  s.tokens = a.M;
+  s.tok_x = a.ldx;
+  s.tok_y = a.ldy;
   const int nch = (((s.d_keep + 7) >> 3) * H + 255) / 256;
   switch (nch) {
     case 1: return a.zeros ? stream_launch<1, 1, true, BF16, false, false, true>(s, stream) : stream_launch<1, 1, false, BF16, false, false, true>(s, stream);

@@ -853,7 +853,7 @@ def test_head_interleaved_o_proj(env, uref, N, heads, d_keep, sym):
 
 @pytest.mark.parametrize("N,heads,d_keep,M", [(4096, 32, 108, 2), (4096, 32, 108, 8), (300, 4, 54, 64), (1000, 64, 128, 5)])
 def test_head_interleaved_decode_batches(env, uref, N, heads, d_keep, M):
-    """2..64 tokens on head-interleaved words (the one-token kernel, token by token), strided x and y: every output
+    """2..64 tokens on head-interleaved words (the one-token kernel, a token per grid row), strided x and y: every output
     against the oracle on the same words, and each token's row bit-identical to the one-token call."""
     uq, torch = env
     rng = wl.rng_for(19, N + heads + d_keep + M)
