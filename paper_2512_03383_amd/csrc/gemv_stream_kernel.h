@@ -126,7 +126,10 @@ __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* L
   // ---- x loads first (memory returns in issue order; x is an L2 hit).  Unit u = stored columns [8u, 8u + 8).
   constexpr int XI = (NCH * 256 + kStreamThreads - 1) / kStreamThreads;
   const int kv = a.k_keep & ~7;
-  const uint16_t* xbits = reinterpret_cast<const uint16_t*>(a.x);
+  // (HI: a launch may serve several tokens, one per grid row)
+  const half_t* const ax = HI ? a.x + (long long)blockIdx.y * a.tok_x : a.x;
+  half_t* const ay = HI ? a.y + (long long)blockIdx.y * a.tok_y : a.y;
+  const uint16_t* xbits = reinterpret_cast<const uint16_t*>(ax);
   uint4 rawv[XI];
   uint32_t tailv[8];
   uint32_t elv[(HI || CS) ? XI : 1][8];   // HI, CS: the kept dims of a unit that is only partly kept, one per register
@@ -143,7 +146,7 @@ __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* L
         int nk = a.d_keep - 8 * dblk;                     // kept dims of the unit, counted from its first
         if constexpr (CS) nk = 8 * u < a.k_span ? nk : 0;
         const int base = head * a.d_keep + 8 * dblk;
-        rawv[i] = load_u4_unaligned(a.x + (nk >= 8 ? base : 0));
+        rawv[i] = load_u4_unaligned(ax + (nk >= 8 ? base : 0));
 #pragma unroll
         for (int j = 0; j < 8; ++j) elv[i][j] = 0;
         if (nk > 0 && nk < 8) {
@@ -157,7 +160,7 @@ __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* L
     for (int i = 0; i < XI; ++i) {
       const int k0 = 8 * (tid + i * kStreamThreads);
       const int k0c = k0 + 8 <= kv ? k0 : kv - 8;     // the host sends k_keep >= 8 only
-      rawv[i] = load_u4_unaligned(a.x + k0c);
+      rawv[i] = load_u4_unaligned(ax + k0c);
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) tailv[j] = 0;
@@ -190,7 +193,7 @@ __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* L
 #pragma unroll
     for (int i = 0; i < XI; ++i) {
       const int k0 = 8 * (tid + i * kStreamThreads);
-      rawv[i] = load_u4_coherent(a.x + (k0 < a.k_keep ? k0 : 0));   // the unit with the last kept columns is read whole
+      rawv[i] = load_u4_coherent(ax + (k0 < a.k_keep ? k0 : 0));   // the unit with the last kept columns is read whole
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) tailv[j] = 0;
@@ -391,9 +394,9 @@ __device__ __forceinline__ bool stream_phase(const StreamArgs& a, uint4* xs /* L
   const Magic mg = make_magic();
   auto store_y = [&](int rc, half_t v) {
     if constexpr (YTHROUGH)
-      __hip_atomic_store(reinterpret_cast<uint16_t*>(a.y + rc), __builtin_bit_cast(uint16_t, v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(reinterpret_cast<uint16_t*>(ay + rc), __builtin_bit_cast(uint16_t, v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     else
-      a.y[rc] = v;
+      ay[rc] = v;
   };
   const bool on_diag = (lane >> 4) == ((lane & 15) >> 2);
   typedef typename GroupOf<BF16>::type Group;
@@ -520,10 +523,6 @@ template <int NCH, int NM, bool ZP, bool BF16, bool SEG, bool PROBE = false, boo
 __global__ __launch_bounds__(kStreamThreads) void w4_gemv_stream_kernel(StreamArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int next_body;
-  if (a.tokens > 1) {
-    a.x += (long long)blockIdx.y * a.tok_x;
-    a.y += (long long)blockIdx.y * a.tok_y;
-  }
   stream_phase<NCH, NM, ZP, BF16, SEG, PROBE, false, false, HI, QKV, CS>(a, reinterpret_cast<uint4*>(smem), &next_body);
 }
 
