@@ -152,7 +152,7 @@ typedef struct uniql_keep {
  * 64 tokens tiles whose K range is split over the waves of a block, large tiles for prefill.
  * Errors: E_NULL, E_SHAPE, E_KEEP, E_ALIGN, E_ARCH, E_HIP.  E_SHAPE also at M = 1 when the last
  * kept column lies past stored column 81920 (the block's image of the activations in LDS holds
- * 40 tiles of 2048 columns), and for 8-bit codes past column 32768 at any M.
+ * 40 tiles of 2048 columns), and for codes of 8, 6 or 3 bits past column 32768 at any M.
  */
 int uniql_w4_linear(const uniql_w4_t* W, const uniql_keep_t* keep, const void* x_f16, int64_t ldx,
                     void* y_f16, int64_t ldy, int32_t M, void* hip_stream);
